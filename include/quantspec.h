@@ -1,0 +1,147 @@
+/*
+ * quantspec.h - C ABI of the MI355X (gfx950) decode-attention library for QuantSpec's
+ * hierarchical 4-bit KV cache.
+ *
+ * The three operations are the per-layer cache operations of the paper's Algorithm 1:
+ *   qs_quantize_flush  - QUANTIZE(C_F1) appended to C_U, C_L, then the buffer move   (Section 4.3.2)
+ *   qs_attn_draft      - attention of DRAFT : upper 4-bit plane C_U + full-precision buffer
+ *   qs_attn_verify     - attention of TARGET: C_U and C_L (INT8 = 16 C_U + C_L) + buffer,
+ *                        gamma + 1 query tokens, causal among them                     (Section 4.2)
+ *
+ * General rules
+ *   - Every pointer inside qs_cache except n_quant / n_buf is a DEVICE pointer owned by the
+ *     caller; n_quant and n_buf are HOST arrays read during the call (they are copied into the
+ *     kernel arguments, so they may change as soon as the call returns).
+ *   - The library never allocates, frees or synchronizes.  Every call enqueues its kernels on
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream) and returns.
+ *   - Return value: QS_OK, or a negative qs_status; on error nothing has been enqueued.
+ *   - head_dim and group must both be 128 (the paper's evaluation setting, Section 5.1).
+ *   - All device pointers must be 16-byte aligned.
+ *
+ * Cache layout (B = batch, Hkv = n_kv_heads, "unit" = one (sequence, kv-head) pair)
+ *   Keys, per-channel groups of 128 tokens (Section 4.3.1):
+ *     k_upper, k_lower : uint8 [B][Hkv][q_cap][64]   two codes per byte; byte j of a token row holds
+ *                        channel 2j in bits 0-3 and channel 2j+1 in bits 4-7.
+ *                        k_upper nibble = C_U (0..15); k_lower nibble = C_L + 8 (0..15).
+ *     k_scale, k_zero  : fp16  [B][Hkv][q_cap/128][128]   S and Z of (token group, channel).
+ *   Values, per-token groups of 128 channels:
+ *     v_upper, v_lower : uint8 [B][Hkv][q_cap/32][2048]   tiled for the matrix-core operand: inside a
+ *                        32-token tile, 32-bit word ((h*64 + 16*g + m)*4 + i) holds channel
+ *                        8*m + 4*h + i (h<2, g<4, m<16, i<4) of eight tokens; nibble (j&1)*4 + (j>>1)
+ *                        (j<8) belongs to token (j>>2)*16 + 4*g + (j&3) of the tile.
+ *                        Same nibble encodings as for keys.
+ *     v_scale, v_zero  : fp16  [B][Hkv][q_cap]   S and Z per token, stored at position 8*g + j of the
+ *                        32-token tile for the token defined above (the order the kernels consume).
+ *   qs_quantize_flush is the only writer of these arrays; qs_export_codes returns them in the
+ *   plain [token][channel] order for inspection.
+ *   Full-precision buffer (Section 4.3.2), plain row-major, written by the caller:
+ *     k_buf, v_buf     : fp16  [B][Hkv][buf_cap][128]   tokens [0, n_buf[b]) are valid.
+ */
+#ifndef QUANTSPEC_H_
+#define QUANTSPEC_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define QS_MAX_BATCH 64     /* per-sequence lengths travel by value in the kernel arguments      */
+#define QS_MAX_NQ 8         /* largest number of query tokens per sequence in one verify call    */
+
+typedef enum qs_status {
+  QS_OK = 0,
+  QS_ERR_NULL = -1,         /* a required pointer is NULL                                         */
+  QS_ERR_SHAPE = -2,        /* batch / head counts / capacities are inconsistent                  */
+  QS_ERR_UNSUPPORTED = -3,  /* head_dim or group != 128, batch > QS_MAX_BATCH, nq > QS_MAX_NQ      */
+  QS_ERR_ALIGN = -4,        /* a device pointer is not 16-byte aligned                            */
+  QS_ERR_RANGE = -5,        /* a length exceeds its capacity, is not a multiple of 128, n_buf < nq */
+  QS_ERR_WORKSPACE = -6,    /* workspace missing or smaller than qs_workspace_bytes()              */
+  QS_ERR_HIP = -7           /* a HIP runtime call failed (no device, launch failure)               */
+} qs_status;
+
+typedef struct qs_cache {
+  int32_t batch, n_q_heads, n_kv_heads;   /* n_q_heads % n_kv_heads == 0 (grouped-query attention)   */
+  int32_t head_dim, group;                /* both 128                                                 */
+  int32_t q_cap;                          /* capacity of the quantized region in tokens, multiple of 128 */
+  int32_t buf_cap;                        /* capacity of the fp16 buffer in tokens                    */
+  void *k_upper, *k_lower;                /* device, see layout above                                 */
+  void *v_upper, *v_lower;
+  void *k_scale, *k_zero;
+  void *v_scale, *v_zero;
+  void *k_buf, *v_buf;
+  const int32_t *n_quant;                 /* HOST int32[batch]: valid quantized tokens (multiple of 128) */
+  const int32_t *n_buf;                   /* HOST int32[batch]: valid buffer tokens                   */
+} qs_cache;
+
+/* Library version: major*10000 + minor*100 + patch. */
+int qs_version(void);
+
+/* Static, NUL-terminated description of a qs_status code. */
+const char *qs_strerror(int code);
+
+/*
+ * Bytes of device scratch the attention calls need for their split-K partial results
+ * (Appendix E: per-chunk partials that are merged afterwards).  Depends only on the shapes and
+ * capacities in `c` and on nq (1 for draft), not on the current lengths, so it can be sized once.
+ * Returns 0 if `c` is invalid.
+ */
+size_t qs_workspace_bytes(const qs_cache *c, int32_t nq);
+
+/*
+ * QUANTIZE on flush (Section 4.2, Section 4.3.2, Algorithm 1 "Quantize the first half of the full
+ * precision cache buffer"): for every sequence b, quantize buffer tokens [0, n_tokens) into both
+ * 4-bit planes with one shared fp16 (S, Z) per group, write them at token offset n_quant[b], then
+ * move buffer tokens [n_tokens, n_buf[b]) to the front of the buffer.
+ *   n_tokens: multiple of 128, <= every n_buf[b]; n_quant[b] + n_tokens <= q_cap.
+ * The host arrays are not modified: afterwards the caller adds n_tokens to n_quant[b] and
+ * subtracts it from n_buf[b].
+ */
+int qs_quantize_flush(const qs_cache *c, int32_t n_tokens, void *stream);
+
+/*
+ * QUANTIZE at prefill (Algorithm 1, "Prepare the hierarchical quantized KV Cache"): quantize
+ * n_tokens tokens of caller-provided fp16 K / V, device [B][Hkv][src_stride_tokens][128], into the
+ * planes at token offset n_quant[b].  n_tokens is a multiple of 128.  The buffer is not touched.
+ */
+int qs_quantize_prefill(const qs_cache *c, const void *k_src, const void *v_src,
+                        int64_t src_stride_tokens, int32_t n_tokens, void *stream);
+
+/*
+ * DRAFT attention (Algorithm 1; Section 4.2 "we only load the upper 4-bit representation"):
+ *   q   : device fp16 [B][1][n_q_heads][128]
+ *   out : device fp16 [B][1][n_q_heads][128]
+ * The query of sequence b attends the decoded upper plane of tokens [0, n_quant[b]) and buffer
+ * tokens [0, n_buf[b]) (its own K/V must already be the last buffer token; Appendix A).
+ * out = softmax(sm_scale * q K^T) V.  lse (device float [B][1][n_q_heads], natural log of the
+ * softmax normaliser) is written if not NULL.
+ */
+int qs_attn_draft(const qs_cache *c, const void *q, void *out, float sm_scale,
+                  void *workspace, size_t workspace_bytes, float *lse, void *stream);
+
+/*
+ * TARGET / verify attention (Algorithm 1; Section 4.2 "both the upper and lower 4-bit
+ * representations to reconstruct the KV cache in INT8"):
+ *   q   : device fp16 [B][nq][n_q_heads][128], 1 <= nq <= QS_MAX_NQ (nq = gamma + 1)
+ *   out : device fp16 [B][nq][n_q_heads][128]
+ * The nq tokens' K/V must already be the LAST nq buffer tokens.  Query i (0-based) attends all
+ * quantized tokens (decoded from 16 C_U + C_L) and buffer tokens [0, n_buf[b] - nq + i].
+ */
+int qs_attn_verify(const qs_cache *c, const void *q, int32_t nq, void *out, float sm_scale,
+                   void *workspace, size_t workspace_bytes, float *lse, void *stream);
+
+/*
+ * Inspection helper: expand the packed planes and metadata of tokens [0, n_tokens) of one unit
+ * into plain arrays (device pointers, any may be NULL to skip):
+ *   k_u, v_u : uint8 [n_tokens][128]  C_U          k_l, v_l : int8 [n_tokens][128]  C_L
+ *   v_s, v_z : fp16  [n_tokens]       per-token S, Z in token order
+ * (k_scale / k_zero are already in plain order.)  n_tokens is a multiple of 32.
+ */
+int qs_export_codes(const qs_cache *c, int32_t b, int32_t kv_head, int32_t n_tokens,
+                    void *k_u, void *k_l, void *v_u, void *v_l, void *v_s, void *v_z, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QUANTSPEC_H_ */

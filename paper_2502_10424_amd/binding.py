@@ -1,0 +1,212 @@
+"""ctypes binding of libquantspec.so: same names as the C ABI, argument marshalling only.
+
+Every step of the hot path runs inside the library's HIP kernels.  PyTorch is used for device
+memory and for the current stream handle, nothing else.  There is no fallback: if the shared
+library has not been built, loading fails with an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libquantspec.so")
+
+QS_MAX_BATCH = 64
+QS_MAX_NQ = 8
+HEAD_DIM = 128
+GROUP = 128
+
+QS_OK = 0
+QS_ERR_NULL, QS_ERR_SHAPE, QS_ERR_UNSUPPORTED, QS_ERR_ALIGN = -1, -2, -3, -4
+QS_ERR_RANGE, QS_ERR_WORKSPACE, QS_ERR_HIP = -5, -6, -7
+
+EXPORTS = ("qs_version", "qs_strerror", "qs_workspace_bytes", "qs_quantize_flush", "qs_quantize_prefill",
+           "qs_attn_draft", "qs_attn_verify", "qs_export_codes")
+
+
+class qs_cache(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("group", ctypes.c_int32),
+        ("q_cap", ctypes.c_int32), ("buf_cap", ctypes.c_int32),
+        ("k_upper", ctypes.c_void_p), ("k_lower", ctypes.c_void_p),
+        ("v_upper", ctypes.c_void_p), ("v_lower", ctypes.c_void_p),
+        ("k_scale", ctypes.c_void_p), ("k_zero", ctypes.c_void_p),
+        ("v_scale", ctypes.c_void_p), ("v_zero", ctypes.c_void_p),
+        ("k_buf", ctypes.c_void_p), ("v_buf", ctypes.c_void_p),
+        ("n_quant", ctypes.POINTER(ctypes.c_int32)), ("n_buf", ctypes.POINTER(ctypes.c_int32)),
+    ]
+
+
+class QsError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {qs_strerror(code)} (status {code})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libquantspec.so (built in-tree by paper_2502_10424_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2502_10424_amd.build` first "
+                               "(there is no fallback implementation)")
+        l = ctypes.CDLL(LIB_PATH)
+        P = ctypes.POINTER(qs_cache)
+        vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
+        l.qs_version.restype, l.qs_version.argtypes = ctypes.c_int, []
+        l.qs_strerror.restype, l.qs_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
+        l.qs_workspace_bytes.restype, l.qs_workspace_bytes.argtypes = sz, [P, i32]
+        l.qs_quantize_flush.restype, l.qs_quantize_flush.argtypes = ctypes.c_int, [P, i32, vp]
+        l.qs_quantize_prefill.restype, l.qs_quantize_prefill.argtypes = ctypes.c_int, [P, vp, vp, i64, i32, vp]
+        l.qs_attn_draft.restype = ctypes.c_int
+        l.qs_attn_draft.argtypes = [P, vp, vp, f32, vp, sz, vp, vp]
+        l.qs_attn_verify.restype = ctypes.c_int
+        l.qs_attn_verify.argtypes = [P, vp, i32, vp, f32, vp, sz, vp, vp]
+        l.qs_export_codes.restype = ctypes.c_int
+        l.qs_export_codes.argtypes = [P, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+        _lib = l
+    return _lib
+
+
+def qs_version() -> int:
+    return lib().qs_version()
+
+
+def qs_strerror(code: int) -> str:
+    return lib().qs_strerror(code).decode()
+
+
+def _ptr(t) -> int | None:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> int | None:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream or None
+    return getattr(stream, "cuda_stream", stream) or None
+
+
+class KVCache:
+    """Device tensors of one layer's hierarchical cache plus the host-side lengths.
+
+    Pure storage: allocation through torch, layout as documented in include/quantspec.h.
+    """
+
+    def __init__(self, batch: int, n_q_heads: int, n_kv_heads: int, q_cap: int, buf_cap: int,
+                 device="cuda", head_dim: int = HEAD_DIM, group: int = GROUP):
+        self.batch, self.n_q_heads, self.n_kv_heads = batch, n_q_heads, n_kv_heads
+        self.head_dim, self.group, self.q_cap, self.buf_cap = head_dim, group, q_cap, buf_cap
+        u8 = dict(dtype=torch.uint8, device=device)
+        f16 = dict(dtype=torch.float16, device=device)
+        qc = max(q_cap, 0)
+        self.k_upper = torch.zeros((batch, n_kv_heads, qc, 64), **u8)
+        self.k_lower = torch.zeros((batch, n_kv_heads, qc, 64), **u8)
+        self.v_upper = torch.zeros((batch, n_kv_heads, qc // 32, 2048), **u8)
+        self.v_lower = torch.zeros((batch, n_kv_heads, qc // 32, 2048), **u8)
+        self.k_scale = torch.zeros((batch, n_kv_heads, qc // 128, 128), **f16)
+        self.k_zero = torch.zeros((batch, n_kv_heads, qc // 128, 128), **f16)
+        self.v_scale = torch.zeros((batch, n_kv_heads, qc), **f16)
+        self.v_zero = torch.zeros((batch, n_kv_heads, qc), **f16)
+        self.k_buf = torch.zeros((batch, n_kv_heads, buf_cap, 128), **f16)
+        self.v_buf = torch.zeros((batch, n_kv_heads, buf_cap, 128), **f16)
+        self.n_quant = np.zeros(batch, np.int32)
+        self.n_buf = np.zeros(batch, np.int32)
+
+    def struct(self) -> qs_cache:
+        c = qs_cache()
+        c.batch, c.n_q_heads, c.n_kv_heads = self.batch, self.n_q_heads, self.n_kv_heads
+        c.head_dim, c.group, c.q_cap, c.buf_cap = self.head_dim, self.group, self.q_cap, self.buf_cap
+        for name in ("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "k_zero", "v_scale", "v_zero",
+                     "k_buf", "v_buf"):
+            setattr(c, name, getattr(self, name).data_ptr())
+        c.n_quant = self.n_quant.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+        c.n_buf = self.n_buf.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+        return c
+
+    def plane_bytes(self) -> int:
+        return sum(getattr(self, n).numel() * getattr(self, n).element_size()
+                   for n in ("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "k_zero", "v_scale", "v_zero"))
+
+
+def _as_struct(cache) -> qs_cache:
+    return cache.struct() if isinstance(cache, KVCache) else cache
+
+
+def _check(rc: int, where: str):
+    if rc != QS_OK:
+        raise QsError(rc, where)
+
+
+def qs_workspace_bytes(cache, nq: int) -> int:
+    c = _as_struct(cache)
+    return int(lib().qs_workspace_bytes(ctypes.byref(c), nq))
+
+
+def qs_quantize_flush(cache, n_tokens: int, stream=None) -> None:
+    """Quantize buffer tokens [0, n_tokens) into the planes and move the rest of the buffer to the
+    front.  Like the C call it leaves the host lengths alone: the caller updates n_quant / n_buf."""
+    c = _as_struct(cache)
+    _check(lib().qs_quantize_flush(ctypes.byref(c), n_tokens, _stream(stream)), "qs_quantize_flush")
+
+
+def qs_quantize_prefill(cache, k_src, v_src, n_tokens: int, stream=None) -> None:
+    """k_src, v_src: fp16 device tensors [B, Hkv, T_src, 128] (contiguous); quantizes their first n_tokens."""
+    c = _as_struct(cache)
+    assert k_src.is_contiguous() and v_src.is_contiguous() and k_src.dtype == torch.float16
+    _check(lib().qs_quantize_prefill(ctypes.byref(c), k_src.data_ptr(), v_src.data_ptr(), k_src.shape[2],
+                                     n_tokens, _stream(stream)), "qs_quantize_prefill")
+
+
+def _attn(fn_name, cache, q, nq, out, sm_scale, workspace, lse, stream):
+    c = _as_struct(cache)
+    assert q.dtype == torch.float16 and q.is_contiguous()
+    if out is None:
+        out = torch.empty_like(q)
+    if workspace is None:
+        workspace = torch.empty(qs_workspace_bytes(c, q.shape[1]), dtype=torch.uint8, device=q.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    l = lib()
+    if fn_name == "qs_attn_draft":
+        rc = l.qs_attn_draft(ctypes.byref(c), q.data_ptr(), out.data_ptr(), sm_scale, workspace.data_ptr(),
+                             ws_bytes, _ptr(lse), _stream(stream))
+    else:
+        rc = l.qs_attn_verify(ctypes.byref(c), q.data_ptr(), nq, out.data_ptr(), sm_scale, workspace.data_ptr(),
+                              ws_bytes, _ptr(lse), _stream(stream))
+    _check(rc, fn_name)
+    return out
+
+
+def qs_attn_draft(cache, q, sm_scale: float, out=None, workspace=None, lse=None, stream=None):
+    """q: fp16 device tensor [B, 1, Hq, 128].  Returns out (same shape)."""
+    assert q.shape[1] == 1
+    return _attn("qs_attn_draft", cache, q, 1, out, sm_scale, workspace, lse, stream)
+
+
+def qs_attn_verify(cache, q, sm_scale: float, out=None, workspace=None, lse=None, stream=None):
+    """q: fp16 device tensor [B, nq, Hq, 128], nq = gamma + 1.  Returns out (same shape)."""
+    return _attn("qs_attn_verify", cache, q, q.shape[1], out, sm_scale, workspace, lse, stream)
+
+
+def qs_export_codes(cache: KVCache, b: int, kv_head: int, n_tokens: int, stream=None):
+    """Plain-order codes and value metadata of one unit, as device tensors:
+    (k_u uint8 [T,128], k_l int8 [T,128], v_u, v_l, v_s fp16 [T], v_z fp16 [T])."""
+    c = cache.struct()
+    dev = cache.k_upper.device
+    k_u = torch.empty((n_tokens, 128), dtype=torch.uint8, device=dev)
+    v_u = torch.empty_like(k_u)
+    k_l = torch.empty((n_tokens, 128), dtype=torch.int8, device=dev)
+    v_l = torch.empty_like(k_l)
+    v_s = torch.empty(n_tokens, dtype=torch.float16, device=dev)
+    v_z = torch.empty_like(v_s)
+    _check(lib().qs_export_codes(ctypes.byref(c), b, kv_head, n_tokens, k_u.data_ptr(), k_l.data_ptr(),
+                                 v_u.data_ptr(), v_l.data_ptr(), v_s.data_ptr(), v_z.data_ptr(), _stream(stream)),
+           "qs_export_codes")
+    return k_u, k_l, v_u, v_l, v_s, v_z

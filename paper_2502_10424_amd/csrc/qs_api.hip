@@ -1,0 +1,260 @@
+// C ABI of libquantspec: argument validation, split planning and kernel launches.
+// All validation happens before the first HIP call, so error paths can be exercised without a GPU.
+#include <algorithm>
+#include <atomic>
+
+#include "qs_internal.h"
+
+namespace qs {
+namespace {
+
+constexpr int kVersion = 100;   // 0.1.0
+constexpr int kDefaultCUs = 256;
+constexpr int kWavesPerCU = 8;  // resident chunk waves per compute unit the split planner aims for
+
+std::atomic<int> g_cu_count{0};
+
+int cu_count() {
+  int n = g_cu_count.load(std::memory_order_relaxed);
+  if (n > 0) return n;
+  int dev = 0;
+  hipDeviceProp_t prop;
+  n = kDefaultCUs;
+  if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+      prop.multiProcessorCount > 0)
+    n = prop.multiProcessorCount;
+  g_cu_count.store(n, std::memory_order_relaxed);
+  return n;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int validate_shape(const qs_cache* c) {
+  if (c == nullptr) return QS_ERR_NULL;
+  if (c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->n_q_heads % c->n_kv_heads != 0)
+    return QS_ERR_SHAPE;
+  if (c->q_cap < 0 || c->q_cap % kG != 0 || c->buf_cap <= 0) return QS_ERR_SHAPE;
+  if (c->head_dim != kD || c->group != kG || c->batch > QS_MAX_BATCH) return QS_ERR_UNSUPPORTED;
+  return QS_OK;
+}
+
+int validate_cache(const qs_cache* c) {
+  int rc = validate_shape(c);
+  if (rc != QS_OK) return rc;
+  const void* ptrs[] = {c->k_upper, c->k_lower, c->v_upper, c->v_lower, c->k_scale,
+                        c->k_zero,  c->v_scale, c->v_zero,  c->k_buf,   c->v_buf};
+  for (const void* p : ptrs)
+    if (p == nullptr) return QS_ERR_NULL;
+  if (c->n_quant == nullptr || c->n_buf == nullptr) return QS_ERR_NULL;
+  for (const void* p : ptrs)
+    if (!aligned16(p)) return QS_ERR_ALIGN;
+  for (int b = 0; b < c->batch; ++b) {
+    if (c->n_quant[b] < 0 || c->n_quant[b] > c->q_cap || c->n_quant[b] % kG != 0) return QS_ERR_RANGE;
+    if (c->n_buf[b] < 0 || c->n_buf[b] > c->buf_cap) return QS_ERR_RANGE;
+  }
+  return QS_OK;
+}
+
+// Number of chunks per unit.  The quantized region is cut so that about kWavesPerCU waves per
+// compute unit are resident; the buffer is cut into 64-token chunks.  Depends on shapes and on the
+// given maximum lengths only.
+struct Plan {
+  int n_split_q, n_split_b;
+};
+
+Plan make_plan(const qs_cache* c, int max_quant, int max_buf) {
+  const int units = c->batch * c->n_kv_heads;
+  const int groups = max_quant / kG;
+  const int want = (cu_count() * kWavesPerCU + units - 1) / units;
+  Plan p;
+  p.n_split_q = std::max(1, std::min(want, groups));
+  p.n_split_b = std::max(1, (max_buf + kBufSplitTok - 1) / kBufSplitTok);
+  return p;
+}
+
+int attn_common(const qs_cache* c, const void* q, int32_t nq, void* out, float sm_scale, void* workspace,
+                size_t workspace_bytes, float* lse, void* stream, bool verify) {
+  int rc = validate_cache(c);
+  if (rc != QS_OK) return rc;
+  if (q == nullptr || out == nullptr) return QS_ERR_NULL;
+  if (nq < 1 || nq > QS_MAX_NQ) return QS_ERR_UNSUPPORTED;
+  if (!aligned16(q) || !aligned16(out) || !aligned16(workspace)) return QS_ERR_ALIGN;
+  int max_quant = 0, max_buf = 0;
+  for (int b = 0; b < c->batch; ++b) {
+    if (c->n_buf[b] < nq) return QS_ERR_RANGE;
+    max_quant = std::max(max_quant, c->n_quant[b]);
+    max_buf = std::max(max_buf, c->n_buf[b]);
+  }
+  if (workspace == nullptr || workspace_bytes < qs_workspace_bytes(c, nq)) return QS_ERR_WORKSPACE;
+
+  const Plan p = make_plan(c, max_quant, max_buf);
+  const int n_split = p.n_split_q + p.n_split_b;
+  const int64_t rows_total = (int64_t)c->batch * nq * c->n_q_heads;
+
+  AttnArgs a;
+  a.k_upper = static_cast<const uint32_t*>(c->k_upper);
+  a.k_lower = static_cast<const uint32_t*>(c->k_lower);
+  a.v_upper = static_cast<const uint32_t*>(c->v_upper);
+  a.v_lower = static_cast<const uint32_t*>(c->v_lower);
+  a.k_scale = static_cast<const _Float16*>(c->k_scale);
+  a.k_zero = static_cast<const _Float16*>(c->k_zero);
+  a.v_scale = static_cast<const _Float16*>(c->v_scale);
+  a.v_zero = static_cast<const _Float16*>(c->v_zero);
+  a.k_buf = static_cast<const _Float16*>(c->k_buf);
+  a.v_buf = static_cast<const _Float16*>(c->v_buf);
+  a.q = static_cast<const _Float16*>(q);
+  a.ws_o = static_cast<float*>(workspace);
+  a.ws_ml = a.ws_o + rows_total * n_split * kD;
+  a.n_q_heads = c->n_q_heads;
+  a.n_kv_heads = c->n_kv_heads;
+  a.rep = c->n_q_heads / c->n_kv_heads;
+  a.nq = nq;
+  a.q_cap = c->q_cap;
+  a.buf_cap = c->buf_cap;
+  a.n_split_q = p.n_split_q;
+  a.n_split_b = p.n_split_b;
+  a.n_rows = nq * a.rep;
+  a.c0 = sm_scale * 1.4426950408889634f;
+  for (int b = 0; b < QS_MAX_BATCH; ++b) {
+    a.len.n_quant[b] = b < c->batch ? c->n_quant[b] : 0;
+    a.len.n_buf[b] = b < c->batch ? c->n_buf[b] : 0;
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (launch_attn(a, c->batch, verify, s) != hipSuccess) return QS_ERR_HIP;
+
+  MergeArgs m;
+  m.ws_o = a.ws_o;
+  m.ws_ml = a.ws_ml;
+  m.out = static_cast<_Float16*>(out);
+  m.lse = lse;
+  m.n_split = n_split;
+  if (launch_merge(m, (int)rows_total, s) != hipSuccess) return QS_ERR_HIP;
+  return QS_OK;
+}
+
+int quantize_common(const qs_cache* c, const _Float16* k_src, const _Float16* v_src, int64_t src_stride,
+                    int32_t n_tokens, hipStream_t s) {
+  FlushArgs f;
+  f.k_src = k_src;
+  f.v_src = v_src;
+  f.src_stride = src_stride;
+  f.k_upper = static_cast<uint32_t*>(c->k_upper);
+  f.k_lower = static_cast<uint32_t*>(c->k_lower);
+  f.v_upper = static_cast<uint32_t*>(c->v_upper);
+  f.v_lower = static_cast<uint32_t*>(c->v_lower);
+  f.k_scale = static_cast<_Float16*>(c->k_scale);
+  f.k_zero = static_cast<_Float16*>(c->k_zero);
+  f.v_scale = static_cast<_Float16*>(c->v_scale);
+  f.v_zero = static_cast<_Float16*>(c->v_zero);
+  f.n_kv_heads = c->n_kv_heads;
+  f.q_cap = c->q_cap;
+  f.n_groups = n_tokens / kG;
+  for (int b = 0; b < QS_MAX_BATCH; ++b) f.n_quant[b] = b < c->batch ? c->n_quant[b] : 0;
+  return launch_flush(f, c->batch, s) == hipSuccess ? QS_OK : QS_ERR_HIP;
+}
+
+}  // namespace
+}  // namespace qs
+
+using namespace qs;
+
+extern "C" {
+
+int qs_version(void) { return kVersion; }
+
+const char* qs_strerror(int code) {
+  switch (code) {
+    case QS_OK: return "ok";
+    case QS_ERR_NULL: return "a required pointer is NULL";
+    case QS_ERR_SHAPE: return "inconsistent batch / head counts / capacities";
+    case QS_ERR_UNSUPPORTED: return "unsupported configuration (head_dim and group must be 128, batch <= 64, nq <= 8)";
+    case QS_ERR_ALIGN: return "a device pointer is not 16-byte aligned";
+    case QS_ERR_RANGE: return "a length is out of range for its capacity or not a multiple of the group size";
+    case QS_ERR_WORKSPACE: return "workspace is missing or smaller than qs_workspace_bytes()";
+    case QS_ERR_HIP: return "a HIP runtime call failed";
+    default: return "unknown status code";
+  }
+}
+
+size_t qs_workspace_bytes(const qs_cache* c, int32_t nq) {
+  if (validate_shape(c) != QS_OK || nq < 1 || nq > QS_MAX_NQ) return 0;
+  const Plan p = make_plan(c, c->q_cap, c->buf_cap);
+  const size_t rows_total = (size_t)c->batch * nq * c->n_q_heads;
+  return rows_total * (size_t)(p.n_split_q + p.n_split_b) * (kD + 2) * sizeof(float);
+}
+
+int qs_quantize_flush(const qs_cache* c, int32_t n_tokens, void* stream) {
+  int rc = validate_cache(c);
+  if (rc != QS_OK) return rc;
+  if (n_tokens < 0 || n_tokens % kG != 0) return QS_ERR_RANGE;
+  for (int b = 0; b < c->batch; ++b)
+    if (n_tokens > c->n_buf[b] || c->n_quant[b] + n_tokens > c->q_cap) return QS_ERR_RANGE;
+  if (n_tokens == 0) return QS_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  rc = quantize_common(c, static_cast<const _Float16*>(c->k_buf), static_cast<const _Float16*>(c->v_buf),
+                       c->buf_cap, n_tokens, s);
+  if (rc != QS_OK) return rc;
+  ShiftArgs sh;
+  sh.k_buf = static_cast<_Float16*>(c->k_buf);
+  sh.v_buf = static_cast<_Float16*>(c->v_buf);
+  sh.n_kv_heads = c->n_kv_heads;
+  sh.buf_cap = c->buf_cap;
+  sh.n_tokens = n_tokens;
+  bool any = false;
+  for (int b = 0; b < QS_MAX_BATCH; ++b) {
+    sh.n_buf[b] = b < c->batch ? c->n_buf[b] : 0;
+    any |= b < c->batch && c->n_buf[b] > n_tokens;
+  }
+  if (any && launch_shift(sh, c->batch, s) != hipSuccess) return QS_ERR_HIP;
+  return QS_OK;
+}
+
+int qs_quantize_prefill(const qs_cache* c, const void* k_src, const void* v_src, int64_t src_stride_tokens,
+                        int32_t n_tokens, void* stream) {
+  int rc = validate_cache(c);
+  if (rc != QS_OK) return rc;
+  if (k_src == nullptr || v_src == nullptr) return QS_ERR_NULL;
+  if (!aligned16(k_src) || !aligned16(v_src)) return QS_ERR_ALIGN;
+  if (n_tokens < 0 || n_tokens % kG != 0 || src_stride_tokens < n_tokens) return QS_ERR_RANGE;
+  for (int b = 0; b < c->batch; ++b)
+    if (c->n_quant[b] + n_tokens > c->q_cap) return QS_ERR_RANGE;
+  if (n_tokens == 0) return QS_OK;
+  return quantize_common(c, static_cast<const _Float16*>(k_src), static_cast<const _Float16*>(v_src),
+                         src_stride_tokens, n_tokens, static_cast<hipStream_t>(stream));
+}
+
+int qs_attn_draft(const qs_cache* c, const void* q, void* out, float sm_scale, void* workspace,
+                  size_t workspace_bytes, float* lse, void* stream) {
+  return attn_common(c, q, 1, out, sm_scale, workspace, workspace_bytes, lse, stream, false);
+}
+
+int qs_attn_verify(const qs_cache* c, const void* q, int32_t nq, void* out, float sm_scale, void* workspace,
+                   size_t workspace_bytes, float* lse, void* stream) {
+  return attn_common(c, q, nq, out, sm_scale, workspace, workspace_bytes, lse, stream, true);
+}
+
+int qs_export_codes(const qs_cache* c, int32_t b, int32_t kv_head, int32_t n_tokens, void* k_u, void* k_l,
+                    void* v_u, void* v_l, void* v_s, void* v_z, void* stream) {
+  int rc = validate_cache(c);
+  if (rc != QS_OK) return rc;
+  if (b < 0 || b >= c->batch || kv_head < 0 || kv_head >= c->n_kv_heads) return QS_ERR_RANGE;
+  if (n_tokens < 0 || n_tokens % kVTileTok != 0 || n_tokens > c->q_cap) return QS_ERR_RANGE;
+  const int64_t unit = (int64_t)b * c->n_kv_heads + kv_head;
+  ExportArgs e;
+  e.k_upper = static_cast<const uint32_t*>(c->k_upper) + unit * c->q_cap * kRowDw;
+  e.k_lower = static_cast<const uint32_t*>(c->k_lower) + unit * c->q_cap * kRowDw;
+  e.v_upper = static_cast<const uint32_t*>(c->v_upper) + unit * c->q_cap * kRowDw;
+  e.v_lower = static_cast<const uint32_t*>(c->v_lower) + unit * c->q_cap * kRowDw;
+  e.v_scale = static_cast<const _Float16*>(c->v_scale) + unit * c->q_cap;
+  e.v_zero = static_cast<const _Float16*>(c->v_zero) + unit * c->q_cap;
+  e.k_u = static_cast<uint8_t*>(k_u);
+  e.k_l = static_cast<int8_t*>(k_l);
+  e.v_u = static_cast<uint8_t*>(v_u);
+  e.v_l = static_cast<int8_t*>(v_l);
+  e.v_s = static_cast<_Float16*>(v_s);
+  e.v_z = static_cast<_Float16*>(v_z);
+  e.n_tokens = n_tokens;
+  return launch_export(e, static_cast<hipStream_t>(stream)) == hipSuccess ? QS_OK : QS_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,479 @@
+// Split-K decode attention over the hierarchical 4-bit KV cache (gfx950, wave64, MFMA).
+//
+// Draft pass (paper Section 4.2 / Algorithm 1 DRAFT): keys and values are decoded from the upper
+// plane only, x = C_U*S + Z.  Verify pass (TARGET): both planes, x = (16*C_U + C_L)*(S/16) + Z.
+// Both also attend the full-precision buffer (Section 4.3.2), which is one more chunk of the
+// split-K scheme (Appendix E), and every chunk's (max, sum, output) partial is merged afterwards.
+//
+// Design
+//  * One wave (a 64-thread workgroup) owns one chunk of one (sequence, kv-head) unit and all query
+//    rows that share that kv-head (grouped-query heads x query tokens), so the planes are read once.
+//  * The contraction runs on the matrix cores (v_mfma_f32_16x16x32_f16): codes are the A operand,
+//    queries / probabilities the B operand.  Scales never touch individual codes:
+//        q . K_hat[t] = sum_d (q_d S_d) c[t,d] + q . Z          (per 128-token group)
+//        o            = sum_t (p_t S_t) c[t,:] + sum_t p_t Z_t  (per token)
+//  * A 4-bit code masked in place inside its 32-bit word is already an fp16 subnormal
+//    (c * 2^-24 for bits 0-3 of a half, c * 2^-20 for bits 4-7); the matrix cores take subnormal
+//    inputs exactly, so "dequantization" is one AND per two codes and the powers of two are folded
+//    into the other operand and the final scale.
+//  * q_d S_d is split exactly into an fp16 high part and an fp16 remainder that occupy two columns
+//    of the same 16-column MFMA tile (8 query rows + 8 remainders), so key metadata costs no accuracy.
+//  * The MFMA output layout of Q K^T (lane = query column, 4 consecutive tokens) is, after packing to
+//    fp16, directly the B operand layout of P V; the value planes are stored by the flush kernel in
+//    exactly the token order this produces, so probabilities never cross lanes.
+#include "qs_internal.h"
+
+namespace qs {
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kNegBig = -1.0e30f;
+
+__device__ __forceinline__ half8 as_half8(u32x4 v) { return __builtin_bit_cast(half8, v); }
+__device__ __forceinline__ u32x4 as_u32x4(half8 v) { return __builtin_bit_cast(u32x4, v); }
+__device__ __forceinline__ half2v as_half2(uint32_t v) { return __builtin_bit_cast(half2v, v); }
+__device__ __forceinline__ uint32_t as_u32(half2v v) { return __builtin_bit_cast(uint32_t, v); }
+
+__device__ __forceinline__ u32x4 ldg128(const void* p) { return *reinterpret_cast<const u32x4*>(p); }
+
+// Eight 4-bit codes of one word -> eight fp16 subnormals.  Operand element j comes from nibble
+// (j&1)*4 + (j>>1); elements 2,3,6,7 carry an extra factor 16 (bits 4-7 of their half).
+__device__ __forceinline__ half8 unpack4(uint32_t x) {
+  const uint32_t y = x >> 8;
+  u32x4 r;
+  r[0] = x & 0x000F000Fu;
+  r[1] = x & 0x00F000F0u;
+  r[2] = y & 0x000F000Fu;
+  r[3] = y & 0x00F000F0u;
+  return as_half8(r);
+}
+
+// Upper and lower nibbles -> eight 8-bit codes 16*C_U + (C_L + 8) as fp16 subnormals (x 2^-24),
+// same element order as unpack4.
+__device__ __forceinline__ half8 unpack8(uint32_t u, uint32_t l) {
+  const uint32_t even = ((u << 4) & 0xF0F0F0F0u) | (l & 0x0F0F0F0Fu);   // nibbles 0,2,4,6 -> bytes 0..3
+  const uint32_t odd = (u & 0xF0F0F0F0u) | ((l >> 4) & 0x0F0F0F0Fu);    // nibbles 1,3,5,7 -> bytes 0..3
+  u32x4 r;
+  r[0] = even & 0x00FF00FFu;                                  // nibbles 0, 4
+  r[1] = odd & 0x00FF00FFu;                                   // nibbles 1, 5
+  r[2] = __builtin_amdgcn_perm(0u, even, 0x0c030c01u);        // nibbles 2, 6
+  r[3] = __builtin_amdgcn_perm(0u, odd, 0x0c030c01u);         // nibbles 3, 7
+  return as_half8(r);
+}
+
+// Reorder eight consecutive channels so that element j holds channel (j&1)*4 + (j>>1), i.e. the
+// channel whose code unpack4/unpack8 deliver at element j.
+__device__ __forceinline__ half8 to_operand_order(half8 c) {
+  half8 r;
+  r[0] = c[0]; r[1] = c[4]; r[2] = c[1]; r[3] = c[5];
+  r[4] = c[2]; r[5] = c[6]; r[6] = c[3]; r[7] = c[7];
+  return r;
+}
+
+__device__ __forceinline__ float xor8_in_row(float x) {   // value of lane (l ^ 8); stays inside a 16-lane row
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x128, 0xF, 0xF, false));
+}
+
+__device__ __forceinline__ float group_max(float x) {     // over the four 16-lane groups of the wave
+  x = fmaxf(x, __shfl_xor(x, 16));
+  return fmaxf(x, __shfl_xor(x, 32));
+}
+__device__ __forceinline__ float group_sum(float x) {
+  x += __shfl_xor(x, 16);
+  return x + __shfl_xor(x, 32);
+}
+
+template <int NRT>
+struct RowState {
+  float m[NRT];        // running max of the scaled scores (log2 units)
+  float l[NRT];        // running sum of p over this lane's tokens
+  float z[NRT];        // running sum of p * zero-point over this lane's tokens
+  float4v o[NRT][8];   // O^T accumulators: tile n, element jj -> channel 8*(4*g + jj) + n
+};
+
+// Online-softmax update for one 32-token block.  raw[rt][j] are this lane's eight scores (query
+// column rho, tokens tile_token(g, j)) before scaling; returns the probabilities in p.
+template <int NRT>
+__device__ __forceinline__ void softmax_block(RowState<NRT>& st, float (&raw)[NRT][8], float mul) {
+  bool changed = false;
+  float alpha[NRT];
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    float mx = raw[rt][0];
+#pragma unroll
+    for (int j = 1; j < 8; ++j) mx = fmaxf(mx, raw[rt][j]);
+    mx = group_max(mx) * mul;                       // mul > 0
+    const float m_new = fmaxf(st.m[rt], mx);
+    alpha[rt] = __builtin_amdgcn_exp2f(st.m[rt] - m_new);
+    changed |= (m_new != st.m[rt]);
+    st.m[rt] = m_new;
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      raw[rt][j] = __builtin_amdgcn_exp2f(__builtin_fmaf(raw[rt][j], mul, -m_new));
+      sum += raw[rt][j];
+    }
+    st.l[rt] = __builtin_fmaf(st.l[rt], alpha[rt], sum);
+  }
+  if (__any(changed)) {
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      st.z[rt] *= alpha[rt];
+#pragma unroll
+      for (int n = 0; n < 8; ++n) st.o[rt][n] *= alpha[rt];
+    }
+  }
+}
+
+template <int NRT>
+__device__ __forceinline__ void write_partial(const AttnArgs& a, RowState<NRT>& st, int b, int kvh, int row0,
+                                              int split, float o_scale) {
+  const int lane = threadIdx.x, rho = lane & 15, g = lane >> 4;
+  const int n_split = a.n_split_q + a.n_split_b;
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    const float l = group_sum(st.l[rt]);
+    const float z = group_sum(st.z[rt]);
+    const int row = row0 + rt * 8 + (rho & 7);
+    if (rho < 8 && row < a.n_rows) {
+      const int qi = row / a.rep, head = kvh * a.rep + row % a.rep;
+      const int64_t r = (((int64_t)b * a.nq + qi) * a.n_q_heads + head) * n_split + split;
+      float* po = a.ws_o + r * kD;
+#pragma unroll
+      for (int n = 0; n < 8; ++n)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) po[8 * (4 * g + jj) + n] = __builtin_fmaf(st.o[rt][n][jj], o_scale, z);
+      if (g == 0) {
+        a.ws_ml[2 * r] = st.m[rt];
+        a.ws_ml[2 * r + 1] = l;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// A chunk of the quantized region: token groups [grp0, grp1) of one unit.
+// ------------------------------------------------------------------------------------------------
+template <int NRT, bool VERIFY>
+__device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, int kvh, int row0, int split) {
+  const int lane = threadIdx.x, rho = lane & 15, g = lane >> 4;
+  const bool lo_part = rho >= 8;
+  const int n_groups = a.len.n_quant[b] / kG;
+  const int grp0 = (int)((int64_t)split * n_groups / a.n_split_q);
+  const int grp1 = (int)((int64_t)(split + 1) * n_groups / a.n_split_q);
+
+  // Powers of two folded out of the operands (see file header).
+  //   draft : code operand carries 2^-24 (elements 0,1,4,5) or 2^-20 (elements 2,3,6,7)
+  //   verify: code operand carries 2^-24 and the codes are 16*C_U + C_L + 8 in units of S/16
+  constexpr float kKeyPos = VERIFY ? 1.0f : 0.0625f;         // factor on q at elements 2,3,6,7
+  constexpr float kKeyRaw = VERIFY ? 1048576.0f : 16777216.0f;   // score = raw * kKeyRaw * c0
+  constexpr float kPA = 4.0f;                                // factor on p*S at elements 0,1,4,5
+  constexpr float kPB = VERIFY ? 4.0f : 0.25f;               // factor on p*S at elements 2,3,6,7
+  constexpr float kOutRaw = VERIFY ? 262144.0f : 4194304.0f; // out = rawO * kOutRaw + sum p*Zeff
+
+  // Queries of this lane's column: channels 32*g + 8*s + operand order, pre-scaled per position.
+  half2v qv[NRT][16];
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    const int row = row0 + rt * 8 + (rho & 7);
+    const bool valid = row < a.n_rows;
+    const int rowc = valid ? row : 0;
+    const int qi = rowc / a.rep, head = kvh * a.rep + rowc % a.rep;
+    const _Float16* qp = a.q + (((int64_t)b * a.nq + qi) * a.n_q_heads + head) * kD + 32 * g;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      u32x4 w = as_u32x4(to_operand_order(as_half8(ldg128(qp + 8 * s))));
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        half2v h = as_half2(valid ? w[r] : 0u);
+        if (r & 1) h = h * (_Float16)kKeyPos;
+        qv[rt][4 * s + r] = h;
+      }
+    }
+  }
+
+  RowState<NRT> st;
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    st.m[rt] = kNegBig; st.l[rt] = 0.f; st.z[rt] = 0.f;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) st.o[rt][n] = (float4v){0.f, 0.f, 0.f, 0.f};
+  }
+  const float mul = a.c0 * kKeyRaw;
+
+  const uint32_t* ku = a.k_upper + ((int64_t)unit * a.q_cap + rho) * kRowDw + 4 * g;
+  const uint32_t* kl = a.k_lower + ((int64_t)unit * a.q_cap + rho) * kRowDw + 4 * g;
+  const uint32_t* vu = a.v_upper + (int64_t)unit * (a.q_cap / kVTileTok) * kVTileDw + 4 * lane;
+  const uint32_t* vl = a.v_lower + (int64_t)unit * (a.q_cap / kVTileTok) * kVTileDw + 4 * lane;
+  const _Float16* vs = a.v_scale + (int64_t)unit * a.q_cap + 8 * g;
+  const _Float16* vz = a.v_zero + (int64_t)unit * a.q_cap + 8 * g;
+  const _Float16* ksc = a.k_scale + (int64_t)unit * (a.q_cap / kG) * kD + 32 * g;
+  const _Float16* kzr = a.k_zero + (int64_t)unit * (a.q_cap / kG) * kD + 32 * g;
+
+  for (int grp = grp0; grp < grp1; ++grp) {
+    // ---- per-group query operand: columns 0-7 hold fp16(q*S), columns 8-15 the exact remainder ----
+    half8 qb[NRT][4];
+    float cin[NRT];
+    {
+      half8 sg[4], zg[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        sg[s] = to_operand_order(as_half8(ldg128(ksc + (int64_t)grp * kD + 8 * s)));
+        zg[s] = to_operand_order(as_half8(ldg128(kzr + (int64_t)grp * kD + 8 * s)));
+      }
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) {
+        float ba = 0.f, bb = 0.f, sa = 0.f, sb = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          u32x4 sw = as_u32x4(sg[s]), zw = as_u32x4(zg[s]), out;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const half2v qh = qv[rt][4 * s + r], sh = as_half2(sw[r]), zh = as_half2(zw[r]);
+            const half2v hi = qh * sh;
+            const half2v lo = __builtin_elementwise_fma(qh, sh, -hi);
+            out[r] = lo_part ? as_u32(lo) : as_u32(hi);
+            if (r & 1) {
+              bb = __builtin_amdgcn_fdot2(qh, zh, bb, false);
+              if (VERIFY) sb = __builtin_amdgcn_fdot2(qh, sh, sb, false);
+            } else {
+              ba = __builtin_amdgcn_fdot2(qh, zh, ba, false);
+              if (VERIFY) sa = __builtin_amdgcn_fdot2(qh, sh, sa, false);
+            }
+          }
+          qb[rt][s] = as_half8(out);
+        }
+        // sum_d q_d * Zeff_d with Zeff = Z (draft) or Z - S/2 (verify: codes are offset by +8 lower steps)
+        float bias = __builtin_fmaf(bb, 1.0f / kKeyPos, ba);
+        if (VERIFY) bias -= 0.5f * __builtin_fmaf(sb, 1.0f / kKeyPos, sa);
+        bias = group_sum(bias);
+        cin[rt] = lo_part ? 0.f : bias * (1.0f / kKeyRaw);
+      }
+    }
+
+    for (int blk = 0; blk < 4; ++blk) {
+      const int64_t t0 = (int64_t)grp * kG + blk * 32;
+      // ---- loads: two 16-token key tiles, one 32-token value tile, value metadata ----
+      u32x4 kU[2], kL[2], vU[2], vL[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        kU[t] = ldg128(ku + (t0 + 16 * t) * kRowDw);
+        if (VERIFY) kL[t] = ldg128(kl + (t0 + 16 * t) * kRowDw);
+        vU[t] = ldg128(vu + (t0 / kVTileTok) * kVTileDw + 256 * t);
+        if (VERIFY) vL[t] = ldg128(vl + (t0 / kVTileTok) * kVTileDw + 256 * t);
+      }
+      const half8 vS = as_half8(ldg128(vs + t0));
+      const half8 vZ = as_half8(ldg128(vz + t0));
+
+      // ---- scores: S^T[token, column] = codes x q ----
+      float raw[NRT][8];
+      {
+        half8 ka[2][4];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int s = 0; s < 4; ++s) ka[t][s] = VERIFY ? unpack8(kU[t][s], kL[t][s]) : unpack4(kU[t][s]);
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            float4v acc = {cin[rt], cin[rt], cin[rt], cin[rt]};
+#pragma unroll
+            for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qb[rt][s], acc, 0, 0, 0);
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) raw[rt][4 * t + jj] = acc[jj] + xor8_in_row(acc[jj]);
+          }
+      }
+      softmax_block<NRT>(st, raw, mul);
+
+      // ---- probabilities x value scale -> B operand; zero-point term ----
+      half8 pb[NRT];
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) {
+        float zs = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const float s = (float)vS[j];
+          const float zeff = VERIFY ? __builtin_fmaf(-0.5f, s, (float)vZ[j]) : (float)vZ[j];
+          zs = __builtin_fmaf(raw[rt][j], zeff, zs);
+          pb[rt][j] = (_Float16)(raw[rt][j] * s * (((j >> 1) & 1) ? kPB : kPA));
+        }
+        st.z[rt] += zs;
+      }
+
+      // ---- O^T[channel, column] += codes^T x p ----
+#pragma unroll
+      for (int n = 0; n < 8; ++n) {
+        const half8 va = VERIFY ? unpack8(vU[n >> 2][n & 3], vL[n >> 2][n & 3]) : unpack4(vU[n >> 2][n & 3]);
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt)
+          st.o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pb[rt], st.o[rt][n], 0, 0, 0);
+      }
+    }
+  }
+  write_partial<NRT>(a, st, b, kvh, row0, split, kOutRaw);
+}
+
+// ------------------------------------------------------------------------------------------------
+// A chunk of the full-precision buffer: up to 64 tokens.  Keys are read straight into the A
+// operand; the value tile is transposed through LDS because the matrix cores need eight tokens of
+// one channel per lane while the buffer is stored token-major.
+// ------------------------------------------------------------------------------------------------
+constexpr int kVtStride = 40;   // halfs per LDS row: 32 tokens + padding, keeps 8-byte reads aligned
+constexpr float kBufP = 16384.0f;
+
+template <int NRT>
+__device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b, int kvh, int row0, int split,
+                                             _Float16 (*vt)[kVtStride]) {
+  const int lane = threadIdx.x, rho = lane & 15, g = lane >> 4;
+  const bool lo_part = rho >= 8;
+  const int nb = a.len.n_buf[b];
+  const int tb0 = (split - a.n_split_q) * kBufSplitTok;
+
+  half8 qb[NRT][4];
+  int vis[NRT];   // buffer tokens [0, vis) are visible to this lane's query (causal among the nq queries)
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    const int row = row0 + rt * 8 + (rho & 7);
+    const bool valid = row < a.n_rows;
+    const int rowc = valid ? row : 0;
+    const int qi = rowc / a.rep, head = kvh * a.rep + rowc % a.rep;
+    const _Float16* qp = a.q + (((int64_t)b * a.nq + qi) * a.n_q_heads + head) * kD + 8 * g;
+    vis[rt] = valid ? nb - a.nq + qi + 1 : 0;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      u32x4 w = ldg128(qp + 32 * s);
+      if (!valid || lo_part) w = (u32x4){0u, 0u, 0u, 0u};
+      qb[rt][s] = as_half8(w);
+    }
+  }
+  RowState<NRT> st;
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    st.m[rt] = kNegBig; st.l[rt] = 0.f; st.z[rt] = 0.f;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) st.o[rt][n] = (float4v){0.f, 0.f, 0.f, 0.f};
+  }
+  const _Float16* kb = a.k_buf + (int64_t)unit * a.buf_cap * kD;
+  const _Float16* vb = a.v_buf + (int64_t)unit * a.buf_cap * kD;
+
+  for (int blk = 0; blk < kBufSplitTok / 32; ++blk) {
+    const int t0 = tb0 + 32 * blk;
+    if (t0 >= nb) break;
+    float raw[NRT][8];
+    {
+      half8 ka[2][4];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int tok = min(t0 + 16 * t + rho, nb - 1);   // rows past the end are masked below
+#pragma unroll
+        for (int s = 0; s < 4; ++s) ka[t][s] = as_half8(ldg128(kb + (int64_t)tok * kD + 32 * s + 8 * g));
+      }
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qb[rt][s], acc, 0, 0, 0);
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) {
+            const int tok = t0 + 16 * t + 4 * g + jj;
+            const float sc = acc[jj] + xor8_in_row(acc[jj]);
+            raw[rt][4 * t + jj] = tok < vis[rt] ? sc : -__builtin_inff();
+          }
+        }
+    }
+    softmax_block<NRT>(st, raw, a.c0);
+
+    __syncthreads();   // the previous block's LDS reads are done
+    {
+      const int tau = lane & 31, cc = lane >> 5;
+      const int tok = min(t0 + tau, nb - 1);
+#pragma unroll
+      for (int it = 0; it < 8; ++it) {
+        const int ch = 8 * (2 * it + cc);
+        const half8 v = as_half8(ldg128(vb + (int64_t)tok * kD + ch));
+#pragma unroll
+        for (int i = 0; i < 8; ++i) vt[ch + i][tau] = v[i];
+      }
+    }
+    __syncthreads();
+    half8 pb[NRT];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) pb[rt][j] = (_Float16)(raw[rt][j] * kBufP);
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      const _Float16* rowp = &vt[8 * rho + n][0];
+      const uint2 lo = *reinterpret_cast<const uint2*>(rowp + 4 * g);
+      const uint2 hi = *reinterpret_cast<const uint2*>(rowp + 16 + 4 * g);
+      const half8 va = as_half8((u32x4){lo.x, lo.y, hi.x, hi.y});
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt)
+        st.o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pb[rt], st.o[rt][n], 0, 0, 0);
+    }
+  }
+  write_partial<NRT>(a, st, b, kvh, row0, split, 1.0f / kBufP);
+}
+
+template <int NRT, bool VERIFY>
+__global__ __launch_bounds__(64) void attn_kernel(AttnArgs a) {
+  __shared__ _Float16 vt[kD][kVtStride];
+  const int split = blockIdx.x, unit = blockIdx.y, row0 = blockIdx.z * 8 * NRT;
+  const int b = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
+  if (split < a.n_split_q)
+    quant_chunk<NRT, VERIFY>(a, unit, b, kvh, row0, split);
+  else
+    buffer_chunk<NRT>(a, unit, b, kvh, row0, split, vt);
+}
+
+// Merge of the per-chunk partials (Appendix E): M = max m_i, L = sum l_i 2^(m_i - M),
+// out = sum o_i 2^(m_i - M) / L.  One workgroup per query row, one thread per channel.
+__global__ __launch_bounds__(128) void merge_kernel(MergeArgs a) {
+  const int64_t row = blockIdx.x;
+  const int d = threadIdx.x;
+  const float* ml = a.ws_ml + row * a.n_split * 2;
+  const float* po = a.ws_o + row * a.n_split * kD + d;
+  float m = kNegBig;
+  for (int s = 0; s < a.n_split; ++s) m = fmaxf(m, ml[2 * s]);
+  float l = 0.f, o = 0.f;
+  for (int s = 0; s < a.n_split; ++s) {
+    const float w = __builtin_amdgcn_exp2f(ml[2 * s] - m);
+    l = __builtin_fmaf(w, ml[2 * s + 1], l);
+    o = __builtin_fmaf(w, po[(int64_t)s * kD], o);
+  }
+  a.out[row * kD + d] = (_Float16)(o / l);
+  if (a.lse != nullptr && d == 0) a.lse[row] = (m + __builtin_log2f(l)) * 0.6931471805599453f;
+}
+
+template <int NRT>
+hipError_t launch_attn_nrt(const AttnArgs& a, int batch, bool verify, hipStream_t s) {
+  dim3 grid(a.n_split_q + a.n_split_b, batch * a.n_kv_heads, (a.n_rows + 8 * NRT - 1) / (8 * NRT));
+  if (verify)
+    hipLaunchKernelGGL((attn_kernel<NRT, true>), grid, dim3(64), 0, s, a);
+  else
+    hipLaunchKernelGGL((attn_kernel<NRT, false>), grid, dim3(64), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_attn(const AttnArgs& a, int batch, bool verify, hipStream_t s) {
+  const int tiles = (a.n_rows + 7) / 8;
+  if (tiles <= 1) return launch_attn_nrt<1>(a, batch, verify, s);
+  if (tiles == 2 || tiles == 4) return launch_attn_nrt<2>(a, batch, verify, s);
+  return launch_attn_nrt<3>(a, batch, verify, s);
+}
+
+hipError_t launch_merge(const MergeArgs& a, int rows_total, hipStream_t s) {
+  hipLaunchKernelGGL(merge_kernel, dim3(rows_total), dim3(128), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace qs

@@ -1,0 +1,74 @@
+// Internal declarations shared by the translation units of libquantspec (host side only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "quantspec.h"
+
+namespace qs {
+
+constexpr int kD = 128;            // head_dim
+constexpr int kG = 128;            // quantization group size
+constexpr int kRowDw = 16;         // 32-bit words per token row of a key plane (128 nibbles)
+constexpr int kVTileTok = 32;      // tokens per value-plane tile
+constexpr int kVTileDw = 512;      // 32-bit words per value-plane tile (32 tokens x 128 nibbles)
+constexpr int kBufSplitTok = 64;   // buffer tokens handled by one wave of the attention kernel
+
+// Per-sequence lengths travel inside the kernel arguments.
+struct SeqLens {
+  int32_t n_quant[QS_MAX_BATCH];
+  int32_t n_buf[QS_MAX_BATCH];
+};
+
+struct FlushArgs {
+  const _Float16* k_src;   // [B][Hkv][src_stride][128]
+  const _Float16* v_src;
+  int64_t src_stride;      // tokens between consecutive units of the source
+  uint32_t *k_upper, *k_lower, *v_upper, *v_lower;
+  _Float16 *k_scale, *k_zero, *v_scale, *v_zero;
+  int32_t n_kv_heads, q_cap, n_groups;   // n_groups = n_tokens / 128
+  int32_t n_quant[QS_MAX_BATCH];
+};
+
+struct ShiftArgs {
+  _Float16 *k_buf, *v_buf;
+  int32_t n_kv_heads, buf_cap, n_tokens;
+  int32_t n_buf[QS_MAX_BATCH];
+};
+
+struct ExportArgs {
+  const uint32_t *k_upper, *k_lower, *v_upper, *v_lower;
+  const _Float16 *v_scale, *v_zero;
+  uint8_t *k_u, *v_u;
+  int8_t *k_l, *v_l;
+  _Float16 *v_s, *v_z;
+  int32_t n_tokens;
+};
+
+struct AttnArgs {
+  const uint32_t *k_upper, *k_lower, *v_upper, *v_lower;
+  const _Float16 *k_scale, *k_zero, *v_scale, *v_zero;
+  const _Float16 *k_buf, *v_buf;
+  const _Float16* q;       // [B][nq][Hq][128]
+  float* ws_o;             // [rows_total][n_split][128] unnormalised partial outputs
+  float* ws_ml;            // [rows_total][n_split][2]   (running max in log2 units, sum)
+  int32_t n_q_heads, n_kv_heads, rep, nq, q_cap, buf_cap;
+  int32_t n_split_q, n_split_b, n_rows;   // n_rows = nq * rep query rows per unit
+  float c0;                // sm_scale * log2(e)
+  SeqLens len;
+};
+
+struct MergeArgs {
+  const float *ws_o, *ws_ml;
+  _Float16* out;           // [rows_total][128]
+  float* lse;              // [rows_total] or null
+  int32_t n_split;
+};
+
+hipError_t launch_flush(const FlushArgs& a, int batch, hipStream_t s);
+hipError_t launch_shift(const ShiftArgs& a, int batch, hipStream_t s);
+hipError_t launch_export(const ExportArgs& a, hipStream_t s);
+hipError_t launch_attn(const AttnArgs& a, int batch, bool verify, hipStream_t s);
+hipError_t launch_merge(const MergeArgs& a, int rows_total, hipStream_t s);
+
+}  // namespace qs

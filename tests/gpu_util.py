@@ -1,0 +1,81 @@
+"""Helpers shared by the GPU parity tests: move seeded host tensors into a device cache through the
+library's own entry points, and pull results back for comparison with the oracle."""
+import numpy as np
+import torch
+
+from oracle import quantspec_oracle as O
+from paper_2502_10424_amd import binding as B
+
+
+def make_device_cache(k, v, n_q_heads, n_buf, q_cap=None, buf_cap=None):
+    """k, v: host fp16 [B, Hkv, T, 128]; the last n_buf[b] tokens go to the buffer, the rest is quantized
+    on the device with qs_quantize_prefill.  n_buf: int or per-sequence list (T - n_buf[b] multiple of 128)."""
+    bsz, hkv, t, d = k.shape
+    nb = [n_buf] * bsz if np.isscalar(n_buf) else list(n_buf)
+    tq = [t - x for x in nb]
+    q_cap = max(tq) if q_cap is None else q_cap
+    buf_cap = max(max(nb), 1) if buf_cap is None else buf_cap
+    cache = B.KVCache(bsz, n_q_heads, hkv, q_cap, buf_cap)
+    kd = torch.from_numpy(k).cuda()
+    vd = torch.from_numpy(v).cuda()
+    if len(set(tq)) == 1:
+        if tq[0]:
+            B.qs_quantize_prefill(cache, kd, vd, tq[0])
+        cache.n_quant[:] = tq[0]
+    else:  # ragged: quantize sequence by sequence through single-sequence views of the same storage
+        for b in range(bsz):
+            if tq[b]:
+                sub = _seq_view(cache, b)
+                B.qs_quantize_prefill(sub, kd[b:b + 1].contiguous(), vd[b:b + 1].contiguous(), tq[b])
+            cache.n_quant[b] = tq[b]
+    for b in range(bsz):
+        if nb[b]:
+            cache.k_buf[b, :, :nb[b]] = kd[b, :, tq[b]:]
+            cache.v_buf[b, :, :nb[b]] = vd[b, :, tq[b]:]
+        cache.n_buf[b] = nb[b]
+    torch.cuda.synchronize()
+    return cache
+
+
+def _seq_view(cache, b):
+    sub = B.KVCache.__new__(B.KVCache)
+    sub.batch, sub.n_q_heads, sub.n_kv_heads = 1, cache.n_q_heads, cache.n_kv_heads
+    sub.head_dim, sub.group, sub.q_cap, sub.buf_cap = cache.head_dim, cache.group, cache.q_cap, cache.buf_cap
+    for name in ("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "k_zero", "v_scale", "v_zero", "k_buf", "v_buf"):
+        setattr(sub, name, getattr(cache, name)[b:b + 1])
+    sub.n_quant = np.zeros(1, np.int32)
+    sub.n_buf = np.zeros(1, np.int32)
+    return sub
+
+
+def export_unit(cache, b, h, n_tokens):
+    """Plain-order numpy view of one unit's planes and metadata."""
+    k_u, k_l, v_u, v_l, v_s, v_z = B.qs_export_codes(cache, b, h, n_tokens)
+    torch.cuda.synchronize()
+    g = n_tokens // 128
+    return dict(ku=k_u.cpu().numpy(), kl=k_l.cpu().numpy(), vu=v_u.cpu().numpy(), vl=v_l.cpu().numpy(),
+                vs=v_s.cpu().numpy(), vz=v_z.cpu().numpy(),
+                ks=cache.k_scale[b, h, :g].cpu().numpy(), kz=cache.k_zero[b, h, :g].cpu().numpy())
+
+
+def assert_unit_equals_oracle(cache, oc: O.CacheOracle, b, h):
+    """Bit-exact comparison of codes, scales and zeros of one unit, plus the buffer contents."""
+    tq = oc.n_quant(b)
+    assert cache.n_quant[b] == tq and cache.n_buf[b] == oc.n_buf(b)
+    if tq:
+        e = export_unit(cache, b, h, tq)
+        for name, ref in (("ku", oc.ku[b][h]), ("kl", oc.kl[b][h]), ("vu", oc.vu[b][h]), ("vl", oc.vl[b][h])):
+            assert np.array_equal(e[name], ref), f"{name} differs for unit ({b},{h})"
+        for name, ref in (("ks", oc.ks[b][h]), ("kz", oc.kz[b][h]), ("vs", oc.vs[b][h][:, 0]), ("vz", oc.vz[b][h][:, 0])):
+            assert np.array_equal(e[name].view(np.uint16), ref.view(np.uint16)), f"{name} differs for unit ({b},{h})"
+    nb = oc.n_buf(b)
+    assert np.array_equal(cache.k_buf[b, h, :nb].cpu().numpy().view(np.uint16), oc.kbuf[b][h].view(np.uint16))
+    assert np.array_equal(cache.v_buf[b, h, :nb].cpu().numpy().view(np.uint16), oc.vbuf[b][h].view(np.uint16))
+
+
+def rel_err(out_gpu, out_ref):
+    """Per output vector: max_d |gpu - ref| / max_d |ref|; returns the maximum over vectors."""
+    g = out_gpu.astype(np.float64)
+    num = np.abs(g - out_ref).max(axis=-1)
+    den = np.abs(out_ref).max(axis=-1)
+    return float((num / den).max())

@@ -1,0 +1,113 @@
+"""The C-ABI library loads, exports every symbol include/quantspec.h declares, and rejects bad
+arguments before touching the GPU (so these checks run on a host without one)."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2502_10424_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return binding
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "quantspec.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qs_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported(B):
+    lib = B.lib()
+    declared = _declared_symbols()
+    assert set(declared) == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert B.qs_version() >= 100
+    assert B.qs_strerror(0) == "ok" and "NULL" in B.qs_strerror(B.QS_ERR_NULL)
+    assert "unknown" in B.qs_strerror(-99)
+
+
+def _fake_cache(B, **over):
+    """A descriptor with plausible, never-dereferenced device addresses (validation only)."""
+    c = B.qs_cache()
+    c.batch, c.n_q_heads, c.n_kv_heads, c.head_dim, c.group, c.q_cap, c.buf_cap = 2, 8, 2, 128, 128, 1024, 264
+    for i, name in enumerate(("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "k_zero", "v_scale", "v_zero",
+                              "k_buf", "v_buf")):
+        setattr(c, name, 0x10000 * (i + 1))
+    nq = np.array([512, 1024], np.int32)
+    nb = np.array([256, 130], np.int32)
+    c.n_quant = nq.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    c.n_buf = nb.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    c._keep = (nq, nb)
+    for k, v in over.items():
+        setattr(c, k, v)
+    return c
+
+
+def test_workspace_bytes(B):
+    c = _fake_cache(B)
+    w1, w5 = B.qs_workspace_bytes(c, 1), B.qs_workspace_bytes(c, 5)
+    assert w1 > 0 and w5 == 5 * w1 and w1 % (130 * 4) == 0
+    assert B.qs_workspace_bytes(_fake_cache(B, head_dim=64), 1) == 0
+    assert B.qs_workspace_bytes(c, 0) == 0 and B.qs_workspace_bytes(c, 9) == 0
+
+
+def test_validation_errors_without_gpu(B):
+    lib = B.lib()
+    ws = 1 << 30
+
+    def draft(c, q=0x200000, out=0x300000, wsp=0x400000, wsb=ws):
+        return lib.qs_attn_draft(ctypes.byref(c), q, out, 0.1, wsp, wsb, None, None)
+
+    def verify(c, nq):
+        return lib.qs_attn_verify(ctypes.byref(c), 0x200000, nq, 0x300000, 0.1, 0x400000, ws, None, None)
+
+    assert lib.qs_attn_draft(None, 0x200000, 0x300000, 0.1, 0x400000, ws, None, None) == B.QS_ERR_NULL
+    assert draft(_fake_cache(B, k_upper=None)) == B.QS_ERR_NULL
+    assert draft(_fake_cache(B), q=None) == B.QS_ERR_NULL
+    assert draft(_fake_cache(B, n_q_heads=7)) == B.QS_ERR_SHAPE
+    assert draft(_fake_cache(B, q_cap=1000)) == B.QS_ERR_SHAPE
+    assert draft(_fake_cache(B, head_dim=64)) == B.QS_ERR_UNSUPPORTED
+    assert draft(_fake_cache(B, group=64)) == B.QS_ERR_UNSUPPORTED
+    assert draft(_fake_cache(B, batch=65)) == B.QS_ERR_UNSUPPORTED
+    assert draft(_fake_cache(B, v_lower=0x10008)) == B.QS_ERR_ALIGN
+    assert draft(_fake_cache(B), q=0x200004) == B.QS_ERR_ALIGN
+    assert draft(_fake_cache(B), wsp=None) == B.QS_ERR_WORKSPACE
+    assert draft(_fake_cache(B), wsb=16) == B.QS_ERR_WORKSPACE
+    assert verify(_fake_cache(B), 0) == B.QS_ERR_UNSUPPORTED
+    assert verify(_fake_cache(B), 9) == B.QS_ERR_UNSUPPORTED
+    c = _fake_cache(B); c._keep[0][0] = 100            # n_quant not a multiple of 128
+    assert draft(c) == B.QS_ERR_RANGE
+    c = _fake_cache(B); c._keep[0][1] = 2048           # n_quant > q_cap
+    assert draft(c) == B.QS_ERR_RANGE
+    c = _fake_cache(B); c._keep[1][0] = 300            # n_buf > buf_cap
+    assert draft(c) == B.QS_ERR_RANGE
+    c = _fake_cache(B); c._keep[1][1] = 3              # fewer buffer tokens than queries
+    assert verify(c, 5) == B.QS_ERR_RANGE
+    # flush: multiple of 128, within the buffer, within capacity
+    fl = lambda c, n: lib.qs_quantize_flush(ctypes.byref(c), n, None)
+    assert fl(_fake_cache(B), 100) == B.QS_ERR_RANGE
+    assert fl(_fake_cache(B), 256) == B.QS_ERR_RANGE       # sequence 1 has only 130 buffered tokens
+    c = _fake_cache(B); c._keep[1][1] = 256
+    assert fl(c, 128) == B.QS_ERR_RANGE                    # sequence 1 is already at q_cap
+    assert fl(_fake_cache(B), 0) == B.QS_OK
+    pf = lambda c, n, stride: lib.qs_quantize_prefill(ctypes.byref(c), 0x500000, 0x600000, stride, n, None)
+    assert pf(_fake_cache(B), 128, 64) == B.QS_ERR_RANGE
+    assert pf(_fake_cache(B), 1024, 1024) == B.QS_ERR_RANGE
+    assert lib.qs_export_codes(ctypes.byref(_fake_cache(B)), 2, 0, 128, None, None, None, None, None, None, None) == B.QS_ERR_RANGE
+    assert lib.qs_export_codes(ctypes.byref(_fake_cache(B)), 0, 0, 100, None, None, None, None, None, None, None) == B.QS_ERR_RANGE
+
+
+def test_missing_library_fails_loudly(B, monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libquantspec.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        B.lib()

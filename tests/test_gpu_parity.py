@@ -1,0 +1,263 @@
+"""GPU parity: the HIP library against the CPU oracle on the same seeded inputs.
+
+Bar: codes, scales and zeros bit-exact; attention outputs within a maximum relative error of 2e-3
+per output vector (max_d |gpu - ref| / max_d |ref|; fp16 output, fp32 accumulation)."""
+import sys
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+
+
+def _say(msg):
+    print(f"[case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from oracle import quantspec_oracle as O
+    from paper_2502_10424_amd import binding as B, synth
+    from tests import gpu_util as U
+    B.lib()
+    return dict(torch=torch, O=O, B=B, synth=synth, U=U)
+
+
+def _workload_tensors(synth, w, ctx=None):
+    k, v = synth.gen_layer_kv(w, n_tokens=ctx)
+    return k, v
+
+
+def _run_attn(env, cache, q, sm_scale, verify):
+    torch, B = env["torch"], env["B"]
+    qd = torch.from_numpy(q).cuda()
+    lse = torch.empty(q.shape[:3], dtype=torch.float32, device="cuda")
+    fn = B.qs_attn_verify if verify else B.qs_attn_draft
+    out = fn(cache, qd, sm_scale, lse=lse)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), lse.cpu().numpy()
+
+
+def _check_attn(env, cache, oc, q, sm_scale, verify, rows=None, tag=""):
+    U = env["U"]
+    out, lse = _run_attn(env, cache, q, sm_scale, verify)
+    ref, ref_lse = (oc.attn_verify if verify else oc.attn_draft)(q, sm_scale, rows=rows)
+    if rows is not None:
+        sel = np.zeros(ref.shape[:1] + ref.shape[2:3], bool)
+        for b, h in rows:
+            sel[b, h] = True
+        out, ref = out.transpose(0, 2, 1, 3)[sel], ref.transpose(0, 2, 1, 3)[sel]
+        lse, ref_lse = lse.transpose(0, 2, 1)[sel], ref_lse.transpose(0, 2, 1)[sel]
+    assert np.isfinite(out).all(), tag
+    err = U.rel_err(out, ref)
+    lerr = float(np.abs(lse - ref_lse).max())
+    _say(f"{tag}: max rel err {err:.2e}, max |lse diff| {lerr:.2e}")
+    assert err <= TOL, f"{tag}: {err}"
+    assert lerr <= 2e-3, f"{tag}: lse {lerr}"
+    return err
+
+
+# ------------------------------------------------------------------------------------------------
+def test_quantize_codes_bit_exact_tiny(env):
+    """Workload 'tiny': prefill-quantize 1792 tokens of 8 kv-heads, then flush the 256 buffered tokens."""
+    synth, O, U, B = env["synth"], env["O"], env["U"], env["B"]
+    w = synth.WORKLOADS["tiny"]
+    k, v = _workload_tensors(synth, w)
+    _say("tiny prefill quantize")
+    cache = U.make_device_cache(k, v, w.n_q_heads, w.n_buf, q_cap=w.ctx, buf_cap=264)
+    oc = O.build_cache(k, v, w.n_q_heads, w.group, w.n_buf)
+    for h in range(w.n_kv_heads):
+        U.assert_unit_equals_oracle(cache, oc, 0, h)
+    _say("tiny flush 256")
+    B.qs_quantize_flush(cache, 256)
+    cache.n_quant += 256
+    cache.n_buf -= 256
+    oc.flush(256)
+    for h in range(w.n_kv_heads):
+        U.assert_unit_equals_oracle(cache, oc, 0, h)
+
+
+def test_flush_with_overlapping_buffer_move(env):
+    """Paper cadence: G tokens are flushed while more than G stay behind (source and destination of
+    the move overlap), on ragged batch lengths; repeated until the planes hold three more groups."""
+    torch, synth, O, U, B = env["torch"], env["synth"], env["O"], env["U"], env["B"]
+    rng = np.random.default_rng(5)
+    bsz, hkv, hq = 3, 2, 4
+    t = 128 * 4 + 261
+    k = (rng.standard_normal((bsz, hkv, t, 128)) * rng.choice([0.05, 1, 20], (bsz, hkv, 1, 128))).astype(np.float16)
+    v = (rng.standard_normal((bsz, hkv, t, 128)) + 3).astype(np.float16)
+    nb = [261, 133, 261 - 128]
+    # same total tokens per sequence is not required: cut each sequence to its own length
+    tq = [128, 256, 384]
+    ks = np.zeros_like(k); vs = np.zeros_like(v)
+    for b in range(bsz):
+        ks[b, :, :tq[b] + nb[b]] = k[b, :, :tq[b] + nb[b]]
+        vs[b, :, :tq[b] + nb[b]] = v[b, :, :tq[b] + nb[b]]
+    cache = B.KVCache(bsz, hq, hkv, 1024, 264)
+    oc = O.CacheOracle(bsz, hq, hkv, 128, 128)
+    kd, vd = torch.from_numpy(ks).cuda(), torch.from_numpy(vs).cuda()
+    for b in range(bsz):
+        sub = U._seq_view(cache, b)
+        B.qs_quantize_prefill(sub, kd[b:b + 1].contiguous(), vd[b:b + 1].contiguous(), tq[b])
+        cache.n_quant[b] = tq[b]
+        cache.k_buf[b, :, :nb[b]] = kd[b, :, tq[b]:tq[b] + nb[b]]
+        cache.v_buf[b, :, :nb[b]] = vd[b, :, tq[b]:tq[b] + nb[b]]
+        cache.n_buf[b] = nb[b]
+        for h in range(hkv):
+            oc.append(b, h, ks[b, h, :tq[b] + nb[b]], vs[b, h, :tq[b] + nb[b]])
+    # oracle: quantize each prefix in one go
+    for b in range(bsz):
+        for h in range(hkv):
+            ku, kl, ks_, kz = O.quantize_k(oc.kbuf[b][h][:tq[b]], 128)
+            vu, vl, vs_, vz = O.quantize_v(oc.vbuf[b][h][:tq[b]], 128)
+            oc.ku[b][h], oc.kl[b][h], oc.ks[b][h], oc.kz[b][h] = ku, kl, ks_, kz
+            oc.vu[b][h], oc.vl[b][h], oc.vs[b][h], oc.vz[b][h] = vu, vl, vs_, vz
+            oc.kbuf[b][h] = oc.kbuf[b][h][tq[b]:].copy(); oc.vbuf[b][h] = oc.vbuf[b][h][tq[b]:].copy()
+    _say("ragged flush 128 with overlap")
+    B.qs_quantize_flush(cache, 128)
+    cache.n_quant += 128; cache.n_buf -= 128
+    oc.flush(128)
+    torch.cuda.synchronize()
+    for b in range(bsz):
+        for h in range(hkv):
+            U.assert_unit_equals_oracle(cache, oc, b, h)
+    # attention over the ragged state, draft and verify
+    q = rng.standard_normal((bsz, 5, hq, 128)).astype(np.float16)
+    _check_attn(env, cache, oc, q, 0.09, True, tag="ragged verify after flush")
+    _check_attn(env, cache, oc, q[:, :1].copy(), 0.09, False, tag="ragged draft after flush")
+
+
+def test_quantizer_edge_values(env):
+    """Constant groups, sub-resolution ranges, huge ranges, ties: still bit-exact."""
+    torch, O, U, B = env["torch"], env["O"], env["U"], env["B"]
+    rng = np.random.default_rng(6)
+    k = rng.standard_normal((1, 2, 256, 128)).astype(np.float16)
+    v = rng.standard_normal((1, 2, 256, 128)).astype(np.float16)
+    k[0, 0, :128, 3] = 1.5                      # constant channel -> S := 1, codes 0
+    k[0, 0, :128, 4] = 0.0; k[0, 0, 5, 4] = 6e-8   # range below the resolution of the fp16 scale
+    k[0, 0, :128, 5] = np.linspace(-60000, 60000, 128).astype(np.float16)   # near the fp16 limits
+    k[0, 1, :128, 7] = (np.arange(128) % 31) * 0.5                          # exact ties at .5 steps
+    v[0, 0, 9, :] = -2.25
+    v[0, 0, 10, :] = (np.arange(128) % 16).astype(np.float16)              # on the 4-bit grid
+    v[0, 1, 11, :] = (np.arange(128) % 31) * 0.5
+    v[0, 1, 12, :] = 0; v[0, 1, 12, 100] = 65504
+    _say("edge-value quantize")
+    cache = U.make_device_cache(k, v, 2, 0, q_cap=256, buf_cap=8)
+    oc = O.build_cache(k, v, 2, 128, 0)
+    for h in range(2):
+        U.assert_unit_equals_oracle(cache, oc, 0, h)
+
+
+@pytest.mark.parametrize("verify", [False, True], ids=["draft", "verify"])
+def test_attention_tiny_workload(env, verify):
+    """Workload 'tiny' (GQA 32/8, ctx 2048 = 1792 quantized + 256 buffered): 1 draft query, 5 verify queries."""
+    synth, O, U = env["synth"], env["O"], env["U"]
+    w = synth.WORKLOADS["tiny"]
+    k, v = _workload_tensors(synth, w)
+    cache = U.make_device_cache(k, v, w.n_q_heads, w.n_buf, buf_cap=264)
+    oc = O.build_cache(k, v, w.n_q_heads, w.group, w.n_buf)
+    nq = w.nq_verify if verify else 1
+    q = synth.gen_layer_q(w, nq)
+    _check_attn(env, cache, oc, q, 1.0 / np.sqrt(128), verify, tag=f"tiny {'verify' if verify else 'draft'}")
+
+
+@pytest.mark.parametrize("hq,hkv,nq", [(2, 2, 1), (4, 1, 2), (8, 2, 3), (16, 2, 5), (8, 1, 8), (16, 2, 7), (3, 3, 4)])
+def test_attention_row_shapes(env, hq, hkv, nq):
+    """1..64 query rows per kv-head (one to several 8-row MFMA tiles and row batches), ragged lengths,
+    buffer lengths that end inside a 16-token tile."""
+    O, U = env["O"], env["U"]
+    rng = np.random.default_rng(100 + hq * 10 + nq)
+    bsz = 2
+    nb = [nq + 3, 77]
+    tq = [384, 128]
+    t = max(a + b for a, b in zip(tq, nb))
+    k = np.zeros((bsz, hkv, t, 128), np.float16); v = np.zeros_like(k)
+    cache_k, cache_v = [], []
+    for b in range(bsz):
+        n = tq[b] + nb[b]
+        k[b, :, :n] = (rng.standard_normal((hkv, n, 128)) * 1.5).astype(np.float16)
+        v[b, :, :n] = rng.standard_normal((hkv, n, 128)).astype(np.float16)
+    # build per sequence (different totals): device side through ragged helper, oracle side directly
+    torch, B = env["torch"], env["B"]
+    cache = B.KVCache(bsz, hq, hkv, 512, 80)
+    oc = O.CacheOracle(bsz, hq, hkv, 128, 128)
+    kd, vd = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    for b in range(bsz):
+        sub = U._seq_view(cache, b)
+        B.qs_quantize_prefill(sub, kd[b:b + 1].contiguous(), vd[b:b + 1].contiguous(), tq[b])
+        cache.n_quant[b] = tq[b]; cache.n_buf[b] = nb[b]
+        cache.k_buf[b, :, :nb[b]] = kd[b, :, tq[b]:tq[b] + nb[b]]
+        cache.v_buf[b, :, :nb[b]] = vd[b, :, tq[b]:tq[b] + nb[b]]
+        ob = O.build_cache(k[b:b + 1, :, :tq[b] + nb[b]], v[b:b + 1, :, :tq[b] + nb[b]], hq, 128, nb[b])
+        for name in ("ku", "kl", "ks", "kz", "vu", "vl", "vs", "vz", "kbuf", "vbuf"):
+            getattr(oc, name)[b] = getattr(ob, name)[0]
+    q = rng.standard_normal((bsz, nq, hq, 128)).astype(np.float16)
+    _check_attn(env, cache, oc, q, 0.11, True, tag=f"verify hq{hq} hkv{hkv} nq{nq}")
+    if nq == 1:
+        _check_attn(env, cache, oc, q, 0.11, False, tag=f"draft hq{hq} hkv{hkv}")
+
+
+def test_attention_degenerate_cases(env):
+    """Buffer only (no quantized tokens); buffer holding exactly the nq query tokens; peaked softmax."""
+    O, U = env["O"], env["U"]
+    rng = np.random.default_rng(7)
+    k = rng.standard_normal((1, 2, 200, 128)).astype(np.float16)
+    v = rng.standard_normal((1, 2, 200, 128)).astype(np.float16)
+    q = rng.standard_normal((1, 4, 4, 128)).astype(np.float16)
+    cache = U.make_device_cache(k, v, 4, 200, q_cap=128, buf_cap=256)
+    oc = O.build_cache(k, v, 4, 128, 200)
+    _check_attn(env, cache, oc, q, 0.1, True, tag="buffer only verify")
+    _check_attn(env, cache, oc, q[:, :1].copy(), 0.1, False, tag="buffer only draft")
+    k2 = rng.standard_normal((1, 2, 256 + 4, 128)).astype(np.float16)
+    v2 = rng.standard_normal((1, 2, 256 + 4, 128)).astype(np.float16)
+    cache = U.make_device_cache(k2, v2, 4, 4, buf_cap=8)
+    oc = O.build_cache(k2, v2, 4, 128, 4)
+    _check_attn(env, cache, oc, q, 0.1, True, tag="buffer == nq tokens")
+    # one key dominates: scores up to ~ +40 above the rest
+    k3 = k2.copy(); k3[0, :, 100, :] = (q[0, 0, 0] * 2).astype(np.float16)
+    cache = U.make_device_cache(k3, v2, 4, 4, buf_cap=8)
+    oc = O.build_cache(k3, v2, 4, 128, 4)
+    _check_attn(env, cache, oc, q, 0.15, True, tag="peaked softmax")
+
+
+def test_attention_lossless_grid_matches_unquantized(env):
+    """Property that holds without the oracle's quantizer: 4-bit-grid data through the draft pass equals
+    plain fp64 attention over the original tensors."""
+    torch, U = env["torch"], env["U"]
+    rng = np.random.default_rng(8)
+    t, nb = 512, 40
+    kk = rng.integers(0, 16, (1, 2, t + nb, 128)); kk[:, :, 0::128] = 0; kk[:, :, 1::128] = 15
+    vv = rng.integers(0, 16, (1, 2, t + nb, 128)); vv[..., 0] = 0; vv[..., 1] = 15
+    k = (-1.0 + kk * 0.125).astype(np.float16)
+    v = (0.5 + vv * 0.25).astype(np.float16)
+    q = rng.standard_normal((1, 1, 4, 128)).astype(np.float16)
+    cache = U.make_device_cache(k, v, 4, nb, buf_cap=64)
+    out, _ = _run_attn(env, cache, q, 0.08, False)
+    kt = torch.tensor(k.astype(np.float64)).repeat_interleave(2, dim=1)
+    vt = torch.tensor(v.astype(np.float64)).repeat_interleave(2, dim=1)
+    qt = torch.tensor(q.astype(np.float64)).permute(0, 2, 1, 3)
+    ref = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, scale=0.08).permute(0, 2, 1, 3).numpy()
+    assert U.rel_err(out, ref) <= TOL
+
+
+def test_split_count_invariance(env):
+    """The result must not depend on how the quantized region is cut into chunks: the same cache with
+    different batch sizes (hence different chunk counts per unit) gives the same outputs per sequence."""
+    synth, U, B, torch = env["synth"], env["U"], env["B"], env["torch"]
+    rng = np.random.default_rng(9)
+    k1 = (rng.standard_normal((1, 1, 128 * 40 + 64, 128))).astype(np.float16)
+    v1 = rng.standard_normal(k1.shape).astype(np.float16)
+    q1 = rng.standard_normal((1, 3, 2, 128)).astype(np.float16)
+    reps = 64   # 64 units -> far fewer chunks per unit than a single unit gets
+    cache1 = U.make_device_cache(k1, v1, 2, 64)
+    cacheN = U.make_device_cache(np.repeat(k1, reps, 0), np.repeat(v1, reps, 0), 2, 64)
+    o1, _ = _run_attn(env, cache1, q1, 0.09, True)
+    oN, _ = _run_attn(env, cacheN, np.repeat(q1, reps, 0), 0.09, True)
+    assert np.abs(oN - oN[:1]).max() == 0.0
+    assert U.rel_err(oN[:1], o1.astype(np.float64)) <= 1e-3
