@@ -1,0 +1,204 @@
+#!/usr/bin/env python3
+"""Benchmark of the QuantSpec decode-attention hot path on one MI355X.
+
+One "step" is one speculation cycle of Algorithm 1 over one layer's cache, every stage of the hot
+path included: gamma = 4 draft attention calls (1 query, upper plane + buffer), one verify call
+(gamma + 1 = 5 causal queries, both planes + buffer) and one quantize-on-flush of G = 128 buffered
+tokens (quantize, append, buffer move).  Inputs are resident in HBM before the timed region.  The
+cycle rotates over several independent cache copies so the 256 MB last-level cache cannot serve the
+planes.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+GAMMA = 4
+
+# HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (calibrated against a plain copy kernel).  Filled from the summaries under profiles/; None = not measured.
+MEASURED_TRAFFIC_BYTES = {
+}
+
+
+def algorithmic_bytes(w, nq, verify):
+    """Bytes one attention call must move (fp16 metadata): per quantized token and unit 64 (K upper)
+    + 64 (V upper) + 4 (K scale/zero, amortised over the group) + 4 (V scale/zero); twice the plane
+    bytes for verify; plus the fp16 buffer and q / out."""
+    per_tok = (128 + 128 + 8) if verify else (64 + 64 + 8)
+    return w.units * (w.n_quant * per_tok + w.n_buf * 128 * 2 * 2) + w.batch * w.n_q_heads * nq * 128 * 2 * 2
+
+
+def flush_bytes(w, n):
+    return w.units * n * (128 * 2 * 2 + (128 + 128 + 4 + 4))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="mha128k")
+    ap.add_argument("--copies", type=int, default=3, help="independent cache copies to rotate over")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build targets one GPU; every figure is the one GPU's throughput. "
+              "Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2502_10424_amd import binding as B, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.lib()
+    w = synth.WORKLOADS[args.workload]
+    sm_scale = 1.0 / float(np.sqrt(w.head_dim))
+    nqv = w.nq_verify
+    dev = "cuda"
+
+    # ---- synthetic inputs, resident in HBM ------------------------------------------------------
+    t0 = time.time()
+    workers = min(16, os.cpu_count() or 8)
+    k_host, v_host = synth.gen_layer_kv(w, workers=workers)
+    q_draft = torch.from_numpy(synth.gen_layer_q(w, 1)).to(dev)
+    q_verify = torch.from_numpy(synth.gen_layer_q(w, nqv)).to(dev)
+    q_cap = w.n_quant + 128            # room for the flushed group
+    caches = []
+    kd, vd = torch.from_numpy(k_host).to(dev), torch.from_numpy(v_host).to(dev)
+    for i in range(args.copies):
+        c = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, q_cap, w.n_buf + 8)
+        if i == 0:
+            B.qs_quantize_prefill(c, kd, vd, w.n_quant)
+        else:
+            for name in ("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "k_zero", "v_scale", "v_zero"):
+                getattr(c, name).copy_(getattr(caches[0], name))
+        c.k_buf[:, :, :w.n_buf] = kd[:, :, w.n_quant:]
+        c.v_buf[:, :, :w.n_buf] = vd[:, :, w.n_quant:]
+        c.n_quant[:] = w.n_quant
+        c.n_buf[:] = w.n_buf
+        caches.append(c)
+    del kd, vd
+    ws = torch.empty(max(B.qs_workspace_bytes(caches[0], nqv), B.qs_workspace_bytes(caches[0], 1)),
+                     dtype=torch.uint8, device=dev)
+    out_d = torch.empty_like(q_draft)
+    out_v = torch.empty_like(q_verify)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    timed = {"draft": [], "verify": [], "flush": []}
+
+    def cycle(i, record):
+        c = caches[i % len(caches)]
+        for _ in range(GAMMA):
+            if record:
+                e0, e1 = ev(), ev(); e0.record()
+            B.qs_attn_draft(c, q_draft, sm_scale, out=out_d, workspace=ws)
+            if record:
+                e1.record(); timed["draft"].append((e0, e1))
+        if record:
+            e0, e1 = ev(), ev(); e0.record()
+        B.qs_attn_verify(c, q_verify, sm_scale, out=out_v, workspace=ws)
+        if record:
+            e1.record(); timed["verify"].append((e0, e1))
+            e0, e1 = ev(), ev(); e0.record()
+        B.qs_quantize_flush(c, 128)     # host lengths stay put: the same group slot is rewritten each cycle
+        if record:
+            e1.record(); timed["flush"].append((e0, e1))
+
+    for i in range(args.warmup):
+        cycle(i, False)
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for i in range(args.steps):
+        cycle(args.warmup + i, True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    avg_us = {k: 1e3 * float(np.mean([a.elapsed_time(b) for a, b in v])) for k, v in timed.items()}
+    bytes_d, bytes_v = algorithmic_bytes(w, 1, False), algorithmic_bytes(w, nqv, True)
+    gbps_d = bytes_d / (avg_us["draft"] * 1e-6) / 1e9
+    gbps_v = bytes_v / (avg_us["verify"] * 1e-6) / 1e9
+    cycle_bytes = GAMMA * bytes_d + bytes_v + flush_bytes(w, 128)
+
+    result = {
+        "metric": "draft/verify attention us per decode step + achieved HBM GB/s at 128k ctx",
+        "value": round(ms_per_step * 1e3 / (GAMMA + 1), 3),
+        "unit": "us/decode-step (mean over a cycle of 4 draft + 1 verify call, flush included)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads} q-heads / {w.n_kv_heads} kv-heads x 128, "
+                               f"ctx {w.ctx} = {w.n_quant} quantized + {w.n_buf} fp16 buffer, G=128, gamma=4",
+                   "cache_copies_rotated": len(caches), "flush_tokens_per_cycle": 128},
+        "draft_us": round(avg_us["draft"], 2), "verify_us": round(avg_us["verify"], 2),
+        "flush_us": round(avg_us["flush"], 2),
+        "draft_GBps": round(gbps_d, 1), "verify_GBps": round(gbps_v, 1),
+        "cycle_GBps": round(cycle_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "roofline": {"bound": "hbm", "kernel": "attn_kernel<1,false> (draft, upper plane)",
+                     "achieved": round(gbps_d, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gbps_d / HBM_PEAK_GBPS, 4),
+                     "algorithmic_bytes_per_launch": bytes_d,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, "draft"))},
+        "roofline_verify": {"bound": "hbm", "kernel": "attn_kernel<1,true> (verify, both planes)",
+                            "achieved": round(gbps_v, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                            "frac": round(gbps_v / HBM_PEAK_GBPS, 4),
+                            "algorithmic_bytes_per_launch": bytes_v,
+                            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, "verify"))},
+        "setup_s": round(setup_s, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, k_host, v_host, sm_scale)
+    print(json.dumps(result), flush=True)
+
+
+def cpu_baseline(w, k_host, v_host, sm_scale, sample_units=6):
+    """The float64 oracle, as it stands, on the same cycle for `sample_units` of the workload's
+    (sequence, kv-head) units, scaled to all units."""
+    from oracle import quantspec_oracle as O
+    from paper_2502_10424_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    rep = w.n_q_heads // w.n_kv_heads
+    ks, vs = k_host[:1, :sample_units], v_host[:1, :sample_units]
+    oc = O.build_cache(ks, vs, rep * sample_units, w.group, w.n_buf)      # prefill quantize: not timed
+    qd = synth.gen_layer_q(w, 1)[:1, :, :rep * sample_units]
+    qv = synth.gen_layer_q(w, w.nq_verify)[:1, :, :rep * sample_units]
+    t0 = time.perf_counter()
+    oc.attn_draft(qd, sm_scale)                                           # one of the gamma draft calls
+    t_draft = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oc.attn_verify(qv, sm_scale)
+    t_verify = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oc.flush(128)
+    t_flush = time.perf_counter() - t0
+    scale = w.units / sample_units
+    cyc = (GAMMA * t_draft + t_verify + t_flush) * scale
+    return {"value": round(cyc * 1e6 / (GAMMA + 1), 1), "unit": "us/decode-step (same cycle, scaled to all units)",
+            "cores": threads, "kind": "oracle",
+            "sample": f"{sample_units} of {w.units} units: 1 draft call (x{GAMMA}), 1 verify call, 1 flush of 128 "
+                      f"tokens; {t_draft:.2f}s + {t_verify:.2f}s + {t_flush:.3f}s measured, scaled x{scale:.0f}",
+            "draft_us": round(t_draft * scale * 1e6, 1), "verify_us": round(t_verify * scale * 1e6, 1)}
+
+
+if __name__ == "__main__":
+    main()

@@ -23,6 +23,13 @@
 //    exactly the token order this produces, so probabilities never cross lanes.
 #include "qs_internal.h"
 
+#ifndef QS_PREFETCH
+#define QS_PREFETCH 0
+#endif
+#ifndef QS_WAVES
+#define QS_WAVES 2
+#endif
+
 namespace qs {
 namespace {
 
@@ -214,105 +221,143 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   const _Float16* ksc = a.k_scale + (int64_t)unit * (a.q_cap / kG) * kD + 32 * g;
   const _Float16* kzr = a.k_zero + (int64_t)unit * (a.q_cap / kG) * kD + 32 * g;
 
-  for (int grp = grp0; grp < grp1; ++grp) {
-    // ---- per-group query operand: columns 0-7 hold fp16(q*S), columns 8-15 the exact remainder ----
-    half8 qb[NRT][4];
-    float cin[NRT];
-    {
-      half8 sg[4], zg[4];
+  // One 32-token block of operands: two 16-token key tiles, one value tile, value metadata.
+  struct Block {
+    u32x4 kU[2], kL[2], vU[2], vL[2];
+    half8 vS, vZ;
+  };
+  auto load_block = [&](Block& d, int64_t t0) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      d.kU[t] = ldg128(ku + (t0 + 16 * t) * kRowDw);
+      if (VERIFY) d.kL[t] = ldg128(kl + (t0 + 16 * t) * kRowDw);
+      d.vU[t] = ldg128(vu + (t0 / kVTileTok) * kVTileDw + 256 * t);
+      if (VERIFY) d.vL[t] = ldg128(vl + (t0 / kVTileTok) * kVTileDw + 256 * t);
+    }
+    d.vS = as_half8(ldg128(vs + t0));
+    d.vZ = as_half8(ldg128(vz + t0));
+  };
+  half8 sg[4], zg[4];   // key scale / zero of the lane's 32 channels, operand order
+  auto load_key_meta = [&](int grp) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      sg[s] = to_operand_order(as_half8(ldg128(ksc + (int64_t)grp * kD + 8 * s)));
+      zg[s] = to_operand_order(as_half8(ldg128(kzr + (int64_t)grp * kD + 8 * s)));
+    }
+  };
+
+  half8 qb[NRT][4];
+  float cin[NRT];
+  // per-group query operand: columns 0-7 hold fp16(q*S), columns 8-15 the exact remainder
+  auto prepare_group = [&]() {
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      float ba = 0.f, bb = 0.f, sa = 0.f, sb = 0.f;
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        sg[s] = to_operand_order(as_half8(ldg128(ksc + (int64_t)grp * kD + 8 * s)));
-        zg[s] = to_operand_order(as_half8(ldg128(kzr + (int64_t)grp * kD + 8 * s)));
-      }
+        u32x4 sw = as_u32x4(sg[s]), zw = as_u32x4(zg[s]), out;
 #pragma unroll
-      for (int rt = 0; rt < NRT; ++rt) {
-        float ba = 0.f, bb = 0.f, sa = 0.f, sb = 0.f;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-          u32x4 sw = as_u32x4(sg[s]), zw = as_u32x4(zg[s]), out;
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const half2v qh = qv[rt][4 * s + r], sh = as_half2(sw[r]), zh = as_half2(zw[r]);
-            const half2v hi = qh * sh;
-            const half2v lo = __builtin_elementwise_fma(qh, sh, -hi);
-            out[r] = lo_part ? as_u32(lo) : as_u32(hi);
-            if (r & 1) {
-              bb = __builtin_amdgcn_fdot2(qh, zh, bb, false);
-              if (VERIFY) sb = __builtin_amdgcn_fdot2(qh, sh, sb, false);
-            } else {
-              ba = __builtin_amdgcn_fdot2(qh, zh, ba, false);
-              if (VERIFY) sa = __builtin_amdgcn_fdot2(qh, sh, sa, false);
-            }
+        for (int r = 0; r < 4; ++r) {
+          const half2v qh = qv[rt][4 * s + r], sh = as_half2(sw[r]), zh = as_half2(zw[r]);
+          const half2v hi = qh * sh;
+          const half2v lo = __builtin_elementwise_fma(qh, sh, -hi);
+          out[r] = lo_part ? as_u32(lo) : as_u32(hi);
+          if (r & 1) {
+            bb = __builtin_amdgcn_fdot2(qh, zh, bb, false);
+            if (VERIFY) sb = __builtin_amdgcn_fdot2(qh, sh, sb, false);
+          } else {
+            ba = __builtin_amdgcn_fdot2(qh, zh, ba, false);
+            if (VERIFY) sa = __builtin_amdgcn_fdot2(qh, sh, sa, false);
           }
-          qb[rt][s] = as_half8(out);
         }
-        // sum_d q_d * Zeff_d with Zeff = Z (draft) or Z - S/2 (verify: codes are offset by +8 lower steps)
-        float bias = __builtin_fmaf(bb, 1.0f / kKeyPos, ba);
-        if (VERIFY) bias -= 0.5f * __builtin_fmaf(sb, 1.0f / kKeyPos, sa);
-        bias = group_sum(bias);
-        cin[rt] = lo_part ? 0.f : bias * (1.0f / kKeyRaw);
+        qb[rt][s] = as_half8(out);
       }
+      // sum_d q_d * Zeff_d with Zeff = Z (draft) or Z - S/2 (verify: codes are offset by +8 lower steps)
+      float bias = __builtin_fmaf(bb, 1.0f / kKeyPos, ba);
+      if (VERIFY) bias -= 0.5f * __builtin_fmaf(sb, 1.0f / kKeyPos, sa);
+      bias = group_sum(bias);
+      cin[rt] = lo_part ? 0.f : bias * (1.0f / kKeyRaw);
+    }
+  };
+
+  auto compute_block = [&](const Block& d) {
+    // ---- scores: S^T[token, column] = codes x q ----
+    float raw[NRT][8];
+    {
+      half8 ka[2][4];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) ka[t][s] = VERIFY ? unpack8(d.kU[t][s], d.kL[t][s]) : unpack4(d.kU[t][s]);
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+          float4v acc = {cin[rt], cin[rt], cin[rt], cin[rt]};
+#pragma unroll
+          for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qb[rt][s], acc, 0, 0, 0);
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) raw[rt][4 * t + jj] = acc[jj] + xor8_in_row(acc[jj]);
+        }
+    }
+    softmax_block<NRT>(st, raw, mul);
+
+    // ---- probabilities x value scale -> B operand; zero-point term ----
+    half8 pb[NRT];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      float zs = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float s = (float)d.vS[j];
+        const float zeff = VERIFY ? __builtin_fmaf(-0.5f, s, (float)d.vZ[j]) : (float)d.vZ[j];
+        zs = __builtin_fmaf(raw[rt][j], zeff, zs);
+        pb[rt][j] = (_Float16)(raw[rt][j] * s * (((j >> 1) & 1) ? kPB : kPA));
+      }
+      st.z[rt] += zs;
     }
 
-    for (int blk = 0; blk < 4; ++blk) {
-      const int64_t t0 = (int64_t)grp * kG + blk * 32;
-      // ---- loads: two 16-token key tiles, one 32-token value tile, value metadata ----
-      u32x4 kU[2], kL[2], vU[2], vL[2];
+    // ---- O^T[channel, column] += codes^T x p ----
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        kU[t] = ldg128(ku + (t0 + 16 * t) * kRowDw);
-        if (VERIFY) kL[t] = ldg128(kl + (t0 + 16 * t) * kRowDw);
-        vU[t] = ldg128(vu + (t0 / kVTileTok) * kVTileDw + 256 * t);
-        if (VERIFY) vL[t] = ldg128(vl + (t0 / kVTileTok) * kVTileDw + 256 * t);
-      }
-      const half8 vS = as_half8(ldg128(vs + t0));
-      const half8 vZ = as_half8(ldg128(vz + t0));
+    for (int n = 0; n < 8; ++n) {
+      const half8 va = VERIFY ? unpack8(d.vU[n >> 2][n & 3], d.vL[n >> 2][n & 3]) : unpack4(d.vU[n >> 2][n & 3]);
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt)
+        st.o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pb[rt], st.o[rt][n], 0, 0, 0);
+    }
+  };
 
-      // ---- scores: S^T[token, column] = codes x q ----
-      float raw[NRT][8];
-      {
-        half8 ka[2][4];
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int s = 0; s < 4; ++s) ka[t][s] = VERIFY ? unpack8(kU[t][s], kL[t][s]) : unpack4(kU[t][s]);
-#pragma unroll
-        for (int rt = 0; rt < NRT; ++rt)
-#pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            float4v acc = {cin[rt], cin[rt], cin[rt], cin[rt]};
-#pragma unroll
-            for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qb[rt][s], acc, 0, 0, 0);
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) raw[rt][4 * t + jj] = acc[jj] + xor8_in_row(acc[jj]);
-          }
-      }
-      softmax_block<NRT>(st, raw, mul);
-
-      // ---- probabilities x value scale -> B operand; zero-point term ----
-      half8 pb[NRT];
-#pragma unroll
-      for (int rt = 0; rt < NRT; ++rt) {
-        float zs = 0.f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          const float s = (float)vS[j];
-          const float zeff = VERIFY ? __builtin_fmaf(-0.5f, s, (float)vZ[j]) : (float)vZ[j];
-          zs = __builtin_fmaf(raw[rt][j], zeff, zs);
-          pb[rt][j] = (_Float16)(raw[rt][j] * s * (((j >> 1) & 1) ? kPB : kPA));
-        }
-        st.z[rt] += zs;
-      }
-
-      // ---- O^T[channel, column] += codes^T x p ----
-#pragma unroll
-      for (int n = 0; n < 8; ++n) {
-        const half8 va = VERIFY ? unpack8(vU[n >> 2][n & 3], vL[n >> 2][n & 3]) : unpack4(vU[n >> 2][n & 3]);
-#pragma unroll
-        for (int rt = 0; rt < NRT; ++rt)
-          st.o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pb[rt], st.o[rt][n], 0, 0, 0);
-      }
+  // Software pipeline: while block i is being computed the loads of block i+1 are in flight, and the
+  // key metadata of the next group is fetched a whole group ahead.
+  if (grp0 < grp1) {
+    Block bufA, bufB;
+    load_key_meta(grp0);
+    load_block(bufA, (int64_t)grp0 * kG);
+    for (int grp = grp0; grp < grp1; ++grp) {
+      const int64_t t0 = (int64_t)grp * kG;
+      const bool more = grp + 1 < grp1;
+#if QS_PREFETCH
+      prepare_group();
+      if (more) load_key_meta(grp + 1);
+      load_block(bufB, t0 + 32);
+      compute_block(bufA);
+      load_block(bufA, t0 + 64);
+      compute_block(bufB);
+      load_block(bufB, t0 + 96);
+      compute_block(bufA);
+      if (more) load_block(bufA, t0 + 128);
+      compute_block(bufB);
+#else
+      if (grp != grp0) { load_key_meta(grp); load_block(bufA, t0); }
+      prepare_group();
+      compute_block(bufA);
+      load_block(bufA, t0 + 32);
+      compute_block(bufA);
+      load_block(bufA, t0 + 64);
+      compute_block(bufA);
+      load_block(bufA, t0 + 96);
+      compute_block(bufA);
+#endif
     }
   }
   write_partial<NRT>(a, st, b, kvh, row0, split, kOutRaw);
@@ -423,7 +468,7 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
 }
 
 template <int NRT, bool VERIFY>
-__global__ __launch_bounds__(64) void attn_kernel(AttnArgs a) {
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(QS_WAVES))) void attn_kernel(AttnArgs a) {
   __shared__ _Float16 vt[kD][kVtStride];
   const int split = blockIdx.x, unit = blockIdx.y, row0 = blockIdx.z * 8 * NRT;
   const int b = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
@@ -434,22 +479,49 @@ __global__ __launch_bounds__(64) void attn_kernel(AttnArgs a) {
 }
 
 // Merge of the per-chunk partials (Appendix E): M = max m_i, L = sum l_i 2^(m_i - M),
-// out = sum o_i 2^(m_i - M) / L.  One workgroup per query row, one thread per channel.
-__global__ __launch_bounds__(128) void merge_kernel(MergeArgs a) {
+// out = sum o_i 2^(m_i - M) / L.  One 256-thread workgroup per query row: thread (sl, c) sums chunks
+// sl, sl+8, ... for channels 4c..4c+3, then the eight partial sums are combined through LDS.
+__global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
+  __shared__ float red_m[256];
+  __shared__ float red_o[8][kD + 4];
+  __shared__ float red_l[8];
   const int64_t row = blockIdx.x;
-  const int d = threadIdx.x;
+  const int tid = threadIdx.x, sl = tid >> 5, c = tid & 31;
   const float* ml = a.ws_ml + row * a.n_split * 2;
-  const float* po = a.ws_o + row * a.n_split * kD + d;
+  const float* po = a.ws_o + row * a.n_split * kD + 4 * c;
   float m = kNegBig;
-  for (int s = 0; s < a.n_split; ++s) m = fmaxf(m, ml[2 * s]);
-  float l = 0.f, o = 0.f;
-  for (int s = 0; s < a.n_split; ++s) {
-    const float w = __builtin_amdgcn_exp2f(ml[2 * s] - m);
-    l = __builtin_fmaf(w, ml[2 * s + 1], l);
-    o = __builtin_fmaf(w, po[(int64_t)s * kD], o);
+  for (int s = tid; s < a.n_split; s += 256) m = fmaxf(m, ml[2 * s]);
+  red_m[tid] = m;
+  __syncthreads();
+#pragma unroll
+  for (int w = 128; w > 0; w >>= 1) {
+    if (tid < w) red_m[tid] = fmaxf(red_m[tid], red_m[tid + w]);
+    __syncthreads();
   }
-  a.out[row * kD + d] = (_Float16)(o / l);
-  if (a.lse != nullptr && d == 0) a.lse[row] = (m + __builtin_log2f(l)) * 0.6931471805599453f;
+  m = red_m[0];
+  float l = 0.f;
+  float4v o = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+  for (int s = sl; s < a.n_split; s += 8) {
+    const float w = __builtin_amdgcn_exp2f(ml[2 * s] - m);
+    const float4v x = *reinterpret_cast<const float4v*>(po + (int64_t)s * kD);
+    l = __builtin_fmaf(w, ml[2 * s + 1], l);
+    o += w * x;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) red_o[sl][4 * c + i] = o[i];
+  if (c == 0) red_l[sl] = l;
+  __syncthreads();
+  if (tid < kD) {
+    float os = 0.f, ls = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      os += red_o[k][tid];
+      ls += red_l[k];
+    }
+    a.out[row * kD + tid] = (_Float16)(os / ls);
+    if (a.lse != nullptr && tid == 0) a.lse[row] = (m + __builtin_log2f(ls)) * 0.6931471805599453f;
+  }
 }
 
 template <int NRT>
@@ -472,7 +544,7 @@ hipError_t launch_attn(const AttnArgs& a, int batch, bool verify, hipStream_t s)
 }
 
 hipError_t launch_merge(const MergeArgs& a, int rows_total, hipStream_t s) {
-  hipLaunchKernelGGL(merge_kernel, dim3(rows_total), dim3(128), 0, s, a);
+  hipLaunchKernelGGL(merge_kernel, dim3(rows_total), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
