@@ -23,7 +23,9 @@
  *     k_upper, k_lower : uint8 [B][Hkv][q_cap][64]   two codes per byte; byte j of a token row holds
  *                        channel 2j in bits 0-3 and channel 2j+1 in bits 4-7.
  *                        k_upper nibble = C_U (0..15); k_lower nibble = C_L + 8 (0..15).
- *     k_scale, k_zero  : fp16  [B][Hkv][q_cap/128][128]   S and Z of (token group, channel).
+ *     k_scale, k_zero  : fp16  [B][Hkv][q_cap/128][128]   S and Z of (token group, channel), stored in the
+ *                        order the kernels consume: position 32*s + 8*g + e (s<4, g<4, e<8) holds channel
+ *                        32*g + 8*s + (e&1)*4 + (e>>1).
  *   Values, per-token groups of 128 channels:
  *     v_upper, v_lower : uint8 [B][Hkv][q_cap/32][2048]   tiled for the matrix-core operand: inside a
  *                        32-token tile, 32-bit word ((h*64 + 16*g + m)*4 + i) holds channel
@@ -134,12 +136,14 @@ int qs_attn_verify(const qs_cache *c, const void *q, int32_t nq, void *out, floa
 /*
  * Inspection helper: expand the packed planes and metadata of tokens [0, n_tokens) of one unit
  * into plain arrays (device pointers, any may be NULL to skip):
- *   k_u, v_u : uint8 [n_tokens][128]  C_U          k_l, v_l : int8 [n_tokens][128]  C_L
- *   v_s, v_z : fp16  [n_tokens]       per-token S, Z in token order
- * (k_scale / k_zero are already in plain order.)  n_tokens is a multiple of 32.
+ *   k_u, v_u : uint8 [n_tokens][128]      C_U       k_l, v_l : int8 [n_tokens][128]  C_L
+ *   k_s, k_z : fp16  [n_tokens/128][128]  per-(group, channel) S, Z in channel order
+ *   v_s, v_z : fp16  [n_tokens]           per-token S, Z in token order
+ * n_tokens is a multiple of 128.
  */
 int qs_export_codes(const qs_cache *c, int32_t b, int32_t kv_head, int32_t n_tokens,
-                    void *k_u, void *k_l, void *v_u, void *v_l, void *v_s, void *v_z, void *stream);
+                    void *k_u, void *k_l, void *k_s, void *k_z,
+                    void *v_u, void *v_l, void *v_s, void *v_z, void *stream);
 
 #ifdef __cplusplus
 }

@@ -71,7 +71,7 @@ def lib() -> ctypes.CDLL:
         l.qs_attn_verify.restype = ctypes.c_int
         l.qs_attn_verify.argtypes = [P, vp, i32, vp, f32, vp, sz, vp, vp]
         l.qs_export_codes.restype = ctypes.c_int
-        l.qs_export_codes.argtypes = [P, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+        l.qs_export_codes.argtypes = [P, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         _lib = l
     return _lib
 
@@ -196,8 +196,8 @@ def qs_attn_verify(cache, q, sm_scale: float, out=None, workspace=None, lse=None
 
 
 def qs_export_codes(cache: KVCache, b: int, kv_head: int, n_tokens: int, stream=None):
-    """Plain-order codes and value metadata of one unit, as device tensors:
-    (k_u uint8 [T,128], k_l int8 [T,128], v_u, v_l, v_s fp16 [T], v_z fp16 [T])."""
+    """Plain-order codes and metadata of one unit, as a dict of device tensors:
+    k_u, v_u uint8 [T,128]; k_l, v_l int8 [T,128]; k_s, k_z fp16 [T/128,128]; v_s, v_z fp16 [T]."""
     c = cache.struct()
     dev = cache.k_upper.device
     k_u = torch.empty((n_tokens, 128), dtype=torch.uint8, device=dev)
@@ -206,7 +206,10 @@ def qs_export_codes(cache: KVCache, b: int, kv_head: int, n_tokens: int, stream=
     v_l = torch.empty_like(k_l)
     v_s = torch.empty(n_tokens, dtype=torch.float16, device=dev)
     v_z = torch.empty_like(v_s)
+    k_s = torch.empty((n_tokens // 128, 128), dtype=torch.float16, device=dev)
+    k_z = torch.empty_like(k_s)
     _check(lib().qs_export_codes(ctypes.byref(c), b, kv_head, n_tokens, k_u.data_ptr(), k_l.data_ptr(),
-                                 v_u.data_ptr(), v_l.data_ptr(), v_s.data_ptr(), v_z.data_ptr(), _stream(stream)),
+                                 k_s.data_ptr(), k_z.data_ptr(), v_u.data_ptr(), v_l.data_ptr(),
+                                 v_s.data_ptr(), v_z.data_ptr(), _stream(stream)),
            "qs_export_codes")
-    return k_u, k_l, v_u, v_l, v_s, v_z
+    return dict(k_u=k_u, k_l=k_l, k_s=k_s, k_z=k_z, v_u=v_u, v_l=v_l, v_s=v_s, v_z=v_z)

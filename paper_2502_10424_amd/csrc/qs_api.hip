@@ -10,7 +10,10 @@ namespace {
 
 constexpr int kVersion = 100;   // 0.1.0
 constexpr int kDefaultCUs = 256;
-constexpr int kWavesPerCU = 8;  // resident chunk waves per compute unit the split planner aims for
+// resident chunk waves per compute unit the split planner aims for: the single-row-tile kernels run two
+// waves per SIMD, the multi-row-tile kernels (more than 8 query rows per kv-head) one
+constexpr int kWavesPerCU = 8;
+constexpr int kWavesPerCUMultiTile = 4;
 
 std::atomic<int> g_cu_count{0};
 
@@ -62,10 +65,12 @@ struct Plan {
   int n_split_q, n_split_b;
 };
 
-Plan make_plan(const qs_cache* c, int max_quant, int max_buf) {
+Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf) {
   const int units = c->batch * c->n_kv_heads;
   const int groups = max_quant / kG;
-  const int want = (cu_count() * kWavesPerCU + units - 1) / units;
+  const int n_rows = nq * (c->n_q_heads / c->n_kv_heads);
+  const int wpc = n_rows <= 8 ? kWavesPerCU : kWavesPerCUMultiTile;
+  const int want = (cu_count() * wpc + units - 1) / units;
   Plan p;
   p.n_split_q = std::max(1, std::min(want, groups));
   p.n_split_b = std::max(1, (max_buf + kBufSplitTok - 1) / kBufSplitTok);
@@ -87,7 +92,7 @@ int attn_common(const qs_cache* c, const void* q, int32_t nq, void* out, float s
   }
   if (workspace == nullptr || workspace_bytes < qs_workspace_bytes(c, nq)) return QS_ERR_WORKSPACE;
 
-  const Plan p = make_plan(c, max_quant, max_buf);
+  const Plan p = make_plan(c, nq, max_quant, max_buf);
   const int n_split = p.n_split_q + p.n_split_b;
   const int64_t rows_total = (int64_t)c->batch * nq * c->n_q_heads;
 
@@ -178,7 +183,7 @@ const char* qs_strerror(int code) {
 
 size_t qs_workspace_bytes(const qs_cache* c, int32_t nq) {
   if (validate_shape(c) != QS_OK || nq < 1 || nq > QS_MAX_NQ) return 0;
-  const Plan p = make_plan(c, c->q_cap, c->buf_cap);
+  const Plan p = make_plan(c, nq, c->q_cap, c->buf_cap);
   const size_t rows_total = (size_t)c->batch * nq * c->n_q_heads;
   return rows_total * (size_t)(p.n_split_q + p.n_split_b) * (kD + 2) * sizeof(float);
 }
@@ -234,17 +239,21 @@ int qs_attn_verify(const qs_cache* c, const void* q, int32_t nq, void* out, floa
 }
 
 int qs_export_codes(const qs_cache* c, int32_t b, int32_t kv_head, int32_t n_tokens, void* k_u, void* k_l,
-                    void* v_u, void* v_l, void* v_s, void* v_z, void* stream) {
+                    void* k_s, void* k_z, void* v_u, void* v_l, void* v_s, void* v_z, void* stream) {
   int rc = validate_cache(c);
   if (rc != QS_OK) return rc;
   if (b < 0 || b >= c->batch || kv_head < 0 || kv_head >= c->n_kv_heads) return QS_ERR_RANGE;
-  if (n_tokens < 0 || n_tokens % kVTileTok != 0 || n_tokens > c->q_cap) return QS_ERR_RANGE;
+  if (n_tokens < 0 || n_tokens % kG != 0 || n_tokens > c->q_cap) return QS_ERR_RANGE;
   const int64_t unit = (int64_t)b * c->n_kv_heads + kv_head;
   ExportArgs e;
   e.k_upper = static_cast<const uint32_t*>(c->k_upper) + unit * c->q_cap * kRowDw;
   e.k_lower = static_cast<const uint32_t*>(c->k_lower) + unit * c->q_cap * kRowDw;
   e.v_upper = static_cast<const uint32_t*>(c->v_upper) + unit * c->q_cap * kRowDw;
   e.v_lower = static_cast<const uint32_t*>(c->v_lower) + unit * c->q_cap * kRowDw;
+  e.k_scale = static_cast<const _Float16*>(c->k_scale) + unit * c->q_cap;
+  e.k_zero = static_cast<const _Float16*>(c->k_zero) + unit * c->q_cap;
+  e.k_s = static_cast<_Float16*>(k_s);
+  e.k_z = static_cast<_Float16*>(k_z);
   e.v_scale = static_cast<const _Float16*>(c->v_scale) + unit * c->q_cap;
   e.v_zero = static_cast<const _Float16*>(c->v_zero) + unit * c->q_cap;
   e.k_u = static_cast<uint8_t*>(k_u);

@@ -8,6 +8,9 @@
 // Design
 //  * One wave (a 64-thread workgroup) owns one chunk of one (sequence, kv-head) unit and all query
 //    rows that share that kv-head (grouped-query heads x query tokens), so the planes are read once.
+//    Every byte of the planes is loaded exactly once, by exactly one lane, with 128-bit loads that a
+//    wave issues as contiguous 1 KB requests, directly into the registers that feed the matrix cores;
+//    LDS is only used to transpose the fp16 value tiles of the buffer chunk.
 //  * The contraction runs on the matrix cores (v_mfma_f32_16x16x32_f16): codes are the A operand,
 //    queries / probabilities the B operand.  Scales never touch individual codes:
 //        q . K_hat[t] = sum_d (q_d S_d) c[t,d] + q . Z          (per 128-token group)
@@ -21,14 +24,9 @@
 //  * The MFMA output layout of Q K^T (lane = query column, 4 consecutive tokens) is, after packing to
 //    fp16, directly the B operand layout of P V; the value planes are stored by the flush kernel in
 //    exactly the token order this produces, so probabilities never cross lanes.
-#include "qs_internal.h"
+#include <type_traits>
 
-#ifndef QS_PREFETCH
-#define QS_PREFETCH 0
-#endif
-#ifndef QS_WAVES
-#define QS_WAVES 2
-#endif
+#include "qs_internal.h"
 
 namespace qs {
 namespace {
@@ -82,7 +80,8 @@ __device__ __forceinline__ half8 to_operand_order(half8 c) {
 }
 
 __device__ __forceinline__ float xor8_in_row(float x) {   // value of lane (l ^ 8); stays inside a 16-lane row
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x128, 0xF, 0xF, false));
+  const int v = __builtin_bit_cast(int, x);
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, 0x128, 0xF, 0xF, true));
 }
 
 __device__ __forceinline__ float group_max(float x) {     // over the four 16-lane groups of the wave
@@ -94,45 +93,50 @@ __device__ __forceinline__ float group_sum(float x) {
   return x + __shfl_xor(x, 32);
 }
 
+
 template <int NRT>
 struct RowState {
-  float m[NRT];        // running max of the scaled scores (log2 units)
+  float m[NRT];        // running max of the scaled scores (log2 units), identical in the 4 lanes of a column
   float l[NRT];        // running sum of p over this lane's tokens
   float z[NRT];        // running sum of p * zero-point over this lane's tokens
   float4v o[NRT][8];   // O^T accumulators: tile n, element jj -> channel 8*(4*g + jj) + n
 };
 
 // Online-softmax update for one 32-token block.  raw[rt][j] are this lane's eight scores (query
-// column rho, tokens tile_token(g, j)) before scaling; returns the probabilities in p.
+// column rho, tokens tile_token(g, j)) before scaling; on return they hold the probabilities.
+// The running max only moves when some score of the wave exceeds it; otherwise the cross-lane
+// reduction and the rescaling of the accumulators are skipped altogether.
 template <int NRT>
 __device__ __forceinline__ void softmax_block(RowState<NRT>& st, float (&raw)[NRT][8], float mul) {
-  bool changed = false;
-  float alpha[NRT];
+  float mx[NRT];
+  bool grow = false;
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
-    float mx = raw[rt][0];
+    mx[rt] = fmaxf(fmaxf(fmaxf(raw[rt][0], raw[rt][1]), fmaxf(raw[rt][2], raw[rt][3])),
+                   fmaxf(fmaxf(raw[rt][4], raw[rt][5]), fmaxf(raw[rt][6], raw[rt][7]))) * mul;   // mul > 0
+    grow |= mx[rt] > st.m[rt];
+  }
+  if (__any(grow)) {
 #pragma unroll
-    for (int j = 1; j < 8; ++j) mx = fmaxf(mx, raw[rt][j]);
-    mx = group_max(mx) * mul;                       // mul > 0
-    const float m_new = fmaxf(st.m[rt], mx);
-    alpha[rt] = __builtin_amdgcn_exp2f(st.m[rt] - m_new);
-    changed |= (m_new != st.m[rt]);
-    st.m[rt] = m_new;
+    for (int rt = 0; rt < NRT; ++rt) {
+      const float m_new = fmaxf(st.m[rt], group_max(mx[rt]));
+      const float alpha = __builtin_amdgcn_exp2f(st.m[rt] - m_new);
+      st.m[rt] = m_new;
+      st.l[rt] *= alpha;
+      st.z[rt] *= alpha;
+#pragma unroll
+      for (int n = 0; n < 8; ++n) st.o[rt][n] *= alpha;
+    }
+  }
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
     float sum = 0.f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      raw[rt][j] = __builtin_amdgcn_exp2f(__builtin_fmaf(raw[rt][j], mul, -m_new));
+      raw[rt][j] = __builtin_amdgcn_exp2f(__builtin_fmaf(raw[rt][j], mul, -st.m[rt]));
       sum += raw[rt][j];
     }
-    st.l[rt] = __builtin_fmaf(st.l[rt], alpha[rt], sum);
-  }
-  if (__any(changed)) {
-#pragma unroll
-    for (int rt = 0; rt < NRT; ++rt) {
-      st.z[rt] *= alpha[rt];
-#pragma unroll
-      for (int n = 0; n < 8; ++n) st.o[rt][n] *= alpha[rt];
-    }
+    st.l[rt] += sum;
   }
 }
 
@@ -163,24 +167,81 @@ __device__ __forceinline__ void write_partial(const AttnArgs& a, RowState<NRT>& 
 }
 
 // ------------------------------------------------------------------------------------------------
-// A chunk of the quantized region: token groups [grp0, grp1) of one unit.
+// A chunk of the quantized region: a contiguous range of 128-token groups of one unit.
+//
+// The wave walks its chunk in 32-token blocks.  Each block is eight (draft: four) 1 KB plane loads
+// and four 16-byte metadata loads per lane, straight into registers; the loads of block i+1 are in
+// flight while block i is computed (register double buffering).  The loop is unrolled over the four
+// blocks of a group so that the query operand of the NEXT group (q*S, needs that group's key
+// metadata) is built one MFMA k-step per block and no bubble appears at group boundaries.
 // ------------------------------------------------------------------------------------------------
 template <int NRT, bool VERIFY>
 __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, int kvh, int row0, int split) {
   const int lane = threadIdx.x, rho = lane & 15, g = lane >> 4;
   const bool lo_part = rho >= 8;
   const int n_groups = a.len.n_quant[b] / kG;
-  const int grp0 = (int)((int64_t)split * n_groups / a.n_split_q);
-  const int grp1 = (int)((int64_t)(split + 1) * n_groups / a.n_split_q);
+  const int first = (int)((int64_t)split * n_groups / a.n_split_q);
+  const int n_local = (int)((int64_t)(split + 1) * n_groups / a.n_split_q) - first;
 
   // Powers of two folded out of the operands (see file header).
   //   draft : code operand carries 2^-24 (elements 0,1,4,5) or 2^-20 (elements 2,3,6,7)
   //   verify: code operand carries 2^-24 and the codes are 16*C_U + C_L + 8 in units of S/16
-  constexpr float kKeyPos = VERIFY ? 1.0f : 0.0625f;         // factor on q at elements 2,3,6,7
+  constexpr float kKeyPos = VERIFY ? 1.0f : 0.0625f;             // factor on q at elements 2,3,6,7
   constexpr float kKeyRaw = VERIFY ? 1048576.0f : 16777216.0f;   // score = raw * kKeyRaw * c0
-  constexpr float kPA = 4.0f;                                // factor on p*S at elements 0,1,4,5
-  constexpr float kPB = VERIFY ? 4.0f : 0.25f;               // factor on p*S at elements 2,3,6,7
-  constexpr float kOutRaw = VERIFY ? 262144.0f : 4194304.0f; // out = rawO * kOutRaw + sum p*Zeff
+  constexpr float kPA = 4.0f;                                    // factor on p*S at elements 0,1,4,5
+  constexpr float kPB = VERIFY ? 4.0f : 0.25f;                   // factor on p*S at elements 2,3,6,7
+  constexpr float kOutRaw = VERIFY ? 262144.0f : 4194304.0f;     // out = rawO * kOutRaw + sum p*Zeff
+
+  RowState<NRT> st;
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    st.m[rt] = kNegBig; st.l[rt] = 0.f; st.z[rt] = 0.f;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) st.o[rt][n] = (float4v){0.f, 0.f, 0.f, 0.f};
+  }
+  if (n_local <= 0) {
+    write_partial<NRT>(a, st, b, kvh, row0, split, kOutRaw);
+    return;
+  }
+  const float mul = a.c0 * kKeyRaw;
+
+  const uint32_t* ku = a.k_upper + ((int64_t)unit * a.q_cap + (int64_t)first * kG + rho) * kRowDw + 4 * g;
+  const uint32_t* kl = a.k_lower + ((int64_t)unit * a.q_cap + (int64_t)first * kG + rho) * kRowDw + 4 * g;
+  const uint32_t* vu = a.v_upper + ((int64_t)unit * a.q_cap + (int64_t)first * kG) * kRowDw + 4 * lane;
+  const uint32_t* vl = a.v_lower + ((int64_t)unit * a.q_cap + (int64_t)first * kG) * kRowDw + 4 * lane;
+  const int64_t meta0 = (int64_t)unit * a.q_cap + (int64_t)first * kG + 8 * g;   // same offset in all four arrays
+  const _Float16 *vsp = a.v_scale + meta0, *vzp = a.v_zero + meta0, *ksp = a.k_scale + meta0, *kzp = a.k_zero + meta0;
+
+  // One 32-token block of operands.
+  struct Blk {
+    u32x4 kU[2], kL[2], vU[2], vL[2];   // two 16-token key tiles, two halves of the value tile
+    u32x4 vS, vZ;                       // value S / Z of this lane group's eight tokens
+    u32x4 kS, kZ;                       // key S / Z of k-step (block mod 4) of the NEXT group
+  };
+  // loads of block j (chunk-local); past the end of the chunk the last block is re-read and never used
+  auto load_block = [&](Blk& d, int j) {
+    const int jc = min(j, 4 * n_local - 1);
+    const int64_t tok = (int64_t)jc * 32;
+    const int64_t nxt = (int64_t)min((jc >> 2) + 1, n_local - 1) * kG + 32 * (jc & 3);
+    d.kU[0] = ldg128(ku + tok * kRowDw);
+    d.kU[1] = ldg128(ku + (tok + 16) * kRowDw);
+    if (VERIFY) {
+      d.kL[0] = ldg128(kl + tok * kRowDw);
+      d.kL[1] = ldg128(kl + (tok + 16) * kRowDw);
+    }
+    d.vU[0] = ldg128(vu + tok * kRowDw);
+    d.vU[1] = ldg128(vu + tok * kRowDw + 256);
+    if (VERIFY) {
+      d.vL[0] = ldg128(vl + tok * kRowDw);
+      d.vL[1] = ldg128(vl + tok * kRowDw + 256);
+    }
+    d.vS = ldg128(vsp + tok);
+    d.vZ = ldg128(vzp + tok);
+    d.kS = ldg128(ksp + nxt);
+    d.kZ = ldg128(kzp + nxt);
+  };
+  Blk bufA, bufB;
+  load_block(bufA, 0);   // in flight while the queries and the first group's metadata arrive
 
   // Queries of this lane's column: channels 32*g + 8*s + operand order, pre-scaled per position.
   half2v qv[NRT][16];
@@ -203,84 +264,51 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
     }
   }
 
-  RowState<NRT> st;
+  // Query operand of the current group (qb, cin) and, built one k-step per block, of the next one.
+  // Columns 0-7 hold fp16(q*S), columns 8-15 the exact fp16 remainder q*S - fp16(q*S).
+  half8 qb[NRT][4], qbn[NRT][4];
+  float cin[NRT], acc_a[NRT], acc_b[NRT], acc_sa[NRT], acc_sb[NRT];
+  auto prep_reset = [&]() {
 #pragma unroll
-  for (int rt = 0; rt < NRT; ++rt) {
-    st.m[rt] = kNegBig; st.l[rt] = 0.f; st.z[rt] = 0.f;
-#pragma unroll
-    for (int n = 0; n < 8; ++n) st.o[rt][n] = (float4v){0.f, 0.f, 0.f, 0.f};
-  }
-  const float mul = a.c0 * kKeyRaw;
-
-  const uint32_t* ku = a.k_upper + ((int64_t)unit * a.q_cap + rho) * kRowDw + 4 * g;
-  const uint32_t* kl = a.k_lower + ((int64_t)unit * a.q_cap + rho) * kRowDw + 4 * g;
-  const uint32_t* vu = a.v_upper + (int64_t)unit * (a.q_cap / kVTileTok) * kVTileDw + 4 * lane;
-  const uint32_t* vl = a.v_lower + (int64_t)unit * (a.q_cap / kVTileTok) * kVTileDw + 4 * lane;
-  const _Float16* vs = a.v_scale + (int64_t)unit * a.q_cap + 8 * g;
-  const _Float16* vz = a.v_zero + (int64_t)unit * a.q_cap + 8 * g;
-  const _Float16* ksc = a.k_scale + (int64_t)unit * (a.q_cap / kG) * kD + 32 * g;
-  const _Float16* kzr = a.k_zero + (int64_t)unit * (a.q_cap / kG) * kD + 32 * g;
-
-  // One 32-token block of operands: two 16-token key tiles, one value tile, value metadata.
-  struct Block {
-    u32x4 kU[2], kL[2], vU[2], vL[2];
-    half8 vS, vZ;
+    for (int rt = 0; rt < NRT; ++rt) acc_a[rt] = acc_b[rt] = acc_sa[rt] = acc_sb[rt] = 0.f;
   };
-  auto load_block = [&](Block& d, int64_t t0) {
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      d.kU[t] = ldg128(ku + (t0 + 16 * t) * kRowDw);
-      if (VERIFY) d.kL[t] = ldg128(kl + (t0 + 16 * t) * kRowDw);
-      d.vU[t] = ldg128(vu + (t0 / kVTileTok) * kVTileDw + 256 * t);
-      if (VERIFY) d.vL[t] = ldg128(vl + (t0 / kVTileTok) * kVTileDw + 256 * t);
-    }
-    d.vS = as_half8(ldg128(vs + t0));
-    d.vZ = as_half8(ldg128(vz + t0));
-  };
-  half8 sg[4], zg[4];   // key scale / zero of the lane's 32 channels, operand order
-  auto load_key_meta = [&](int grp) {
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      sg[s] = to_operand_order(as_half8(ldg128(ksc + (int64_t)grp * kD + 8 * s)));
-      zg[s] = to_operand_order(as_half8(ldg128(kzr + (int64_t)grp * kD + 8 * s)));
-    }
-  };
-
-  half8 qb[NRT][4];
-  float cin[NRT];
-  // per-group query operand: columns 0-7 hold fp16(q*S), columns 8-15 the exact remainder
-  auto prepare_group = [&]() {
+  auto prep_kstep = [&](auto S, u32x4 sw, u32x4 zw) {   // sw, zw: key S / Z of channels 32g + 8s.., operand order
+    constexpr int s = decltype(S)::value;
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt) {
-      float ba = 0.f, bb = 0.f, sa = 0.f, sb = 0.f;
+      u32x4 out;
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        u32x4 sw = as_u32x4(sg[s]), zw = as_u32x4(zg[s]), out;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const half2v qh = qv[rt][4 * s + r], sh = as_half2(sw[r]), zh = as_half2(zw[r]);
-          const half2v hi = qh * sh;
-          const half2v lo = __builtin_elementwise_fma(qh, sh, -hi);
-          out[r] = lo_part ? as_u32(lo) : as_u32(hi);
-          if (r & 1) {
-            bb = __builtin_amdgcn_fdot2(qh, zh, bb, false);
-            if (VERIFY) sb = __builtin_amdgcn_fdot2(qh, sh, sb, false);
-          } else {
-            ba = __builtin_amdgcn_fdot2(qh, zh, ba, false);
-            if (VERIFY) sa = __builtin_amdgcn_fdot2(qh, sh, sa, false);
-          }
+      for (int r = 0; r < 4; ++r) {
+        const half2v qh = qv[rt][4 * s + r], sh = as_half2(sw[r]), zh = as_half2(zw[r]);
+        const half2v hi = qh * sh;
+        const half2v lo = __builtin_elementwise_fma(qh, sh, -hi);
+        out[r] = lo_part ? as_u32(lo) : as_u32(hi);
+        if (r & 1) {
+          acc_b[rt] = __builtin_amdgcn_fdot2(qh, zh, acc_b[rt], false);
+          if (VERIFY) acc_sb[rt] = __builtin_amdgcn_fdot2(qh, sh, acc_sb[rt], false);
+        } else {
+          acc_a[rt] = __builtin_amdgcn_fdot2(qh, zh, acc_a[rt], false);
+          if (VERIFY) acc_sa[rt] = __builtin_amdgcn_fdot2(qh, sh, acc_sa[rt], false);
         }
-        qb[rt][s] = as_half8(out);
       }
-      // sum_d q_d * Zeff_d with Zeff = Z (draft) or Z - S/2 (verify: codes are offset by +8 lower steps)
-      float bias = __builtin_fmaf(bb, 1.0f / kKeyPos, ba);
-      if (VERIFY) bias -= 0.5f * __builtin_fmaf(sb, 1.0f / kKeyPos, sa);
-      bias = group_sum(bias);
-      cin[rt] = lo_part ? 0.f : bias * (1.0f / kKeyRaw);
+      qbn[rt][s] = as_half8(out);
     }
   };
+  auto prep_commit = [&]() {   // sum_d q_d * Zeff_d, Zeff = Z (draft) or Z - S/2 (verify: codes carry +8 lower steps)
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      float bias = __builtin_fmaf(acc_b[rt], 1.0f / kKeyPos, acc_a[rt]);
+      if (VERIFY) bias -= 0.5f * __builtin_fmaf(acc_sb[rt], 1.0f / kKeyPos, acc_sa[rt]);
+      bias = group_sum(bias);
+      cin[rt] = lo_part ? 0.f : bias * (1.0f / kKeyRaw);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) qb[rt][s] = qbn[rt][s];
+    }
+    prep_reset();
+  };
 
-  auto compute_block = [&](const Block& d) {
+  auto compute_block = [&](const Blk& d, auto P) {
+    constexpr int p = decltype(P)::value;
     // ---- scores: S^T[token, column] = codes x q ----
     float raw[NRT][8];
     {
@@ -300,21 +328,28 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
           for (int jj = 0; jj < 4; ++jj) raw[rt][4 * t + jj] = acc[jj] + xor8_in_row(acc[jj]);
         }
     }
+    prep_kstep(P, d.kS, d.kZ);   // one k-step of the next group's query operand
     softmax_block<NRT>(st, raw, mul);
 
     // ---- probabilities x value scale -> B operand; zero-point term ----
+    const half8 vS = as_half8(d.vS), vZ = as_half8(d.vZ);
     half8 pb[NRT];
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt) {
       float zs = 0.f;
+      half8 ps;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const float s = (float)d.vS[j];
-        const float zeff = VERIFY ? __builtin_fmaf(-0.5f, s, (float)d.vZ[j]) : (float)d.vZ[j];
-        zs = __builtin_fmaf(raw[rt][j], zeff, zs);
-        pb[rt][j] = (_Float16)(raw[rt][j] * s * (((j >> 1) & 1) ? kPB : kPA));
+      for (int jj = 0; jj < 8; ++jj) {
+        const float sv = (float)vS[jj];
+        const float zeff = VERIFY ? __builtin_fmaf(-0.5f, sv, (float)vZ[jj]) : (float)vZ[jj];
+        zs = __builtin_fmaf(raw[rt][jj], zeff, zs);
+        ps[jj] = (_Float16)(raw[rt][jj] * sv);
       }
       st.z[rt] += zs;
+      u32x4 pw = as_u32x4(ps);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) pw[r] = as_u32(as_half2(pw[r]) * (_Float16)((r & 1) ? kPB : kPA));
+      pb[rt] = as_half8(pw);
     }
 
     // ---- O^T[channel, column] += codes^T x p ----
@@ -325,40 +360,27 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
       for (int rt = 0; rt < NRT; ++rt)
         st.o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pb[rt], st.o[rt][n], 0, 0, 0);
     }
+    if (p == 3) prep_commit();
   };
 
-  // Software pipeline: while block i is being computed the loads of block i+1 are in flight, and the
-  // key metadata of the next group is fetched a whole group ahead.
-  if (grp0 < grp1) {
-    Block bufA, bufB;
-    load_key_meta(grp0);
-    load_block(bufA, (int64_t)grp0 * kG);
-    for (int grp = grp0; grp < grp1; ++grp) {
-      const int64_t t0 = (int64_t)grp * kG;
-      const bool more = grp + 1 < grp1;
-#if QS_PREFETCH
-      prepare_group();
-      if (more) load_key_meta(grp + 1);
-      load_block(bufB, t0 + 32);
-      compute_block(bufA);
-      load_block(bufA, t0 + 64);
-      compute_block(bufB);
-      load_block(bufB, t0 + 96);
-      compute_block(bufA);
-      if (more) load_block(bufA, t0 + 128);
-      compute_block(bufB);
-#else
-      if (grp != grp0) { load_key_meta(grp); load_block(bufA, t0); }
-      prepare_group();
-      compute_block(bufA);
-      load_block(bufA, t0 + 32);
-      compute_block(bufA);
-      load_block(bufA, t0 + 64);
-      compute_block(bufA);
-      load_block(bufA, t0 + 96);
-      compute_block(bufA);
-#endif
-    }
+  // the first group's query operand straight from global memory
+  prep_reset();
+  prep_kstep(std::integral_constant<int, 0>{}, ldg128(ksp), ldg128(kzp));
+  prep_kstep(std::integral_constant<int, 1>{}, ldg128(ksp + 32), ldg128(kzp + 32));
+  prep_kstep(std::integral_constant<int, 2>{}, ldg128(ksp + 64), ldg128(kzp + 64));
+  prep_kstep(std::integral_constant<int, 3>{}, ldg128(ksp + 96), ldg128(kzp + 96));
+  prep_commit();
+
+  for (int lg = 0; lg < n_local; ++lg) {
+    const int j = 4 * lg;
+    load_block(bufB, j + 1);
+    compute_block(bufA, std::integral_constant<int, 0>{});
+    load_block(bufA, j + 2);
+    compute_block(bufB, std::integral_constant<int, 1>{});
+    load_block(bufB, j + 3);
+    compute_block(bufA, std::integral_constant<int, 2>{});
+    load_block(bufA, j + 4);
+    compute_block(bufB, std::integral_constant<int, 3>{});
   }
   write_partial<NRT>(a, st, b, kvh, row0, split, kOutRaw);
 }
@@ -468,8 +490,8 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
 }
 
 template <int NRT, bool VERIFY>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(QS_WAVES))) void attn_kernel(AttnArgs a) {
-  __shared__ _Float16 vt[kD][kVtStride];
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NRT == 1 ? 2 : 1))) void attn_kernel(AttnArgs a) {
+  __shared__ _Float16 vt[kD][kVtStride];   // value-tile transpose of the buffer chunk
   const int split = blockIdx.x, unit = blockIdx.y, row0 = blockIdx.z * 8 * NRT;
   const int b = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   if (split < a.n_split_q)

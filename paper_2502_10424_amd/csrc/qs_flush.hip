@@ -112,8 +112,16 @@ __global__ __launch_bounds__(256) void flush_kernel(FlushArgs a) {
   }
   const int64_t grp_dst = (int64_t)unit * (a.q_cap / kG) + tq0 / kG;
   if (oct == 0) {
-    *reinterpret_cast<half8*>(a.k_scale + grp_dst * kD + 8 * c8) = ksh;
-    *reinterpret_cast<half8*>(a.k_zero + grp_dst * kD + 8 * c8) = kzh;
+    // stored in the order the attention kernel's B operand wants them: [k-step][lane group][element]
+    half8 so, zo;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      so[e] = ksh[tile_nibble(e)];
+      zo[e] = kzh[tile_nibble(e)];
+    }
+    const int pos = (c8 & 3) * 32 + (c8 >> 2) * 8;
+    *reinterpret_cast<half8*>(a.k_scale + grp_dst * kD + pos) = so;
+    *reinterpret_cast<half8*>(a.k_zero + grp_dst * kD + pos) = zo;
   }
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
@@ -214,6 +222,12 @@ __global__ __launch_bounds__(256) void export_kernel(ExportArgs a) {
       if (a.v_u) a.v_u[tok * kD + ch] = (uint8_t)((wu >> nib) & 15u);
       if (a.v_l) a.v_l[tok * kD + ch] = (int8_t)((int)((wl >> nib) & 15u) - 8);
     }
+  }
+  if (idx < a.n_tokens) {  // key metadata: position 32*s + 8*g + e of a group -> channel 32*g + 8*s + nibble(e)
+    const int grp = idx >> 7, pos = idx & 127;
+    const int ch = 32 * ((pos >> 3) & 3) + 8 * (pos >> 5) + tile_nibble(pos & 7);
+    if (a.k_s) a.k_s[grp * kD + ch] = a.k_scale[idx];
+    if (a.k_z) a.k_z[grp * kD + ch] = a.k_zero[idx];
   }
   if (idx < a.n_tokens) {  // value metadata: position 8*g + j of a tile -> token order
     const int tile = idx >> 5, p = idx & 31;

@@ -38,10 +38,10 @@ struct ShiftArgs {
 
 struct ExportArgs {
   const uint32_t *k_upper, *k_lower, *v_upper, *v_lower;
-  const _Float16 *v_scale, *v_zero;
+  const _Float16 *k_scale, *k_zero, *v_scale, *v_zero;
   uint8_t *k_u, *v_u;
   int8_t *k_l, *v_l;
-  _Float16 *v_s, *v_z;
+  _Float16 *k_s, *k_z, *v_s, *v_z;
   int32_t n_tokens;
 };
 

@@ -50,12 +50,9 @@ def _seq_view(cache, b):
 
 def export_unit(cache, b, h, n_tokens):
     """Plain-order numpy view of one unit's planes and metadata."""
-    k_u, k_l, v_u, v_l, v_s, v_z = B.qs_export_codes(cache, b, h, n_tokens)
+    e = B.qs_export_codes(cache, b, h, n_tokens)
     torch.cuda.synchronize()
-    g = n_tokens // 128
-    return dict(ku=k_u.cpu().numpy(), kl=k_l.cpu().numpy(), vu=v_u.cpu().numpy(), vl=v_l.cpu().numpy(),
-                vs=v_s.cpu().numpy(), vz=v_z.cpu().numpy(),
-                ks=cache.k_scale[b, h, :g].cpu().numpy(), kz=cache.k_zero[b, h, :g].cpu().numpy())
+    return {k.replace("_", ""): v.cpu().numpy() for k, v in e.items()}
 
 
 def assert_unit_equals_oracle(cache, oc: O.CacheOracle, b, h):

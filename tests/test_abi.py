@@ -102,8 +102,8 @@ def test_validation_errors_without_gpu(B):
     pf = lambda c, n, stride: lib.qs_quantize_prefill(ctypes.byref(c), 0x500000, 0x600000, stride, n, None)
     assert pf(_fake_cache(B), 128, 64) == B.QS_ERR_RANGE
     assert pf(_fake_cache(B), 1024, 1024) == B.QS_ERR_RANGE
-    assert lib.qs_export_codes(ctypes.byref(_fake_cache(B)), 2, 0, 128, None, None, None, None, None, None, None) == B.QS_ERR_RANGE
-    assert lib.qs_export_codes(ctypes.byref(_fake_cache(B)), 0, 0, 100, None, None, None, None, None, None, None) == B.QS_ERR_RANGE
+    assert lib.qs_export_codes(ctypes.byref(_fake_cache(B)), 2, 0, 128, None, None, None, None, None, None, None, None, None) == B.QS_ERR_RANGE
+    assert lib.qs_export_codes(ctypes.byref(_fake_cache(B)), 0, 0, 100, None, None, None, None, None, None, None, None, None) == B.QS_ERR_RANGE
 
 
 def test_missing_library_fails_loudly(B, monkeypatch):
