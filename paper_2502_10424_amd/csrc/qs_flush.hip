@@ -6,10 +6,8 @@
 // C_L = clamp(rne(E_U / (S/16)), -8, 7).  Keys are grouped per channel over 128 tokens, values per
 // token over the 128 channels (Section 4.3.1).
 //
-// One workgroup of 256 threads handles one 128-token group of one (sequence, kv-head) unit, keys
-// and values together.  Thread (c8 = tid & 15, oct = tid >> 4) owns channels [8*c8, 8*c8+8) of the
-// eight tokens that share one 32-bit word of the value-plane tile, so every value word and every
-// key word is assembled in registers and each plane is written exactly once.
+// Every thread owns a few channels of the eight tokens that share one 32-bit word of the value-plane
+// tile, so value words are assembled in registers and each plane is written exactly once.
 #include "qs_internal.h"
 
 namespace qs {
@@ -51,149 +49,159 @@ __device__ __forceinline__ _Float16 make_scale(float mn, float mx) {
   return h;
 }
 
+// Four workgroups share one 128-token group of one unit so that a single flushed group already
+// spreads over several compute units.  Workgroup q of the four handles
+//   threads   0..127 : keys, channels [32q, 32q+32) of all 128 tokens
+//   threads 128..255 : values, tokens [32q, 32q+32) (one value tile) of all 128 channels
+// Each thread owns 4 channels of the eight tokens that share a value-plane word (32 codes).
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+
 __global__ __launch_bounds__(256) void flush_kernel(FlushArgs a) {
-  __shared__ float red[4][128][2];
-  const int grp = blockIdx.x, unit = blockIdx.y;
+  __shared__ float red[2][32][2];
+  const int grp = blockIdx.x >> 2, q = blockIdx.x & 3, unit = blockIdx.y;
   const int b = unit / a.n_kv_heads;
-  const int tid = threadIdx.x, c8 = tid & 15, oct = tid >> 4, blk = oct >> 2, g = oct & 3;
-  const int wave = tid >> 6;
+  const int tid = threadIdx.x;
   const int tq0 = a.n_quant[b] + grp * kG;     // destination token offset inside the unit
-  const _Float16* ksrc = a.k_src + ((int64_t)unit * a.src_stride + (int64_t)grp * kG) * kD + 8 * c8;
-  const _Float16* vsrc = a.v_src + ((int64_t)unit * a.src_stride + (int64_t)grp * kG) * kD + 8 * c8;
+  const int64_t src0 = ((int64_t)unit * a.src_stride + (int64_t)grp * kG) * kD;
 
-  half8 kx[8], vx[8];
+  if (tid < 128) {
+    // ---- keys: min / max per channel over the 128 tokens of the group --------------------------
+    const int c4 = tid & 7, oct = tid >> 3, blk = oct >> 2, g = oct & 3;
+    const int ch0 = 32 * q + 4 * c4;
+    half4 x[8];
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int tok = 32 * blk + tile_token(g, j);
-    kx[j] = ld_half8(ksrc + (int64_t)tok * kD);
-    vx[j] = ld_half8(vsrc + (int64_t)tok * kD);
-  }
-
-  // ---- keys: min / max per channel over the 128 tokens of the group -------------------------
-  float kmn[8], kmx[8];
+    for (int j = 0; j < 8; ++j)
+      x[j] = *reinterpret_cast<const half4*>(a.k_src + src0 + (int64_t)(32 * blk + tile_token(g, j)) * kD + ch0);
+    float mn[4], mx[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    float mn = (float)kx[0][i], mx = mn;
+    for (int i = 0; i < 4; ++i) {
+      float lo = (float)x[0][i], hi = lo;
 #pragma unroll
-    for (int j = 1; j < 8; ++j) {
-      mn = fminf(mn, (float)kx[j][i]);
-      mx = fmaxf(mx, (float)kx[j][i]);
+      for (int j = 1; j < 8; ++j) {
+        lo = fminf(lo, (float)x[j][i]);
+        hi = fmaxf(hi, (float)x[j][i]);
+      }
+#pragma unroll
+      for (int sft = 8; sft < 64; sft <<= 1) {   // the eight octets held by this wave
+        lo = fminf(lo, __shfl_xor(lo, sft));
+        hi = fmaxf(hi, __shfl_xor(hi, sft));
+      }
+      mn[i] = lo;
+      mx[i] = hi;
     }
-    // the four lane groups of a wave hold the other tokens of this 32-token tile
-    mn = fminf(mn, __shfl_xor(mn, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mn = fminf(mn, __shfl_xor(mn, 32));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    kmn[i] = mn;
-    kmx[i] = mx;
-  }
-  if (g == 0) {
+    const int wave = tid >> 6;
+    if ((tid & 63) < 8) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      red[wave][8 * c8 + i][0] = kmn[i];
-      red[wave][8 * c8 + i][1] = kmx[i];
+      for (int i = 0; i < 4; ++i) {
+        red[wave][4 * c4 + i][0] = mn[i];
+        red[wave][4 * c4 + i][1] = mx[i];
+      }
     }
-  }
-  __syncthreads();
-  float ks[8], kz[8];
-  half8 ksh, kzh;
+    __syncthreads();
+    float ks[4], kz[4];
+    _Float16 ksh[4];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    float mn = red[0][8 * c8 + i][0], mx = red[0][8 * c8 + i][1];
-#pragma unroll
-    for (int w = 1; w < 4; ++w) {
-      mn = fminf(mn, red[w][8 * c8 + i][0]);
-      mx = fmaxf(mx, red[w][8 * c8 + i][1]);
+    for (int i = 0; i < 4; ++i) {
+      const float lo = fminf(red[0][4 * c4 + i][0], red[1][4 * c4 + i][0]);
+      const float hi = fmaxf(red[0][4 * c4 + i][1], red[1][4 * c4 + i][1]);
+      ksh[i] = make_scale(lo, hi);
+      ks[i] = (float)ksh[i];
+      kz[i] = lo;
     }
-    ksh[i] = make_scale(mn, mx);
-    kzh[i] = (_Float16)mn;
-    ks[i] = (float)ksh[i];
-    kz[i] = mn;
-  }
-  const int64_t grp_dst = (int64_t)unit * (a.q_cap / kG) + tq0 / kG;
-  if (oct == 0) {
-    // stored in the order the attention kernel's B operand wants them: [k-step][lane group][element]
-    half8 so, zo;
+    if (oct == 0) {
+      // stored in the order the attention kernel's B operand wants them: position 32*s + 8*g' + e
+      // holds channel 32*g' + 8*s + nibble(e); here g' = q, s = c4 >> 1, nibble = 4*(c4 & 1) + i
+      const int64_t dst = ((int64_t)unit * (a.q_cap / kG) + tq0 / kG) * kD + 32 * (c4 >> 1) + 8 * q;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      so[e] = ksh[tile_nibble(e)];
-      zo[e] = kzh[tile_nibble(e)];
+      for (int i = 0; i < 4; ++i) {
+        const int nib = 4 * (c4 & 1) + i;
+        const int e = ((nib & 3) << 1) + (nib >> 2);
+        a.k_scale[dst + e] = ksh[i];
+        a.k_zero[dst + e] = (_Float16)kz[i];
+      }
     }
-    const int pos = (c8 & 3) * 32 + (c8 >> 2) * 8;
-    *reinterpret_cast<half8*>(a.k_scale + grp_dst * kD + pos) = so;
-    *reinterpret_cast<half8*>(a.k_zero + grp_dst * kD + pos) = zo;
-  }
+    uint16_t* ku16 = reinterpret_cast<uint16_t*>(a.k_upper);
+    uint16_t* kl16 = reinterpret_cast<uint16_t*>(a.k_lower);
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    uint32_t wu = 0, wl = 0;
+    for (int j = 0; j < 8; ++j) {
+      uint32_t wu = 0, wl = 0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      Codes c = encode((float)kx[j][i], ks[i], kz[i]);
-      wu |= c.u << (4 * i);
-      wl |= c.l << (4 * i);
+      for (int i = 0; i < 4; ++i) {
+        Codes c = encode((float)x[j][i], ks[i], kz[i]);
+        wu |= c.u << (4 * i);
+        wl |= c.l << (4 * i);
+      }
+      const int tok = 32 * blk + tile_token(g, j);
+      const int64_t w = (((int64_t)unit * a.q_cap + tq0 + tok) * kRowDw) * 2 + (ch0 >> 2);   // 16-bit units
+      ku16[w] = (uint16_t)wu;
+      kl16[w] = (uint16_t)wl;
     }
-    const int tok = 32 * blk + tile_token(g, j);
-    const int64_t w = ((int64_t)unit * a.q_cap + tq0 + tok) * kRowDw + c8;
-    a.k_upper[w] = wu;
-    a.k_lower[w] = wl;
-  }
-
-  // ---- values: min / max per token over its 128 channels --------------------------------------
-  half8 vsh, vzh;
-  uint32_t vu[8], vl[8];
+  } else {
+    __syncthreads();   // matches the barrier of the key half
+    // ---- values: min / max per token over its 128 channels --------------------------------------
+    const int t = tid - 128, c4 = t & 31, g = t >> 5;
+    half4 x[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) vu[i] = vl[i] = 0;
+    for (int j = 0; j < 8; ++j)
+      x[j] = *reinterpret_cast<const half4*>(a.v_src + src0 + (int64_t)(32 * q + tile_token(g, j)) * kD + 4 * c4);
+    half8 vsh, vzh;
+    uint32_t vu[4] = {0, 0, 0, 0}, vl[4] = {0, 0, 0, 0};
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    float mn = (float)vx[j][0], mx = mn;
+    for (int j = 0; j < 8; ++j) {
+      float lo = (float)x[j][0], hi = lo;
 #pragma unroll
-    for (int i = 1; i < 8; ++i) {
-      mn = fminf(mn, (float)vx[j][i]);
-      mx = fmaxf(mx, (float)vx[j][i]);
+      for (int i = 1; i < 4; ++i) {
+        lo = fminf(lo, (float)x[j][i]);
+        hi = fmaxf(hi, (float)x[j][i]);
+      }
+#pragma unroll
+      for (int sft = 1; sft < 32; sft <<= 1) {   // the 32 lanes that hold the token's other channels
+        lo = fminf(lo, __shfl_xor(lo, sft));
+        hi = fmaxf(hi, __shfl_xor(hi, sft));
+      }
+      vsh[j] = make_scale(lo, hi);
+      vzh[j] = (_Float16)lo;
+      const float s = (float)vsh[j];
+      const int nib = 4 * tile_nibble(j);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        Codes c = encode((float)x[j][i], s, lo);
+        vu[i] |= c.u << nib;
+        vl[i] |= c.l << nib;
+      }
     }
-#pragma unroll
-    for (int sft = 1; sft < 16; sft <<= 1) {   // the 16 lanes c8 = 0..15 hold the token's other channels
-      mn = fminf(mn, __shfl_xor(mn, sft));
-      mx = fmaxf(mx, __shfl_xor(mx, sft));
+    if (c4 == 0) {
+      const int64_t m = (int64_t)unit * a.q_cap + tq0 + 32 * q + 8 * g;
+      *reinterpret_cast<half8*>(a.v_scale + m) = vsh;
+      *reinterpret_cast<half8*>(a.v_zero + m) = vzh;
     }
-    vsh[j] = make_scale(mn, mx);
-    vzh[j] = (_Float16)mn;
-    const float s = (float)vsh[j], z = mn;
-    const int nib = 4 * tile_nibble(j);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      Codes c = encode((float)vx[j][i], s, z);
-      vu[i] |= c.u << nib;
-      vl[i] |= c.l << nib;
-    }
-  }
-  const int64_t tile = (int64_t)unit * (a.q_cap / kVTileTok) + tq0 / kVTileTok + blk;
-  if (c8 == 0) {
-    const int64_t m = (int64_t)unit * a.q_cap + tq0 + 32 * blk + 8 * g;
-    *reinterpret_cast<half8*>(a.v_scale + m) = vsh;
-    *reinterpret_cast<half8*>(a.v_zero + m) = vzh;
-  }
-#pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    const int64_t w = tile * kVTileDw + (h * 64 + 16 * g + c8) * 4;
-    *reinterpret_cast<uint4*>(a.v_upper + w) = make_uint4(vu[4 * h], vu[4 * h + 1], vu[4 * h + 2], vu[4 * h + 3]);
-    *reinterpret_cast<uint4*>(a.v_lower + w) = make_uint4(vl[4 * h], vl[4 * h + 1], vl[4 * h + 2], vl[4 * h + 3]);
+    // channels 4*c4 .. 4*c4+3 = 8*m + 4*h + i with m = c4 >> 1, h = c4 & 1: four consecutive words
+    const int64_t tile = (int64_t)unit * (a.q_cap / kVTileTok) + tq0 / kVTileTok + q;
+    const int64_t w = tile * kVTileDw + ((c4 & 1) * 64 + 16 * g + (c4 >> 1)) * 4;
+    *reinterpret_cast<uint4*>(a.v_upper + w) = make_uint4(vu[0], vu[1], vu[2], vu[3]);
+    *reinterpret_cast<uint4*>(a.v_lower + w) = make_uint4(vl[0], vl[1], vl[2], vl[3]);
   }
 }
 
 // Buffer move (Section 4.3.2): rows [n_tokens, n_buf) become rows [0, n_buf - n_tokens).  Source and
 // destination may overlap.  Thread (lane = tid >> 4, c = tid & 15) walks rows lane, lane+16, ...
-// of its own 16-byte column; n_tokens is a multiple of 16, so the row a thread overwrites was read
-// by the same thread in an earlier iteration and no cross-thread ordering is needed.
+// of its own 16-byte column; n_tokens is a multiple of 16, so a row is only ever overwritten by the
+// thread that read it as a source, and no cross-thread ordering is needed.
 __global__ __launch_bounds__(256) void shift_kernel(ShiftArgs a) {
   const int unit = blockIdx.x;
   const int b = unit / a.n_kv_heads;
   _Float16* buf = (blockIdx.y == 0 ? a.k_buf : a.v_buf) + (int64_t)unit * a.buf_cap * kD;
   const int n_keep = a.n_buf[b] - a.n_tokens;
   const int c = threadIdx.x & 15;
-  for (int r = threadIdx.x >> 4; r < n_keep; r += 16) {
-    uint4 x = *reinterpret_cast<const uint4*>(buf + (int64_t)(r + a.n_tokens) * kD + 8 * c);
-    *reinterpret_cast<uint4*>(buf + (int64_t)r * kD + 8 * c) = x;
+  // up to eight rows per thread are read before the first one is written (one memory round trip)
+  for (int r0 = threadIdx.x >> 4; r0 < n_keep; r0 += 128) {
+    uint4 x[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      if (r0 + 16 * k < n_keep) x[k] = *reinterpret_cast<const uint4*>(buf + (int64_t)(r0 + 16 * k + a.n_tokens) * kD + 8 * c);
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      if (r0 + 16 * k < n_keep) *reinterpret_cast<uint4*>(buf + (int64_t)(r0 + 16 * k) * kD + 8 * c) = x[k];
   }
 }
 
@@ -241,7 +249,7 @@ __global__ __launch_bounds__(256) void export_kernel(ExportArgs a) {
 
 hipError_t launch_flush(const FlushArgs& a, int batch, hipStream_t s) {
   if (a.n_groups <= 0) return hipSuccess;
-  dim3 grid(a.n_groups, batch * a.n_kv_heads);
+  dim3 grid(4 * a.n_groups, batch * a.n_kv_heads);
   hipLaunchKernelGGL(flush_kernel, grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }
