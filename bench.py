@@ -27,6 +27,9 @@ GAMMA = 4
 # HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (calibrated against a plain copy kernel).  Filled from the summaries under profiles/; None = not measured.
 MEASURED_TRAFFIC_BYTES = {
+    # profiles/attn_mha128k_hbm_traffic.md: (FETCH_SIZE x 1.99982 + WRITE_SIZE x 1.0) KiB per dispatch
+    ("mha128k", "draft"): int((280306.9 * 1.99982 + 1159.5) * 1024),
+    ("mha128k", "verify"): int((543711.2 * 1.99982 + 5872.1) * 1024),
 }
 
 

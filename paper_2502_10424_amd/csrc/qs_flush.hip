@@ -184,24 +184,26 @@ __global__ __launch_bounds__(256) void flush_kernel(FlushArgs a) {
 }
 
 // Buffer move (Section 4.3.2): rows [n_tokens, n_buf) become rows [0, n_buf - n_tokens).  Source and
-// destination may overlap.  Thread (lane = tid >> 4, c = tid & 15) walks rows lane, lane+16, ...
-// of its own 16-byte column; n_tokens is a multiple of 16, so a row is only ever overwritten by the
-// thread that read it as a source, and no cross-thread ordering is needed.
-__global__ __launch_bounds__(256) void shift_kernel(ShiftArgs a) {
+// destination may overlap.  Thread (rl = tid >> 4, c = tid & 15) of the 1024 moves rows rl, rl+64, ...
+// of its own 16-byte column; n_tokens is a multiple of 64, so a row is only ever overwritten by the
+// thread that read it as a source, and no cross-thread ordering is needed.  Up to four rows per
+// thread are read before the first one is written, so a typical move is one memory round trip.
+__global__ __launch_bounds__(1024) void shift_kernel(ShiftArgs a) {
   const int unit = blockIdx.x;
   const int b = unit / a.n_kv_heads;
   _Float16* buf = (blockIdx.y == 0 ? a.k_buf : a.v_buf) + (int64_t)unit * a.buf_cap * kD;
   const int n_keep = a.n_buf[b] - a.n_tokens;
-  const int c = threadIdx.x & 15;
-  // up to eight rows per thread are read before the first one is written (one memory round trip)
-  for (int r0 = threadIdx.x >> 4; r0 < n_keep; r0 += 128) {
-    uint4 x[8];
+  const int c = threadIdx.x & 15, rl = threadIdx.x >> 4;
+  for (int base = rl; base < n_keep; base += 256) {
+    uint4 x[4];
 #pragma unroll
-    for (int k = 0; k < 8; ++k)
-      if (r0 + 16 * k < n_keep) x[k] = *reinterpret_cast<const uint4*>(buf + (int64_t)(r0 + 16 * k + a.n_tokens) * kD + 8 * c);
+    for (int k = 0; k < 4; ++k) {
+      const int r = min(base + 64 * k, n_keep - 1);
+      x[k] = *reinterpret_cast<const uint4*>(buf + (int64_t)(r + a.n_tokens) * kD + 8 * c);
+    }
 #pragma unroll
-    for (int k = 0; k < 8; ++k)
-      if (r0 + 16 * k < n_keep) *reinterpret_cast<uint4*>(buf + (int64_t)(r0 + 16 * k) * kD + 8 * c) = x[k];
+    for (int k = 0; k < 4; ++k)
+      if (base + 64 * k < n_keep) *reinterpret_cast<uint4*>(buf + (int64_t)(base + 64 * k) * kD + 8 * c) = x[k];
   }
 }
 
@@ -256,7 +258,7 @@ hipError_t launch_flush(const FlushArgs& a, int batch, hipStream_t s) {
 
 hipError_t launch_shift(const ShiftArgs& a, int batch, hipStream_t s) {
   dim3 grid(batch * a.n_kv_heads, 2);
-  hipLaunchKernelGGL(shift_kernel, grid, dim3(256), 0, s, a);
+  hipLaunchKernelGGL(shift_kernel, grid, dim3(1024), 0, s, a);
   return hipGetLastError();
 }
 
