@@ -140,7 +140,7 @@ __device__ __forceinline__ void softmax_block(RowState<NRT>& st, float (&raw)[NR
   }
 }
 
-template <int NRT>
+template <int NRT, int RPT>
 __device__ __forceinline__ void write_partial(const AttnArgs& a, RowState<NRT>& st, int b, int kvh, int row0,
                                               int split, float o_scale) {
   const int lane = threadIdx.x, rho = lane & 15, g = lane >> 4;
@@ -149,8 +149,8 @@ __device__ __forceinline__ void write_partial(const AttnArgs& a, RowState<NRT>& 
   for (int rt = 0; rt < NRT; ++rt) {
     const float l = group_sum(st.l[rt]);
     const float z = group_sum(st.z[rt]);
-    const int row = row0 + rt * 8 + (rho & 7);
-    if (rho < 8 && row < a.n_rows) {
+    const int row = row0 + rt * RPT + (rho & (RPT - 1));
+    if (rho < RPT && row < a.n_rows) {
       const int qi = row / a.rep, head = kvh * a.rep + row % a.rep;
       const int64_t r = (((int64_t)b * a.nq + qi) * a.n_q_heads + head) * n_split + split;
       float* po = a.ws_o + r * kD;
@@ -175,10 +175,11 @@ __device__ __forceinline__ void write_partial(const AttnArgs& a, RowState<NRT>& 
 // blocks of a group so that the query operand of the NEXT group (q*S, needs that group's key
 // metadata) is built one MFMA k-step per block and no bubble appears at group boundaries.
 // ------------------------------------------------------------------------------------------------
-template <int NRT, bool VERIFY>
+template <int NRT, bool VERIFY, bool KSPLIT>
 __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, int kvh, int row0, int split) {
+  constexpr int RPT = KSPLIT ? 16 : 8;   // query rows per 16-column MFMA tile
   const int lane = threadIdx.x, rho = lane & 15, g = lane >> 4;
-  const bool lo_part = rho >= 8;
+  const bool lo_part = !KSPLIT && rho >= 8;
   const int n_groups = a.len.n_quant[b] / kG;
   const int first = (int)((int64_t)split * n_groups / a.n_split_q);
   const int n_local = (int)((int64_t)(split + 1) * n_groups / a.n_split_q) - first;
@@ -200,7 +201,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
     for (int n = 0; n < 8; ++n) st.o[rt][n] = (float4v){0.f, 0.f, 0.f, 0.f};
   }
   if (n_local <= 0) {
-    write_partial<NRT>(a, st, b, kvh, row0, split, kOutRaw);
+    write_partial<NRT, RPT>(a, st, b, kvh, row0, split, kOutRaw);
     return;
   }
   const float mul = a.c0 * kKeyRaw;
@@ -247,7 +248,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   half2v qv[NRT][16];
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
-    const int row = row0 + rt * 8 + (rho & 7);
+    const int row = row0 + rt * RPT + (rho & (RPT - 1));
     const bool valid = row < a.n_rows;
     const int rowc = valid ? row : 0;
     const int qi = rowc / a.rep, head = kvh * a.rep + rowc % a.rep;
@@ -265,8 +266,12 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   }
 
   // Query operand of the current group (qb, cin) and, built one k-step per block, of the next one.
-  // Columns 0-7 hold fp16(q*S), columns 8-15 the exact fp16 remainder q*S - fp16(q*S).
-  half8 qb[NRT][4], qbn[NRT][4];
+  // q*S is split exactly into fp16(q*S) and the fp16 remainder q*S - fp16(q*S).  With up to 8 query
+  // rows per tile the two parts sit in columns 0-7 and 8-15 of one operand and a DPP add recombines the
+  // scores; with up to 16 rows per tile (KSPLIT) every column is a query row and the remainder is a
+  // second operand accumulated into the same MFMA result.
+  constexpr int NQB = KSPLIT ? 2 : 1;
+  half8 qb[NRT][NQB][4], qbn[NRT][NQB][4];
   float cin[NRT], acc_a[NRT], acc_b[NRT], acc_sa[NRT], acc_sb[NRT];
   auto prep_reset = [&]() {
 #pragma unroll
@@ -276,13 +281,18 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
     constexpr int s = decltype(S)::value;
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt) {
-      u32x4 out;
+      u32x4 out, out_lo;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const half2v qh = qv[rt][4 * s + r], sh = as_half2(sw[r]), zh = as_half2(zw[r]);
         const half2v hi = qh * sh;
         const half2v lo = __builtin_elementwise_fma(qh, sh, -hi);
-        out[r] = lo_part ? as_u32(lo) : as_u32(hi);
+        if (KSPLIT) {
+          out[r] = as_u32(hi);
+          out_lo[r] = as_u32(lo);
+        } else {
+          out[r] = lo_part ? as_u32(lo) : as_u32(hi);
+        }
         if (r & 1) {
           acc_b[rt] = __builtin_amdgcn_fdot2(qh, zh, acc_b[rt], false);
           if (VERIFY) acc_sb[rt] = __builtin_amdgcn_fdot2(qh, sh, acc_sb[rt], false);
@@ -291,7 +301,8 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
           if (VERIFY) acc_sa[rt] = __builtin_amdgcn_fdot2(qh, sh, acc_sa[rt], false);
         }
       }
-      qbn[rt][s] = as_half8(out);
+      qbn[rt][0][s] = as_half8(out);
+      if (KSPLIT) qbn[rt][1][s] = as_half8(out_lo);
     }
   };
   auto prep_commit = [&]() {   // sum_d q_d * Zeff_d, Zeff = Z (draft) or Z - S/2 (verify: codes carry +8 lower steps)
@@ -302,7 +313,9 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
       bias = group_sum(bias);
       cin[rt] = lo_part ? 0.f : bias * (1.0f / kKeyRaw);
 #pragma unroll
-      for (int s = 0; s < 4; ++s) qb[rt][s] = qbn[rt][s];
+      for (int h = 0; h < NQB; ++h)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) qb[rt][h][s] = qbn[rt][h][s];
     }
     prep_reset();
   };
@@ -323,9 +336,12 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
         for (int t = 0; t < 2; ++t) {
           float4v acc = {cin[rt], cin[rt], cin[rt], cin[rt]};
 #pragma unroll
-          for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qb[rt][s], acc, 0, 0, 0);
+          for (int s = 0; s < 4; ++s) {
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qb[rt][0][s], acc, 0, 0, 0);
+            if (KSPLIT) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qb[rt][1][s], acc, 0, 0, 0);
+          }
 #pragma unroll
-          for (int jj = 0; jj < 4; ++jj) raw[rt][4 * t + jj] = acc[jj] + xor8_in_row(acc[jj]);
+          for (int jj = 0; jj < 4; ++jj) raw[rt][4 * t + jj] = KSPLIT ? acc[jj] : acc[jj] + xor8_in_row(acc[jj]);
         }
     }
     prep_kstep(P, d.kS, d.kZ);   // one k-step of the next group's query operand
@@ -382,7 +398,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
     load_block(bufA, j + 4);
     compute_block(bufB, std::integral_constant<int, 3>{});
   }
-  write_partial<NRT>(a, st, b, kvh, row0, split, kOutRaw);
+  write_partial<NRT, RPT>(a, st, b, kvh, row0, split, kOutRaw);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -393,11 +409,12 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
 constexpr int kVtStride = 40;   // halfs per LDS row: 32 tokens + padding, keeps 8-byte reads aligned
 constexpr float kBufP = 16384.0f;
 
-template <int NRT>
+template <int NRT, bool KSPLIT>
 __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b, int kvh, int row0, int split,
                                              _Float16 (*vt)[kVtStride]) {
+  constexpr int RPT = KSPLIT ? 16 : 8;
   const int lane = threadIdx.x, rho = lane & 15, g = lane >> 4;
-  const bool lo_part = rho >= 8;
+  const bool lo_part = !KSPLIT && rho >= 8;   // the fp16 queries and keys need no remainder part
   const int nb = a.len.n_buf[b];
   const int tb0 = (split - a.n_split_q) * kBufSplitTok;
 
@@ -405,7 +422,7 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
   int vis[NRT];   // buffer tokens [0, vis) are visible to this lane's query (causal among the nq queries)
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
-    const int row = row0 + rt * 8 + (rho & 7);
+    const int row = row0 + rt * RPT + (rho & (RPT - 1));
     const bool valid = row < a.n_rows;
     const int rowc = valid ? row : 0;
     const int qi = rowc / a.rep, head = kvh * a.rep + rowc % a.rep;
@@ -450,7 +467,7 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
 #pragma unroll
           for (int jj = 0; jj < 4; ++jj) {
             const int tok = t0 + 16 * t + 4 * g + jj;
-            const float sc = acc[jj] + xor8_in_row(acc[jj]);
+            const float sc = KSPLIT ? acc[jj] : acc[jj] + xor8_in_row(acc[jj]);
             raw[rt][4 * t + jj] = tok < vis[rt] ? sc : -__builtin_inff();
           }
         }
@@ -486,18 +503,20 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
         st.o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pb[rt], st.o[rt][n], 0, 0, 0);
     }
   }
-  write_partial<NRT>(a, st, b, kvh, row0, split, 1.0f / kBufP);
+  write_partial<NRT, RPT>(a, st, b, kvh, row0, split, 1.0f / kBufP);
 }
 
-template <int NRT, bool VERIFY>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NRT == 1 ? 2 : 1))) void attn_kernel(AttnArgs a) {
+// NRT 16-column tiles per wave; KSPLIT = 16 query rows per tile instead of 8 (see quant_chunk).  The
+// kernels that carry at most one tile of 8 rows run two waves per SIMD, the others one.
+template <int NRT, bool VERIFY, bool KSPLIT>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NRT == 1 && !KSPLIT ? 2 : 1))) void attn_kernel(AttnArgs a) {
   __shared__ _Float16 vt[kD][kVtStride];   // value-tile transpose of the buffer chunk
-  const int split = blockIdx.x, unit = blockIdx.y, row0 = blockIdx.z * 8 * NRT;
+  const int split = blockIdx.x, unit = blockIdx.y, row0 = blockIdx.z * (KSPLIT ? 16 : 8) * NRT;
   const int b = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   if (split < a.n_split_q)
-    quant_chunk<NRT, VERIFY>(a, unit, b, kvh, row0, split);
+    quant_chunk<NRT, VERIFY, KSPLIT>(a, unit, b, kvh, row0, split);
   else
-    buffer_chunk<NRT>(a, unit, b, kvh, row0, split, vt);
+    buffer_chunk<NRT, KSPLIT>(a, unit, b, kvh, row0, split, vt);
 }
 
 // Merge of the per-chunk partials (Appendix E): M = max m_i, L = sum l_i 2^(m_i - M),
@@ -546,23 +565,25 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
   }
 }
 
-template <int NRT>
+template <int NRT, bool KSPLIT>
 hipError_t launch_attn_nrt(const AttnArgs& a, int batch, bool verify, hipStream_t s) {
-  dim3 grid(a.n_split_q + a.n_split_b, batch * a.n_kv_heads, (a.n_rows + 8 * NRT - 1) / (8 * NRT));
+  constexpr int rows = (KSPLIT ? 16 : 8) * NRT;
+  dim3 grid(a.n_split_q + a.n_split_b, batch * a.n_kv_heads, (a.n_rows + rows - 1) / rows);
   if (verify)
-    hipLaunchKernelGGL((attn_kernel<NRT, true>), grid, dim3(64), 0, s, a);
+    hipLaunchKernelGGL((attn_kernel<NRT, true, KSPLIT>), grid, dim3(64), 0, s, a);
   else
-    hipLaunchKernelGGL((attn_kernel<NRT, false>), grid, dim3(64), 0, s, a);
+    hipLaunchKernelGGL((attn_kernel<NRT, false, KSPLIT>), grid, dim3(64), 0, s, a);
   return hipGetLastError();
 }
 
 }  // namespace
 
+// up to 8 query rows per kv-head: one tile, remainder in columns 8-15; up to 16: one tile, remainder as a
+// second operand; more: two such tiles per wave (and row batches over grid.z beyond 32 rows)
 hipError_t launch_attn(const AttnArgs& a, int batch, bool verify, hipStream_t s) {
-  const int tiles = (a.n_rows + 7) / 8;
-  if (tiles <= 1) return launch_attn_nrt<1>(a, batch, verify, s);
-  if (tiles == 2 || tiles == 4) return launch_attn_nrt<2>(a, batch, verify, s);
-  return launch_attn_nrt<3>(a, batch, verify, s);
+  if (a.n_rows <= 8) return launch_attn_nrt<1, false>(a, batch, verify, s);
+  if (a.n_rows <= 16) return launch_attn_nrt<1, true>(a, batch, verify, s);
+  return launch_attn_nrt<2, true>(a, batch, verify, s);
 }
 
 hipError_t launch_merge(const MergeArgs& a, int rows_total, hipStream_t s) {
