@@ -107,13 +107,13 @@ struct RowState {
 // The running max only moves when some score of the wave exceeds it; otherwise the cross-lane
 // reduction and the rescaling of the accumulators are skipped altogether.
 template <int NRT>
-__device__ __forceinline__ void softmax_block(RowState<NRT>& st, float (&raw)[NRT][8], float mul) {
+__device__ __forceinline__ void softmax_block(RowState<NRT>& st, float (&raw)[NRT][8], const float (&mul)[NRT]) {
   float mx[NRT];
   bool grow = false;
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
     mx[rt] = fmaxf(fmaxf(fmaxf(raw[rt][0], raw[rt][1]), fmaxf(raw[rt][2], raw[rt][3])),
-                   fmaxf(fmaxf(raw[rt][4], raw[rt][5]), fmaxf(raw[rt][6], raw[rt][7]))) * mul;   // mul > 0
+                   fmaxf(fmaxf(raw[rt][4], raw[rt][5]), fmaxf(raw[rt][6], raw[rt][7]))) * mul[rt];   // mul > 0
     grow |= mx[rt] > st.m[rt];
   }
   if (__any(grow)) {
@@ -133,7 +133,7 @@ __device__ __forceinline__ void softmax_block(RowState<NRT>& st, float (&raw)[NR
     float sum = 0.f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      raw[rt][j] = __builtin_amdgcn_exp2f(__builtin_fmaf(raw[rt][j], mul, -st.m[rt]));
+      raw[rt][j] = __builtin_amdgcn_exp2f(__builtin_fmaf(raw[rt][j], mul[rt], -st.m[rt]));
       sum += raw[rt][j];
     }
     st.l[rt] += sum;
@@ -204,7 +204,6 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
     write_partial<NRT, RPT>(a, st, b, kvh, row0, split, kOutRaw);
     return;
   }
-  const float mul = a.c0 * kKeyRaw;
 
   const uint32_t* ku = a.k_upper + ((int64_t)unit * a.q_cap + (int64_t)first * kG + rho) * kRowDw + 4 * g;
   const uint32_t* kl = a.k_lower + ((int64_t)unit * a.q_cap + (int64_t)first * kG + rho) * kRowDw + 4 * g;
@@ -244,8 +243,11 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   Blk bufA, bufB;
   load_block(bufA, 0);   // in flight while the queries and the first group's metadata arrive
 
-  // Queries of this lane's column: channels 32*g + 8*s + operand order, pre-scaled per position.
+  // Queries of this lane's column: channels 32*g + 8*s + operand order.  Each row is scaled by a power
+  // of two so that max|q| <= 1 (then |q*S| <= 8734 cannot overflow fp16 whatever the inputs are); the
+  // power goes into the row's score multiplier.  Elements 2,3,6,7 also take the code operand's 2^-4.
   half2v qv[NRT][16];
+  float mul[NRT];
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
     const int row = row0 + rt * RPT + (rho & (RPT - 1));
@@ -253,16 +255,28 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
     const int rowc = valid ? row : 0;
     const int qi = rowc / a.rep, head = kvh * a.rep + rowc % a.rep;
     const _Float16* qp = a.q + (((int64_t)b * a.nq + qi) * a.n_q_heads + head) * kD + 32 * g;
+    u32x4 w[4];
+    float amax = 0.f;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      u32x4 w = as_u32x4(to_operand_order(as_half8(ldg128(qp + 8 * s))));
+      const half8 h = to_operand_order(as_half8(ldg128(qp + 8 * s)));
+      w[s] = as_u32x4(h);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) amax = fmaxf(amax, __builtin_fabsf((float)h[e]));
+    }
+    amax = group_max(amax);
+    // 2^-e with 2^e >= max|q| (e = 0 for an all-zero row); exact in fp16 and fp32
+    const int e = amax > 0.f ? max(-14, (int)((__builtin_bit_cast(uint32_t, amax) >> 23) & 0xff) - 126) : 0;
+    const float down = __builtin_bit_cast(float, (uint32_t)(127 - e) << 23);
+    mul[rt] = a.c0 * kKeyRaw * __builtin_bit_cast(float, (uint32_t)(127 + e) << 23);
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        half2v h = as_half2(valid ? w[r] : 0u);
-        if (r & 1) h = h * (_Float16)kKeyPos;
+        half2v h = as_half2(valid ? w[s][r] : 0u);
+        h = h * (_Float16)(down * ((r & 1) ? kKeyPos : 1.0f));
         qv[rt][4 * s + r] = h;
       }
-    }
   }
 
   // Query operand of the current group (qb, cin) and, built one k-step per block, of the next one.
@@ -442,6 +456,9 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
 #pragma unroll
     for (int n = 0; n < 8; ++n) st.o[rt][n] = (float4v){0.f, 0.f, 0.f, 0.f};
   }
+  float mulb[NRT];
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) mulb[rt] = a.c0;
   const _Float16* kb = a.k_buf + (int64_t)unit * a.buf_cap * kD;
   const _Float16* vb = a.v_buf + (int64_t)unit * a.buf_cap * kD;
 
@@ -472,7 +489,7 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
           }
         }
     }
-    softmax_block<NRT>(st, raw, a.c0);
+    softmax_block<NRT>(st, raw, mulb);
 
     __syncthreads();   // the previous block's LDS reads are done
     {

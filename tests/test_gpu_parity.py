@@ -226,6 +226,24 @@ def test_attention_degenerate_cases(env):
     _check_attn(env, cache, oc, q, 0.15, True, tag="peaked softmax")
 
 
+def test_attention_large_and_small_magnitudes(env):
+    """Queries and keys far from unit scale: q * S would overflow fp16 without the per-row power-of-two
+    prescale of the queries (|q| ~ 3000, key scales ~ 40), and tiny queries must not lose precision."""
+    O, U = env["O"], env["U"]
+    rng = np.random.default_rng(21)
+    t, nb = 384, 19
+    for qmag, kmag in ((3000.0, 100.0), (1e-3, 0.05), (20000.0, 1.0)):
+        k = (rng.standard_normal((1, 2, t + nb, 128)) * kmag).astype(np.float16)
+        v = (rng.standard_normal((1, 2, t + nb, 128)) * 7).astype(np.float16)
+        q = np.clip(rng.standard_normal((1, 3, 4, 128)) * qmag, -60000, 60000).astype(np.float16)
+        q[0, 1, 2] = 0                                  # an all-zero query row: uniform attention
+        cache = U.make_device_cache(k, v, 4, nb, buf_cap=32)
+        oc = O.build_cache(k, v, 4, 128, nb)
+        sm = 2.0 / (qmag * kmag * np.sqrt(128))
+        _check_attn(env, cache, oc, q, sm, True, tag=f"verify |q|~{qmag:g} |k|~{kmag:g}")
+        _check_attn(env, cache, oc, q[:, :1].copy(), sm, False, tag=f"draft |q|~{qmag:g} |k|~{kmag:g}")
+
+
 def test_attention_lossless_grid_matches_unquantized(env):
     """Property that holds without the oracle's quantizer: 4-bit-grid data through the draft pass equals
     plain fp64 attention over the original tensors."""
