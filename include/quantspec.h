@@ -111,6 +111,16 @@ int qs_quantize_prefill(const qs_cache *c, const void *k_src, const void *v_src,
                         int64_t src_stride_tokens, int32_t n_tokens, void *stream);
 
 /*
+ * Append new tokens to the full-precision buffer (Appendix A: C_K = concat(C_K, c_k), likewise C_V;
+ * Section 4.3.2: "newly generated tokens are stored in full precision in the second buffer"):
+ *   k_new, v_new : device fp16 [B][n_new][n_kv_heads][128]  (token-major, as a projection produces them)
+ * are written to buffer rows [n_buf[b], n_buf[b] + n_new) of every sequence.  n_buf[b] + n_new must not
+ * exceed buf_cap.  The host lengths are not modified (the caller adds n_new).  Rejecting drafted tokens
+ * (Algorithm 1 REJECTCACHE) needs no call at all: the caller lowers n_buf[b].
+ */
+int qs_append(const qs_cache *c, const void *k_new, const void *v_new, int32_t n_new, void *stream);
+
+/*
  * DRAFT attention (Algorithm 1; Section 4.2 "we only load the upper 4-bit representation"):
  *   q   : device fp16 [B][1][n_q_heads][128]
  *   out : device fp16 [B][1][n_q_heads][128]

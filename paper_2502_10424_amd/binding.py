@@ -25,7 +25,7 @@ QS_ERR_NULL, QS_ERR_SHAPE, QS_ERR_UNSUPPORTED, QS_ERR_ALIGN = -1, -2, -3, -4
 QS_ERR_RANGE, QS_ERR_WORKSPACE, QS_ERR_HIP = -5, -6, -7
 
 EXPORTS = ("qs_version", "qs_strerror", "qs_workspace_bytes", "qs_quantize_flush", "qs_quantize_prefill",
-           "qs_attn_draft", "qs_attn_verify", "qs_export_codes")
+           "qs_append", "qs_attn_draft", "qs_attn_verify", "qs_export_codes")
 
 
 class qs_cache(ctypes.Structure):
@@ -66,6 +66,7 @@ def lib() -> ctypes.CDLL:
         l.qs_workspace_bytes.restype, l.qs_workspace_bytes.argtypes = sz, [P, i32]
         l.qs_quantize_flush.restype, l.qs_quantize_flush.argtypes = ctypes.c_int, [P, i32, vp]
         l.qs_quantize_prefill.restype, l.qs_quantize_prefill.argtypes = ctypes.c_int, [P, vp, vp, i64, i32, vp]
+        l.qs_append.restype, l.qs_append.argtypes = ctypes.c_int, [P, vp, vp, i32, vp]
         l.qs_attn_draft.restype = ctypes.c_int
         l.qs_attn_draft.argtypes = [P, vp, vp, f32, vp, sz, vp, vp]
         l.qs_attn_verify.restype = ctypes.c_int
@@ -163,6 +164,15 @@ def qs_quantize_prefill(cache, k_src, v_src, n_tokens: int, stream=None) -> None
     assert k_src.is_contiguous() and v_src.is_contiguous() and k_src.dtype == torch.float16
     _check(lib().qs_quantize_prefill(ctypes.byref(c), k_src.data_ptr(), v_src.data_ptr(), k_src.shape[2],
                                      n_tokens, _stream(stream)), "qs_quantize_prefill")
+
+
+def qs_append(cache, k_new, v_new, stream=None) -> None:
+    """k_new, v_new: fp16 device tensors [B, n_new, Hkv, 128] written to buffer rows n_buf[b].. of every
+    sequence.  Like the C call it leaves the host lengths alone: the caller adds n_new to n_buf."""
+    c = _as_struct(cache)
+    assert k_new.dtype == torch.float16 and k_new.is_contiguous() and v_new.is_contiguous()
+    _check(lib().qs_append(ctypes.byref(c), k_new.data_ptr(), v_new.data_ptr(), k_new.shape[1], _stream(stream)),
+           "qs_append")
 
 
 def _attn(fn_name, cache, q, nq, out, sm_scale, workspace, lse, stream):

@@ -228,6 +228,27 @@ int qs_quantize_prefill(const qs_cache* c, const void* k_src, const void* v_src,
                          src_stride_tokens, n_tokens, static_cast<hipStream_t>(stream));
 }
 
+int qs_append(const qs_cache* c, const void* k_new, const void* v_new, int32_t n_new, void* stream) {
+  int rc = validate_cache(c);
+  if (rc != QS_OK) return rc;
+  if (k_new == nullptr || v_new == nullptr) return QS_ERR_NULL;
+  if (!aligned16(k_new) || !aligned16(v_new)) return QS_ERR_ALIGN;
+  if (n_new < 0) return QS_ERR_RANGE;
+  for (int b = 0; b < c->batch; ++b)
+    if (c->n_buf[b] + n_new > c->buf_cap) return QS_ERR_RANGE;
+  if (n_new == 0) return QS_OK;
+  AppendArgs a;
+  a.k_new = static_cast<const _Float16*>(k_new);
+  a.v_new = static_cast<const _Float16*>(v_new);
+  a.k_buf = static_cast<_Float16*>(c->k_buf);
+  a.v_buf = static_cast<_Float16*>(c->v_buf);
+  a.n_kv_heads = c->n_kv_heads;
+  a.buf_cap = c->buf_cap;
+  a.n_new = n_new;
+  for (int b = 0; b < QS_MAX_BATCH; ++b) a.n_buf[b] = b < c->batch ? c->n_buf[b] : 0;
+  return launch_append(a, c->batch, static_cast<hipStream_t>(stream)) == hipSuccess ? QS_OK : QS_ERR_HIP;
+}
+
 int qs_attn_draft(const qs_cache* c, const void* q, void* out, float sm_scale, void* workspace,
                   size_t workspace_bytes, float* lse, void* stream) {
   return attn_common(c, q, 1, out, sm_scale, workspace, workspace_bytes, lse, stream, false);

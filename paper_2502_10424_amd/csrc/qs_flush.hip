@@ -207,6 +207,19 @@ __global__ __launch_bounds__(1024) void shift_kernel(ShiftArgs a) {
   }
 }
 
+// Append: one 16-byte chunk per thread, [B][n_new][Hkv][128] -> buffer rows n_buf[b] .. of every unit.
+__global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
+  const int b = blockIdx.y;
+  const int idx = blockIdx.x * 256 + threadIdx.x;           // (token, kv-head, 16-byte chunk)
+  const int per_tok = a.n_kv_heads * 16;
+  if (idx >= a.n_new * per_tok) return;
+  const int tok = idx / per_tok, h = (idx % per_tok) >> 4, c = idx & 15;
+  const int64_t src = (((int64_t)b * a.n_new + tok) * a.n_kv_heads + h) * kD + 8 * c;
+  const int64_t dst = (((int64_t)b * a.n_kv_heads + h) * a.buf_cap + a.n_buf[b] + tok) * kD + 8 * c;
+  *reinterpret_cast<uint4*>(a.k_buf + dst) = *reinterpret_cast<const uint4*>(a.k_new + src);
+  *reinterpret_cast<uint4*>(a.v_buf + dst) = *reinterpret_cast<const uint4*>(a.v_new + src);
+}
+
 // Expand packed planes into one code per byte, plain [token][channel] order.
 __global__ __launch_bounds__(256) void export_kernel(ExportArgs a) {
   const int idx = blockIdx.x * 256 + threadIdx.x;      // one 32-bit word of each plane
@@ -259,6 +272,12 @@ hipError_t launch_flush(const FlushArgs& a, int batch, hipStream_t s) {
 hipError_t launch_shift(const ShiftArgs& a, int batch, hipStream_t s) {
   dim3 grid(batch * a.n_kv_heads, 2);
   hipLaunchKernelGGL(shift_kernel, grid, dim3(1024), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_append(const AppendArgs& a, int batch, hipStream_t s) {
+  const int chunks = a.n_new * a.n_kv_heads * 16;
+  hipLaunchKernelGGL(append_kernel, dim3((chunks + 255) / 256, batch), dim3(256), 0, s, a);
   return hipGetLastError();
 }
 

@@ -36,6 +36,13 @@ struct ShiftArgs {
   int32_t n_buf[QS_MAX_BATCH];
 };
 
+struct AppendArgs {
+  const _Float16 *k_new, *v_new;   // [B][n_new][Hkv][128]
+  _Float16 *k_buf, *v_buf;
+  int32_t n_kv_heads, buf_cap, n_new;
+  int32_t n_buf[QS_MAX_BATCH];
+};
+
 struct ExportArgs {
   const uint32_t *k_upper, *k_lower, *v_upper, *v_lower;
   const _Float16 *k_scale, *k_zero, *v_scale, *v_zero;
@@ -68,6 +75,7 @@ struct MergeArgs {
 hipError_t launch_flush(const FlushArgs& a, int batch, hipStream_t s);
 hipError_t launch_shift(const ShiftArgs& a, int batch, hipStream_t s);
 hipError_t launch_export(const ExportArgs& a, hipStream_t s);
+hipError_t launch_append(const AppendArgs& a, int batch, hipStream_t s);
 hipError_t launch_attn(const AttnArgs& a, int batch, bool verify, hipStream_t s);
 hipError_t launch_merge(const MergeArgs& a, int rows_total, hipStream_t s);
 

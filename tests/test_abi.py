@@ -102,6 +102,13 @@ def test_validation_errors_without_gpu(B):
     pf = lambda c, n, stride: lib.qs_quantize_prefill(ctypes.byref(c), 0x500000, 0x600000, stride, n, None)
     assert pf(_fake_cache(B), 128, 64) == B.QS_ERR_RANGE
     assert pf(_fake_cache(B), 1024, 1024) == B.QS_ERR_RANGE
+    # append: sources present and aligned, room for n_new rows in every sequence's buffer
+    ap = lambda c, n, k=0x500000, v=0x600000: lib.qs_append(ctypes.byref(c), k, v, n, None)
+    assert ap(_fake_cache(B), 1, k=None) == B.QS_ERR_NULL
+    assert ap(_fake_cache(B), 1, v=0x600008) == B.QS_ERR_ALIGN
+    assert ap(_fake_cache(B), -1) == B.QS_ERR_RANGE
+    assert ap(_fake_cache(B), 9) == B.QS_ERR_RANGE           # sequence 0 holds 256 of 264 rows
+    assert ap(_fake_cache(B), 0) == B.QS_OK
     assert lib.qs_export_codes(ctypes.byref(_fake_cache(B)), 2, 0, 128, None, None, None, None, None, None, None, None, None) == B.QS_ERR_RANGE
     assert lib.qs_export_codes(ctypes.byref(_fake_cache(B)), 0, 0, 100, None, None, None, None, None, None, None, None, None) == B.QS_ERR_RANGE
 
