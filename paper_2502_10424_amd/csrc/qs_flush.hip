@@ -49,12 +49,107 @@ __device__ __forceinline__ _Float16 make_scale(float mn, float mx) {
   return h;
 }
 
-// Four workgroups share one 128-token group of one unit so that a single flushed group already
-// spreads over several compute units.  Workgroup q of the four handles
+// Same codes as encode() at a fraction of the arithmetic.  Both quotients are first formed with the
+// group's reciprocal r = fl(1/s): t' = fl((x - z) * r) and q' = fl(e * 16r).  A quotient of magnitude
+// below 32 differs from its correctly rounded value by less than 2^-17 this way (relative error of
+// r and of the product 2^-24 each, plus half an ulp of the exact result); larger ones lie beyond
+// the clamp on either route.  So whenever t' and q' both stay at least 2^-16 away from every
+// half-integer, rounding them gives the codes of encode(): x - z, C_U*S + Z and E_U are the very
+// same operations in both.  Otherwise the element takes encode() itself; on fp16 data that is a
+// few elements in ten thousand.
+struct GroupScale {
+  float s, z, r, rl;
+};
+
+__device__ __forceinline__ GroupScale group_scale(float s, float z) {
+  GroupScale g;
+  g.s = s;
+  g.z = z;
+  g.r = 1.0f / s;
+  g.rl = 16.0f * g.r;   // exact
+  return g;
+}
+
+__device__ __forceinline__ Codes encode_fast(float x, const GroupScale& g) {
+  constexpr float kTie = 0.5f - 0x1p-16f;
+  const float t = (x - g.z) * g.r;
+  const float tr = rintf(t);
+  const float u = fminf(fmaxf(tr, 0.0f), 15.0f);
+  float deq = u * g.s;
+  deq = deq + g.z;
+  const float e = x - deq;
+  const float q = e * g.rl;
+  const float qr = rintf(q);
+  const float l = fminf(fmaxf(qr, -8.0f), 7.0f);
+  Codes c;
+  c.u = (uint32_t)(int)u;
+  c.l = (uint32_t)((int)l + 8);
+  if (__builtin_expect(fabsf(t - tr) > kTie || fabsf(q - qr) > kTie, 0)) c = encode(x, g.s, g.z);
+  return c;
+}
+
+// Decode-time flush: four workgroups share one 128-token group of one unit so that a single flushed
+// group already spreads over several compute units.  Workgroup q of the four handles
 //   threads   0..127 : keys, channels [32q, 32q+32) of all 128 tokens
 //   threads 128..255 : values, tokens [32q, 32q+32) (one value tile) of all 128 channels
 // Each thread owns 4 channels of the eight tokens that share a value-plane word (32 codes).
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+
+// One value tile: tokens [32*tile, 32*tile+32) of the group, 128 threads (t = 0..127).
+__device__ __forceinline__ void load_value_tile(const FlushArgs& a, int64_t src0, int tile, int t, half4 (&x)[8]) {
+  const int c4 = t & 31, g = t >> 5;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    x[j] = *reinterpret_cast<const half4*>(a.v_src + src0 + (int64_t)(32 * tile + tile_token(g, j)) * kD + 4 * c4);
+}
+
+__device__ __forceinline__ void quantize_value_tile(const FlushArgs& a, int unit, int tq0, int tile, int t,
+                                                    const half4 (&x)[8]) {
+  const int c4 = t & 31, g = t >> 5;
+  half8 vsh, vzh;
+  uint32_t vu[4] = {0, 0, 0, 0}, vl[4] = {0, 0, 0, 0};
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    float lo = (float)x[j][0], hi = lo;
+#pragma unroll
+    for (int i = 1; i < 4; ++i) {
+      lo = fminf(lo, (float)x[j][i]);
+      hi = fmaxf(hi, (float)x[j][i]);
+    }
+#pragma unroll
+    for (int sft = 1; sft < 32; sft <<= 1) {   // the 32 lanes that hold the token's other channels
+      lo = fminf(lo, __shfl_xor(lo, sft));
+      hi = fmaxf(hi, __shfl_xor(hi, sft));
+    }
+    vsh[j] = make_scale(lo, hi);
+    vzh[j] = (_Float16)lo;
+    const GroupScale gs = group_scale((float)vsh[j], lo);
+    const int nib = 4 * tile_nibble(j);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      Codes c = encode_fast((float)x[j][i], gs);
+      vu[i] |= c.u << nib;
+      vl[i] |= c.l << nib;
+    }
+  }
+  if (c4 == 0) {
+    const int64_t m = (int64_t)unit * a.q_cap + tq0 + 32 * tile + 8 * g;
+    *reinterpret_cast<half8*>(a.v_scale + m) = vsh;
+    *reinterpret_cast<half8*>(a.v_zero + m) = vzh;
+  }
+  // channels 4*c4 .. 4*c4+3 = 8*m + 4*h + i with m = c4 >> 1, h = c4 & 1: four consecutive words
+  const int64_t vt = (int64_t)unit * (a.q_cap / kVTileTok) + tq0 / kVTileTok + tile;
+  const int64_t w = vt * kVTileDw + ((c4 & 1) * 64 + 16 * g + (c4 >> 1)) * 4;
+  *reinterpret_cast<uint4*>(a.v_upper + w) = make_uint4(vu[0], vu[1], vu[2], vu[3]);
+  *reinterpret_cast<uint4*>(a.v_lower + w) = make_uint4(vl[0], vl[1], vl[2], vl[3]);
+}
+
+// Key scale / zero are stored in the order the attention kernel's B operand wants them: position
+// 32*s + 8*g + e of a group's 128 holds channel 32*g + 8*s + nibble(e).
+__device__ __forceinline__ int key_meta_position(int ch) {
+  const int g = ch >> 5, s = (ch >> 3) & 3, nib = ch & 7;
+  return 32 * s + 8 * g + ((nib & 3) << 1) + (nib >> 2);
+}
 
 __global__ __launch_bounds__(256) void flush_kernel(FlushArgs a) {
   __shared__ float red[2][32][2];
@@ -98,26 +193,22 @@ __global__ __launch_bounds__(256) void flush_kernel(FlushArgs a) {
       }
     }
     __syncthreads();
-    float ks[4], kz[4];
+    GroupScale gs[4];
     _Float16 ksh[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const float lo = fminf(red[0][4 * c4 + i][0], red[1][4 * c4 + i][0]);
       const float hi = fmaxf(red[0][4 * c4 + i][1], red[1][4 * c4 + i][1]);
       ksh[i] = make_scale(lo, hi);
-      ks[i] = (float)ksh[i];
-      kz[i] = lo;
+      gs[i] = group_scale((float)ksh[i], lo);
     }
     if (oct == 0) {
-      // stored in the order the attention kernel's B operand wants them: position 32*s + 8*g' + e
-      // holds channel 32*g' + 8*s + nibble(e); here g' = q, s = c4 >> 1, nibble = 4*(c4 & 1) + i
-      const int64_t dst = ((int64_t)unit * (a.q_cap / kG) + tq0 / kG) * kD + 32 * (c4 >> 1) + 8 * q;
+      const int64_t dst = ((int64_t)unit * (a.q_cap / kG) + tq0 / kG) * kD;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int nib = 4 * (c4 & 1) + i;
-        const int e = ((nib & 3) << 1) + (nib >> 2);
-        a.k_scale[dst + e] = ksh[i];
-        a.k_zero[dst + e] = (_Float16)kz[i];
+        const int pos = key_meta_position(ch0 + i);
+        a.k_scale[dst + pos] = ksh[i];
+        a.k_zero[dst + pos] = (_Float16)gs[i].z;
       }
     }
     uint16_t* ku16 = reinterpret_cast<uint16_t*>(a.k_upper);
@@ -127,7 +218,7 @@ __global__ __launch_bounds__(256) void flush_kernel(FlushArgs a) {
       uint32_t wu = 0, wl = 0;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        Codes c = encode((float)x[j][i], ks[i], kz[i]);
+        Codes c = encode_fast((float)x[j][i], gs[i]);
         wu |= c.u << (4 * i);
         wl |= c.l << (4 * i);
       }
@@ -137,50 +228,92 @@ __global__ __launch_bounds__(256) void flush_kernel(FlushArgs a) {
       kl16[w] = (uint16_t)wl;
     }
   } else {
-    __syncthreads();   // matches the barrier of the key half
     // ---- values: min / max per token over its 128 channels --------------------------------------
-    const int t = tid - 128, c4 = t & 31, g = t >> 5;
     half4 x[8];
+    load_value_tile(a, src0, q, tid - 128, x);
+    quantize_value_tile(a, unit, tq0, q, tid - 128, x);
+    __syncthreads();   // matches the barrier of the key half
+  }
+}
+
+// Bulk quantization (prefill): one workgroup per 128-token group of one unit, every load issued
+// before the first use.  Keys: thread (l16 = tid & 15, rg = tid >> 4) owns channels [8*l16, 8*l16+8)
+// of tokens rg, rg+16, ..., rg+112, so a wave reads and writes whole rows (1 KB of source, 256 B of
+// each plane per instruction).  Values: the two halves of the workgroup take the tiles 2*pass and
+// 2*pass+1 of the group, in the thread layout of the flush kernel.
+__global__ __launch_bounds__(256) void quantize_group_kernel(FlushArgs a) {
+  __shared__ float part[4][128][2];   // per wave: channel min, max
+  __shared__ float4 ksc[128];         // per channel: S, Z, 1/S, 16/S
+  const int grp = blockIdx.x, unit = blockIdx.y;
+  const int b = unit / a.n_kv_heads;
+  const int tid = threadIdx.x;
+  const int tq0 = a.n_quant[b] + grp * kG;
+  const int64_t src0 = ((int64_t)unit * a.src_stride + (int64_t)grp * kG) * kD;
+  const int l16 = tid & 15, rg = tid >> 4;
+  const int vt = tid & 127, vhalf = tid >> 7;
+
+  half8 xk[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
-      x[j] = *reinterpret_cast<const half4*>(a.v_src + src0 + (int64_t)(32 * q + tile_token(g, j)) * kD + 4 * c4);
-    half8 vsh, vzh;
-    uint32_t vu[4] = {0, 0, 0, 0}, vl[4] = {0, 0, 0, 0};
+  for (int j = 0; j < 8; ++j) xk[j] = ld_half8(a.k_src + src0 + (int64_t)(rg + 16 * j) * kD + 8 * l16);
+  half4 xv0[8], xv1[8];
+  load_value_tile(a, src0, vhalf, vt, xv0);
+  load_value_tile(a, src0, 2 + vhalf, vt, xv1);
+
+  // ---- keys: min / max per channel over the 128 tokens ----------------------------------------
+  const int wave = tid >> 6;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float lo = (float)xk[0][i], hi = lo;
+#pragma unroll
+    for (int j = 1; j < 8; ++j) {
+      lo = fminf(lo, (float)xk[j][i]);
+      hi = fmaxf(hi, (float)xk[j][i]);
+    }
+    lo = fminf(lo, __shfl_xor(lo, 16));   // the four row groups of this wave
+    hi = fmaxf(hi, __shfl_xor(hi, 16));
+    lo = fminf(lo, __shfl_xor(lo, 32));
+    hi = fmaxf(hi, __shfl_xor(hi, 32));
+    if ((tid & 63) < 16) {
+      part[wave][8 * l16 + i][0] = lo;
+      part[wave][8 * l16 + i][1] = hi;
+    }
+  }
+  __syncthreads();
+  if (tid < 128) {
+    const float lo = fminf(fminf(part[0][tid][0], part[1][tid][0]), fminf(part[2][tid][0], part[3][tid][0]));
+    const float hi = fmaxf(fmaxf(part[0][tid][1], part[1][tid][1]), fmaxf(part[2][tid][1], part[3][tid][1]));
+    const _Float16 sh = make_scale(lo, hi);
+    const GroupScale gs = group_scale((float)sh, lo);
+    ksc[tid] = make_float4(gs.s, gs.z, gs.r, gs.rl);
+    const int64_t dst = ((int64_t)unit * (a.q_cap / kG) + tq0 / kG) * kD + key_meta_position(tid);
+    a.k_scale[dst] = sh;
+    a.k_zero[dst] = (_Float16)lo;
+  }
+  __syncthreads();
+  {
+    uint32_t wu[8] = {0, 0, 0, 0, 0, 0, 0, 0}, wl[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float4 m = ksc[8 * l16 + i];
+      GroupScale gs;
+      gs.s = m.x, gs.z = m.y, gs.r = m.z, gs.rl = m.w;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        Codes c = encode_fast((float)xk[j][i], gs);
+        wu[j] |= c.u << (4 * i);
+        wl[j] |= c.l << (4 * i);
+      }
+    }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      float lo = (float)x[j][0], hi = lo;
-#pragma unroll
-      for (int i = 1; i < 4; ++i) {
-        lo = fminf(lo, (float)x[j][i]);
-        hi = fmaxf(hi, (float)x[j][i]);
-      }
-#pragma unroll
-      for (int sft = 1; sft < 32; sft <<= 1) {   // the 32 lanes that hold the token's other channels
-        lo = fminf(lo, __shfl_xor(lo, sft));
-        hi = fmaxf(hi, __shfl_xor(hi, sft));
-      }
-      vsh[j] = make_scale(lo, hi);
-      vzh[j] = (_Float16)lo;
-      const float s = (float)vsh[j];
-      const int nib = 4 * tile_nibble(j);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        Codes c = encode((float)x[j][i], s, lo);
-        vu[i] |= c.u << nib;
-        vl[i] |= c.l << nib;
-      }
+      const int64_t w = ((int64_t)unit * a.q_cap + tq0 + rg + 16 * j) * kRowDw + l16;
+      a.k_upper[w] = wu[j];
+      a.k_lower[w] = wl[j];
     }
-    if (c4 == 0) {
-      const int64_t m = (int64_t)unit * a.q_cap + tq0 + 32 * q + 8 * g;
-      *reinterpret_cast<half8*>(a.v_scale + m) = vsh;
-      *reinterpret_cast<half8*>(a.v_zero + m) = vzh;
-    }
-    // channels 4*c4 .. 4*c4+3 = 8*m + 4*h + i with m = c4 >> 1, h = c4 & 1: four consecutive words
-    const int64_t tile = (int64_t)unit * (a.q_cap / kVTileTok) + tq0 / kVTileTok + q;
-    const int64_t w = tile * kVTileDw + ((c4 & 1) * 64 + 16 * g + (c4 >> 1)) * 4;
-    *reinterpret_cast<uint4*>(a.v_upper + w) = make_uint4(vu[0], vu[1], vu[2], vu[3]);
-    *reinterpret_cast<uint4*>(a.v_lower + w) = make_uint4(vl[0], vl[1], vl[2], vl[3]);
   }
+  // ---- values ------------------------------------------------------------------------------------
+  quantize_value_tile(a, unit, tq0, vhalf, vt, xv0);
+  quantize_value_tile(a, unit, tq0, 2 + vhalf, vt, xv1);
 }
 
 // Buffer move (Section 4.3.2): rows [n_tokens, n_buf) become rows [0, n_buf - n_tokens).  Source and
@@ -264,8 +397,12 @@ __global__ __launch_bounds__(256) void export_kernel(ExportArgs a) {
 
 hipError_t launch_flush(const FlushArgs& a, int batch, hipStream_t s) {
   if (a.n_groups <= 0) return hipSuccess;
-  dim3 grid(4 * a.n_groups, batch * a.n_kv_heads);
-  hipLaunchKernelGGL(flush_kernel, grid, dim3(256), 0, s, a);
+  const int units = batch * a.n_kv_heads;
+  if ((int64_t)a.n_groups * units >= kBulkGroups) {
+    hipLaunchKernelGGL(quantize_group_kernel, dim3(a.n_groups, units), dim3(256), 0, s, a);
+  } else {
+    hipLaunchKernelGGL(flush_kernel, dim3(4 * a.n_groups, units), dim3(256), 0, s, a);
+  }
   return hipGetLastError();
 }
 

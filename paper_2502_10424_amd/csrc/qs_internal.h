@@ -12,6 +12,7 @@ constexpr int kG = 128;            // quantization group size
 constexpr int kRowDw = 16;         // 32-bit words per token row of a key plane (128 nibbles)
 constexpr int kVTileTok = 32;      // tokens per value-plane tile
 constexpr int kVTileDw = 512;      // 32-bit words per value-plane tile (32 tokens x 128 nibbles)
+constexpr int kBulkGroups = 512;   // from this many (group, unit) pairs on, quantization takes the bulk kernel
 constexpr int kBufSplitTok = 64;   // buffer tokens handled by one wave of the attention kernel
 
 // Per-sequence lengths travel inside the kernel arguments.

@@ -154,6 +154,32 @@ def test_quantizer_edge_values(env):
         U.assert_unit_equals_oracle(cache, oc, 0, h)
 
 
+def test_bulk_quantize_bit_exact(env):
+    """Enough (group, unit) pairs for the prefill quantization to take its bulk kernel: 8 units x 64
+    groups.  Units differ in what they stress: plain normal data, coarse grids full of exact rounding
+    ties, ranges so small that the fp16 scale is subnormal, outlier channels and constant stretches."""
+    torch, O, U, B = env["torch"], env["O"], env["U"], env["B"]
+    rng = np.random.default_rng(61)
+    t = 64 * 128
+    k = (rng.standard_normal((2, 4, t, 128)) * 1.3).astype(np.float16)
+    v = (rng.standard_normal((2, 4, t, 128)) * 1.3).astype(np.float16)
+    k[0, 1] = (rng.integers(-40, 41, (t, 128)) * 0.125).astype(np.float16)          # ties at every step
+    v[0, 1] = (rng.integers(-40, 41, (t, 128)) * 0.0625).astype(np.float16)
+    k[0, 2] = (rng.integers(0, 40, (t, 128)) * 2.0 ** -24).astype(np.float16)       # subnormal scales
+    v[0, 2] = (rng.integers(0, 25, (t, 128)) * 2.0 ** -24).astype(np.float16)
+    k[0, 3, :, ::17] *= 30                                                           # outlier channels
+    v[0, 3, ::5] = 0.75                                                              # constant tokens
+    k[1, 0, 128:384, 5] = -3.0                                                       # constant channel groups
+    k[1, 1] = np.clip(rng.standard_normal((t, 128)) * 20000, -65504, 65504).astype(np.float16)
+    v[1, 1] = np.clip(rng.standard_normal((t, 128)) * 20000, -65504, 65504).astype(np.float16)
+    _say("bulk quantize, 8 units x 64 groups")
+    cache = U.make_device_cache(k, v, 4, 0, q_cap=t, buf_cap=8)
+    oc = O.build_cache(k, v, 4, 128, 0)
+    for b in range(2):
+        for h in range(4):
+            U.assert_unit_equals_oracle(cache, oc, b, h)
+
+
 @pytest.mark.parametrize("verify", [False, True], ids=["draft", "verify"])
 def test_attention_tiny_workload(env, verify):
     """Workload 'tiny' (GQA 32/8, ctx 2048 = 1792 quantized + 256 buffered): 1 draft query, 5 verify queries."""
