@@ -14,6 +14,8 @@ namespace qs {
 namespace {
 
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ half8 ld_half8(const _Float16* p) {
   return *reinterpret_cast<const half8*>(p);
@@ -24,10 +26,13 @@ __device__ __forceinline__ half8 ld_half8(const _Float16* p) {
 __device__ __forceinline__ int tile_token(int g, int j) { return ((j >> 2) << 4) + 4 * g + (j & 3); }
 __device__ __forceinline__ int tile_nibble(int j) { return ((j & 1) << 2) + (j >> 1); }
 
+// C_U in [0, 15] and C_L in [-8, 7], kept as floats: codes are packed into plane words with exact
+// float arithmetic (see pack4) and converted to integers four at a time.
 struct Codes {
-  uint32_t u, l;   // C_U and C_L + 8, both in [0, 15]
+  float u, l;
 };
 
+// The definition: every operation rounds once, in binary32 (Section 4.2).
 __device__ __forceinline__ Codes encode(float x, float s, float z) {
   float t = (x - z) / s;
   float u = fminf(fmaxf(rintf(t), 0.0f), 15.0f);
@@ -36,10 +41,7 @@ __device__ __forceinline__ Codes encode(float x, float s, float z) {
   float e = x - deq;
   float sl = s / 16.0f;
   float l = fminf(fmaxf(rintf(e / sl), -8.0f), 7.0f);
-  Codes c;
-  c.u = (uint32_t)(int)u;
-  c.l = (uint32_t)((int)l + 8);
-  return c;
+  return Codes{u, l};
 }
 
 __device__ __forceinline__ _Float16 make_scale(float mn, float mx) {
@@ -49,13 +51,15 @@ __device__ __forceinline__ _Float16 make_scale(float mn, float mx) {
   return h;
 }
 
-// Same codes as encode() at a fraction of the arithmetic.  Both quotients are first formed with the
-// group's reciprocal r = fl(1/s): t' = fl((x - z) * r) and q' = fl(e * 16r).  A quotient of magnitude
-// below 32 differs from its correctly rounded value by less than 2^-17 this way (relative error of
-// r and of the product 2^-24 each, plus half an ulp of the exact result); larger ones lie beyond
-// the clamp on either route.  So whenever t' and q' both stay at least 2^-16 away from every
-// half-integer, rounding them gives the codes of encode(): x - z, C_U*S + Z and E_U are the very
-// same operations in both.  Otherwise the element takes encode() itself; on fp16 data that is a
+// Same codes as encode() at a fraction of the arithmetic.  Both quotients are first formed with an
+// approximate reciprocal r of the group's scale (relative error at most 2^-22): t' = fl((x - z) * r)
+// and q' = fl(e * 16r).  A quotient of magnitude below 16 differs from its correctly rounded value by
+// less than 2^-17 this way (16 * (2^-22 + 2^-24) for r and the product, 2^-21 for the rounding of the
+// exact quotient); larger ones only occur beyond the clamps, where both routes give the end code.  So
+// whenever t' and q' both stay at least 2^-16 away from every half-integer, rounding them gives the
+// codes of encode().  Everything else is the same operation in both: x - z; C_U*S is exact (4 bits
+// times 11), so fma(C_U, S, Z) is fl(fl(C_U*S) + Z); E_U = x - that.  x >= Z makes t' >= 0, so the
+// lower clamp of C_U never acts.  Otherwise the element takes encode() itself; on fp16 data that is a
 // few elements in ten thousand.
 struct GroupScale {
   float s, z, r, rl;
@@ -65,83 +69,60 @@ __device__ __forceinline__ GroupScale group_scale(float s, float z) {
   GroupScale g;
   g.s = s;
   g.z = z;
-  g.r = 1.0f / s;
-  g.rl = 16.0f * g.r;   // exact
+  g.r = __builtin_amdgcn_rcpf(s);   // s is a normal binary32 number in [2^-24, 2^14)
+  g.rl = 16.0f * g.r;               // exact
   return g;
 }
 
-__device__ __forceinline__ Codes encode_fast(float x, const GroupScale& g) {
-  constexpr float kTie = 0.5f - 0x1p-16f;
+struct FastCodes {
+  Codes c;
+  float off;   // larger distance of t' and q' from their roundings, in [0, 0.5]
+};
+constexpr float kTie = 0.5f - 0x1p-16f;
+
+__device__ __forceinline__ FastCodes encode_candidate(float x, const GroupScale& g) {
   const float t = (x - g.z) * g.r;
   const float tr = rintf(t);
-  const float u = fminf(fmaxf(tr, 0.0f), 15.0f);
-  float deq = u * g.s;
-  deq = deq + g.z;
-  const float e = x - deq;
+  const float u = fminf(tr, 15.0f);
+  const float e = x - __builtin_fmaf(u, g.s, g.z);
   const float q = e * g.rl;
   const float qr = rintf(q);
-  const float l = fminf(fmaxf(qr, -8.0f), 7.0f);
-  Codes c;
-  c.u = (uint32_t)(int)u;
-  c.l = (uint32_t)((int)l + 8);
-  if (__builtin_expect(fabsf(t - tr) > kTie || fabsf(q - qr) > kTie, 0)) c = encode(x, g.s, g.z);
-  return c;
+  FastCodes f;
+  f.c = Codes{u, __builtin_amdgcn_fmed3f(qr, -8.0f, 7.0f)};
+  // both distances are at most 0.5, so the median of them and 1 is the larger one
+  f.off = __builtin_amdgcn_fmed3f(fabsf(t - tr), fabsf(q - qr), 1.0f);
+  return f;
 }
 
-// Decode-time flush: four workgroups share one 128-token group of one unit so that a single flushed
-// group already spreads over several compute units.  Workgroup q of the four handles
-//   threads   0..127 : keys, channels [32q, 32q+32) of all 128 tokens
-//   threads 128..255 : values, tokens [32q, 32q+32) (one value tile) of all 128 channels
-// Each thread owns 4 channels of the eight tokens that share a value-plane word (32 codes).
-typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-
-// One value tile: tokens [32*tile, 32*tile+32) of the group, 128 threads (t = 0..127).
-__device__ __forceinline__ void load_value_tile(const FlushArgs& a, int64_t src0, int tile, int t, half4 (&x)[8]) {
-  const int c4 = t & 31, g = t >> 5;
-#pragma unroll
-  for (int j = 0; j < 8; ++j)
-    x[j] = *reinterpret_cast<const half4*>(a.v_src + src0 + (int64_t)(32 * tile + tile_token(g, j)) * kD + 4 * c4);
+__device__ __forceinline__ Codes encode_fast(float x, const GroupScale& g) {
+  FastCodes f = encode_candidate(x, g);
+  if (__builtin_expect(f.off > kTie, 0)) f.c = encode(x, g.s, g.z);
+  return f.c;
 }
 
-__device__ __forceinline__ void quantize_value_tile(const FlushArgs& a, int unit, int tq0, int tile, int t,
-                                                    const half4 (&x)[8]) {
-  const int c4 = t & 31, g = t >> 5;
-  half8 vsh, vzh;
-  uint32_t vu[4] = {0, 0, 0, 0}, vl[4] = {0, 0, 0, 0};
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    float lo = (float)x[j][0], hi = lo;
-#pragma unroll
-    for (int i = 1; i < 4; ++i) {
-      lo = fminf(lo, (float)x[j][i]);
-      hi = fmaxf(hi, (float)x[j][i]);
-    }
-#pragma unroll
-    for (int sft = 1; sft < 32; sft <<= 1) {   // the 32 lanes that hold the token's other channels
-      lo = fminf(lo, __shfl_xor(lo, sft));
-      hi = fmaxf(hi, __shfl_xor(hi, sft));
-    }
-    vsh[j] = make_scale(lo, hi);
-    vzh[j] = (_Float16)lo;
-    const GroupScale gs = group_scale((float)vsh[j], lo);
-    const int nib = 4 * tile_nibble(j);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      Codes c = encode_fast((float)x[j][i], gs);
-      vu[i] |= c.u << nib;
-      vl[i] |= c.l << nib;
-    }
+// Two elements behind one test: the rare path is entered half as often per element and still
+// recomputes only the element that is near a tie.
+__device__ __forceinline__ void encode_fast2(float x0, const GroupScale& g0, float x1, const GroupScale& g1,
+                                             Codes& c0, Codes& c1) {
+  FastCodes f0 = encode_candidate(x0, g0), f1 = encode_candidate(x1, g1);
+  if (__builtin_expect(fmaxf(f0.off, f1.off) > kTie, 0)) {
+    if (f0.off > kTie) f0.c = encode(x0, g0.s, g0.z);
+    if (f1.off > kTie) f1.c = encode(x1, g1.s, g1.z);
   }
-  if (c4 == 0) {
-    const int64_t m = (int64_t)unit * a.q_cap + tq0 + 32 * tile + 8 * g;
-    *reinterpret_cast<half8*>(a.v_scale + m) = vsh;
-    *reinterpret_cast<half8*>(a.v_zero + m) = vzh;
-  }
-  // channels 4*c4 .. 4*c4+3 = 8*m + 4*h + i with m = c4 >> 1, h = c4 & 1: four consecutive words
-  const int64_t vt = (int64_t)unit * (a.q_cap / kVTileTok) + tq0 / kVTileTok + tile;
-  const int64_t w = vt * kVTileDw + ((c4 & 1) * 64 + 16 * g + (c4 >> 1)) * 4;
-  *reinterpret_cast<uint4*>(a.v_upper + w) = make_uint4(vu[0], vu[1], vu[2], vu[3]);
-  *reinterpret_cast<uint4*>(a.v_lower + w) = make_uint4(vl[0], vl[1], vl[2], vl[3]);
+  c0 = f0.c;
+  c1 = f1.c;
+}
+
+// Four 4-bit codes -> 16 bits of a plane word: acc += code * 16^k stays below 2^16, exact in binary32.
+// The lower plane stores C_L + 8, so its accumulators start at 0x8888.
+constexpr float kLowerBias = 34952.0f;
+__device__ __forceinline__ void pack4(float& acc_u, float& acc_l, const Codes& c, int k) {
+  const float w = (float)(1 << (4 * k));
+  acc_u = __builtin_fmaf(c.u, w, acc_u);
+  acc_l = __builtin_fmaf(c.l, w, acc_l);
+}
+__device__ __forceinline__ uint32_t packed_word(float lo16, float hi16) {
+  return (uint32_t)lo16 | ((uint32_t)hi16 << 16);
 }
 
 // Key scale / zero are stored in the order the attention kernel's B operand wants them: position
@@ -151,6 +132,12 @@ __device__ __forceinline__ int key_meta_position(int ch) {
   return 32 * s + 8 * g + ((nib & 3) << 1) + (nib >> 2);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Decode-time flush: four workgroups share one 128-token group of one unit so that a single flushed
+// group already spreads over several compute units.  Workgroup q of the four handles
+//   threads   0..127 : keys, channels [32q, 32q+32) of all 128 tokens
+//   threads 128..255 : values, tokens [32q, 32q+32) (one value tile) of all 128 channels
+// Each thread owns 4 channels of the eight tokens that share a value-plane word (32 codes).
 __global__ __launch_bounds__(256) void flush_kernel(FlushArgs a) {
   __shared__ float red[2][32][2];
   const int grp = blockIdx.x >> 2, q = blockIdx.x & 3, unit = blockIdx.y;
@@ -215,73 +202,135 @@ __global__ __launch_bounds__(256) void flush_kernel(FlushArgs a) {
     uint16_t* kl16 = reinterpret_cast<uint16_t*>(a.k_lower);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      uint32_t wu = 0, wl = 0;
+      float wu = 0.0f, wl = kLowerBias;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        Codes c = encode_fast((float)x[j][i], gs[i]);
-        wu |= c.u << (4 * i);
-        wl |= c.l << (4 * i);
-      }
+      for (int i = 0; i < 4; ++i) pack4(wu, wl, encode_fast((float)x[j][i], gs[i]), i);
       const int tok = 32 * blk + tile_token(g, j);
       const int64_t w = (((int64_t)unit * a.q_cap + tq0 + tok) * kRowDw) * 2 + (ch0 >> 2);   // 16-bit units
-      ku16[w] = (uint16_t)wu;
-      kl16[w] = (uint16_t)wl;
+      ku16[w] = (uint16_t)(uint32_t)wu;
+      kl16[w] = (uint16_t)(uint32_t)wl;
     }
   } else {
     // ---- values: min / max per token over its 128 channels --------------------------------------
+    const int t = tid - 128, c4 = t & 31, g = t >> 5;
     half4 x[8];
-    load_value_tile(a, src0, q, tid - 128, x);
-    quantize_value_tile(a, unit, tq0, q, tid - 128, x);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      x[j] = *reinterpret_cast<const half4*>(a.v_src + src0 + (int64_t)(32 * q + tile_token(g, j)) * kD + 4 * c4);
+    half8 vsh, vzh;
+    float vu[4][2], vl[4][2];   // per channel: nibbles 0..3 (even j) and 4..7 (odd j) of its plane word
+#pragma unroll
+    for (int i = 0; i < 4; ++i) vu[i][0] = vu[i][1] = 0.0f, vl[i][0] = vl[i][1] = kLowerBias;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      float lo = (float)x[j][0], hi = lo;
+#pragma unroll
+      for (int i = 1; i < 4; ++i) {
+        lo = fminf(lo, (float)x[j][i]);
+        hi = fmaxf(hi, (float)x[j][i]);
+      }
+#pragma unroll
+      for (int sft = 1; sft < 32; sft <<= 1) {   // the 32 lanes that hold the token's other channels
+        lo = fminf(lo, __shfl_xor(lo, sft));
+        hi = fmaxf(hi, __shfl_xor(hi, sft));
+      }
+      vsh[j] = make_scale(lo, hi);
+      vzh[j] = (_Float16)lo;
+      const GroupScale gs = group_scale((float)vsh[j], lo);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) pack4(vu[i][j & 1], vl[i][j & 1], encode_fast((float)x[j][i], gs), j >> 1);
+    }
+    if (c4 == 0) {
+      const int64_t m = (int64_t)unit * a.q_cap + tq0 + 32 * q + 8 * g;
+      *reinterpret_cast<half8*>(a.v_scale + m) = vsh;
+      *reinterpret_cast<half8*>(a.v_zero + m) = vzh;
+    }
+    // channels 4*c4 .. 4*c4+3 = 8*m + 4*h + i with m = c4 >> 1, h = c4 & 1: four consecutive words
+    const int64_t vt = (int64_t)unit * (a.q_cap / kVTileTok) + tq0 / kVTileTok + q;
+    const int64_t w = vt * kVTileDw + ((c4 & 1) * 64 + 16 * g + (c4 >> 1)) * 4;
+    *reinterpret_cast<uint4*>(a.v_upper + w) = make_uint4(packed_word(vu[0][0], vu[0][1]), packed_word(vu[1][0], vu[1][1]),
+                                                          packed_word(vu[2][0], vu[2][1]), packed_word(vu[3][0], vu[3][1]));
+    *reinterpret_cast<uint4*>(a.v_lower + w) = make_uint4(packed_word(vl[0][0], vl[0][1]), packed_word(vl[1][0], vl[1][1]),
+                                                          packed_word(vl[2][0], vl[2][1]), packed_word(vl[3][0], vl[3][1]));
     __syncthreads();   // matches the barrier of the key half
   }
 }
 
+// ------------------------------------------------------------------------------------------------
 // Bulk quantization (prefill): one workgroup per 128-token group of one unit, every load issued
-// before the first use.  Keys: thread (l16 = tid & 15, rg = tid >> 4) owns channels [8*l16, 8*l16+8)
-// of tokens rg, rg+16, ..., rg+112, so a wave reads and writes whole rows (1 KB of source, 256 B of
-// each plane per instruction).  Values: the two halves of the workgroup take the tiles 2*pass and
-// 2*pass+1 of the group, in the thread layout of the flush kernel.
-__global__ __launch_bounds__(256) void quantize_group_kernel(FlushArgs a) {
-  __shared__ float part[4][128][2];   // per wave: channel min, max
-  __shared__ float4 ksc[128];         // per channel: S, Z, 1/S, 16/S
+// before the first use, 8 channels x 8 tokens of K and of V per thread, whole rows per wave access
+// (1 KB of source, 256 B of a plane per instruction).  Minima and maxima are taken on packed fp16
+// pairs, which is exact.
+//   keys:   thread (l16 = tid & 15, rg = tid >> 4) owns channels [8*l16, 8*l16+8) of tokens rg + 16*j;
+//           channel statistics: in-thread over j, over the wave's four row groups, over the waves (LDS)
+//   values: thread (l16, tg = tid >> 4) owns the same channels of the eight tokens that share the
+//           plane words of value tile tg >> 2, lane group tg & 3; token statistics: in-thread over
+//           the 8 channels, then over the 16 lanes of the row by rotation (min and -max side by side)
+__device__ __forceinline__ half2 pmin(half2 a, half2 b) { return __builtin_elementwise_min(a, b); }
+__device__ __forceinline__ half2 pmax(half2 a, half2 b) { return __builtin_elementwise_max(a, b); }
+__device__ __forceinline__ half8 pmin(half8 a, half8 b) { return __builtin_elementwise_min(a, b); }
+__device__ __forceinline__ half8 pmax(half8 a, half8 b) { return __builtin_elementwise_max(a, b); }
+
+__device__ __forceinline__ half8 shfl_xor_h8(half8 v, int mask) {
+  uint4 w = __builtin_bit_cast(uint4, v);
+  w.x = __shfl_xor(w.x, mask);
+  w.y = __shfl_xor(w.y, mask);
+  w.z = __shfl_xor(w.z, mask);
+  w.w = __shfl_xor(w.w, mask);
+  return __builtin_bit_cast(half8, w);
+}
+
+template <int ROR>
+__device__ __forceinline__ half2 row_rotate(half2 v) {   // lane i of each 16-lane row reads lane i + ROR (mod 16)
+  const int w = __builtin_bit_cast(int, v);
+  return __builtin_bit_cast(half2, __builtin_amdgcn_update_dpp(w, w, 0x120 + ROR, 0xF, 0xF, true));
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void quantize_group_kernel(FlushArgs a) {
+  __shared__ uint4 part_lo[4][16], part_hi[4][16];   // per wave: 128 channel minima / maxima, fp16
+  __shared__ float4 ksc[128];                        // per channel: S, Z, ~1/S, ~16/S
   const int grp = blockIdx.x, unit = blockIdx.y;
   const int b = unit / a.n_kv_heads;
   const int tid = threadIdx.x;
   const int tq0 = a.n_quant[b] + grp * kG;
   const int64_t src0 = ((int64_t)unit * a.src_stride + (int64_t)grp * kG) * kD;
   const int l16 = tid & 15, rg = tid >> 4;
-  const int vt = tid & 127, vhalf = tid >> 7;
+  const int vtile = rg >> 2, vg = rg & 3;
 
-  half8 xk[8];
+  half8 xk[8], xv[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) xk[j] = ld_half8(a.k_src + src0 + (int64_t)(rg + 16 * j) * kD + 8 * l16);
-  half4 xv0[8], xv1[8];
-  load_value_tile(a, src0, vhalf, vt, xv0);
-  load_value_tile(a, src0, 2 + vhalf, vt, xv1);
-
-  // ---- keys: min / max per channel over the 128 tokens ----------------------------------------
-  const int wave = tid >> 6;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    float lo = (float)xk[0][i], hi = lo;
+  for (int j = 0; j < 8; ++j)
+    xv[j] = ld_half8(a.v_src + src0 + (int64_t)(32 * vtile + tile_token(vg, j)) * kD + 8 * l16);
+
+  // ---- keys ------------------------------------------------------------------------------------
+  {
+    half8 lo = xk[0], hi = xk[0];
 #pragma unroll
     for (int j = 1; j < 8; ++j) {
-      lo = fminf(lo, (float)xk[j][i]);
-      hi = fmaxf(hi, (float)xk[j][i]);
+      lo = pmin(lo, xk[j]);
+      hi = pmax(hi, xk[j]);
     }
-    lo = fminf(lo, __shfl_xor(lo, 16));   // the four row groups of this wave
-    hi = fmaxf(hi, __shfl_xor(hi, 16));
-    lo = fminf(lo, __shfl_xor(lo, 32));
-    hi = fmaxf(hi, __shfl_xor(hi, 32));
+    lo = pmin(lo, shfl_xor_h8(lo, 16));
+    hi = pmax(hi, shfl_xor_h8(hi, 16));
+    lo = pmin(lo, shfl_xor_h8(lo, 32));
+    hi = pmax(hi, shfl_xor_h8(hi, 32));
     if ((tid & 63) < 16) {
-      part[wave][8 * l16 + i][0] = lo;
-      part[wave][8 * l16 + i][1] = hi;
+      part_lo[tid >> 6][l16] = __builtin_bit_cast(uint4, lo);
+      part_hi[tid >> 6][l16] = __builtin_bit_cast(uint4, hi);
     }
   }
   __syncthreads();
   if (tid < 128) {
-    const float lo = fminf(fminf(part[0][tid][0], part[1][tid][0]), fminf(part[2][tid][0], part[3][tid][0]));
-    const float hi = fmaxf(fmaxf(part[0][tid][1], part[1][tid][1]), fmaxf(part[2][tid][1], part[3][tid][1]));
+    const _Float16* pl = reinterpret_cast<const _Float16*>(&part_lo[0][0]);
+    const _Float16* ph = reinterpret_cast<const _Float16*>(&part_hi[0][0]);
+    float lo = (float)pl[tid], hi = (float)ph[tid];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+      lo = fminf(lo, (float)pl[128 * w + tid]);
+      hi = fmaxf(hi, (float)ph[128 * w + tid]);
+    }
     const _Float16 sh = make_scale(lo, hi);
     const GroupScale gs = group_scale((float)sh, lo);
     ksc[tid] = make_float4(gs.s, gs.z, gs.r, gs.rl);
@@ -291,29 +340,75 @@ __global__ __launch_bounds__(256) void quantize_group_kernel(FlushArgs a) {
   }
   __syncthreads();
   {
-    uint32_t wu[8] = {0, 0, 0, 0, 0, 0, 0, 0}, wl[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    float wu[8][2], wl[8][2];   // per token: channels 0..3 and 4..7 of this thread's plane word
+#pragma unroll
+    for (int j = 0; j < 8; ++j) wu[j][0] = wu[j][1] = 0.0f, wl[j][0] = wl[j][1] = kLowerBias;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float4 m = ksc[8 * l16 + i];
-      GroupScale gs;
-      gs.s = m.x, gs.z = m.y, gs.r = m.z, gs.rl = m.w;
+      const GroupScale gs{m.x, m.y, m.z, m.w};
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        Codes c = encode_fast((float)xk[j][i], gs);
-        wu[j] |= c.u << (4 * i);
-        wl[j] |= c.l << (4 * i);
+      for (int j = 0; j < 8; j += 2) {
+        Codes c0, c1;
+        encode_fast2((float)xk[j][i], gs, (float)xk[j + 1][i], gs, c0, c1);
+        pack4(wu[j][i >> 2], wl[j][i >> 2], c0, i & 3);
+        pack4(wu[j + 1][i >> 2], wl[j + 1][i >> 2], c1, i & 3);
       }
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int64_t w = ((int64_t)unit * a.q_cap + tq0 + rg + 16 * j) * kRowDw + l16;
-      a.k_upper[w] = wu[j];
-      a.k_lower[w] = wl[j];
+      a.k_upper[w] = packed_word(wu[j][0], wu[j][1]);
+      a.k_lower[w] = packed_word(wl[j][0], wl[j][1]);
     }
   }
   // ---- values ------------------------------------------------------------------------------------
-  quantize_value_tile(a, unit, tq0, vhalf, vt, xv0);
-  quantize_value_tile(a, unit, tq0, 2 + vhalf, vt, xv1);
+  {
+    half8 vsh, vzh;
+    float vu[8][2], vl[8][2];   // per channel: nibbles 0..3 (even j) and 4..7 (odd j) of its plane word
+#pragma unroll
+    for (int i = 0; i < 8; ++i) vu[i][0] = vu[i][1] = 0.0f, vl[i][0] = vl[i][1] = kLowerBias;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const half8 x = xv[j];
+      const half2 x01 = x.s01, x23 = x.s23, x45 = x.s45, x67 = x.s67;
+      const half2 mn2 = pmin(pmin(x01, x23), pmin(x45, x67));
+      const half2 mx2 = pmax(pmax(x01, x23), pmax(x45, x67));
+      half2 p = pmin(half2{mn2.x, -mx2.x}, half2{mn2.y, -mx2.y});   // (min, -max) of the 8 channels
+      p = pmin(p, row_rotate<1>(p));
+      p = pmin(p, row_rotate<2>(p));
+      p = pmin(p, row_rotate<4>(p));
+      p = pmin(p, row_rotate<8>(p));
+      const float lo = (float)p.x, hi = -(float)p.y;
+      vsh[j] = make_scale(lo, hi);
+      vzh[j] = p.x;
+      const GroupScale gs = group_scale((float)vsh[j], lo);
+#pragma unroll
+      for (int i = 0; i < 8; i += 2) {
+        Codes c0, c1;
+        encode_fast2((float)x[i], gs, (float)x[i + 1], gs, c0, c1);
+        pack4(vu[i][j & 1], vl[i][j & 1], c0, j >> 1);
+        pack4(vu[i + 1][j & 1], vl[i + 1][j & 1], c1, j >> 1);
+      }
+    }
+    if (l16 == 0) {
+      const int64_t m = (int64_t)unit * a.q_cap + tq0 + 32 * vtile + 8 * vg;
+      *reinterpret_cast<half8*>(a.v_scale + m) = vsh;
+      *reinterpret_cast<half8*>(a.v_zero + m) = vzh;
+    }
+    // channel 8*l16 + 4*h + i lives in word (h*64 + 16*vg + l16)*4 + i of the tile
+    const int64_t vt = (int64_t)unit * (a.q_cap / kVTileTok) + tq0 / kVTileTok + vtile;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int64_t w = vt * kVTileDw + (h * 64 + 16 * vg + l16) * 4;
+      *reinterpret_cast<uint4*>(a.v_upper + w) =
+          make_uint4(packed_word(vu[4 * h][0], vu[4 * h][1]), packed_word(vu[4 * h + 1][0], vu[4 * h + 1][1]),
+                     packed_word(vu[4 * h + 2][0], vu[4 * h + 2][1]), packed_word(vu[4 * h + 3][0], vu[4 * h + 3][1]));
+      *reinterpret_cast<uint4*>(a.v_lower + w) =
+          make_uint4(packed_word(vl[4 * h][0], vl[4 * h][1]), packed_word(vl[4 * h + 1][0], vl[4 * h + 1][1]),
+                     packed_word(vl[4 * h + 2][0], vl[4 * h + 2][1]), packed_word(vl[4 * h + 3][0], vl[4 * h + 3][1]));
+    }
+  }
 }
 
 // Buffer move (Section 4.3.2): rows [n_tokens, n_buf) become rows [0, n_buf - n_tokens).  Source and
