@@ -23,6 +23,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
 GAMMA = 4
+SPEC_GAMMAS = (1, 2, 4, 6)      # speculation lengths of the simulated decode loop (Table 6)
 
 # HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (calibrated against a plain copy kernel).  Filled from the summaries under profiles/; None = not measured.
@@ -77,13 +78,14 @@ def main():
     k_host, v_host = synth.gen_layer_kv(w, workers=workers)
     q_draft = torch.from_numpy(synth.gen_layer_q(w, 1)).to(dev)
     q_verify = torch.from_numpy(synth.gen_layer_q(w, nqv)).to(dev)
-    q_cap = w.n_quant + 128            # room for the flushed group
+    q_cap = w.n_quant + 640            # room for the groups flushed during the run
     caches = []
     kd, vd = torch.from_numpy(k_host).to(dev), torch.from_numpy(v_host).to(dev)
     for i in range(args.copies):
         c = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, q_cap, w.n_buf + 8)
         if i == 0:
             B.qs_quantize_prefill(c, kd, vd, w.n_quant)
+            prefill = time_prefill(torch, B, c, kd, vd, w)
         else:
             for name in ("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "k_zero", "v_scale", "v_zero"):
                 getattr(c, name).copy_(getattr(caches[0], name))
@@ -93,7 +95,7 @@ def main():
         c.n_buf[:] = w.n_buf
         caches.append(c)
     del kd, vd
-    ws = torch.empty(max(B.qs_workspace_bytes(caches[0], nqv), B.qs_workspace_bytes(caches[0], 1)),
+    ws = torch.empty(max(B.qs_workspace_bytes(caches[0], n) for n in (1, nqv, max(SPEC_GAMMAS) + 1)),
                      dtype=torch.uint8, device=dev)
     out_d = torch.empty_like(q_draft)
     out_v = torch.empty_like(q_verify)
@@ -168,9 +170,74 @@ def main():
         "setup_s": round(setup_s, 1),
     }
 
+    result["prefill_quantize"] = prefill
+    result["speculation"] = speculation_loop(torch, B, caches[0], w, sm_scale, ws)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, k_host, v_host, sm_scale)
     print(json.dumps(result), flush=True)
+
+
+def time_prefill(torch, B, cache, kd, vd, w, reps=3):
+    """Bulk quantization of the whole prompt (Algorithm 1, prefill stage): fp16 K/V read once, both
+    planes and the metadata written once.  The kernel is bound by the quantizer's vector arithmetic."""
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    for i in range(reps):
+        ev[i].record()
+        B.qs_quantize_prefill(cache, kd, vd, w.n_quant)
+    ev[reps].record()
+    torch.cuda.synchronize()
+    us = min(ev[i].elapsed_time(ev[i + 1]) for i in range(reps)) * 1e3
+    nbytes = w.units * w.n_quant * (128 * 2 * 2 + 264)
+    return {"us": round(us, 1), "GBps_read_plus_write": round(nbytes / us / 1e3, 1), "bytes": nbytes,
+            "tokens_per_unit": w.n_quant, "bound": "alu"}
+
+
+def speculation_loop(torch, B, cache, w, sm_scale, ws, gammas=SPEC_GAMMAS, accept=0.9, cycles=24):
+    """Algorithm 1's decode loop with the buffer policy of Section 4.3.2, acceptance simulated: per
+    cycle gamma x (append one token, draft attention), rollback, append gamma + 1 target tokens,
+    verify attention, drop the rejected tokens, flush G tokens once 2G verified ones are buffered.
+    Reports cache-side microseconds per generated token (accepted drafts + the target's own token)."""
+    rng = np.random.default_rng(2502)
+    dev = cache.k_buf.device
+    out = {"accept_prob": accept, "cycles": cycles, "per_gamma": {}}
+    hkv, hq, G = w.n_kv_heads, w.n_q_heads, 128
+    for gamma in gammas:
+        nq = gamma + 1
+        k_new = torch.randn((w.batch, nq, hkv, 128), device=dev, dtype=torch.float16)
+        v_new = torch.randn_like(k_new)
+        q1 = torch.randn((w.batch, 1, hq, 128), device=dev, dtype=torch.float16)
+        qv = torch.randn((w.batch, nq, hq, 128), device=dev, dtype=torch.float16)
+        o1, ov = torch.empty_like(q1), torch.empty_like(qv)
+        tokens = flushes = 0
+        warm = 2                                        # untimed cycles: first launches of this gamma's kernels
+        for cyc in range(warm + cycles):
+            if cyc == warm:
+                tokens = flushes = 0
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+            if cache.n_buf.max() >= 2 * G:
+                B.qs_quantize_flush(cache, G)
+                cache.n_quant += G
+                cache.n_buf -= G
+                flushes += 1
+            for i in range(gamma):
+                B.qs_append(cache, k_new[:, i:i + 1].contiguous(), v_new[:, i:i + 1].contiguous())
+                cache.n_buf += 1
+                B.qs_attn_draft(cache, q1, sm_scale, out=o1, workspace=ws)
+            cache.n_buf -= gamma                        # the target pass rewrites the drafted positions
+            B.qs_append(cache, k_new, v_new)
+            cache.n_buf += nq
+            B.qs_attn_verify(cache, qv, sm_scale, out=ov, workspace=ws)
+            n_acc = 0
+            while n_acc < gamma and rng.random() < accept:
+                n_acc += 1
+            cache.n_buf -= gamma - n_acc                # rejected tokens leave the buffer
+            tokens += n_acc + 1
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        out["per_gamma"][str(gamma)] = {"us_per_token": round(dt * 1e6 / tokens, 2),
+                                        "tokens_per_cycle": round(tokens / cycles, 3), "flushes": flushes}
+    return out
 
 
 def cpu_baseline(w, k_host, v_host, sm_scale, sample_units=6):

@@ -14,6 +14,7 @@ constexpr int kDefaultCUs = 256;
 // waves per SIMD, the multi-row-tile kernels (more than 8 query rows per kv-head) one
 constexpr int kWavesPerCU = 8;
 constexpr int kWavesPerCUMultiTile = 4;
+constexpr int kMinBufSplits = 8;   // a decode-time buffer (2G + gamma + 1 tokens) always gets its 64-token chunks
 
 std::atomic<int> g_cu_count{0};
 
@@ -44,10 +45,11 @@ int validate_shape(const qs_cache* c) {
 int validate_cache(const qs_cache* c) {
   int rc = validate_shape(c);
   if (rc != QS_OK) return rc;
-  const void* ptrs[] = {c->k_upper, c->k_lower, c->v_upper, c->v_lower, c->k_scale,
-                        c->k_zero,  c->v_scale, c->v_zero,  c->k_buf,   c->v_buf};
-  for (const void* p : ptrs)
-    if (p == nullptr) return QS_ERR_NULL;
+  const void* ptrs[] = {c->k_buf,   c->v_buf,  c->k_upper, c->k_lower, c->v_upper,
+                        c->v_lower, c->k_scale, c->k_zero, c->v_scale, c->v_zero};
+  // a cache without a quantized region (q_cap == 0, everything in the fp16 buffer) needs no planes
+  for (int i = 0; i < (c->q_cap > 0 ? 10 : 2); ++i)
+    if (ptrs[i] == nullptr) return QS_ERR_NULL;
   if (c->n_quant == nullptr || c->n_buf == nullptr) return QS_ERR_NULL;
   for (const void* p : ptrs)
     if (!aligned16(p)) return QS_ERR_ALIGN;
@@ -59,8 +61,9 @@ int validate_cache(const qs_cache* c) {
 }
 
 // Number of chunks per unit.  The quantized region is cut so that about kWavesPerCU waves per
-// compute unit are resident; the buffer is cut into 64-token chunks.  Depends on shapes and on the
-// given maximum lengths only.
+// compute unit are resident; the buffer is cut into 64-token chunks, or, when it is so long that
+// these would exceed that budget too, into as many equal chunks as the budget allows.  Depends on
+// shapes and on the given maximum lengths only.
 struct Plan {
   int n_split_q, n_split_b;
 };
@@ -73,7 +76,8 @@ Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf) {
   const int want = (cu_count() * wpc + units - 1) / units;
   Plan p;
   p.n_split_q = std::max(1, std::min(want, groups));
-  p.n_split_b = std::max(1, (max_buf + kBufSplitTok - 1) / kBufSplitTok);
+  // the buffer: 64-token chunks while they fit the same budget of resident waves, longer ones beyond
+  p.n_split_b = std::max(1, std::min((max_buf + kBufSplitTok - 1) / kBufSplitTok, std::max(want, kMinBufSplits)));
   return p;
 }
 

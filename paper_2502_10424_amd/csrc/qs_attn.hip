@@ -430,7 +430,10 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
   const int lane = threadIdx.x, rho = lane & 15, g = lane >> 4;
   const bool lo_part = !KSPLIT && rho >= 8;   // the fp16 queries and keys need no remainder part
   const int nb = a.len.n_buf[b];
-  const int tb0 = (split - a.n_split_q) * kBufSplitTok;
+  // the buffer's 32-token blocks are dealt out evenly to its n_split_b chunks
+  const int n_blk = (nb + 31) >> 5, piece = split - a.n_split_q;
+  const int blk0 = (int)((int64_t)piece * n_blk / a.n_split_b);
+  const int blk1 = (int)((int64_t)(piece + 1) * n_blk / a.n_split_b);
 
   half8 qb[NRT][4];
   int vis[NRT];   // buffer tokens [0, vis) are visible to this lane's query (causal among the nq queries)
@@ -461,47 +464,55 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
   for (int rt = 0; rt < NRT; ++rt) mulb[rt] = a.c0;
   const _Float16* kb = a.k_buf + (int64_t)unit * a.buf_cap * kD;
   const _Float16* vb = a.v_buf + (int64_t)unit * a.buf_cap * kD;
+  const int tau = lane & 31, cc = lane >> 5;   // value rows: this lane's token of the block, channel half
 
-  for (int blk = 0; blk < kBufSplitTok / 32; ++blk) {
-    const int t0 = tb0 + 32 * blk;
-    if (t0 >= nb) break;
+  // One block = 32 tokens: keys as the A operand (lane = token rho of tile t, channels 32s + 8g ..),
+  // values as whole rows that go through the LDS transpose.  Rows past the end are clamped here and
+  // masked by the causal test below.
+  auto load_block = [&](int blk, u32x4 (&k)[2][4], u32x4 (&v)[8]) {
+    const int t0 = 32 * blk;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int tok = min(t0 + 16 * t + rho, nb - 1);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) k[t][s] = ldg128(kb + (int64_t)tok * kD + 32 * s + 8 * g);
+    }
+    const int tok = min(t0 + tau, nb - 1);
+#pragma unroll
+    for (int it = 0; it < 8; ++it) v[it] = ldg128(vb + (int64_t)tok * kD + 8 * (2 * it + cc));
+  };
+
+  u32x4 ka[2][4], va[8];   // the block being computed; the next one is in flight meanwhile
+  if (blk0 < blk1) load_block(blk0, ka, va);
+  for (int blk = blk0; blk < blk1; ++blk) {
+    const int t0 = 32 * blk;
+    u32x4 kn[2][4] = {}, vn[8] = {};
+    if (blk + 1 < blk1) load_block(blk + 1, kn, vn);
     float raw[NRT][8];
-    {
-      half8 ka[2][4];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        const int tok = min(t0 + 16 * t + rho, nb - 1);   // rows past the end are masked below
+        float4v acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s = 0; s < 4; ++s) ka[t][s] = as_half8(ldg128(kb + (int64_t)tok * kD + 32 * s + 8 * g));
-      }
+        for (int s = 0; s < 4; ++s)
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_half8(ka[t][s]), qb[rt][s], acc, 0, 0, 0);
 #pragma unroll
-      for (int rt = 0; rt < NRT; ++rt)
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          float4v acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-          for (int s = 0; s < 4; ++s) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qb[rt][s], acc, 0, 0, 0);
-#pragma unroll
-          for (int jj = 0; jj < 4; ++jj) {
-            const int tok = t0 + 16 * t + 4 * g + jj;
-            const float sc = KSPLIT ? acc[jj] : acc[jj] + xor8_in_row(acc[jj]);
-            raw[rt][4 * t + jj] = tok < vis[rt] ? sc : -__builtin_inff();
-          }
+        for (int jj = 0; jj < 4; ++jj) {
+          const int tok = t0 + 16 * t + 4 * g + jj;
+          const float sc = KSPLIT ? acc[jj] : acc[jj] + xor8_in_row(acc[jj]);
+          raw[rt][4 * t + jj] = tok < vis[rt] ? sc : -__builtin_inff();
         }
-    }
+      }
     softmax_block<NRT>(st, raw, mulb);
 
     __syncthreads();   // the previous block's LDS reads are done
-    {
-      const int tau = lane & 31, cc = lane >> 5;
-      const int tok = min(t0 + tau, nb - 1);
 #pragma unroll
-      for (int it = 0; it < 8; ++it) {
-        const int ch = 8 * (2 * it + cc);
-        const half8 v = as_half8(ldg128(vb + (int64_t)tok * kD + ch));
+    for (int it = 0; it < 8; ++it) {
+      const int ch = 8 * (2 * it + cc);
+      const half8 v = as_half8(va[it]);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) vt[ch + i][tau] = v[i];
-      }
+      for (int i = 0; i < 8; ++i) vt[ch + i][tau] = v[i];
     }
     __syncthreads();
     half8 pb[NRT];
@@ -514,11 +525,17 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
       const _Float16* rowp = &vt[8 * rho + n][0];
       const uint2 lo = *reinterpret_cast<const uint2*>(rowp + 4 * g);
       const uint2 hi = *reinterpret_cast<const uint2*>(rowp + 16 + 4 * g);
-      const half8 va = as_half8((u32x4){lo.x, lo.y, hi.x, hi.y});
+      const half8 vop = as_half8((u32x4){lo.x, lo.y, hi.x, hi.y});
 #pragma unroll
       for (int rt = 0; rt < NRT; ++rt)
-        st.o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pb[rt], st.o[rt][n], 0, 0, 0);
+        st.o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vop, pb[rt], st.o[rt][n], 0, 0, 0);
     }
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int s = 0; s < 4; ++s) ka[t][s] = kn[t][s];
+#pragma unroll
+    for (int it = 0; it < 8; ++it) va[it] = vn[it];
   }
   write_partial<NRT, RPT>(a, st, b, kvh, row0, split, 1.0f / kBufP);
 }

@@ -229,6 +229,39 @@ def test_attention_row_shapes(env, hq, hkv, nq):
         _check_attn(env, cache, oc, q, 0.11, False, tag=f"draft hq{hq} hkv{hkv}")
 
 
+@pytest.mark.parametrize("hq,hkv,nq,tq", [(4, 4, 1, 0), (8, 2, 5, 0), (16, 2, 7, 0), (4, 2, 3, 1024)])
+def test_attention_long_fp16_buffer(env, hq, hkv, nq, tq):
+    """Buffers far longer than a decode-time one: every chunk of the buffer walks many 32-token blocks.
+    With tq == 0 the cache has no quantized region at all (q_cap 0, no planes): plain fp16 attention,
+    the baseline the quantized paths are compared with.  Lengths are ragged and differ per sequence."""
+    torch, O, U, B = env["torch"], env["O"], env["U"], env["B"]
+    rng = np.random.default_rng(300 + hq + nq)
+    bsz = 2
+    nb = [5003, 2311]
+    cache = B.KVCache(bsz, hq, hkv, tq, 5120)
+    if tq == 0:
+        for name in ("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "k_zero", "v_scale", "v_zero"):
+            assert getattr(cache, name).numel() == 0
+    oc = O.CacheOracle(bsz, hq, hkv, 128, 128)
+    for b in range(bsz):
+        n = tq + nb[b]
+        k = (rng.standard_normal((1, hkv, n, 128)) * 1.5).astype(np.float16)
+        v = rng.standard_normal((1, hkv, n, 128)).astype(np.float16)
+        kd, vd = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+        if tq:
+            B.qs_quantize_prefill(U._seq_view(cache, b), kd, vd, tq)
+        cache.n_quant[b], cache.n_buf[b] = tq, nb[b]
+        cache.k_buf[b, :, :nb[b]] = kd[0, :, tq:]
+        cache.v_buf[b, :, :nb[b]] = vd[0, :, tq:]
+        ob = O.build_cache(k, v, hq, 128, nb[b])
+        for name in ("ku", "kl", "ks", "kz", "vu", "vl", "vs", "vz", "kbuf", "vbuf"):
+            getattr(oc, name)[b] = getattr(ob, name)[0]
+    q = rng.standard_normal((bsz, nq, hq, 128)).astype(np.float16)
+    _check_attn(env, cache, oc, q, 0.1, True, tag=f"long buffer verify hq{hq} hkv{hkv} nq{nq} tq{tq}")
+    if nq == 1:
+        _check_attn(env, cache, oc, q, 0.1, False, tag=f"long buffer draft hq{hq} hkv{hkv} tq{tq}")
+
+
 def test_attention_degenerate_cases(env):
     """Buffer only (no quantized tokens); buffer holding exactly the nq query tokens; peaked softmax."""
     O, U = env["O"], env["U"]
