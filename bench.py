@@ -94,6 +94,10 @@ def main():
         c.n_quant[:] = w.n_quant
         c.n_buf[:] = w.n_buf
         caches.append(c)
+    # the same tokens as a plain fp16 cache (no quantized region): the baseline of Table 4
+    fp16_cache = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, 0, w.ctx)
+    fp16_cache.k_buf, fp16_cache.v_buf = kd, vd
+    fp16_cache.n_buf[:] = w.ctx
     del kd, vd
     ws = torch.empty(max(B.qs_workspace_bytes(caches[0], n) for n in (1, nqv, max(SPEC_GAMMAS) + 1)),
                      dtype=torch.uint8, device=dev)
@@ -171,6 +175,9 @@ def main():
     }
 
     result["prefill_quantize"] = prefill
+    result["fp16_baseline"] = fp16_baseline(torch, B, fp16_cache, w, sm_scale, q_draft, q_verify,
+                                            avg_us["draft"], avg_us["verify"])
+    del fp16_cache
     result["speculation"] = speculation_loop(torch, B, caches[0], w, sm_scale, ws)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, k_host, v_host, sm_scale)
@@ -190,6 +197,30 @@ def time_prefill(torch, B, cache, kd, vd, w, reps=3):
     nbytes = w.units * w.n_quant * (128 * 2 * 2 + 264)
     return {"us": round(us, 1), "GBps_read_plus_write": round(nbytes / us / 1e3, 1), "bytes": nbytes,
             "tokens_per_unit": w.n_quant, "bound": "alu"}
+
+
+def fp16_baseline(torch, B, cache, w, sm_scale, q_draft, q_verify, draft_us, verify_us, reps=10):
+    """The library's own attention over the same context held entirely in fp16 (q_cap = 0): what the
+    INT4 draft and INT8 verify calls are compared with, as in Table 4."""
+    ws = torch.empty(B.qs_workspace_bytes(cache, q_verify.shape[1]), dtype=torch.uint8, device=q_draft.device)
+    res = {}
+    nbytes = w.units * w.ctx * 128 * 2 * 2
+    for tag, q in (("1_query", q_draft), (f"{q_verify.shape[1]}_queries", q_verify)):
+        out = torch.empty_like(q)
+        for _ in range(3):
+            B.qs_attn_verify(cache, q, sm_scale, out=out, workspace=ws)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        for i in range(reps):
+            ev[i].record()
+            B.qs_attn_verify(cache, q, sm_scale, out=out, workspace=ws)
+        ev[reps].record()
+        torch.cuda.synchronize()
+        us = float(np.mean([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)])) * 1e3
+        res[tag] = {"us": round(us, 2), "GBps": round(nbytes / us / 1e3, 1)}
+    res["bytes"] = nbytes
+    res["draft_speedup_vs_fp16"] = round(res["1_query"]["us"] / draft_us, 3)
+    res["verify_speedup_vs_fp16"] = round(res[f"{q_verify.shape[1]}_queries"]["us"] / verify_us, 3)
+    return res
 
 
 def speculation_loop(torch, B, cache, w, sm_scale, ws, gammas=SPEC_GAMMAS, accept=0.9, cycles=24):
