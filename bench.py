@@ -54,6 +54,8 @@ def main():
     ap.add_argument("--workload", default="mha128k")
     ap.add_argument("--copies", type=int, default=3, help="independent cache copies to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the timed cycle: no prefill timing, fp16 baseline or speculation loop (for kernel traces)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; every figure is the one GPU's throughput. "
@@ -85,7 +87,7 @@ def main():
         c = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, q_cap, w.n_buf + 8)
         if i == 0:
             B.qs_quantize_prefill(c, kd, vd, w.n_quant)
-            prefill = time_prefill(torch, B, c, kd, vd, w)
+            prefill = None if args.no_extras else time_prefill(torch, B, c, kd, vd, w)
         else:
             for name in ("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "k_zero", "v_scale", "v_zero"):
                 getattr(c, name).copy_(getattr(caches[0], name))
@@ -174,11 +176,12 @@ def main():
         "setup_s": round(setup_s, 1),
     }
 
-    result["prefill_quantize"] = prefill
-    result["fp16_baseline"] = fp16_baseline(torch, B, fp16_cache, w, sm_scale, q_draft, q_verify,
-                                            avg_us["draft"], avg_us["verify"])
+    if not args.no_extras:
+        result["prefill_quantize"] = prefill
+        result["fp16_baseline"] = fp16_baseline(torch, B, fp16_cache, w, sm_scale, q_draft, q_verify,
+                                                avg_us["draft"], avg_us["verify"])
+        result["speculation"] = speculation_loop(torch, B, caches[0], w, sm_scale, ws)
     del fp16_cache
-    result["speculation"] = speculation_loop(torch, B, caches[0], w, sm_scale, ws)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, k_host, v_host, sm_scale)
     print(json.dumps(result), flush=True)
