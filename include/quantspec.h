@@ -36,8 +36,11 @@
  *                        32-token tile for the token defined above (the order the kernels consume).
  *   qs_quantize_flush is the only writer of these arrays; qs_export_codes returns them in the
  *   plain [token][channel] order for inspection.
- *   Full-precision buffer (Section 4.3.2), plain row-major, written by the caller:
+ *   Full-precision buffer (Section 4.3.2), plain row-major, written by the caller or by qs_append:
  *     k_buf, v_buf     : fp16  [B][Hkv][buf_cap][128]   tokens [0, n_buf[b]) are valid.
+ *   A cache may have no quantized region at all: q_cap == 0, n_quant[b] == 0, and the eight plane and
+ *   metadata pointers may then be NULL.  The attention calls are then plain fp16 attention over the
+ *   buffer, of any length up to buf_cap (the full-precision baseline of the paper's Table 4).
  */
 #ifndef QUANTSPEC_H_
 #define QUANTSPEC_H_
