@@ -11,6 +11,7 @@ planes.  Prints ONE JSON line.
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -135,11 +136,18 @@ def main():
     for i in range(args.warmup):
         cycle(i, False)
     torch.cuda.synchronize()
+    gc.collect()
+    gc.disable()                      # no collector pause inside the timed region
     t_start = time.perf_counter()
     for i in range(args.steps):
         cycle(args.warmup + i, True)
+        if i >= 2:
+            # stay at most two cycles ahead of the GPU (a decoder reads each cycle's outcome anyway);
+            # letting the host queue hundreds of launches ahead has stalled the runtime for tens of ms
+            timed["flush"][i - 2][1].synchronize()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
+    gc.enable()
 
     ms_per_step = elapsed * 1e3 / args.steps
     avg_us = {k: 1e3 * float(np.mean([a.elapsed_time(b) / n for a, b, n in v])) for k, v in timed.items()}

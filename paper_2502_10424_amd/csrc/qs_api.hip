@@ -73,7 +73,8 @@ Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf) {
   const int groups = max_quant / kG;
   const int n_rows = nq * (c->n_q_heads / c->n_kv_heads);
   const int wpc = n_rows <= 8 ? kWavesPerCU : kWavesPerCUMultiTile;
-  const int want = (cu_count() * wpc + units - 1) / units;
+  // never more long chunks than resident slots: a chunk that starts late doubles the launch time
+  const int want = std::max(1, cu_count() * wpc / units);
   Plan p;
   p.n_split_q = std::max(1, std::min(want, groups));
   // the buffer: 64-token chunks while they fit the same budget of resident waves, longer ones beyond

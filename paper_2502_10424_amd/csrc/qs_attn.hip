@@ -545,7 +545,12 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
 template <int NRT, bool VERIFY, bool KSPLIT>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NRT == 1 && !KSPLIT ? 2 : 1))) void attn_kernel(AttnArgs a) {
   __shared__ _Float16 vt[kD][kVtStride];   // value-tile transpose of the buffer chunk
-  const int split = blockIdx.x, unit = blockIdx.y, row0 = blockIdx.z * (KSPLIT ? 16 : 8) * NRT;
+  // Dispatch order: unit fastest, the (short) buffer chunks of every unit before any quantized
+  // chunk, so that the long chunks all start together once the short ones have drained and none
+  // has to wait for a slot behind a long one.  `split` is the chunk's slot in the workspace:
+  // quantized chunks first, buffer chunks after them.
+  const int unit = blockIdx.x, row0 = blockIdx.z * (KSPLIT ? 16 : 8) * NRT;
+  const int split = (int)blockIdx.y < a.n_split_b ? a.n_split_q + blockIdx.y : blockIdx.y - a.n_split_b;
   const int b = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   if (split < a.n_split_q)
     quant_chunk<NRT, VERIFY, KSPLIT>(a, unit, b, kvh, row0, split);
@@ -602,7 +607,7 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
 template <int NRT, bool KSPLIT>
 hipError_t launch_attn_nrt(const AttnArgs& a, int batch, bool verify, hipStream_t s) {
   constexpr int rows = (KSPLIT ? 16 : 8) * NRT;
-  dim3 grid(a.n_split_q + a.n_split_b, batch * a.n_kv_heads, (a.n_rows + rows - 1) / rows);
+  dim3 grid(batch * a.n_kv_heads, a.n_split_q + a.n_split_b, (a.n_rows + rows - 1) / rows);
   if (verify)
     hipLaunchKernelGGL((attn_kernel<NRT, true, KSPLIT>), grid, dim3(64), 0, s, a);
   else
