@@ -60,8 +60,11 @@ __device__ __forceinline__ half8 unpack4(uint32_t x) {
 // Upper and lower nibbles -> eight 8-bit codes 16*C_U + (C_L + 8) as fp16 subnormals (x 2^-24),
 // same element order as unpack4.
 __device__ __forceinline__ half8 unpack8(uint32_t u, uint32_t l) {
-  const uint32_t even = ((u << 4) & 0xF0F0F0F0u) | (l & 0x0F0F0F0Fu);   // nibbles 0,2,4,6 -> bytes 0..3
-  const uint32_t odd = (u & 0xF0F0F0F0u) | ((l >> 4) & 0x0F0F0F0Fu);    // nibbles 1,3,5,7 -> bytes 0..3
+  uint32_t even = ((u << 4) & 0xF0F0F0F0u) | (l & 0x0F0F0F0Fu);   // nibbles 0,2,4,6 -> bytes 0..3
+  uint32_t odd = (u & 0xF0F0F0F0u) | ((l >> 4) & 0x0F0F0F0Fu);    // nibbles 1,3,5,7 -> bytes 0..3
+  // keep the two merged words as they are: folding the masks below into their construction costs
+  // four more instructions per call than using them (8 instead of 12 for eight codes)
+  asm volatile("" : "+v"(even), "+v"(odd));
   u32x4 r;
   r[0] = even & 0x00FF00FFu;                                  // nibbles 0, 4
   r[1] = odd & 0x00FF00FFu;                                   // nibbles 1, 5
@@ -103,17 +106,19 @@ struct RowState {
 };
 
 // Online-softmax update for one 32-token block.  raw[rt][j] are this lane's eight scores (query
-// column rho, tokens tile_token(g, j)) before scaling; on return they hold the probabilities.
-// The running max only moves when some score of the wave exceeds it; otherwise the cross-lane
-// reduction and the rescaling of the accumulators are skipped altogether.
+// column rho, tokens tile_token(g, j)) before scaling, each still short of the additive term
+// bias[rt] (the zero-point part of the score, the same for every token of a group); on return they
+// hold the probabilities.  The running max only moves when some score of the wave exceeds it;
+// otherwise the cross-lane reduction and the rescaling of the accumulators are skipped altogether.
 template <int NRT>
-__device__ __forceinline__ void softmax_block(RowState<NRT>& st, float (&raw)[NRT][8], const float (&mul)[NRT]) {
+__device__ __forceinline__ void softmax_block(RowState<NRT>& st, float (&raw)[NRT][8], const float (&mul)[NRT],
+                                              const float (&bias)[NRT]) {
   float mx[NRT];
   bool grow = false;
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
-    mx[rt] = fmaxf(fmaxf(fmaxf(raw[rt][0], raw[rt][1]), fmaxf(raw[rt][2], raw[rt][3])),
-                   fmaxf(fmaxf(raw[rt][4], raw[rt][5]), fmaxf(raw[rt][6], raw[rt][7]))) * mul[rt];   // mul > 0
+    mx[rt] = (fmaxf(fmaxf(fmaxf(raw[rt][0], raw[rt][1]), fmaxf(raw[rt][2], raw[rt][3])),
+                    fmaxf(fmaxf(raw[rt][4], raw[rt][5]), fmaxf(raw[rt][6], raw[rt][7]))) + bias[rt]) * mul[rt];   // mul > 0
     grow |= mx[rt] > st.m[rt];
   }
   if (__any(grow)) {
@@ -130,10 +135,11 @@ __device__ __forceinline__ void softmax_block(RowState<NRT>& st, float (&raw)[NR
   }
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
+    const float shift = __builtin_fmaf(bias[rt], mul[rt], -st.m[rt]);
     float sum = 0.f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      raw[rt][j] = __builtin_amdgcn_exp2f(__builtin_fmaf(raw[rt][j], mul[rt], -st.m[rt]));
+      raw[rt][j] = __builtin_amdgcn_exp2f(__builtin_fmaf(raw[rt][j], mul[rt], shift));
       sum += raw[rt][j];
     }
     st.l[rt] += sum;
@@ -325,7 +331,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
       float bias = __builtin_fmaf(acc_b[rt], 1.0f / kKeyPos, acc_a[rt]);
       if (VERIFY) bias -= 0.5f * __builtin_fmaf(acc_sb[rt], 1.0f / kKeyPos, acc_sa[rt]);
       bias = group_sum(bias);
-      cin[rt] = lo_part ? 0.f : bias * (1.0f / kKeyRaw);
+      cin[rt] = bias * (1.0f / kKeyRaw);   // added to the raw scores inside the softmax step
 #pragma unroll
       for (int h = 0; h < NQB; ++h)
 #pragma unroll
@@ -348,7 +354,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
       for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-          float4v acc = {cin[rt], cin[rt], cin[rt], cin[rt]};
+          float4v acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int s = 0; s < 4; ++s) {
             acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qb[rt][0][s], acc, 0, 0, 0);
@@ -359,7 +365,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
         }
     }
     prep_kstep(P, d.kS, d.kZ);   // one k-step of the next group's query operand
-    softmax_block<NRT>(st, raw, mul);
+    softmax_block<NRT>(st, raw, mul, cin);
 
     // ---- probabilities x value scale -> B operand; zero-point term ----
     const half8 vS = as_half8(d.vS), vZ = as_half8(d.vZ);
@@ -459,9 +465,9 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
 #pragma unroll
     for (int n = 0; n < 8; ++n) st.o[rt][n] = (float4v){0.f, 0.f, 0.f, 0.f};
   }
-  float mulb[NRT];
+  float mulb[NRT], zero_bias[NRT];
 #pragma unroll
-  for (int rt = 0; rt < NRT; ++rt) mulb[rt] = a.c0;
+  for (int rt = 0; rt < NRT; ++rt) mulb[rt] = a.c0, zero_bias[rt] = 0.f;
   const _Float16* kb = a.k_buf + (int64_t)unit * a.buf_cap * kD;
   const _Float16* vb = a.v_buf + (int64_t)unit * a.buf_cap * kD;
   const int tau = lane & 31, cc = lane >> 5;   // value rows: this lane's token of the block, channel half
@@ -504,7 +510,7 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
           raw[rt][4 * t + jj] = tok < vis[rt] ? sc : -__builtin_inff();
         }
       }
-    softmax_block<NRT>(st, raw, mulb);
+    softmax_block<NRT>(st, raw, mulb, zero_bias);
 
     __syncthreads();   // the previous block's LDS reads are done
 #pragma unroll
