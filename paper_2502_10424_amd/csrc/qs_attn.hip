@@ -565,48 +565,66 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NRT == 1 && 
 }
 
 // Merge of the per-chunk partials (Appendix E): M = max m_i, L = sum l_i 2^(m_i - M),
-// out = sum o_i 2^(m_i - M) / L.  One 256-thread workgroup per query row: thread (sl, c) sums chunks
-// sl, sl+8, ... for channels 4c..4c+3, then the eight partial sums are combined through LDS.
+// out = sum o_i 2^(m_i - M) / L.  One 256-thread workgroup per query row: thread (sl, c) folds chunks
+// sl, sl+8, ... for channels 4c..4c+3 into a running (m, l, o) of its own, eight chunks per step
+// with all their loads issued together, so a typical row is one memory round trip; the eight slices
+// are then combined through LDS.
 __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
-  __shared__ float red_m[256];
   __shared__ float red_o[8][kD + 4];
-  __shared__ float red_l[8];
+  __shared__ float red_m[8], red_l[8];
+  constexpr int U = 8;
   const int64_t row = blockIdx.x;
   const int tid = threadIdx.x, sl = tid >> 5, c = tid & 31;
-  const float* ml = a.ws_ml + row * a.n_split * 2;
-  const float* po = a.ws_o + row * a.n_split * kD + 4 * c;
-  float m = kNegBig;
-  for (int s = tid; s < a.n_split; s += 256) m = fmaxf(m, ml[2 * s]);
-  red_m[tid] = m;
-  __syncthreads();
-#pragma unroll
-  for (int w = 128; w > 0; w >>= 1) {
-    if (tid < w) red_m[tid] = fmaxf(red_m[tid], red_m[tid + w]);
-    __syncthreads();
-  }
-  m = red_m[0];
-  float l = 0.f;
+  const float* __restrict__ ml = a.ws_ml + row * a.n_split * 2;
+  const float* __restrict__ po = a.ws_o + row * a.n_split * kD + 4 * c;
+  float m = kNegBig, l = 0.f;
   float4v o = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-  for (int s = sl; s < a.n_split; s += 8) {
-    const float w = __builtin_amdgcn_exp2f(ml[2 * s] - m);
-    const float4v x = *reinterpret_cast<const float4v*>(po + (int64_t)s * kD);
-    l = __builtin_fmaf(w, ml[2 * s + 1], l);
-    o += w * x;
+  for (int s0 = sl; s0 < a.n_split; s0 += 8 * U) {
+    float ms[U], ls[U];
+    float4v xs[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int s = s0 + 8 * u;
+      const int sc = min(s, a.n_split - 1);   // past the end: a valid address, weight 0
+      const float2 p = *reinterpret_cast<const float2*>(ml + 2 * sc);
+      ms[u] = s < a.n_split ? p.x : kNegBig;
+      ls[u] = p.y;
+      xs[u] = *reinterpret_cast<const float4v*>(po + (int64_t)sc * kD);
+    }
+    float mb = m;
+#pragma unroll
+    for (int u = 0; u < U; ++u) mb = fmaxf(mb, ms[u]);
+    const float down = __builtin_amdgcn_exp2f(m - mb);
+    l *= down;
+    o *= down;
+    m = mb;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float w = __builtin_amdgcn_exp2f(ms[u] - m);   // 0 for an empty chunk or past the end
+      l = __builtin_fmaf(w, ls[u], l);
+      o += w * xs[u];
+    }
   }
 #pragma unroll
   for (int i = 0; i < 4; ++i) red_o[sl][4 * c + i] = o[i];
-  if (c == 0) red_l[sl] = l;
+  if (c == 0) {
+    red_m[sl] = m;
+    red_l[sl] = l;
+  }
   __syncthreads();
   if (tid < kD) {
-    float os = 0.f, ls = 0.f;
+    float mm = red_m[0];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) mm = fmaxf(mm, red_m[k]);
+    float os = 0.f, lsum = 0.f;
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
-      os += red_o[k][tid];
-      ls += red_l[k];
+      const float w = __builtin_amdgcn_exp2f(red_m[k] - mm);
+      os = __builtin_fmaf(w, red_o[k][tid], os);
+      lsum = __builtin_fmaf(w, red_l[k], lsum);
     }
-    a.out[row * kD + tid] = (_Float16)(os / ls);
-    if (a.lse != nullptr && tid == 0) a.lse[row] = (m + __builtin_log2f(ls)) * 0.6931471805599453f;
+    a.out[row * kD + tid] = (_Float16)(os / lsum);
+    if (a.lse != nullptr && tid == 0) a.lse[row] = (mm + __builtin_log2f(lsum)) * 0.6931471805599453f;
   }
 }
 
