@@ -90,7 +90,7 @@ def main():
             B.qs_quantize_prefill(c, kd, vd, w.n_quant)
             prefill = None if args.no_extras else time_prefill(torch, B, c, kd, vd, w)
         else:
-            for name in ("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "k_zero", "v_scale", "v_zero"):
+            for name in B.PLANES:
                 getattr(c, name).copy_(getattr(caches[0], name))
         c.k_buf[:, :, :w.n_buf] = kd[:, :, w.n_quant:]
         c.v_buf[:, :, :w.n_buf] = vd[:, :, w.n_quant:]

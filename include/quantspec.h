@@ -19,27 +19,32 @@
  *   - All device pointers must be 16-byte aligned.
  *
  * Cache layout (B = batch, Hkv = n_kv_heads, "unit" = one (sequence, kv-head) pair)
- *   Keys, per-channel groups of 128 tokens (Section 4.3.1):
- *     k_upper, k_lower : uint8 [B][Hkv][q_cap][64]   two codes per byte; byte j of a token row holds
- *                        channel 2j in bits 0-3 and channel 2j+1 in bits 4-7.
- *                        k_upper nibble = C_U (0..15); k_lower nibble = C_L + 8 (0..15).
- *     k_scale, k_zero  : fp16  [B][Hkv][q_cap/128][128]   S and Z of (token group, channel), stored in the
- *                        order the kernels consume: position 32*s + 8*g + e (s<4, g<4, e<8) holds channel
- *                        32*g + 8*s + (e&1)*4 + (e>>1).
- *   Values, per-token groups of 128 channels:
- *     v_upper, v_lower : uint8 [B][Hkv][q_cap/32][2048]   tiled for the matrix-core operand: inside a
- *                        32-token tile, 32-bit word ((h*64 + 16*g + m)*4 + i) holds channel
- *                        8*m + 4*h + i (h<2, g<4, m<16, i<4) of eight tokens; nibble (j&1)*4 + (j>>1)
- *                        (j<8) belongs to token (j>>2)*16 + 4*g + (j&3) of the tile.
- *                        Same nibble encodings as for keys.
- *     v_scale, v_zero  : fp16  [B][Hkv][q_cap]   S and Z per token, stored at position 8*g + j of the
- *                        32-token tile for the token defined above (the order the kernels consume).
- *   qs_quantize_flush is the only writer of these arrays; qs_export_codes returns them in the
- *   plain [token][channel] order for inspection.
+ *   The quantized region is two arrays, the paper's C_U and C_L, cut into blocks of 32 tokens so that
+ *   the draft pass streams one array and the target pass two, each front to back:
+ *     upper : uint8 [B][Hkv][q_cap/32][4352]   per block
+ *               [   0, 2048)  key codes C_U, 32 token rows of 64 bytes: byte j of a row holds channel 2j
+ *                             in bits 0-3 and channel 2j+1 in bits 4-7
+ *               [2048, 4096)  value codes C_U, tiled for the matrix-core operand: 32-bit word
+ *                             ((h*64 + 16*g + m)*4 + i) holds channel 8*m + 4*h + i (h<2, g<4, m<16, i<4)
+ *                             of eight tokens; nibble (j&1)*4 + (j>>1) (j<8) belongs to token
+ *                             (j>>2)*16 + 4*g + (j&3) of the block
+ *               [4096, 4160)  value scale S, fp16, one per token, at position 8*g + j for the token above
+ *               [4160, 4224)  value zero Z, same order
+ *               [4224, 4288)  key scale S, fp16: 32 of the 128 per-channel values of the block's
+ *                             128-token group.  Block p (= block index mod 4) of a group holds positions
+ *                             [32p, 32p+32) of the group's operand order, in which position
+ *                             32*s + 8*g + e (s<4, g<4, e<8) is channel 32*g + 8*s + (e&1)*4 + (e>>1)
+ *               [4288, 4352)  key zero Z, same order
+ *     lower : uint8 [B][Hkv][q_cap/32][4096]   per block
+ *               [   0, 2048)  key codes C_L + 8 (0..15), same arrangement as in the upper array
+ *               [2048, 4096)  value codes C_L + 8, likewise
+ *   Keys are grouped per channel over 128 consecutive tokens, values per token over the 128 channels
+ *   (Section 4.3.1); both planes share S and Z.  qs_quantize_flush / qs_quantize_prefill are the only
+ *   writers of these arrays; qs_export_codes returns plain [token][channel] codes and metadata.
  *   Full-precision buffer (Section 4.3.2), plain row-major, written by the caller or by qs_append:
  *     k_buf, v_buf     : fp16  [B][Hkv][buf_cap][128]   tokens [0, n_buf[b]) are valid.
- *   A cache may have no quantized region at all: q_cap == 0, n_quant[b] == 0, and the eight plane and
- *   metadata pointers may then be NULL.  The attention calls are then plain fp16 attention over the
+ *   A cache may have no quantized region at all: q_cap == 0, n_quant[b] == 0, and upper / lower may
+ *   then be NULL.  The attention calls are then plain fp16 attention over the
  *   buffer, of any length up to buf_cap (the full-precision baseline of the paper's Table 4).
  */
 #ifndef QUANTSPEC_H_
@@ -71,10 +76,7 @@ typedef struct qs_cache {
   int32_t head_dim, group;                /* both 128                                                 */
   int32_t q_cap;                          /* capacity of the quantized region in tokens, multiple of 128 */
   int32_t buf_cap;                        /* capacity of the fp16 buffer in tokens                    */
-  void *k_upper, *k_lower;                /* device, see layout above                                 */
-  void *v_upper, *v_lower;
-  void *k_scale, *k_zero;
-  void *v_scale, *v_zero;
+  void *upper, *lower;                    /* device, C_U and C_L, see layout above                    */
   void *k_buf, *v_buf;
   const int32_t *n_quant;                 /* HOST int32[batch]: valid quantized tokens (multiple of 128) */
   const int32_t *n_buf;                   /* HOST int32[batch]: valid buffer tokens                   */

@@ -19,6 +19,9 @@ QS_MAX_BATCH = 64
 QS_MAX_NQ = 8
 HEAD_DIM = 128
 GROUP = 128
+UPPER_BLOCK_BYTES = 4352     # per 32 tokens: key codes, value codes, value S/Z, a quarter of the group's key S/Z
+LOWER_BLOCK_BYTES = 4096     # per 32 tokens: key codes, value codes
+PLANES = ("upper", "lower")  # the device arrays of the quantized region (C_U and C_L)
 
 QS_OK = 0
 QS_ERR_NULL, QS_ERR_SHAPE, QS_ERR_UNSUPPORTED, QS_ERR_ALIGN = -1, -2, -3, -4
@@ -33,10 +36,7 @@ class qs_cache(ctypes.Structure):
         ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
         ("head_dim", ctypes.c_int32), ("group", ctypes.c_int32),
         ("q_cap", ctypes.c_int32), ("buf_cap", ctypes.c_int32),
-        ("k_upper", ctypes.c_void_p), ("k_lower", ctypes.c_void_p),
-        ("v_upper", ctypes.c_void_p), ("v_lower", ctypes.c_void_p),
-        ("k_scale", ctypes.c_void_p), ("k_zero", ctypes.c_void_p),
-        ("v_scale", ctypes.c_void_p), ("v_zero", ctypes.c_void_p),
+        ("upper", ctypes.c_void_p), ("lower", ctypes.c_void_p),
         ("k_buf", ctypes.c_void_p), ("v_buf", ctypes.c_void_p),
         ("n_quant", ctypes.POINTER(ctypes.c_int32)), ("n_buf", ctypes.POINTER(ctypes.c_int32)),
     ]
@@ -108,14 +108,8 @@ class KVCache:
         u8 = dict(dtype=torch.uint8, device=device)
         f16 = dict(dtype=torch.float16, device=device)
         qc = max(q_cap, 0)
-        self.k_upper = torch.zeros((batch, n_kv_heads, qc, 64), **u8)
-        self.k_lower = torch.zeros((batch, n_kv_heads, qc, 64), **u8)
-        self.v_upper = torch.zeros((batch, n_kv_heads, qc // 32, 2048), **u8)
-        self.v_lower = torch.zeros((batch, n_kv_heads, qc // 32, 2048), **u8)
-        self.k_scale = torch.zeros((batch, n_kv_heads, qc // 128, 128), **f16)
-        self.k_zero = torch.zeros((batch, n_kv_heads, qc // 128, 128), **f16)
-        self.v_scale = torch.zeros((batch, n_kv_heads, qc), **f16)
-        self.v_zero = torch.zeros((batch, n_kv_heads, qc), **f16)
+        self.upper = torch.zeros((batch, n_kv_heads, qc // 32, UPPER_BLOCK_BYTES), **u8)
+        self.lower = torch.zeros((batch, n_kv_heads, qc // 32, LOWER_BLOCK_BYTES), **u8)
         self.k_buf = torch.zeros((batch, n_kv_heads, buf_cap, 128), **f16)
         self.v_buf = torch.zeros((batch, n_kv_heads, buf_cap, 128), **f16)
         self.n_quant = np.zeros(batch, np.int32)
@@ -125,7 +119,7 @@ class KVCache:
         c = qs_cache()
         c.batch, c.n_q_heads, c.n_kv_heads = self.batch, self.n_q_heads, self.n_kv_heads
         c.head_dim, c.group, c.q_cap, c.buf_cap = self.head_dim, self.group, self.q_cap, self.buf_cap
-        for name in ("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "k_zero", "v_scale", "v_zero",
+        for name in ("upper", "lower",
                      "k_buf", "v_buf"):
             setattr(c, name, getattr(self, name).data_ptr())
         c.n_quant = self.n_quant.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
@@ -134,7 +128,7 @@ class KVCache:
 
     def plane_bytes(self) -> int:
         return sum(getattr(self, n).numel() * getattr(self, n).element_size()
-                   for n in ("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "k_zero", "v_scale", "v_zero"))
+                   for n in PLANES)
 
 
 def _as_struct(cache) -> qs_cache:
@@ -209,7 +203,7 @@ def qs_export_codes(cache: KVCache, b: int, kv_head: int, n_tokens: int, stream=
     """Plain-order codes and metadata of one unit, as a dict of device tensors:
     k_u, v_u uint8 [T,128]; k_l, v_l int8 [T,128]; k_s, k_z fp16 [T/128,128]; v_s, v_z fp16 [T]."""
     c = cache.struct()
-    dev = cache.k_upper.device
+    dev = cache.k_buf.device
     k_u = torch.empty((n_tokens, 128), dtype=torch.uint8, device=dev)
     v_u = torch.empty_like(k_u)
     k_l = torch.empty((n_tokens, 128), dtype=torch.int8, device=dev)

@@ -45,10 +45,9 @@ int validate_shape(const qs_cache* c) {
 int validate_cache(const qs_cache* c) {
   int rc = validate_shape(c);
   if (rc != QS_OK) return rc;
-  const void* ptrs[] = {c->k_buf,   c->v_buf,  c->k_upper, c->k_lower, c->v_upper,
-                        c->v_lower, c->k_scale, c->k_zero, c->v_scale, c->v_zero};
+  const void* ptrs[] = {c->k_buf, c->v_buf, c->upper, c->lower};
   // a cache without a quantized region (q_cap == 0, everything in the fp16 buffer) needs no planes
-  for (int i = 0; i < (c->q_cap > 0 ? 10 : 2); ++i)
+  for (int i = 0; i < (c->q_cap > 0 ? 4 : 2); ++i)
     if (ptrs[i] == nullptr) return QS_ERR_NULL;
   if (c->n_quant == nullptr || c->n_buf == nullptr) return QS_ERR_NULL;
   for (const void* p : ptrs)
@@ -102,14 +101,8 @@ int attn_common(const qs_cache* c, const void* q, int32_t nq, void* out, float s
   const int64_t rows_total = (int64_t)c->batch * nq * c->n_q_heads;
 
   AttnArgs a;
-  a.k_upper = static_cast<const uint32_t*>(c->k_upper);
-  a.k_lower = static_cast<const uint32_t*>(c->k_lower);
-  a.v_upper = static_cast<const uint32_t*>(c->v_upper);
-  a.v_lower = static_cast<const uint32_t*>(c->v_lower);
-  a.k_scale = static_cast<const _Float16*>(c->k_scale);
-  a.k_zero = static_cast<const _Float16*>(c->k_zero);
-  a.v_scale = static_cast<const _Float16*>(c->v_scale);
-  a.v_zero = static_cast<const _Float16*>(c->v_zero);
+  a.upper = static_cast<const uint8_t*>(c->upper);
+  a.lower = static_cast<const uint8_t*>(c->lower);
   a.k_buf = static_cast<const _Float16*>(c->k_buf);
   a.v_buf = static_cast<const _Float16*>(c->v_buf);
   a.q = static_cast<const _Float16*>(q);
@@ -148,14 +141,8 @@ int quantize_common(const qs_cache* c, const _Float16* k_src, const _Float16* v_
   f.k_src = k_src;
   f.v_src = v_src;
   f.src_stride = src_stride;
-  f.k_upper = static_cast<uint32_t*>(c->k_upper);
-  f.k_lower = static_cast<uint32_t*>(c->k_lower);
-  f.v_upper = static_cast<uint32_t*>(c->v_upper);
-  f.v_lower = static_cast<uint32_t*>(c->v_lower);
-  f.k_scale = static_cast<_Float16*>(c->k_scale);
-  f.k_zero = static_cast<_Float16*>(c->k_zero);
-  f.v_scale = static_cast<_Float16*>(c->v_scale);
-  f.v_zero = static_cast<_Float16*>(c->v_zero);
+  f.upper = static_cast<uint8_t*>(c->upper);
+  f.lower = static_cast<uint8_t*>(c->lower);
   f.n_kv_heads = c->n_kv_heads;
   f.q_cap = c->q_cap;
   f.n_groups = n_tokens / kG;
@@ -272,16 +259,10 @@ int qs_export_codes(const qs_cache* c, int32_t b, int32_t kv_head, int32_t n_tok
   if (n_tokens < 0 || n_tokens % kG != 0 || n_tokens > c->q_cap) return QS_ERR_RANGE;
   const int64_t unit = (int64_t)b * c->n_kv_heads + kv_head;
   ExportArgs e;
-  e.k_upper = static_cast<const uint32_t*>(c->k_upper) + unit * c->q_cap * kRowDw;
-  e.k_lower = static_cast<const uint32_t*>(c->k_lower) + unit * c->q_cap * kRowDw;
-  e.v_upper = static_cast<const uint32_t*>(c->v_upper) + unit * c->q_cap * kRowDw;
-  e.v_lower = static_cast<const uint32_t*>(c->v_lower) + unit * c->q_cap * kRowDw;
-  e.k_scale = static_cast<const _Float16*>(c->k_scale) + unit * c->q_cap;
-  e.k_zero = static_cast<const _Float16*>(c->k_zero) + unit * c->q_cap;
+  e.upper = static_cast<const uint8_t*>(c->upper) + unit * (c->q_cap / kBlkTok) * kUpperBlk;
+  e.lower = static_cast<const uint8_t*>(c->lower) + unit * (c->q_cap / kBlkTok) * kLowerBlk;
   e.k_s = static_cast<_Float16*>(k_s);
   e.k_z = static_cast<_Float16*>(k_z);
-  e.v_scale = static_cast<const _Float16*>(c->v_scale) + unit * c->q_cap;
-  e.v_zero = static_cast<const _Float16*>(c->v_zero) + unit * c->q_cap;
   e.k_u = static_cast<uint8_t*>(k_u);
   e.k_l = static_cast<int8_t*>(k_l);
   e.v_u = static_cast<uint8_t*>(v_u);

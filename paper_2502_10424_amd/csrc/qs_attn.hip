@@ -28,6 +28,10 @@
 
 #include "qs_internal.h"
 
+#ifndef QS_AHEAD
+#define QS_AHEAD ((!VERIFY && !KSPLIT) ? 2 : 1)
+#endif
+
 namespace qs {
 namespace {
 
@@ -211,12 +215,13 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
     return;
   }
 
-  const uint32_t* ku = a.k_upper + ((int64_t)unit * a.q_cap + (int64_t)first * kG + rho) * kRowDw + 4 * g;
-  const uint32_t* kl = a.k_lower + ((int64_t)unit * a.q_cap + (int64_t)first * kG + rho) * kRowDw + 4 * g;
-  const uint32_t* vu = a.v_upper + ((int64_t)unit * a.q_cap + (int64_t)first * kG) * kRowDw + 4 * lane;
-  const uint32_t* vl = a.v_lower + ((int64_t)unit * a.q_cap + (int64_t)first * kG) * kRowDw + 4 * lane;
-  const int64_t meta0 = (int64_t)unit * a.q_cap + (int64_t)first * kG + 8 * g;   // same offset in all four arrays
-  const _Float16 *vsp = a.v_scale + meta0, *vzp = a.v_zero + meta0, *ksp = a.k_scale + meta0, *kzp = a.k_zero + meta0;
+  // This lane's addresses inside block 0 of the chunk; blocks follow at kUpperBlk / kLowerBlk strides.
+  const int64_t blk0 = (int64_t)unit * (a.q_cap / kBlkTok) + (int64_t)first * (kG / kBlkTok);
+  const uint8_t* ub = a.upper + blk0 * kUpperBlk;
+  const uint8_t* lb = a.lower + blk0 * kLowerBlk;
+  const int k_off = kOffK + rho * 64 + 16 * g;   // key rows rho and 16 + rho, channels 32g ..
+  const int v_off = kOffV + 16 * lane;           // value tile, two halves of 1 KB
+  const int m_off = 16 * g;                      // metadata: eight fp16 of lane group g
 
   // One 32-token block of operands.
   struct Blk {
@@ -227,27 +232,32 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   // loads of block j (chunk-local); past the end of the chunk the last block is re-read and never used
   auto load_block = [&](Blk& d, int j) {
     const int jc = min(j, 4 * n_local - 1);
-    const int64_t tok = (int64_t)jc * 32;
-    const int64_t nxt = (int64_t)min((jc >> 2) + 1, n_local - 1) * kG + 32 * (jc & 3);
-    d.kU[0] = ldg128(ku + tok * kRowDw);
-    d.kU[1] = ldg128(ku + (tok + 16) * kRowDw);
+    const uint8_t* u = ub + (int64_t)jc * kUpperBlk;
+    const uint8_t* un = ub + (int64_t)(min((jc >> 2) + 1, n_local - 1) * 4 + (jc & 3)) * kUpperBlk;
+    d.kU[0] = ldg128(u + k_off);
+    d.kU[1] = ldg128(u + k_off + 1024);
+    d.vU[0] = ldg128(u + v_off);
+    d.vU[1] = ldg128(u + v_off + 1024);
+    d.vS = ldg128(u + kOffVS + m_off);
+    d.vZ = ldg128(u + kOffVZ + m_off);
+    d.kS = ldg128(un + kOffKS + m_off);
+    d.kZ = ldg128(un + kOffKZ + m_off);
     if (VERIFY) {
-      d.kL[0] = ldg128(kl + tok * kRowDw);
-      d.kL[1] = ldg128(kl + (tok + 16) * kRowDw);
+      const uint8_t* l = lb + (int64_t)jc * kLowerBlk;
+      d.kL[0] = ldg128(l + k_off);
+      d.kL[1] = ldg128(l + k_off + 1024);
+      d.vL[0] = ldg128(l + v_off);
+      d.vL[1] = ldg128(l + v_off + 1024);
     }
-    d.vU[0] = ldg128(vu + tok * kRowDw);
-    d.vU[1] = ldg128(vu + tok * kRowDw + 256);
-    if (VERIFY) {
-      d.vL[0] = ldg128(vl + tok * kRowDw);
-      d.vL[1] = ldg128(vl + tok * kRowDw + 256);
-    }
-    d.vS = ldg128(vsp + tok);
-    d.vZ = ldg128(vzp + tok);
-    d.kS = ldg128(ksp + nxt);
-    d.kZ = ldg128(kzp + nxt);
   };
-  Blk bufA, bufB;
+  // Blocks in flight ahead of the one being computed.  With a single block ahead the bytes a wave
+  // keeps in flight, divided by the memory latency under load, cap the bandwidth below what the
+  // memory delivers; the draft kernel has the registers for a second one (three of the four named
+  // buffers are live at any time).
+  constexpr int kAhead = QS_AHEAD;
+  Blk bufA, bufB, bufC, bufD;
   load_block(bufA, 0);   // in flight while the queries and the first group's metadata arrive
+  if (kAhead == 2) load_block(bufB, 1);
 
   // Queries of this lane's column: channels 32*g + 8*s + operand order.  Each row is scaled by a power
   // of two so that max|q| <= 1 (then |q*S| <= 8734 cannot overflow fp16 whatever the inputs are); the
@@ -401,22 +411,35 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
 
   // the first group's query operand straight from global memory
   prep_reset();
-  prep_kstep(std::integral_constant<int, 0>{}, ldg128(ksp), ldg128(kzp));
-  prep_kstep(std::integral_constant<int, 1>{}, ldg128(ksp + 32), ldg128(kzp + 32));
-  prep_kstep(std::integral_constant<int, 2>{}, ldg128(ksp + 64), ldg128(kzp + 64));
-  prep_kstep(std::integral_constant<int, 3>{}, ldg128(ksp + 96), ldg128(kzp + 96));
+  prep_kstep(std::integral_constant<int, 0>{}, ldg128(ub + kOffKS + m_off), ldg128(ub + kOffKZ + m_off));
+  prep_kstep(std::integral_constant<int, 1>{}, ldg128(ub + kUpperBlk + kOffKS + m_off), ldg128(ub + kUpperBlk + kOffKZ + m_off));
+  prep_kstep(std::integral_constant<int, 2>{}, ldg128(ub + 2 * kUpperBlk + kOffKS + m_off),
+             ldg128(ub + 2 * kUpperBlk + kOffKZ + m_off));
+  prep_kstep(std::integral_constant<int, 3>{}, ldg128(ub + 3 * kUpperBlk + kOffKS + m_off),
+             ldg128(ub + 3 * kUpperBlk + kOffKZ + m_off));
   prep_commit();
 
   for (int lg = 0; lg < n_local; ++lg) {
     const int j = 4 * lg;
-    load_block(bufB, j + 1);
-    compute_block(bufA, std::integral_constant<int, 0>{});
-    load_block(bufA, j + 2);
-    compute_block(bufB, std::integral_constant<int, 1>{});
-    load_block(bufB, j + 3);
-    compute_block(bufA, std::integral_constant<int, 2>{});
-    load_block(bufA, j + 4);
-    compute_block(bufB, std::integral_constant<int, 3>{});
+    if (kAhead == 2) {
+      load_block(bufC, j + 2);
+      compute_block(bufA, std::integral_constant<int, 0>{});
+      load_block(bufD, j + 3);
+      compute_block(bufB, std::integral_constant<int, 1>{});
+      load_block(bufA, j + 4);
+      compute_block(bufC, std::integral_constant<int, 2>{});
+      load_block(bufB, j + 5);
+      compute_block(bufD, std::integral_constant<int, 3>{});
+    } else {
+      load_block(bufB, j + 1);
+      compute_block(bufA, std::integral_constant<int, 0>{});
+      load_block(bufA, j + 2);
+      compute_block(bufB, std::integral_constant<int, 1>{});
+      load_block(bufB, j + 3);
+      compute_block(bufA, std::integral_constant<int, 2>{});
+      load_block(bufA, j + 4);
+      compute_block(bufB, std::integral_constant<int, 3>{});
+    }
   }
   write_partial<NRT, RPT>(a, st, b, kvh, row0, split, kOutRaw);
 }

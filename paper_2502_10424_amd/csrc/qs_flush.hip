@@ -132,6 +132,25 @@ __device__ __forceinline__ int key_meta_position(int ch) {
   return 32 * s + 8 * g + ((nib & 3) << 1) + (nib >> 2);
 }
 
+// Start of the cache block that holds token `tok` (unit-local) in the upper / lower array.
+template <typename Args>
+__device__ __forceinline__ auto upper_block(const Args& a, int unit, int tok) {
+  return a.upper + ((int64_t)unit * (a.q_cap / kBlkTok) + tok / kBlkTok) * kUpperBlk;
+}
+template <typename Args>
+__device__ __forceinline__ auto lower_block(const Args& a, int unit, int tok) {
+  return a.lower + ((int64_t)unit * (a.q_cap / kBlkTok) + tok / kBlkTok) * kLowerBlk;
+}
+// Key scale / zero of channel ch of the group that starts at token tq0: k-step s = position / 32 of
+// the group's operand order lives in the group's block s.
+template <typename Args>
+__device__ __forceinline__ void store_key_meta(const Args& a, int unit, int tq0, int ch, _Float16 s, _Float16 z) {
+  const int pos = key_meta_position(ch);
+  uint8_t* blk = upper_block(a, unit, tq0 + kBlkTok * (pos >> 5));
+  reinterpret_cast<_Float16*>(blk + kOffKS)[pos & 31] = s;
+  reinterpret_cast<_Float16*>(blk + kOffKZ)[pos & 31] = z;
+}
+
 // ------------------------------------------------------------------------------------------------
 // Decode-time flush: four workgroups share one 128-token group of one unit so that a single flushed
 // group already spreads over several compute units.  Workgroup q of the four handles
@@ -190,25 +209,18 @@ __global__ __launch_bounds__(256) void flush_kernel(FlushArgs a) {
       gs[i] = group_scale((float)ksh[i], lo);
     }
     if (oct == 0) {
-      const int64_t dst = ((int64_t)unit * (a.q_cap / kG) + tq0 / kG) * kD;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int pos = key_meta_position(ch0 + i);
-        a.k_scale[dst + pos] = ksh[i];
-        a.k_zero[dst + pos] = (_Float16)gs[i].z;
-      }
+      for (int i = 0; i < 4; ++i) store_key_meta(a, unit, tq0, ch0 + i, ksh[i], (_Float16)gs[i].z);
     }
-    uint16_t* ku16 = reinterpret_cast<uint16_t*>(a.k_upper);
-    uint16_t* kl16 = reinterpret_cast<uint16_t*>(a.k_lower);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       float wu = 0.0f, wl = kLowerBias;
 #pragma unroll
       for (int i = 0; i < 4; ++i) pack4(wu, wl, encode_fast((float)x[j][i], gs[i]), i);
-      const int tok = 32 * blk + tile_token(g, j);
-      const int64_t w = (((int64_t)unit * a.q_cap + tq0 + tok) * kRowDw) * 2 + (ch0 >> 2);   // 16-bit units
-      ku16[w] = (uint16_t)(uint32_t)wu;
-      kl16[w] = (uint16_t)(uint32_t)wl;
+      const int tok = tq0 + 32 * blk + tile_token(g, j);
+      const int off = kOffK + (tok % kBlkTok) * 64 + (ch0 >> 1);   // four channels = two bytes of the token's row
+      *reinterpret_cast<uint16_t*>(upper_block(a, unit, tok) + off) = (uint16_t)(uint32_t)wu;
+      *reinterpret_cast<uint16_t*>(lower_block(a, unit, tok) + off) = (uint16_t)(uint32_t)wl;
     }
   } else {
     // ---- values: min / max per token over its 128 channels --------------------------------------
@@ -240,17 +252,17 @@ __global__ __launch_bounds__(256) void flush_kernel(FlushArgs a) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) pack4(vu[i][j & 1], vl[i][j & 1], encode_fast((float)x[j][i], gs), j >> 1);
     }
+    uint8_t* ub = upper_block(a, unit, tq0 + 32 * q);
+    uint8_t* lb = lower_block(a, unit, tq0 + 32 * q);
     if (c4 == 0) {
-      const int64_t m = (int64_t)unit * a.q_cap + tq0 + 32 * q + 8 * g;
-      *reinterpret_cast<half8*>(a.v_scale + m) = vsh;
-      *reinterpret_cast<half8*>(a.v_zero + m) = vzh;
+      *reinterpret_cast<half8*>(ub + kOffVS + 16 * g) = vsh;
+      *reinterpret_cast<half8*>(ub + kOffVZ + 16 * g) = vzh;
     }
     // channels 4*c4 .. 4*c4+3 = 8*m + 4*h + i with m = c4 >> 1, h = c4 & 1: four consecutive words
-    const int64_t vt = (int64_t)unit * (a.q_cap / kVTileTok) + tq0 / kVTileTok + q;
-    const int64_t w = vt * kVTileDw + ((c4 & 1) * 64 + 16 * g + (c4 >> 1)) * 4;
-    *reinterpret_cast<uint4*>(a.v_upper + w) = make_uint4(packed_word(vu[0][0], vu[0][1]), packed_word(vu[1][0], vu[1][1]),
+    const int w = kOffV + ((c4 & 1) * 64 + 16 * g + (c4 >> 1)) * 16;
+    *reinterpret_cast<uint4*>(ub + w) = make_uint4(packed_word(vu[0][0], vu[0][1]), packed_word(vu[1][0], vu[1][1]),
                                                           packed_word(vu[2][0], vu[2][1]), packed_word(vu[3][0], vu[3][1]));
-    *reinterpret_cast<uint4*>(a.v_lower + w) = make_uint4(packed_word(vl[0][0], vl[0][1]), packed_word(vl[1][0], vl[1][1]),
+    *reinterpret_cast<uint4*>(lb + w) = make_uint4(packed_word(vl[0][0], vl[0][1]), packed_word(vl[1][0], vl[1][1]),
                                                           packed_word(vl[2][0], vl[2][1]), packed_word(vl[3][0], vl[3][1]));
     __syncthreads();   // matches the barrier of the key half
   }
@@ -334,9 +346,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const _Float16 sh = make_scale(lo, hi);
     const GroupScale gs = group_scale((float)sh, lo);
     ksc[tid] = make_float4(gs.s, gs.z, gs.r, gs.rl);
-    const int64_t dst = ((int64_t)unit * (a.q_cap / kG) + tq0 / kG) * kD + key_meta_position(tid);
-    a.k_scale[dst] = sh;
-    a.k_zero[dst] = (_Float16)lo;
+    store_key_meta(a, unit, tq0, tid, sh, (_Float16)lo);
   }
   __syncthreads();
   {
@@ -357,9 +367,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const int64_t w = ((int64_t)unit * a.q_cap + tq0 + rg + 16 * j) * kRowDw + l16;
-      a.k_upper[w] = packed_word(wu[j][0], wu[j][1]);
-      a.k_lower[w] = packed_word(wl[j][0], wl[j][1]);
+      const int tok = tq0 + rg + 16 * j;
+      const int off = kOffK + (tok % kBlkTok) * 64 + 4 * l16;
+      *reinterpret_cast<uint32_t*>(upper_block(a, unit, tok) + off) = packed_word(wu[j][0], wu[j][1]);
+      *reinterpret_cast<uint32_t*>(lower_block(a, unit, tok) + off) = packed_word(wl[j][0], wl[j][1]);
     }
   }
   // ---- values ------------------------------------------------------------------------------------
@@ -391,20 +402,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
         pack4(vu[i + 1][j & 1], vl[i + 1][j & 1], c1, j >> 1);
       }
     }
+    uint8_t* ub = upper_block(a, unit, tq0 + 32 * vtile);
+    uint8_t* lb = lower_block(a, unit, tq0 + 32 * vtile);
     if (l16 == 0) {
-      const int64_t m = (int64_t)unit * a.q_cap + tq0 + 32 * vtile + 8 * vg;
-      *reinterpret_cast<half8*>(a.v_scale + m) = vsh;
-      *reinterpret_cast<half8*>(a.v_zero + m) = vzh;
+      *reinterpret_cast<half8*>(ub + kOffVS + 16 * vg) = vsh;
+      *reinterpret_cast<half8*>(ub + kOffVZ + 16 * vg) = vzh;
     }
     // channel 8*l16 + 4*h + i lives in word (h*64 + 16*vg + l16)*4 + i of the tile
-    const int64_t vt = (int64_t)unit * (a.q_cap / kVTileTok) + tq0 / kVTileTok + vtile;
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-      const int64_t w = vt * kVTileDw + (h * 64 + 16 * vg + l16) * 4;
-      *reinterpret_cast<uint4*>(a.v_upper + w) =
+      const int w = kOffV + (h * 64 + 16 * vg + l16) * 16;
+      *reinterpret_cast<uint4*>(ub + w) =
           make_uint4(packed_word(vu[4 * h][0], vu[4 * h][1]), packed_word(vu[4 * h + 1][0], vu[4 * h + 1][1]),
                      packed_word(vu[4 * h + 2][0], vu[4 * h + 2][1]), packed_word(vu[4 * h + 3][0], vu[4 * h + 3][1]));
-      *reinterpret_cast<uint4*>(a.v_lower + w) =
+      *reinterpret_cast<uint4*>(lb + w) =
           make_uint4(packed_word(vl[4 * h][0], vl[4 * h][1]), packed_word(vl[4 * h + 1][0], vl[4 * h + 1][1]),
                      packed_word(vl[4 * h + 2][0], vl[4 * h + 2][1]), packed_word(vl[4 * h + 3][0], vl[4 * h + 3][1]));
     }
@@ -448,43 +459,45 @@ __global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
   *reinterpret_cast<uint4*>(a.v_buf + dst) = *reinterpret_cast<const uint4*>(a.v_new + src);
 }
 
-// Expand packed planes into one code per byte, plain [token][channel] order.
+// Expand the blocked arrays of one unit into one code per byte, plain [token][channel] order.
 __global__ __launch_bounds__(256) void export_kernel(ExportArgs a) {
-  const int idx = blockIdx.x * 256 + threadIdx.x;      // one 32-bit word of each plane
+  const int idx = blockIdx.x * 256 + threadIdx.x;      // one 32-bit word of key codes and one of value codes
   if (idx >= a.n_tokens * kRowDw) return;
-  {  // keys: word idx = token * 16 + c8
-    const int tok = idx >> 4, c8 = idx & 15;
-    const uint32_t wu = a.k_upper[idx], wl = a.k_lower[idx];
+  const int blk = idx >> 9, w = idx & 511;             // 512 words of either kind per 32-token block
+  const uint8_t* ub = a.upper + (int64_t)blk * kUpperBlk;
+  const uint8_t* lb = a.lower + (int64_t)blk * kLowerBlk;
+  {  // keys: word w of the block = row (w >> 4), channels 8*(w & 15) ..
+    const int tok = 32 * blk + (w >> 4), c8 = w & 15;
+    const uint32_t wu = *reinterpret_cast<const uint32_t*>(ub + kOffK + 4 * w);
+    const uint32_t wl = *reinterpret_cast<const uint32_t*>(lb + kOffK + 4 * w);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       if (a.k_u) a.k_u[tok * kD + 8 * c8 + i] = (uint8_t)((wu >> (4 * i)) & 15u);
       if (a.k_l) a.k_l[tok * kD + 8 * c8 + i] = (int8_t)((int)((wl >> (4 * i)) & 15u) - 8);
     }
   }
-  {  // values: word idx = tile * 512 + (h*64 + 16*g + m)*4 + i
-    const int tile = idx >> 9, w = idx & 511;
+  {  // values: word w = (h*64 + 16*g + m)*4 + i of the tile
     const int h = w >> 8, g = (w >> 6) & 3, m = (w >> 2) & 15, i = w & 3;
     const int ch = 8 * m + 4 * h + i;
-    const uint32_t wu = a.v_upper[idx], wl = a.v_lower[idx];
+    const uint32_t wu = *reinterpret_cast<const uint32_t*>(ub + kOffV + 4 * w);
+    const uint32_t wl = *reinterpret_cast<const uint32_t*>(lb + kOffV + 4 * w);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-      const int tok = 32 * tile + tile_token(g, j);
+      const int tok = 32 * blk + tile_token(g, j);
       const int nib = 4 * tile_nibble(j);
       if (a.v_u) a.v_u[tok * kD + ch] = (uint8_t)((wu >> nib) & 15u);
       if (a.v_l) a.v_l[tok * kD + ch] = (int8_t)((int)((wl >> nib) & 15u) - 8);
     }
   }
-  if (idx < a.n_tokens) {  // key metadata: position 32*s + 8*g + e of a group -> channel 32*g + 8*s + nibble(e)
-    const int grp = idx >> 7, pos = idx & 127;
-    const int ch = 32 * ((pos >> 3) & 3) + 8 * (pos >> 5) + tile_nibble(pos & 7);
-    if (a.k_s) a.k_s[grp * kD + ch] = a.k_scale[idx];
-    if (a.k_z) a.k_z[grp * kD + ch] = a.k_zero[idx];
-  }
-  if (idx < a.n_tokens) {  // value metadata: position 8*g + j of a tile -> token order
-    const int tile = idx >> 5, p = idx & 31;
-    const int tok = 32 * tile + tile_token(p >> 3, p & 7);
-    if (a.v_s) a.v_s[tok] = a.v_scale[idx];
-    if (a.v_z) a.v_z[tok] = a.v_zero[idx];
+  if (w < 32) {  // key metadata: position 32*s + 8*g + e of a group (s = block mod 4) -> channel 32*g + 8*s + nibble(e)
+    const int grp = blk >> 2, s = blk & 3;
+    const int ch = 32 * (w >> 3) + 8 * s + tile_nibble(w & 7);
+    if (a.k_s) a.k_s[grp * kD + ch] = reinterpret_cast<const _Float16*>(ub + kOffKS)[w];
+    if (a.k_z) a.k_z[grp * kD + ch] = reinterpret_cast<const _Float16*>(ub + kOffKZ)[w];
+    // value metadata: position 8*g + j of the block -> token order
+    const int tok = 32 * blk + tile_token(w >> 3, w & 7);
+    if (a.v_s) a.v_s[tok] = reinterpret_cast<const _Float16*>(ub + kOffVS)[w];
+    if (a.v_z) a.v_z[tok] = reinterpret_cast<const _Float16*>(ub + kOffVZ)[w];
   }
 }
 

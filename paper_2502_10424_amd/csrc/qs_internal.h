@@ -9,9 +9,18 @@ namespace qs {
 
 constexpr int kD = 128;            // head_dim
 constexpr int kG = 128;            // quantization group size
-constexpr int kRowDw = 16;         // 32-bit words per token row of a key plane (128 nibbles)
-constexpr int kVTileTok = 32;      // tokens per value-plane tile
-constexpr int kVTileDw = 512;      // 32-bit words per value-plane tile (32 tokens x 128 nibbles)
+constexpr int kRowDw = 16;         // 32-bit words per token row of key codes (128 nibbles)
+constexpr int kBlkTok = 32;        // tokens per cache block
+// Byte offsets inside one 32-token block of the upper array (see quantspec.h) ...
+constexpr int kOffK = 0;           // key codes: 32 token rows of 64 bytes
+constexpr int kOffV = 2048;        // value codes: one 2 KB tile in operand order
+constexpr int kOffVS = 4096;       // value scale, 32 fp16 in tile order
+constexpr int kOffVZ = 4160;       // value zero
+constexpr int kOffKS = 4224;       // key scale of k-step (block mod 4) of the block's group, 32 fp16
+constexpr int kOffKZ = 4288;       // key zero, likewise
+constexpr int kUpperBlk = 4352;    // bytes per block of the upper array
+// ... and of the lower array: key codes at 0, value codes at 2048
+constexpr int kLowerBlk = 4096;
 constexpr int kBulkGroups = 512;   // from this many (group, unit) pairs on, quantization takes the bulk kernel
 constexpr int kBufSplitTok = 64;   // buffer tokens handled by one wave of the attention kernel
 
@@ -25,8 +34,7 @@ struct FlushArgs {
   const _Float16* k_src;   // [B][Hkv][src_stride][128]
   const _Float16* v_src;
   int64_t src_stride;      // tokens between consecutive units of the source
-  uint32_t *k_upper, *k_lower, *v_upper, *v_lower;
-  _Float16 *k_scale, *k_zero, *v_scale, *v_zero;
+  uint8_t *upper, *lower;
   int32_t n_kv_heads, q_cap, n_groups;   // n_groups = n_tokens / 128
   int32_t n_quant[QS_MAX_BATCH];
 };
@@ -45,8 +53,7 @@ struct AppendArgs {
 };
 
 struct ExportArgs {
-  const uint32_t *k_upper, *k_lower, *v_upper, *v_lower;
-  const _Float16 *k_scale, *k_zero, *v_scale, *v_zero;
+  const uint8_t *upper, *lower;   // already offset to the unit
   uint8_t *k_u, *v_u;
   int8_t *k_l, *v_l;
   _Float16 *k_s, *k_z, *v_s, *v_z;
@@ -54,8 +61,7 @@ struct ExportArgs {
 };
 
 struct AttnArgs {
-  const uint32_t *k_upper, *k_lower, *v_upper, *v_lower;
-  const _Float16 *k_scale, *k_zero, *v_scale, *v_zero;
+  const uint8_t *upper, *lower;
   const _Float16 *k_buf, *v_buf;
   const _Float16* q;       // [B][nq][Hq][128]
   float* ws_o;             // [rows_total][n_split][128] unnormalised partial outputs

@@ -41,7 +41,7 @@ def _seq_view(cache, b):
     sub = B.KVCache.__new__(B.KVCache)
     sub.batch, sub.n_q_heads, sub.n_kv_heads = 1, cache.n_q_heads, cache.n_kv_heads
     sub.head_dim, sub.group, sub.q_cap, sub.buf_cap = cache.head_dim, cache.group, cache.q_cap, cache.buf_cap
-    for name in ("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "k_zero", "v_scale", "v_zero", "k_buf", "v_buf"):
+    for name in B.PLANES + ("k_buf", "v_buf"):
         setattr(sub, name, getattr(cache, name)[b:b + 1])
     sub.n_quant = np.zeros(1, np.int32)
     sub.n_buf = np.zeros(1, np.int32)

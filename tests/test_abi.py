@@ -39,7 +39,7 @@ def _fake_cache(B, **over):
     """A descriptor with plausible, never-dereferenced device addresses (validation only)."""
     c = B.qs_cache()
     c.batch, c.n_q_heads, c.n_kv_heads, c.head_dim, c.group, c.q_cap, c.buf_cap = 2, 8, 2, 128, 128, 1024, 264
-    for i, name in enumerate(("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "k_zero", "v_scale", "v_zero",
+    for i, name in enumerate(("upper", "lower",
                               "k_buf", "v_buf")):
         setattr(c, name, 0x10000 * (i + 1))
     nq = np.array([512, 1024], np.int32)
@@ -71,14 +71,15 @@ def test_validation_errors_without_gpu(B):
         return lib.qs_attn_verify(ctypes.byref(c), 0x200000, nq, 0x300000, 0.1, 0x400000, ws, None, None)
 
     assert lib.qs_attn_draft(None, 0x200000, 0x300000, 0.1, 0x400000, ws, None, None) == B.QS_ERR_NULL
-    assert draft(_fake_cache(B, k_upper=None)) == B.QS_ERR_NULL
+    assert draft(_fake_cache(B, upper=None)) == B.QS_ERR_NULL
+    assert draft(_fake_cache(B, q_cap=0, upper=None, lower=None)) == B.QS_ERR_RANGE   # planes optional, but n_quant > 0
     assert draft(_fake_cache(B), q=None) == B.QS_ERR_NULL
     assert draft(_fake_cache(B, n_q_heads=7)) == B.QS_ERR_SHAPE
     assert draft(_fake_cache(B, q_cap=1000)) == B.QS_ERR_SHAPE
     assert draft(_fake_cache(B, head_dim=64)) == B.QS_ERR_UNSUPPORTED
     assert draft(_fake_cache(B, group=64)) == B.QS_ERR_UNSUPPORTED
     assert draft(_fake_cache(B, batch=65)) == B.QS_ERR_UNSUPPORTED
-    assert draft(_fake_cache(B, v_lower=0x10008)) == B.QS_ERR_ALIGN
+    assert draft(_fake_cache(B, lower=0x10008)) == B.QS_ERR_ALIGN
     assert draft(_fake_cache(B), q=0x200004) == B.QS_ERR_ALIGN
     assert draft(_fake_cache(B), wsp=None) == B.QS_ERR_WORKSPACE
     assert draft(_fake_cache(B), wsb=16) == B.QS_ERR_WORKSPACE

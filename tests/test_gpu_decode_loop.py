@@ -157,7 +157,8 @@ def test_hip_graph_replay_matches_eager(env):
     e_v = B.qs_attn_verify(c, qv, 0.1, workspace=ws).clone()
     B.qs_quantize_flush(c, G)
     torch.cuda.synchronize()
-    e_planes = [getattr(c, n).clone() for n in ("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "v_zero", "k_buf")]
+    checked = B.PLANES + ("k_buf",)
+    e_planes = [getattr(c, n).clone() for n in checked]
 
     c2 = fresh()
     o_d, o_v = torch.empty_like(qd), torch.empty_like(qv)
@@ -176,12 +177,12 @@ def test_hip_graph_replay_matches_eager(env):
     for rep in range(3):
         # restore the state the graph starts from (the flush inside it moves the buffer)
         c3 = fresh()
-        for n in ("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "k_zero", "v_scale", "v_zero", "k_buf", "v_buf"):
+        for n in B.PLANES + ("k_buf", "v_buf"):
             getattr(c2, n).copy_(getattr(c3, n))
         o_d.zero_(); o_v.zero_()
         (torch.ones(1000, device="cuda") * rep).sum().item()      # unrelated eager work + a synchronization
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(o_d, e_d) and torch.equal(o_v, e_v), f"replay {rep}"
-        for n, ref in zip(("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "v_zero", "k_buf"), e_planes):
+        for n, ref in zip(checked, e_planes):
             assert torch.equal(getattr(c2, n), ref), f"replay {rep}: {n}"

@@ -240,7 +240,7 @@ def test_attention_long_fp16_buffer(env, hq, hkv, nq, tq):
     nb = [5003, 2311]
     cache = B.KVCache(bsz, hq, hkv, tq, 5120)
     if tq == 0:
-        for name in ("k_upper", "k_lower", "v_upper", "v_lower", "k_scale", "k_zero", "v_scale", "v_zero"):
+        for name in B.PLANES:
             assert getattr(cache, name).numel() == 0
     oc = O.CacheOracle(bsz, hq, hkv, 128, 128)
     for b in range(bsz):
