@@ -262,6 +262,55 @@ def test_attention_long_fp16_buffer(env, hq, hkv, nq, tq):
         _check_attn(env, cache, oc, q, 0.1, False, tag=f"long buffer draft hq{hq} hkv{hkv} tq{tq}")
 
 
+def _random_case(env, rng, bsz, hkv, rep, nq, max_groups, max_buf):
+    """One seeded random cache (ragged quantized and buffer lengths per sequence) on both sides."""
+    torch, O, U, B = env["torch"], env["O"], env["U"], env["B"]
+    hq = hkv * rep
+    tq = [128 * int(rng.integers(0, max_groups + 1)) for _ in range(bsz)]
+    nb = [int(rng.integers(nq, max_buf + 1)) for _ in range(bsz)]
+    cache = B.KVCache(bsz, hq, hkv, max(max(tq), 128), max(nb) + 3)
+    oc = O.CacheOracle(bsz, hq, hkv, 128, 128)
+    scale = float(rng.choice([0.05, 1.0, 30.0]))
+    for b in range(bsz):
+        n = tq[b] + nb[b]
+        k = (rng.standard_normal((1, hkv, n, 128)) * scale).astype(np.float16)
+        v = (rng.standard_normal((1, hkv, n, 128)) * scale + rng.uniform(-2, 2)).astype(np.float16)
+        kd, vd = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+        if tq[b]:
+            B.qs_quantize_prefill(U._seq_view(cache, b), kd, vd, tq[b])
+        cache.n_quant[b], cache.n_buf[b] = tq[b], nb[b]
+        cache.k_buf[b, :, :nb[b]] = kd[0, :, tq[b]:]
+        cache.v_buf[b, :, :nb[b]] = vd[0, :, tq[b]:]
+        ob = O.build_cache(k, v, hq, 128, nb[b])
+        for name in ("ku", "kl", "ks", "kz", "vu", "vl", "vs", "vz", "kbuf", "vbuf"):
+            getattr(oc, name)[b] = getattr(ob, name)[0]
+    q = (rng.standard_normal((bsz, nq, hq, 128)) / scale).astype(np.float16)
+    return cache, oc, q, f"B{bsz} Hkv{hkv} rep{rep} nq{nq} tq{tq} nb{nb} scale{scale}"
+
+
+def test_attention_random_shapes(env):
+    """Seeded sweep over batch, head counts, GQA ratios, query counts, ragged lengths and magnitudes:
+    every kernel instantiation and planner branch (few / many units, chunk counts 1..many) is hit."""
+    rng = np.random.default_rng(4242)
+    for case in range(24):
+        bsz = int(rng.integers(1, 4))
+        hkv = int(rng.choice([1, 2, 3, 8]))
+        rep = int(rng.choice([1, 2, 4, 8]))
+        nq = int(rng.integers(1, 9))
+        cache, oc, q, tag = _random_case(env, rng, bsz, hkv, rep, nq, max_groups=6, max_buf=140)
+        _check_attn(env, cache, oc, q, 0.09, True, tag=f"random {case} verify {tag}")
+        if nq == 1 or case % 3 == 0:
+            _check_attn(env, cache, oc, q[:, -1:], 0.09, False, tag=f"random {case} draft {tag}")
+
+
+def test_attention_maximum_batch(env):
+    """64 sequences (the most the by-value length arrays hold), different lengths each: 128 units."""
+    rng = np.random.default_rng(64)
+    cache, oc, q, tag = _random_case(env, rng, 64, 2, 2, 2, max_groups=2, max_buf=40)
+    _check_attn(env, cache, oc, q, 0.09, True, tag=f"batch 64 verify {tag[:40]}")
+    _check_attn(env, cache, oc, q[:, -1:], 0.09, False, tag=f"batch 64 draft {tag[:40]}")
+
+
 def test_attention_degenerate_cases(env):
     """Buffer only (no quantized tokens); buffer holding exactly the nq query tokens; peaked softmax."""
     O, U = env["O"], env["U"]
