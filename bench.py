@@ -29,9 +29,9 @@ SPEC_GAMMAS = (1, 2, 4, 6)      # speculation lengths of the simulated decode lo
 # HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (calibrated against a plain copy kernel).  Filled from the summaries under profiles/; None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/attn_mha128k_hbm_traffic.md: (FETCH_SIZE x 1.99982 + WRITE_SIZE x 1.0) KiB per dispatch
-    ("mha128k", "draft"): int((280306.9 * 1.99982 + 1159.5) * 1024),
-    ("mha128k", "verify"): int((543711.2 * 1.99982 + 5872.1) * 1024),
+    # profiles/attn_mha128k_hbm_traffic.md: (FETCH_SIZE x 1.99991 + WRITE_SIZE x 1.0) KiB per dispatch
+    ("mha128k", "draft"): int((280268.2 * 1.99991 + 1106.3) * 1024),
+    ("mha128k", "verify"): int((542206.6 * 1.99991 + 5554.1) * 1024),
 }
 
 
@@ -206,8 +206,13 @@ def time_prefill(torch, B, cache, kd, vd, w, reps=3):
     torch.cuda.synchronize()
     us = min(ev[i].elapsed_time(ev[i + 1]) for i in range(reps)) * 1e3
     nbytes = w.units * w.n_quant * (128 * 2 * 2 + 264)
+    # vector instructions per element from the SQ counters in profiles/quantize_mha128k_pipe_utilisation.md;
+    # peak = 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations per second
+    lane_ops = 24.3 * w.units * w.n_quant * 128 * 2
     return {"us": round(us, 1), "GBps_read_plus_write": round(nbytes / us / 1e3, 1), "bytes": nbytes,
-            "tokens_per_unit": w.n_quant, "bound": "alu"}
+            "tokens_per_unit": w.n_quant,
+            "roofline": {"bound": "alu", "achieved": round(lane_ops / us / 1e6, 2), "peak": 39.32,
+                         "unit": "T lane-ops/s", "frac": round(lane_ops / us / 1e6 / 39.32, 4)}}
 
 
 def fp16_baseline(torch, B, cache, w, sm_scale, q_draft, q_verify, draft_us, verify_us, reps=10):

@@ -349,28 +349,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     store_key_meta(a, unit, tq0, tid, sh, (_Float16)lo);
   }
   __syncthreads();
-  {
-    float wu[8][2], wl[8][2];   // per token: channels 0..3 and 4..7 of this thread's plane word
+  // two tokens at a time, the channel's (S, Z, 1/S, 16/S) read from LDS for each pair: this keeps
+  // only eight packing accumulators live and releases the source registers as the tokens are done
 #pragma unroll
-    for (int j = 0; j < 8; ++j) wu[j][0] = wu[j][1] = 0.0f, wl[j][0] = wl[j][1] = kLowerBias;
+  for (int j = 0; j < 8; j += 2) {
+    float wu[2][2] = {{0.0f, 0.0f}, {0.0f, 0.0f}};   // [token of the pair][channels 0..3 / 4..7]
+    float wl[2][2] = {{kLowerBias, kLowerBias}, {kLowerBias, kLowerBias}};
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float4 m = ksc[8 * l16 + i];
       const GroupScale gs{m.x, m.y, m.z, m.w};
-#pragma unroll
-      for (int j = 0; j < 8; j += 2) {
-        Codes c0, c1;
-        encode_fast2((float)xk[j][i], gs, (float)xk[j + 1][i], gs, c0, c1);
-        pack4(wu[j][i >> 2], wl[j][i >> 2], c0, i & 3);
-        pack4(wu[j + 1][i >> 2], wl[j + 1][i >> 2], c1, i & 3);
-      }
+      Codes c0, c1;
+      encode_fast2((float)xk[j][i], gs, (float)xk[j + 1][i], gs, c0, c1);
+      pack4(wu[0][i >> 2], wl[0][i >> 2], c0, i & 3);
+      pack4(wu[1][i >> 2], wl[1][i >> 2], c1, i & 3);
     }
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      const int tok = tq0 + rg + 16 * j;
+    for (int t = 0; t < 2; ++t) {
+      const int tok = tq0 + rg + 16 * (j + t);
       const int off = kOffK + (tok % kBlkTok) * 64 + 4 * l16;
-      *reinterpret_cast<uint32_t*>(upper_block(a, unit, tok) + off) = packed_word(wu[j][0], wu[j][1]);
-      *reinterpret_cast<uint32_t*>(lower_block(a, unit, tok) + off) = packed_word(wl[j][0], wl[j][1]);
+      *reinterpret_cast<uint32_t*>(upper_block(a, unit, tok) + off) = packed_word(wu[t][0], wu[t][1]);
+      *reinterpret_cast<uint32_t*>(lower_block(a, unit, tok) + off) = packed_word(wl[t][0], wl[t][1]);
     }
   }
   // ---- values ------------------------------------------------------------------------------------
