@@ -10,7 +10,8 @@
 //    rows that share that kv-head (grouped-query heads x query tokens), so the planes are read once.
 //    Every byte of the planes is loaded exactly once, by exactly one lane, with 128-bit loads that a
 //    wave issues as contiguous 1 KB requests, directly into the registers that feed the matrix cores;
-//    LDS is only used to transpose the fp16 value tiles of the buffer chunk.
+//    the cache is laid out in 32-token blocks so that these requests walk one array (draft) or two
+//    (verify) front to back.  LDS is only used to transpose the fp16 value tiles of the buffer chunk.
 //  * The contraction runs on the matrix cores (v_mfma_f32_16x16x32_f16): codes are the A operand,
 //    queries / probabilities the B operand.  Scales never touch individual codes:
 //        q . K_hat[t] = sum_d (q_d S_d) c[t,d] + q . Z          (per 128-token group)
@@ -445,9 +446,11 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
 }
 
 // ------------------------------------------------------------------------------------------------
-// A chunk of the full-precision buffer: up to 64 tokens.  Keys are read straight into the A
-// operand; the value tile is transposed through LDS because the matrix cores need eight tokens of
-// one channel per lane while the buffer is stored token-major.
+// A chunk of the full-precision buffer: a range of its 32-token blocks (two for a decode-time
+// buffer, many when the buffer is long, e.g. a cache that keeps every token in fp16).  Keys are read
+// straight into the A operand; the value rows are transposed through LDS because the matrix cores
+// need eight tokens of one channel per lane while the buffer is stored token-major.  The next
+// block's keys and values are in flight while the current one is computed.
 // ------------------------------------------------------------------------------------------------
 constexpr int kVtStride = 40;   // halfs per LDS row: 32 tokens + padding, keeps 8-byte reads aligned
 constexpr float kBufP = 16384.0f;
