@@ -114,6 +114,22 @@ def test_validation_errors_without_gpu(B):
     assert lib.qs_export_codes(ctypes.byref(_fake_cache(B)), 0, 0, 100, None, None, None, None, None, None, None, None, None) == B.QS_ERR_RANGE
 
 
+def test_header_is_plain_c_and_library_works_without_python(B, tmp_path):
+    """include/quantspec.h compiles as C99 and a C program drives the library through dlopen."""
+    import shutil
+    import subprocess
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    exe = str(tmp_path / "abi_check")
+    src = os.path.join(ROOT, "tests", "c_abi", "abi_check.c")
+    subprocess.run([cc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    src, "-o", exe, "-ldl"], check=True)
+    B.lib()
+    out = subprocess.run([exe, B.LIB_PATH], check=True, capture_output=True, text=True)
+    assert out.stdout.strip() == "ok"
+
+
 def test_missing_library_fails_loudly(B, monkeypatch):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libquantspec.so")
