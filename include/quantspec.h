@@ -38,6 +38,11 @@
  *     lower : uint8 [B][Hkv][q_cap/32][4096]   per block
  *               [   0, 2048)  key codes C_L + 8 (0..15), same arrangement as in the upper array
  *               [2048, 4096)  value codes C_L + 8, likewise
+ *   Paging: by default unit u = b*Hkv + kv_head owns the q_cap/128 consecutive 128-token groups (of
+ *   four blocks each) that start at group u*(q_cap/128) of both arrays.  With a group table
+ *   (group_table != NULL) entry [b][kv_head][g] is instead the index, counted in groups, of the place
+ *   in upper / lower that holds logical group g of that unit: upper and lower are then pools of
+ *   pool_groups groups in any order, and q_cap is only the longest a sequence may get.
  *   Keys are grouped per channel over 128 consecutive tokens, values per token over the 128 channels
  *   (Section 4.3.1); both planes share S and Z.  qs_quantize_flush / qs_quantize_prefill are the only
  *   writers of these arrays; qs_export_codes returns plain [token][channel] codes and metadata.
@@ -80,6 +85,10 @@ typedef struct qs_cache {
   void *k_buf, *v_buf;
   const int32_t *n_quant;                 /* HOST int32[batch]: valid quantized tokens (multiple of 128) */
   const int32_t *n_buf;                   /* HOST int32[batch]: valid buffer tokens                   */
+  const int32_t *group_table;             /* DEVICE int32 [batch][n_kv_heads][q_cap/128], or NULL = contiguous.
+                                             Entries must lie in [0, pool_groups) and be distinct where the
+                                             groups are live; the library cannot check device memory        */
+  int32_t pool_groups;                    /* groups held by upper / lower when group_table is given        */
 } qs_cache;
 
 /* Library version: major*10000 + minor*100 + patch. */

@@ -39,6 +39,7 @@ class qs_cache(ctypes.Structure):
         ("upper", ctypes.c_void_p), ("lower", ctypes.c_void_p),
         ("k_buf", ctypes.c_void_p), ("v_buf", ctypes.c_void_p),
         ("n_quant", ctypes.POINTER(ctypes.c_int32)), ("n_buf", ctypes.POINTER(ctypes.c_int32)),
+        ("group_table", ctypes.c_void_p), ("pool_groups", ctypes.c_int32),
     ]
 
 
@@ -102,14 +103,23 @@ class KVCache:
     """
 
     def __init__(self, batch: int, n_q_heads: int, n_kv_heads: int, q_cap: int, buf_cap: int,
-                 device="cuda", head_dim: int = HEAD_DIM, group: int = GROUP):
+                 device="cuda", head_dim: int = HEAD_DIM, group: int = GROUP, pool_groups: int | None = None):
+        """pool_groups: None = every unit owns q_cap/128 consecutive groups; a number = paged cache:
+        upper / lower are pools of that many 128-token groups and group_table (int32, device,
+        [batch][n_kv_heads][q_cap/128], filled by the caller) says where each logical group lives."""
         self.batch, self.n_q_heads, self.n_kv_heads = batch, n_q_heads, n_kv_heads
         self.head_dim, self.group, self.q_cap, self.buf_cap = head_dim, group, q_cap, buf_cap
         u8 = dict(dtype=torch.uint8, device=device)
         f16 = dict(dtype=torch.float16, device=device)
         qc = max(q_cap, 0)
-        self.upper = torch.zeros((batch, n_kv_heads, qc // 32, UPPER_BLOCK_BYTES), **u8)
-        self.lower = torch.zeros((batch, n_kv_heads, qc // 32, LOWER_BLOCK_BYTES), **u8)
+        self.pool_groups, self.group_table = pool_groups, None
+        if pool_groups is None:
+            self.upper = torch.zeros((batch, n_kv_heads, qc // 32, UPPER_BLOCK_BYTES), **u8)
+            self.lower = torch.zeros((batch, n_kv_heads, qc // 32, LOWER_BLOCK_BYTES), **u8)
+        else:
+            self.upper = torch.zeros((pool_groups * 4, UPPER_BLOCK_BYTES), **u8)
+            self.lower = torch.zeros((pool_groups * 4, LOWER_BLOCK_BYTES), **u8)
+            self.group_table = torch.zeros((batch, n_kv_heads, qc // 128), dtype=torch.int32, device=device)
         self.k_buf = torch.zeros((batch, n_kv_heads, buf_cap, 128), **f16)
         self.v_buf = torch.zeros((batch, n_kv_heads, buf_cap, 128), **f16)
         self.n_quant = np.zeros(batch, np.int32)
@@ -124,6 +134,8 @@ class KVCache:
             setattr(c, name, getattr(self, name).data_ptr())
         c.n_quant = self.n_quant.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
         c.n_buf = self.n_buf.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+        if self.group_table is not None:
+            c.group_table, c.pool_groups = self.group_table.data_ptr(), self.pool_groups
         return c
 
     def plane_bytes(self) -> int:

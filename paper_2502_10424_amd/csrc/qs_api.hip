@@ -38,6 +38,7 @@ int validate_shape(const qs_cache* c) {
   if (c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->n_q_heads % c->n_kv_heads != 0)
     return QS_ERR_SHAPE;
   if (c->q_cap < 0 || c->q_cap % kG != 0 || c->buf_cap <= 0) return QS_ERR_SHAPE;
+  if (c->group_table != nullptr && c->pool_groups <= 0) return QS_ERR_SHAPE;
   if (c->head_dim != kD || c->group != kG || c->batch > QS_MAX_BATCH) return QS_ERR_UNSUPPORTED;
   return QS_OK;
 }
@@ -103,6 +104,7 @@ int attn_common(const qs_cache* c, const void* q, int32_t nq, void* out, float s
   AttnArgs a;
   a.upper = static_cast<const uint8_t*>(c->upper);
   a.lower = static_cast<const uint8_t*>(c->lower);
+  a.group_table = c->group_table;
   a.k_buf = static_cast<const _Float16*>(c->k_buf);
   a.v_buf = static_cast<const _Float16*>(c->v_buf);
   a.q = static_cast<const _Float16*>(q);
@@ -143,6 +145,7 @@ int quantize_common(const qs_cache* c, const _Float16* k_src, const _Float16* v_
   f.src_stride = src_stride;
   f.upper = static_cast<uint8_t*>(c->upper);
   f.lower = static_cast<uint8_t*>(c->lower);
+  f.group_table = c->group_table;
   f.n_kv_heads = c->n_kv_heads;
   f.q_cap = c->q_cap;
   f.n_groups = n_tokens / kG;
@@ -259,8 +262,11 @@ int qs_export_codes(const qs_cache* c, int32_t b, int32_t kv_head, int32_t n_tok
   if (n_tokens < 0 || n_tokens % kG != 0 || n_tokens > c->q_cap) return QS_ERR_RANGE;
   const int64_t unit = (int64_t)b * c->n_kv_heads + kv_head;
   ExportArgs e;
-  e.upper = static_cast<const uint8_t*>(c->upper) + unit * (c->q_cap / kBlkTok) * kUpperBlk;
-  e.lower = static_cast<const uint8_t*>(c->lower) + unit * (c->q_cap / kBlkTok) * kLowerBlk;
+  e.upper = static_cast<const uint8_t*>(c->upper);
+  e.lower = static_cast<const uint8_t*>(c->lower);
+  e.group_table = c->group_table;
+  e.unit = (int32_t)unit;
+  e.q_cap = c->q_cap;
   e.k_s = static_cast<_Float16*>(k_s);
   e.k_z = static_cast<_Float16*>(k_z);
   e.k_u = static_cast<uint8_t*>(k_u);

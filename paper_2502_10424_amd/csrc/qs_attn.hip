@@ -216,10 +216,13 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
     return;
   }
 
-  // This lane's addresses inside block 0 of the chunk; blocks follow at kUpperBlk / kLowerBlk strides.
-  const int64_t blk0 = (int64_t)unit * (a.q_cap / kBlkTok) + (int64_t)first * (kG / kBlkTok);
-  const uint8_t* ub = a.upper + blk0 * kUpperBlk;
-  const uint8_t* lb = a.lower + blk0 * kLowerBlk;
+  // Start of chunk-local block j in the upper / lower array.  Contiguous units: blocks follow each
+  // other; with a group table every 128-token group (four blocks) is looked up.
+  const bool paged = a.group_table != nullptr;
+  const int64_t blk0 = ((int64_t)unit * (a.q_cap / kG) + first) * (kG / kBlkTok);
+  auto block_index = [&](int j) -> int64_t {
+    return paged ? physical_group(a, unit, first + (j >> 2)) * (kG / kBlkTok) + (j & 3) : blk0 + j;
+  };
   const int k_off = kOffK + rho * 64 + 16 * g;   // key rows rho and 16 + rho, channels 32g ..
   const int v_off = kOffV + 16 * lane;           // value tile, two halves of 1 KB
   const int m_off = 16 * g;                      // metadata: eight fp16 of lane group g
@@ -233,8 +236,9 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   // loads of block j (chunk-local); past the end of the chunk the last block is re-read and never used
   auto load_block = [&](Blk& d, int j) {
     const int jc = min(j, 4 * n_local - 1);
-    const uint8_t* u = ub + (int64_t)jc * kUpperBlk;
-    const uint8_t* un = ub + (int64_t)(min((jc >> 2) + 1, n_local - 1) * 4 + (jc & 3)) * kUpperBlk;
+    const int64_t bj = block_index(jc);
+    const uint8_t* u = a.upper + bj * kUpperBlk;
+    const uint8_t* un = a.upper + block_index(min((jc >> 2) + 1, n_local - 1) * 4 + (jc & 3)) * kUpperBlk;
     d.kU[0] = ldg128(u + k_off);
     d.kU[1] = ldg128(u + k_off + 1024);
     d.vU[0] = ldg128(u + v_off);
@@ -244,7 +248,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
     d.kS = ldg128(un + kOffKS + m_off);
     d.kZ = ldg128(un + kOffKZ + m_off);
     if (VERIFY) {
-      const uint8_t* l = lb + (int64_t)jc * kLowerBlk;
+      const uint8_t* l = a.lower + bj * kLowerBlk;
       d.kL[0] = ldg128(l + k_off);
       d.kL[1] = ldg128(l + k_off + 1024);
       d.vL[0] = ldg128(l + v_off);
@@ -412,6 +416,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
 
   // the first group's query operand straight from global memory
   prep_reset();
+  const uint8_t* ub = a.upper + block_index(0) * kUpperBlk;   // the four blocks of a group are adjacent
   prep_kstep(std::integral_constant<int, 0>{}, ldg128(ub + kOffKS + m_off), ldg128(ub + kOffKZ + m_off));
   prep_kstep(std::integral_constant<int, 1>{}, ldg128(ub + kUpperBlk + kOffKS + m_off), ldg128(ub + kUpperBlk + kOffKZ + m_off));
   prep_kstep(std::integral_constant<int, 2>{}, ldg128(ub + 2 * kUpperBlk + kOffKS + m_off),

@@ -135,11 +135,11 @@ __device__ __forceinline__ int key_meta_position(int ch) {
 // Start of the cache block that holds token `tok` (unit-local) in the upper / lower array.
 template <typename Args>
 __device__ __forceinline__ auto upper_block(const Args& a, int unit, int tok) {
-  return a.upper + ((int64_t)unit * (a.q_cap / kBlkTok) + tok / kBlkTok) * kUpperBlk;
+  return a.upper + (physical_group(a, unit, tok / kG) * (kG / kBlkTok) + (tok % kG) / kBlkTok) * kUpperBlk;
 }
 template <typename Args>
 __device__ __forceinline__ auto lower_block(const Args& a, int unit, int tok) {
-  return a.lower + ((int64_t)unit * (a.q_cap / kBlkTok) + tok / kBlkTok) * kLowerBlk;
+  return a.lower + (physical_group(a, unit, tok / kG) * (kG / kBlkTok) + (tok % kG) / kBlkTok) * kLowerBlk;
 }
 // Key scale / zero of channel ch of the group that starts at token tq0: k-step s = position / 32 of
 // the group's operand order lives in the group's block s.
@@ -463,8 +463,8 @@ __global__ __launch_bounds__(256) void export_kernel(ExportArgs a) {
   const int idx = blockIdx.x * 256 + threadIdx.x;      // one 32-bit word of key codes and one of value codes
   if (idx >= a.n_tokens * kRowDw) return;
   const int blk = idx >> 9, w = idx & 511;             // 512 words of either kind per 32-token block
-  const uint8_t* ub = a.upper + (int64_t)blk * kUpperBlk;
-  const uint8_t* lb = a.lower + (int64_t)blk * kLowerBlk;
+  const uint8_t* ub = upper_block(a, a.unit, kBlkTok * blk);
+  const uint8_t* lb = lower_block(a, a.unit, kBlkTok * blk);
   {  // keys: word w of the block = row (w >> 4), channels 8*(w & 15) ..
     const int tok = 32 * blk + (w >> 4), c8 = w & 15;
     const uint32_t wu = *reinterpret_cast<const uint32_t*>(ub + kOffK + 4 * w);

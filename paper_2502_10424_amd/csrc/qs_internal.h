@@ -35,6 +35,7 @@ struct FlushArgs {
   const _Float16* v_src;
   int64_t src_stride;      // tokens between consecutive units of the source
   uint8_t *upper, *lower;
+  const int32_t* group_table;            // device, [units][q_cap/128], or null: contiguous units
   int32_t n_kv_heads, q_cap, n_groups;   // n_groups = n_tokens / 128
   int32_t n_quant[QS_MAX_BATCH];
 };
@@ -53,7 +54,9 @@ struct AppendArgs {
 };
 
 struct ExportArgs {
-  const uint8_t *upper, *lower;   // already offset to the unit
+  const uint8_t *upper, *lower;
+  const int32_t* group_table;     // see FlushArgs
+  int32_t unit, q_cap;
   uint8_t *k_u, *v_u;
   int8_t *k_l, *v_l;
   _Float16 *k_s, *k_z, *v_s, *v_z;
@@ -62,6 +65,7 @@ struct ExportArgs {
 
 struct AttnArgs {
   const uint8_t *upper, *lower;
+  const int32_t* group_table;     // see FlushArgs
   const _Float16 *k_buf, *v_buf;
   const _Float16* q;       // [B][nq][Hq][128]
   float* ws_o;             // [rows_total][n_split][128] unnormalised partial outputs
@@ -78,6 +82,13 @@ struct MergeArgs {
   float* lse;              // [rows_total] or null
   int32_t n_split;
 };
+
+// Place, counted in 128-token groups, of logical group g of a unit inside the upper / lower arrays.
+template <typename Args>
+__device__ __forceinline__ int64_t physical_group(const Args& a, int unit, int g) {
+  const int64_t logical = (int64_t)unit * (a.q_cap / kG) + g;
+  return a.group_table != nullptr ? (int64_t)a.group_table[logical] : logical;
+}
 
 hipError_t launch_flush(const FlushArgs& a, int batch, hipStream_t s);
 hipError_t launch_shift(const ShiftArgs& a, int batch, hipStream_t s);

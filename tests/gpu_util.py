@@ -43,6 +43,10 @@ def _seq_view(cache, b):
     sub.head_dim, sub.group, sub.q_cap, sub.buf_cap = cache.head_dim, cache.group, cache.q_cap, cache.buf_cap
     for name in B.PLANES + ("k_buf", "v_buf"):
         setattr(sub, name, getattr(cache, name)[b:b + 1])
+    sub.pool_groups, sub.group_table = cache.pool_groups, None
+    if cache.group_table is not None:      # paged: the pools are shared, the view selects the table rows
+        sub.upper, sub.lower = cache.upper, cache.lower
+        sub.group_table = cache.group_table[b:b + 1]
     sub.n_quant = np.zeros(1, np.int32)
     sub.n_buf = np.zeros(1, np.int32)
     return sub

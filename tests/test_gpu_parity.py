@@ -311,6 +311,48 @@ def test_attention_maximum_batch(env):
     _check_attn(env, cache, oc, q[:, -1:], 0.09, False, tag=f"batch 64 draft {tag[:40]}")
 
 
+@pytest.mark.parametrize("hq,hkv,nq", [(4, 2, 1), (8, 2, 5), (16, 2, 5)])
+def test_paged_cache_matches_oracle(env, hq, hkv, nq):
+    """Group-table mode: the 128-token groups of every unit live at shuffled places of a shared pool.
+    Prefill, a flush (which appends through the table) and both attention passes must give exactly
+    what the oracle gives; the oracle knows nothing about placement."""
+    torch, O, U, B = env["torch"], env["O"], env["U"], env["B"]
+    rng = np.random.default_rng(900 + hq + nq)
+    bsz, tq, nb, q_cap = 3, 5 * 128, 128 + nq + 9, 8 * 128
+    n_logical = bsz * hkv * (q_cap // 128)
+    pool = n_logical + 7
+    cache = B.KVCache(bsz, hq, hkv, q_cap, nb + 8, pool_groups=pool)
+    table = rng.permutation(pool)[:n_logical].astype(np.int32).reshape(bsz, hkv, q_cap // 128)
+    cache.group_table.copy_(torch.from_numpy(table))
+    cache.upper.fill_(0xA5)                  # whatever sits in unused pool places must not matter
+    cache.lower.fill_(0x5A)
+    k = (rng.standard_normal((bsz, hkv, tq + nb, 128)) * 1.5).astype(np.float16)
+    v = rng.standard_normal((bsz, hkv, tq + nb, 128)).astype(np.float16)
+    kd, vd = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    B.qs_quantize_prefill(cache, kd, vd, tq)
+    cache.n_quant[:] = tq
+    cache.k_buf[:, :, :nb] = kd[:, :, tq:]
+    cache.v_buf[:, :, :nb] = vd[:, :, tq:]
+    cache.n_buf[:] = nb
+    oc = O.build_cache(k, v, hq, 128, nb)
+    q = rng.standard_normal((bsz, nq, hq, 128)).astype(np.float16)
+    _check_attn(env, cache, oc, q, 0.1, True, tag=f"paged verify hq{hq} hkv{hkv} nq{nq}")
+    _check_attn(env, cache, oc, q[:, -1:], 0.1, False, tag=f"paged draft hq{hq} hkv{hkv}")
+    B.qs_quantize_flush(cache, 128)          # group 5 of every unit goes to its table entry
+    cache.n_quant += 128
+    cache.n_buf -= 128
+    oc.flush(128)
+    for b in range(bsz):
+        for h in range(hkv):
+            U.assert_unit_equals_oracle(cache, oc, b, h)
+    _check_attn(env, cache, oc, q, 0.1, True, tag=f"paged verify after flush hq{hq} hkv{hkv} nq{nq}")
+    # pool places no table entry points at are untouched
+    used = np.zeros(pool, bool)
+    used[table.reshape(-1)] = True
+    up = cache.upper.view(pool, -1).cpu().numpy()
+    assert (up[~used] == 0xA5).all()
+
+
 def test_attention_degenerate_cases(env):
     """Buffer only (no quantized tokens); buffer holding exactly the nq query tokens; peaked softmax."""
     O, U = env["O"], env["U"]
