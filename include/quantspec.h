@@ -106,8 +106,8 @@ const char *qs_strerror(int code);
 size_t qs_workspace_bytes(const qs_cache *c, int32_t nq);
 
 /*
- * QUANTIZE on flush (Section 4.2, Section 4.3.2, Algorithm 1 "Quantize the first half of the full
- * precision cache buffer"): for every sequence b, quantize buffer tokens [0, n_tokens) into both
+ * QUANTIZE on flush (Section 4.2, Section 4.3.2; the step of Algorithm 1's decode loop that quantizes
+ * the older half of the full-precision buffer once it is full): for every sequence b, quantize buffer tokens [0, n_tokens) into both
  * 4-bit planes with one shared fp16 (S, Z) per group, write them at token offset n_quant[b], then
  * move buffer tokens [n_tokens, n_buf[b]) to the front of the buffer.
  *   n_tokens: multiple of 128, <= every n_buf[b]; n_quant[b] + n_tokens <= q_cap.
@@ -117,7 +117,7 @@ size_t qs_workspace_bytes(const qs_cache *c, int32_t nq);
 int qs_quantize_flush(const qs_cache *c, int32_t n_tokens, void *stream);
 
 /*
- * QUANTIZE at prefill (Algorithm 1, "Prepare the hierarchical quantized KV Cache"): quantize
+ * QUANTIZE at prefill (Algorithm 1, prefill stage, where the two planes are first built): quantize
  * n_tokens tokens of caller-provided fp16 K / V, device [B][Hkv][src_stride_tokens][128], into the
  * planes at token offset n_quant[b].  n_tokens is a multiple of 128.  The buffer is not touched.
  */
@@ -126,7 +126,7 @@ int qs_quantize_prefill(const qs_cache *c, const void *k_src, const void *v_src,
 
 /*
  * Append new tokens to the full-precision buffer (Appendix A: C_K = concat(C_K, c_k), likewise C_V;
- * Section 4.3.2: "newly generated tokens are stored in full precision in the second buffer"):
+ * Section 4.3.2: tokens generated during decoding go, in full precision, to the second half of the buffer):
  *   k_new, v_new : device fp16 [B][n_new][n_kv_heads][128]  (token-major, as a projection produces them)
  * are written to buffer rows [n_buf[b], n_buf[b] + n_new) of every sequence.  n_buf[b] + n_new must not
  * exceed buf_cap.  The host lengths are not modified (the caller adds n_new).  Rejecting drafted tokens
@@ -135,20 +135,21 @@ int qs_quantize_prefill(const qs_cache *c, const void *k_src, const void *v_src,
 int qs_append(const qs_cache *c, const void *k_new, const void *v_new, int32_t n_new, void *stream);
 
 /*
- * DRAFT attention (Algorithm 1; Section 4.2 "we only load the upper 4-bit representation"):
+ * DRAFT attention (Algorithm 1; Section 4.2: the draft pass loads the upper 4-bit plane only):
  *   q   : device fp16 [B][1][n_q_heads][128]
  *   out : device fp16 [B][1][n_q_heads][128]
  * The query of sequence b attends the decoded upper plane of tokens [0, n_quant[b]) and buffer
  * tokens [0, n_buf[b]) (its own K/V must already be the last buffer token; Appendix A).
- * out = softmax(sm_scale * q K^T) V.  lse (device float [B][1][n_q_heads], natural log of the
+ * out = softmax(sm_scale * q K^T) V, sm_scale > 0 and finite (QS_ERR_RANGE otherwise).
+ * lse (device float [B][1][n_q_heads], natural log of the
  * softmax normaliser) is written if not NULL.
  */
 int qs_attn_draft(const qs_cache *c, const void *q, void *out, float sm_scale,
                   void *workspace, size_t workspace_bytes, float *lse, void *stream);
 
 /*
- * TARGET / verify attention (Algorithm 1; Section 4.2 "both the upper and lower 4-bit
- * representations to reconstruct the KV cache in INT8"):
+ * TARGET / verify attention (Algorithm 1; Section 4.2: the target pass loads both 4-bit planes and
+ * combines them into the INT8 code):
  *   q   : device fp16 [B][nq][n_q_heads][128], 1 <= nq <= QS_MAX_NQ (nq = gamma + 1)
  *   out : device fp16 [B][nq][n_q_heads][128]
  * The nq tokens' K/V must already be the LAST nq buffer tokens.  Query i (0-based) attends all

@@ -8,7 +8,7 @@ call it.
 
 What it follows
 ---------------
-* Section 4.2 ("Hierarchical KV Cache"): an asymmetric round-to-nearest 4-bit
+* Section 4.2 (the hierarchical cache): an asymmetric round-to-nearest 4-bit
   code C_U in [0, 15] is computed first, then the quantization error E_U of that
   code is quantized with symmetric round-to-nearest into C_L in [-8, 7]; the
   lower plane has no metadata of its own, its scale is S_INT4 / 2^4, and

@@ -88,6 +88,7 @@ int attn_common(const qs_cache* c, const void* q, int32_t nq, void* out, float s
   if (rc != QS_OK) return rc;
   if (q == nullptr || out == nullptr) return QS_ERR_NULL;
   if (nq < 1 || nq > QS_MAX_NQ) return QS_ERR_UNSUPPORTED;
+  if (!(sm_scale > 0.0f) || !(sm_scale < 3.0e38f)) return QS_ERR_RANGE;   // the kernels rely on a positive, finite scale
   if (!aligned16(q) || !aligned16(out) || !aligned16(workspace)) return QS_ERR_ALIGN;
   int max_quant = 0, max_buf = 0;
   for (int b = 0; b < c->batch; ++b) {

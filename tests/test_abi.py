@@ -83,6 +83,8 @@ def test_validation_errors_without_gpu(B):
     assert draft(_fake_cache(B), q=0x200004) == B.QS_ERR_ALIGN
     assert draft(_fake_cache(B), wsp=None) == B.QS_ERR_WORKSPACE
     assert draft(_fake_cache(B), wsb=16) == B.QS_ERR_WORKSPACE
+    for bad in (0.0, -0.1, float("inf"), float("nan")):
+        assert lib.qs_attn_draft(ctypes.byref(_fake_cache(B)), 0x200000, 0x300000, bad, 0x400000, ws, None, None) == B.QS_ERR_RANGE
     assert verify(_fake_cache(B), 0) == B.QS_ERR_UNSUPPORTED
     assert verify(_fake_cache(B), 9) == B.QS_ERR_UNSUPPORTED
     c = _fake_cache(B); c._keep[0][0] = 100            # n_quant not a multiple of 128
