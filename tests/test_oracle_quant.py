@@ -173,7 +173,7 @@ def test_error_bounds_and_clamp_rate():
         else:
             ug = u.reshape(-1, 128, 128)
             assert np.all(ug.min(axis=1) == 0) and np.all(ug.max(axis=1) == 15)
-        # "E_U is symmetric with expectation close to zero" (Section 4.2)
+        # the error left by C_U is symmetric around zero with a mean near zero (Section 4.2)
         assert abs(l.astype(np.float64).mean()) < 0.1
         assert abs((x64 - x4).mean()) < 0.01 * se.mean()
 
