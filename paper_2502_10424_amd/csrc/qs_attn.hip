@@ -29,10 +29,6 @@
 
 #include "qs_internal.h"
 
-#ifndef QS_AHEAD
-#define QS_AHEAD ((!VERIFY && !KSPLIT) ? 2 : 1)
-#endif
-
 namespace qs {
 namespace {
 
@@ -259,7 +255,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   // keeps in flight, divided by the memory latency under load, cap the bandwidth below what the
   // memory delivers; the draft kernel has the registers for a second one (three of the four named
   // buffers are live at any time).
-  constexpr int kAhead = QS_AHEAD;
+  constexpr int kAhead = (!VERIFY && !KSPLIT) ? 2 : 1;
   Blk bufA, bufB, bufC, bufD;
   load_block(bufA, 0);   // in flight while the queries and the first group's metadata arrive
   if (kAhead == 2) load_block(bufB, 1);
