@@ -50,10 +50,10 @@ def flush_bytes(w, n):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="mha128k")
-    ap.add_argument("--copies", type=int, default=3, help="independent cache copies to rotate over")
+    ap.add_argument("--copies", type=int, default=4, help="independent cache copies to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the timed cycle: no prefill timing, fp16 baseline or speculation loop (for kernel traces)")
@@ -150,7 +150,8 @@ def main():
     gc.enable()
 
     ms_per_step = elapsed * 1e3 / args.steps
-    avg_us = {k: 1e3 * float(np.mean([a.elapsed_time(b) / n for a, b, n in v])) for k, v in timed.items()}
+    per_call = {k: np.array([1e3 * a.elapsed_time(b) / n for a, b, n in v]) for k, v in timed.items()}
+    avg_us = {k: float(v.mean()) for k, v in per_call.items()}
     bytes_d, bytes_v = algorithmic_bytes(w, 1, False), algorithmic_bytes(w, nqv, True)
     gbps_d = bytes_d / (avg_us["draft"] * 1e-6) / 1e9
     gbps_v = bytes_v / (avg_us["verify"] * 1e-6) / 1e9
@@ -169,6 +170,8 @@ def main():
                    "cache_copies_rotated": len(caches), "flush_tokens_per_cycle": 128},
         "draft_us": round(avg_us["draft"], 2), "verify_us": round(avg_us["verify"], 2),
         "flush_us": round(avg_us["flush"], 2),
+        "median_us": {k: round(float(np.median(v)), 2) for k, v in per_call.items()},
+        "min_us": {k: round(float(v.min()), 2) for k, v in per_call.items()},
         "draft_GBps": round(gbps_d, 1), "verify_GBps": round(gbps_v, 1),
         "cycle_GBps": round(cycle_bytes / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": {"bound": "hbm", "kernel": "draft call: attn_kernel<1,false> + merge_kernel (upper plane)",
