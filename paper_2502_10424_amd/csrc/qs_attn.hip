@@ -196,6 +196,8 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   //   verify: code operand carries 2^-24 and the codes are 16*C_U + C_L + 8 in units of S/16
   constexpr float kKeyPos = VERIFY ? 1.0f : 0.0625f;             // factor on q at elements 2,3,6,7
   constexpr float kKeyRaw = VERIFY ? 1048576.0f : 16777216.0f;   // score = raw * kKeyRaw * c0
+  // p*S is lifted by 4 before it becomes fp16: the largest factor that cannot overflow whatever S is
+  // (S <= 2 * 65504 / 15), and two more bits before small p*S turn subnormal.
   constexpr float kPA = 4.0f;                                    // factor on p*S at elements 0,1,4,5
   constexpr float kPB = VERIFY ? 4.0f : 0.25f;                   // factor on p*S at elements 2,3,6,7
   constexpr float kOutRaw = VERIFY ? 262144.0f : 4194304.0f;     // out = rawO * kOutRaw + sum p*Zeff
