@@ -394,6 +394,24 @@ def test_attention_large_and_small_magnitudes(env):
         _check_attn(env, cache, oc, q[:, :1].copy(), sm, False, tag=f"draft |q|~{qmag:g} |k|~{kmag:g}")
 
 
+@pytest.mark.parametrize("vmag", [1e-2, 0.1, 100.0, 3000.0])
+def test_attention_value_magnitudes(env, vmag):
+    """Values five orders of magnitude apart, flat and peaked softmax.  p * S_V travels as fp16 (times 4,
+    the largest factor that is safe for every representable S_V), so value ranges down to about 1e-2
+    keep full accuracy; far smaller ones would lose bits to fp16 subnormals and are out of range."""
+    O, U = env["O"], env["U"]
+    rng = np.random.default_rng(int(vmag * 1000) + 3)
+    t, nb = 1024, 19
+    for qmag in (0.3, 4.0):
+        k = rng.standard_normal((1, 2, t + nb, 128)).astype(np.float16)
+        v = (rng.standard_normal((1, 2, t + nb, 128)) * vmag).astype(np.float16)
+        q = (rng.standard_normal((1, 3, 4, 128)) * qmag).astype(np.float16)
+        cache = U.make_device_cache(k, v, 4, nb, buf_cap=32)
+        oc = O.build_cache(k, v, 4, 128, nb)
+        _check_attn(env, cache, oc, q, 0.088, True, tag=f"verify |v|~{vmag:g} |q|~{qmag:g}")
+        _check_attn(env, cache, oc, q[:, :1].copy(), 0.088, False, tag=f"draft |v|~{vmag:g} |q|~{qmag:g}")
+
+
 def test_attention_lossless_grid_matches_unquantized(env):
     """Property that holds without the oracle's quantizer: 4-bit-grid data through the draft pass equals
     plain fp64 attention over the original tensors."""
