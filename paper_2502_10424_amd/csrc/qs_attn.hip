@@ -100,7 +100,9 @@ __device__ __forceinline__ float group_sum(float x) {
 
 template <int NRT>
 struct RowState {
-  float m[NRT];        // running max of the scaled scores (log2 units), identical in the 4 lanes of a column
+  float m[NRT];        // reference exponent of the row: running max of the scaled scores (log2 units) plus e
+  float e;             // floor(log2) of the largest value scale met so far by the wave; 0 in the buffer chunk
+  float s_limit;       // 2^(e + 1): a larger value scale raises e
   float l[NRT];        // running sum of p over this lane's tokens
   float z[NRT];        // running sum of p * zero-point over this lane's tokens
   float4v o[NRT][8];   // O^T accumulators: tile n, element jj -> channel 8*(4*g + jj) + n
@@ -109,7 +111,8 @@ struct RowState {
 // Online-softmax update for one 32-token block.  raw[rt][j] are this lane's eight scores (query
 // column rho, tokens tile_token(g, j)) before scaling, each still short of the additive term
 // bias[rt] (the zero-point part of the score, the same for every token of a group); on return they
-// hold the probabilities.  The running max only moves when some score of the wave exceeds it;
+// hold the probabilities relative to the row's reference exponent m = (largest score so far) + e
+// (e: see raise_scale_reference).  The reference only moves when some score of the wave exceeds it;
 // otherwise the cross-lane reduction and the rescaling of the accumulators are skipped altogether.
 template <int NRT>
 __device__ __forceinline__ void softmax_block(RowState<NRT>& st, float (&raw)[NRT][8], const float (&mul)[NRT],
@@ -118,8 +121,9 @@ __device__ __forceinline__ void softmax_block(RowState<NRT>& st, float (&raw)[NR
   bool grow = false;
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
-    mx[rt] = (fmaxf(fmaxf(fmaxf(raw[rt][0], raw[rt][1]), fmaxf(raw[rt][2], raw[rt][3])),
-                    fmaxf(fmaxf(raw[rt][4], raw[rt][5]), fmaxf(raw[rt][6], raw[rt][7]))) + bias[rt]) * mul[rt];   // mul > 0
+    const float top = fmaxf(fmaxf(fmaxf(raw[rt][0], raw[rt][1]), fmaxf(raw[rt][2], raw[rt][3])),
+                            fmaxf(fmaxf(raw[rt][4], raw[rt][5]), fmaxf(raw[rt][6], raw[rt][7])));
+    mx[rt] = __builtin_fmaf(top + bias[rt], mul[rt], st.e);   // mul > 0
     grow |= mx[rt] > st.m[rt];
   }
   if (__any(grow)) {
@@ -144,6 +148,37 @@ __device__ __forceinline__ void softmax_block(RowState<NRT>& st, float (&raw)[NR
       sum += raw[rt][j];
     }
     st.l[rt] += sum;
+  }
+}
+
+// The row reference carries, on top of the largest score, the exponent e of the largest value scale S
+// met so far, so that p * S, which enters the second contraction as fp16, is at most 2 for the
+// largest S and keeps its bits however small or large the values are.  A reference is only a
+// convention between the accumulators and the partial written at the end: sum, zero-point term and
+// output all carry it and the merge of the partials is indifferent to it.  Called with this lane's
+// largest scale of the block after the block's probabilities exist and before they are used: when a
+// scale of the wave exceeds 2^(e+1), e is raised and everything that carries the old reference,
+// the block's probabilities included, is scaled down by the same power of two.
+template <int NRT>
+__device__ __forceinline__ void raise_scale_reference(RowState<NRT>& st, float (&p)[NRT][8], float smax) {
+  if (__any(smax > st.s_limit)) {
+    const float s_all = group_max(smax);   // the same in every lane: lanes of one group share their tokens
+    const uint32_t ebits = __builtin_bit_cast(uint32_t, s_all) & 0x7f800000u;   // 2^floor(log2 s_all)
+    const float e_new = (float)((int)(ebits >> 23) - 127);
+    const float delta = e_new - st.e;                     // > 0
+    const float alpha = __builtin_amdgcn_exp2f(-delta);   // a power of two: exact
+    st.e = e_new;
+    st.s_limit = 2.0f * __builtin_bit_cast(float, ebits);
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      st.m[rt] += delta;
+      st.l[rt] *= alpha;
+      st.z[rt] *= alpha;
+#pragma unroll
+      for (int n = 0; n < 8; ++n) st.o[rt][n] *= alpha;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) p[rt][j] *= alpha;
+    }
   }
 }
 
@@ -196,13 +231,15 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   //   verify: code operand carries 2^-24 and the codes are 16*C_U + C_L + 8 in units of S/16
   constexpr float kKeyPos = VERIFY ? 1.0f : 0.0625f;             // factor on q at elements 2,3,6,7
   constexpr float kKeyRaw = VERIFY ? 1048576.0f : 16777216.0f;   // score = raw * kKeyRaw * c0
-  // p*S is lifted by 4 before it becomes fp16: the largest factor that cannot overflow whatever S is
-  // (S <= 2 * 65504 / 15), and two more bits before small p*S turn subnormal.
+  // p*S (at most 2, see raise_scale_reference) takes a factor 4 or 1/4 that evens out the two bit
+  // positions a code can sit at.
   constexpr float kPA = 4.0f;                                    // factor on p*S at elements 0,1,4,5
   constexpr float kPB = VERIFY ? 4.0f : 0.25f;                   // factor on p*S at elements 2,3,6,7
   constexpr float kOutRaw = VERIFY ? 262144.0f : 4194304.0f;     // out = rawO * kOutRaw + sum p*Zeff
 
   RowState<NRT> st;
+  st.e = -40.f;   // below every value scale (>= 2^-24): the first block raises it
+  st.s_limit = 0x1p-39f;
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
     st.m[rt] = kNegBig; st.l[rt] = 0.f; st.z[rt] = 0.f;
@@ -382,6 +419,11 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
 
     // ---- probabilities x value scale -> B operand; zero-point term ----
     const half8 vS = as_half8(d.vS), vZ = as_half8(d.vZ);
+    float sv[8];
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj) sv[jj] = (float)vS[jj];
+    raise_scale_reference<NRT>(st, raw, fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
+                                              fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7]))));
     half8 pb[NRT];
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt) {
@@ -389,10 +431,9 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
       half8 ps;
 #pragma unroll
       for (int jj = 0; jj < 8; ++jj) {
-        const float sv = (float)vS[jj];
-        const float zeff = VERIFY ? __builtin_fmaf(-0.5f, sv, (float)vZ[jj]) : (float)vZ[jj];
+        const float zeff = VERIFY ? __builtin_fmaf(-0.5f, sv[jj], (float)vZ[jj]) : (float)vZ[jj];
         zs = __builtin_fmaf(raw[rt][jj], zeff, zs);
-        ps[jj] = (_Float16)(raw[rt][jj] * sv);
+        ps[jj] = (_Float16)(raw[rt][jj] * sv[jj]);
       }
       st.z[rt] += zs;
       u32x4 pw = as_u32x4(ps);
@@ -488,6 +529,8 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
     }
   }
   RowState<NRT> st;
+  st.e = 0.f;   // no value scales here: the reference is the largest score itself
+  st.s_limit = __builtin_inff();
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
     st.m[rt] = kNegBig; st.l[rt] = 0.f; st.z[rt] = 0.f;

@@ -394,11 +394,11 @@ def test_attention_large_and_small_magnitudes(env):
         _check_attn(env, cache, oc, q[:, :1].copy(), sm, False, tag=f"draft |q|~{qmag:g} |k|~{kmag:g}")
 
 
-@pytest.mark.parametrize("vmag", [1e-2, 0.1, 100.0, 3000.0])
+@pytest.mark.parametrize("vmag", [1e-3, 1e-2, 0.1, 100.0, 3000.0])
 def test_attention_value_magnitudes(env, vmag):
-    """Values five orders of magnitude apart, flat and peaked softmax.  p * S_V travels as fp16 (times 4,
-    the largest factor that is safe for every representable S_V), so value ranges down to about 1e-2
-    keep full accuracy; far smaller ones would lose bits to fp16 subnormals and are out of range."""
+    """Values six orders of magnitude apart, flat and peaked softmax.  p * S_V travels as fp16; the
+    reference exponent of the online softmax follows the largest value scale, so small value ranges
+    keep their bits.  (Below about 1e-3 the fp16 *output* itself runs into subnormals.)"""
     O, U = env["O"], env["U"]
     rng = np.random.default_rng(int(vmag * 1000) + 3)
     t, nb = 1024, 19
@@ -410,6 +410,26 @@ def test_attention_value_magnitudes(env, vmag):
         oc = O.build_cache(k, v, 4, 128, nb)
         _check_attn(env, cache, oc, q, 0.088, True, tag=f"verify |v|~{vmag:g} |q|~{qmag:g}")
         _check_attn(env, cache, oc, q[:, :1].copy(), 0.088, False, tag=f"draft |v|~{vmag:g} |q|~{qmag:g}")
+
+
+def test_attention_value_scale_jumps(env):
+    """Value scales that change by many orders of magnitude inside one chunk: near-zero values at the
+    start (an attention-sink-like prefix), a stretch 2000 times larger than the rest, constant rows.
+    The reference exponent has to rise in mid-stream and rescale what was accumulated before."""
+    O, U = env["O"], env["U"]
+    rng = np.random.default_rng(77)
+    t, nb = 2048, 21
+    k = rng.standard_normal((2, 1, t + nb, 128)).astype(np.float16)
+    v = (rng.standard_normal((2, 1, t + nb, 128)) * 0.5).astype(np.float16)
+    v[:, :, :70] *= np.float16(1e-4)            # tiny scales first
+    v[:, :, 700:900] *= np.float16(2000.0)      # then a jump of seven orders of magnitude
+    v[0, :, 1000:1010] = 0.25                   # constant rows: S := 1
+    v[1, :, 1500:] *= np.float16(1e-3)          # and small again (the exponent stays up)
+    q = (rng.standard_normal((2, 4, 2, 128)) * 1.5).astype(np.float16)
+    cache = U.make_device_cache(k, v, 2, nb, buf_cap=32)
+    oc = O.build_cache(k, v, 2, 128, nb)
+    _check_attn(env, cache, oc, q, 0.088, True, tag="verify, value scale jumps")
+    _check_attn(env, cache, oc, q[:, :1].copy(), 0.088, False, tag="draft, value scale jumps")
 
 
 def test_attention_lossless_grid_matches_unquantized(env):
