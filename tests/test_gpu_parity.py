@@ -412,6 +412,26 @@ def test_attention_value_magnitudes(env, vmag):
         _check_attn(env, cache, oc, q[:, :1].copy(), 0.088, False, tag=f"draft |v|~{vmag:g} |q|~{qmag:g}")
 
 
+@pytest.mark.parametrize("kmag", [0.1, 100.0, 3000.0])
+def test_attention_key_magnitudes(env, kmag):
+    """Keys four orders of magnitude apart with a softmax scale that keeps the scores at O(1), flat and
+    peaked.  q * S_K travels as two fp16 numbers with q normalised to at most 1 per row, so key scales
+    down to about 1e-2 (key spread 0.1) are safe; much smaller ones push q * S_K into fp16 subnormals
+    and are out of range (the quantized keys of a model are O(1))."""
+    O, U = env["O"], env["U"]
+    rng = np.random.default_rng(int(kmag * 10) + 11)
+    t, nb = 1024, 19
+    for peak in (0.5, 3.0):
+        k = (rng.standard_normal((1, 2, t + nb, 128)) * kmag).astype(np.float16)
+        v = rng.standard_normal((1, 2, t + nb, 128)).astype(np.float16)
+        q = rng.standard_normal((1, 3, 4, 128)).astype(np.float16)
+        sm = peak / (kmag * np.sqrt(128))
+        cache = U.make_device_cache(k, v, 4, nb, buf_cap=32)
+        oc = O.build_cache(k, v, 4, 128, nb)
+        _check_attn(env, cache, oc, q, sm, True, tag=f"verify |k|~{kmag:g} peak {peak}")
+        _check_attn(env, cache, oc, q[:, :1].copy(), sm, False, tag=f"draft |k|~{kmag:g} peak {peak}")
+
+
 def test_attention_value_scale_jumps(env):
     """Value scales that change by many orders of magnitude inside one chunk: near-zero values at the
     start (an attention-sink-like prefix), a stretch 2000 times larger than the rest, constant rows.
