@@ -30,8 +30,8 @@ SPEC_GAMMAS = (1, 2, 4, 6)      # speculation lengths of the simulated decode lo
 # (calibrated against a plain copy kernel).  Filled from the summaries under profiles/; None = not measured.
 MEASURED_TRAFFIC_BYTES = {
     # profiles/attn_mha128k_hbm_traffic.md: (FETCH_SIZE x 1.99991 + WRITE_SIZE x 1.0) KiB per dispatch
-    ("mha128k", "draft"): int((280268.2 * 1.99991 + 1106.3) * 1024),
-    ("mha128k", "verify"): int((542206.6 * 1.99991 + 5554.1) * 1024),
+    ("mha128k", "draft"): int((280287.4 * 1.99991 + 1106.0) * 1024),
+    ("mha128k", "verify"): int((542234.9 * 1.99991 + 5554.9) * 1024),
 }
 
 
