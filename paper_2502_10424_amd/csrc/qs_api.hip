@@ -139,7 +139,7 @@ int attn_common(const qs_cache* c, const void* q, int32_t nq, void* out, float s
 }
 
 int quantize_common(const qs_cache* c, const _Float16* k_src, const _Float16* v_src, int64_t src_stride,
-                    int32_t n_tokens, hipStream_t s) {
+                    int32_t n_tokens, bool move_buffer, hipStream_t s) {
   FlushArgs f;
   f.k_src = k_src;
   f.v_src = v_src;
@@ -150,7 +150,12 @@ int quantize_common(const qs_cache* c, const _Float16* k_src, const _Float16* v_
   f.n_kv_heads = c->n_kv_heads;
   f.q_cap = c->q_cap;
   f.n_groups = n_tokens / kG;
-  for (int b = 0; b < QS_MAX_BATCH; ++b) f.n_quant[b] = b < c->batch ? c->n_quant[b] : 0;
+  f.k_move = move_buffer ? static_cast<_Float16*>(c->k_buf) : nullptr;
+  f.v_move = move_buffer ? static_cast<_Float16*>(c->v_buf) : nullptr;
+  for (int b = 0; b < QS_MAX_BATCH; ++b) {
+    f.n_quant[b] = b < c->batch ? c->n_quant[b] : 0;
+    f.n_buf[b] = b < c->batch ? c->n_buf[b] : 0;
+  }
   return launch_flush(f, c->batch, s) == hipSuccess ? QS_OK : QS_ERR_HIP;
 }
 
@@ -192,9 +197,11 @@ int qs_quantize_flush(const qs_cache* c, int32_t n_tokens, void* stream) {
     if (n_tokens > c->n_buf[b] || c->n_quant[b] + n_tokens > c->q_cap) return QS_ERR_RANGE;
   if (n_tokens == 0) return QS_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  // one group: the flush kernel moves the rest of the buffer itself; more: a second kernel does
+  const bool fused = flush_moves_buffer(n_tokens / kG, c->batch * c->n_kv_heads);
   rc = quantize_common(c, static_cast<const _Float16*>(c->k_buf), static_cast<const _Float16*>(c->v_buf),
-                       c->buf_cap, n_tokens, s);
-  if (rc != QS_OK) return rc;
+                       c->buf_cap, n_tokens, fused, s);
+  if (rc != QS_OK || fused) return rc;
   ShiftArgs sh;
   sh.k_buf = static_cast<_Float16*>(c->k_buf);
   sh.v_buf = static_cast<_Float16*>(c->v_buf);
@@ -221,7 +228,7 @@ int qs_quantize_prefill(const qs_cache* c, const void* k_src, const void* v_src,
     if (c->n_quant[b] + n_tokens > c->q_cap) return QS_ERR_RANGE;
   if (n_tokens == 0) return QS_OK;
   return quantize_common(c, static_cast<const _Float16*>(k_src), static_cast<const _Float16*>(v_src),
-                         src_stride_tokens, n_tokens, static_cast<hipStream_t>(stream));
+                         src_stride_tokens, n_tokens, false, static_cast<hipStream_t>(stream));
 }
 
 int qs_append(const qs_cache* c, const void* k_new, const void* v_new, int32_t n_new, void* stream) {

@@ -157,6 +157,15 @@ __device__ __forceinline__ void store_key_meta(const Args& a, int unit, int tq0,
 //   threads   0..127 : keys, channels [32q, 32q+32) of all 128 tokens
 //   threads 128..255 : values, tokens [32q, 32q+32) (one value tile) of all 128 channels
 // Each thread owns 4 channels of the eight tokens that share a value-plane word (32 codes).
+//
+// Buffer move (Section 4.3.2), when the source is the buffer and one group is flushed: rows
+// [128, n_buf) become rows [0, n_buf - 128) in the same launch.  Every buffer byte is read - as
+// input of the quantization or as source of the move - only by the workgroup that overwrites it:
+// workgroup q moves byte columns [64q, 64q+64) of the key rows (it alone quantizes them) and all
+// columns of the value rows r with (r mod 128) / 32 = q (its value tile and the rows that land on
+// it), and a thread keeps one row residue mod 128, so a row that is both destination and source is
+// read and later written by the same thread.  The barrier after the statistics, which consume every
+// quantization input, orders the reads of rows [0, 128) before the first store of the move.
 __global__ __launch_bounds__(256) void flush_kernel(FlushArgs a) {
   __shared__ float red[2][32][2];
   const int grp = blockIdx.x >> 2, q = blockIdx.x & 3, unit = blockIdx.y;
@@ -164,6 +173,22 @@ __global__ __launch_bounds__(256) void flush_kernel(FlushArgs a) {
   const int tid = threadIdx.x;
   const int tq0 = a.n_quant[b] + grp * kG;     // destination token offset inside the unit
   const int64_t src0 = ((int64_t)unit * a.src_stride + (int64_t)grp * kG) * kD;
+
+  // move: 64 bytes of one row per thread and round.  The first round's sources are fetched up front,
+  // unconditionally (a thread with nothing to move reads a valid address and drops the data), so the
+  // loads stay in flight under the quantization.
+  const bool move = a.k_move != nullptr;
+  const int n_keep = move ? a.n_buf[b] - kG : 0;
+  const int mrow = tid < 128 ? tid : 32 * q + ((tid - 128) >> 2);
+  _Float16* mcol = !move ? nullptr
+                         : (tid < 128 ? a.k_move + 32 * q : a.v_move + 32 * (tid & 3)) + (int64_t)unit * a.src_stride * kD;
+  const _Float16* mfirst = mrow < n_keep ? mcol + (int64_t)(mrow + kG) * kD : a.k_src + src0;
+  auto load64 = [](const _Float16* p, uint4& x0, uint4& x1, uint4& x2, uint4& x3) {
+    const uint4* w = reinterpret_cast<const uint4*>(p);
+    x0 = w[0], x1 = w[1], x2 = w[2], x3 = w[3];
+  };
+  uint4 mv0, mv1, mv2, mv3;   // named registers: an array here is moved to LDS by the compiler
+  load64(mfirst, mv0, mv1, mv2, mv3);
 
   if (tid < 128) {
     // ---- keys: min / max per channel over the 128 tokens of the group --------------------------
@@ -265,6 +290,11 @@ __global__ __launch_bounds__(256) void flush_kernel(FlushArgs a) {
     *reinterpret_cast<uint4*>(lb + w) = make_uint4(packed_word(vl[0][0], vl[0][1]), packed_word(vl[1][0], vl[1][1]),
                                                           packed_word(vl[2][0], vl[2][1]), packed_word(vl[3][0], vl[3][1]));
     __syncthreads();   // matches the barrier of the key half
+  }
+  for (int r = mrow; r < n_keep; r += kG) {
+    uint4* w = reinterpret_cast<uint4*>(mcol + (int64_t)r * kD);
+    w[0] = mv0, w[1] = mv1, w[2] = mv2, w[3] = mv3;
+    if (r + kG < n_keep) load64(mcol + (int64_t)(r + 2 * kG) * kD, mv0, mv1, mv2, mv3);
   }
 }
 
@@ -501,6 +531,8 @@ __global__ __launch_bounds__(256) void export_kernel(ExportArgs a) {
 }
 
 }  // namespace
+
+bool flush_moves_buffer(int n_groups, int units) { return n_groups == 1 && units < kBulkGroups; }
 
 hipError_t launch_flush(const FlushArgs& a, int batch, hipStream_t s) {
   if (a.n_groups <= 0) return hipSuccess;

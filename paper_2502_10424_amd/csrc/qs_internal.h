@@ -38,6 +38,10 @@ struct FlushArgs {
   const int32_t* group_table;            // device, [units][q_cap/128], or null: contiguous units
   int32_t n_kv_heads, q_cap, n_groups;   // n_groups = n_tokens / 128
   int32_t n_quant[QS_MAX_BATCH];
+  // Buffer move done by the flush kernel itself (one flushed group, source = the buffer): rows
+  // [128, n_buf) of k_move / v_move become rows [0, n_buf - 128).  Null: no move.
+  _Float16 *k_move, *v_move;
+  int32_t n_buf[QS_MAX_BATCH];
 };
 
 struct ShiftArgs {
@@ -90,6 +94,8 @@ __device__ __forceinline__ int64_t physical_group(const Args& a, int unit, int g
   return a.group_table != nullptr ? (int64_t)a.group_table[logical] : logical;
 }
 
+// True if a flush of n_groups groups of `units` units takes the kernel that can also move the buffer.
+bool flush_moves_buffer(int n_groups, int units);
 hipError_t launch_flush(const FlushArgs& a, int batch, hipStream_t s);
 hipError_t launch_shift(const ShiftArgs& a, int batch, hipStream_t s);
 hipError_t launch_export(const ExportArgs& a, hipStream_t s);

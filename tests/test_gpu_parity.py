@@ -83,6 +83,30 @@ def test_quantize_codes_bit_exact_tiny(env):
         U.assert_unit_equals_oracle(cache, oc, 0, h)
 
 
+@pytest.mark.parametrize("n_flush,n_buf,buf_cap", [(128, 428, 440), (128, 129, 264), (128, 128, 264), (256, 326, 400), (384, 517, 520)])
+def test_flush_moves_long_buffers(env, n_flush, n_buf, buf_cap):
+    """The rows left in the buffer after a flush move to its start: one flushed group (the flush
+    kernel moves them itself, here up to three rounds of 128 rows) and several groups (separate
+    kernel), with sources and destinations overlapping."""
+    torch, O, U, B = env["torch"], env["O"], env["U"], env["B"]
+    rng = np.random.default_rng(n_flush + n_buf)
+    bsz, hkv, hq = 2, 3, 6
+    t = 256 + n_buf
+    k = rng.standard_normal((bsz, hkv, t, 128)).astype(np.float16)
+    v = (rng.standard_normal((bsz, hkv, t, 128)) * 2 - 1).astype(np.float16)
+    _say(f"flush {n_flush} of {n_buf} buffered tokens, capacity {buf_cap}")
+    cache = U.make_device_cache(k, v, hq, n_buf, q_cap=256 + 512, buf_cap=buf_cap)
+    oc = O.build_cache(k, v, hq, 128, n_buf)
+    B.qs_quantize_flush(cache, n_flush)
+    cache.n_quant += n_flush
+    cache.n_buf -= n_flush
+    oc.flush(n_flush)
+    torch.cuda.synchronize()
+    for b in range(bsz):
+        for h in range(hkv):
+            U.assert_unit_equals_oracle(cache, oc, b, h)
+
+
 def test_flush_with_overlapping_buffer_move(env):
     """Paper cadence: G tokens are flushed while more than G stay behind (source and destination of
     the move overlap), on ragged batch lengths; repeated until the planes hold three more groups."""
