@@ -66,6 +66,7 @@ int validate_cache(const qs_cache* c) {
 // shapes and on the given maximum lengths only.
 struct Plan {
   int n_split_q, n_split_b;
+  int cu_wgs;   // > 0: workgroups of eight waves per unit, groups drawn dynamically (n_split_q = 8 * cu_wgs)
 };
 
 Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf) {
@@ -79,6 +80,16 @@ Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf) {
   p.n_split_q = std::max(1, std::min(want, groups));
   // the buffer: 64-token chunks while they fit the same budget of resident waves, longer ones beyond
   p.n_split_b = std::max(1, std::min((max_buf + kBufSplitTok - 1) / kBufSplitTok, std::max(want, kMinBufSplits)));
+  // Two waves per SIMD do not advance at the same pace (the older one wins the issue conflicts), so
+  // the one-tile kernels run as one eight-wave workgroup per compute unit whose waves share their
+  // groups through a queue - when every wave still gets a group and the workgroup's share of the
+  // buffer chunks fits its transpose tiles.
+  p.cu_wgs = 0;
+  const int wgs = want / kWavesPerCU;
+  if (n_rows <= 8 && wgs >= 1 && groups >= kWavesPerCU * wgs && p.n_split_b <= 4 * wgs) {
+    p.cu_wgs = wgs;
+    p.n_split_q = kWavesPerCU * wgs;
+  }
   return p;
 }
 
@@ -119,6 +130,7 @@ int attn_common(const qs_cache* c, const void* q, int32_t nq, void* out, float s
   a.buf_cap = c->buf_cap;
   a.n_split_q = p.n_split_q;
   a.n_split_b = p.n_split_b;
+  a.cu_wgs = p.cu_wgs;
   a.n_rows = nq * a.rep;
   a.c0 = sm_scale * 1.4426950408889634f;
   for (int b = 0; b < QS_MAX_BATCH; ++b) {

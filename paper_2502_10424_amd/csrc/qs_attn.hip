@@ -96,6 +96,28 @@ __device__ __forceinline__ float group_sum(float x) {
   x += __shfl_xor(x, 16);
   return x + __shfl_xor(x, 32);
 }
+// Over the eight lanes (l & ~7) .. (l | 7): used by the single-row path, where the eight tokens a
+// lane group shares are spread over eight lanes.
+__device__ __forceinline__ float octet_max(float x) {
+  x = fmaxf(x, __shfl_xor(x, 1));
+  x = fmaxf(x, __shfl_xor(x, 2));
+  return fmaxf(x, __shfl_xor(x, 4));
+}
+__device__ __forceinline__ float octet_sum(float x) {
+  x += __shfl_xor(x, 1);
+  x += __shfl_xor(x, 2);
+  return x + __shfl_xor(x, 4);
+}
+// Lane i of a 16-lane row takes `src` of lane i - K (K = 1..15); lanes i < K keep `old`.
+template <int K>
+__device__ __forceinline__ uint32_t row_shr_keep(uint32_t old, uint32_t src) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)old, (int)src, 0x110 + K, 0xF, 0xF, false);
+}
+// Lane i of a 16-lane row takes `src` of lane i + K; lanes past the end of the row take 0.
+template <int K>
+__device__ __forceinline__ uint32_t row_shl_zero(uint32_t src) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)src, 0x100 + K, 0xF, 0xF, true);
+}
 
 
 template <int NRT>
@@ -182,10 +204,74 @@ __device__ __forceinline__ void raise_scale_reference(RowState<NRT>& st, float (
   }
 }
 
+// One 32-token block of a kv-head with a single query row (multi-head attention, one decode query).
+// After the first contraction the row's 32 scores sit eight per lane in the four lanes of column 0
+// and the other 60 lanes would repeat the whole softmax on columns nobody reads.  Instead the eight
+// scores of lane (0, g) are dealt out to lanes (k, g), k = 0..7 (lanes 8..15 mirror them), so that
+// every lane carries ONE token: one exponential, one value scale, one zero-point per lane and block.
+// The probabilities go back as fp16 pairs, which leaves the second operand of the value contraction
+// complete in lane (0, g) - the only column whose result is kept.  Sums (l, z) stay per lane and are
+// folded over the eight lanes once, before the partial is written.
+// raw: this lane's eight combined scores (meaningful in column 0); s_bits, z_bits: fp16 scale and
+// zero-point of token tile_token(g, rho & 7).  Returns the lane's operand of the value contraction.
+template <bool VERIFY>
+__device__ __forceinline__ half8 single_row_block(RowState<1>& st, const float (&raw)[8], float mul, float bias,
+                                                  uint32_t s_bits, uint32_t z_bits, int rho, float pos_a, float pos_b) {
+  auto bits = [](float f) { return __builtin_bit_cast(uint32_t, f); };
+  uint32_t w = bits(raw[0]);
+  w = row_shr_keep<1>(w, bits(raw[1]));
+  w = row_shr_keep<2>(w, bits(raw[2]));
+  w = row_shr_keep<3>(w, bits(raw[3]));
+  w = row_shr_keep<4>(w, bits(raw[4]));
+  w = row_shr_keep<5>(w, bits(raw[5]));
+  w = row_shr_keep<6>(w, bits(raw[6]));
+  w = row_shr_keep<7>(w, bits(raw[7]));
+  w = (uint32_t)__builtin_amdgcn_update_dpp((int)w, (int)w, 0x118, 0xF, 0xC, false);   // lanes 8..15 <- lanes 0..7
+  const float x = __builtin_bit_cast(float, w);
+
+  const float s = __builtin_fmaf(x + bias, mul, st.e);
+  if (__any(s > st.m[0])) {
+    const float m_new = fmaxf(st.m[0], group_max(octet_max(s)));
+    const float alpha = __builtin_amdgcn_exp2f(st.m[0] - m_new);
+    st.m[0] = m_new;
+    st.l[0] *= alpha;
+    st.z[0] *= alpha;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) st.o[0][n] *= alpha;
+  }
+  float p = __builtin_amdgcn_exp2f(__builtin_fmaf(x, mul, __builtin_fmaf(bias, mul, -st.m[0])));
+
+  const float sv = (float)__builtin_bit_cast(_Float16, (uint16_t)s_bits);
+  const float zv = (float)__builtin_bit_cast(_Float16, (uint16_t)z_bits);
+  if (__any(sv > st.s_limit)) {   // see raise_scale_reference
+    const float s_all = group_max(octet_max(sv));
+    const uint32_t ebits = bits(s_all) & 0x7f800000u;
+    const float e_new = (float)((int)(ebits >> 23) - 127);
+    const float delta = e_new - st.e;
+    const float alpha = __builtin_amdgcn_exp2f(-delta);
+    st.e = e_new;
+    st.s_limit = 2.0f * __builtin_bit_cast(float, ebits);
+    st.m[0] += delta;
+    st.l[0] *= alpha;
+    st.z[0] *= alpha;
+#pragma unroll
+    for (int n = 0; n < 8; ++n) st.o[0][n] *= alpha;
+    p *= alpha;
+  }
+  st.l[0] += p;
+  st.z[0] = __builtin_fmaf(p, VERIFY ? __builtin_fmaf(-0.5f, sv, zv) : zv, st.z[0]);
+  _Float16 h = (_Float16)(p * sv);
+  h = h * (_Float16)((rho & 2) ? pos_b : pos_a);   // elements 2,3,6,7 of the operand: see the value unpacking
+  const uint32_t hb = __builtin_bit_cast(uint16_t, h);
+  const uint32_t pair = hb | (row_shl_zero<1>(hb) << 16);
+  const u32x4 pw = {pair, row_shl_zero<2>(pair), row_shl_zero<4>(pair), row_shl_zero<6>(pair)};
+  return as_half8(pw);
+}
+
 template <int NRT, int RPT>
 __device__ __forceinline__ void write_partial(const AttnArgs& a, RowState<NRT>& st, int b, int kvh, int row0,
                                               int split, float o_scale) {
-  const int lane = threadIdx.x, rho = lane & 15, g = lane >> 4;
+  const int lane = threadIdx.x & 63, rho = lane & 15, g = lane >> 4;
   const int n_split = a.n_split_q + a.n_split_b;
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
@@ -217,14 +303,37 @@ __device__ __forceinline__ void write_partial(const AttnArgs& a, RowState<NRT>& 
 // blocks of a group so that the query operand of the NEXT group (q*S, needs that group's key
 // metadata) is built one MFMA k-step per block and no bubble appears at group boundaries.
 // ------------------------------------------------------------------------------------------------
-template <int NRT, bool VERIFY, bool KSPLIT>
-__device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, int kvh, int row0, int split) {
+//
+// Which groups a wave walks: a fixed contiguous range (split `split` of n_split_q of the unit), or -
+// DYN - groups [g_base, g_base + g_count) handed out one at a time through the counter `queue` that
+// the waves of a workgroup share in LDS (first_claim: the value this wave already drew).  The
+// pipeline looks two groups ahead (block prefetch, key metadata of the next group), so the wave
+// always holds the group it computes and the next two it has drawn.
+template <int NRT, bool VERIFY, bool KSPLIT, bool SINGLE, bool DYN = false>
+__device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, int kvh, int row0, int split,
+                                            int* queue = nullptr, int g_base = 0, int g_count = 0, int first_claim = 0) {
+  static_assert(!SINGLE || (NRT == 1 && !KSPLIT), "the single-row path is a variant of the one-tile kernel");
   constexpr int RPT = KSPLIT ? 16 : 8;   // query rows per 16-column MFMA tile
-  const int lane = threadIdx.x, rho = lane & 15, g = lane >> 4;
+  const int lane = threadIdx.x & 63, rho = lane & 15, g = lane >> 4;
   const bool lo_part = !KSPLIT && rho >= 8;
   const int n_groups = a.len.n_quant[b] / kG;
-  const int first = (int)((int64_t)split * n_groups / a.n_split_q);
-  const int n_local = (int)((int64_t)(split + 1) * n_groups / a.n_split_q) - first;
+  int first = 0, n_local = 0;
+  int gq[3] = {-1, -1, -1};   // DYN: the group being computed and the two drawn after it (-1: none left)
+  auto draw = [&]() -> int {
+    int v = 0;
+    if (lane == 0) v = atomicAdd(queue, 1);
+    v = __builtin_amdgcn_readfirstlane(v);
+    return v < g_count ? g_base + v : -1;
+  };
+  if constexpr (DYN) {
+    gq[0] = first_claim < g_count ? g_base + first_claim : -1;
+    gq[1] = gq[0] >= 0 ? draw() : -1;
+    gq[2] = gq[1] >= 0 ? draw() : -1;
+    n_local = gq[0] >= 0 ? 1 : 0;
+  } else {
+    first = (int)((int64_t)split * n_groups / a.n_split_q);
+    n_local = (int)((int64_t)(split + 1) * n_groups / a.n_split_q) - first;
+  }
 
   // Powers of two folded out of the operands (see file header).
   //   draft : code operand carries 2^-24 (elements 0,1,4,5) or 2^-20 (elements 2,3,6,7)
@@ -256,7 +365,15 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   const bool paged = a.group_table != nullptr;
   const int64_t blk0 = ((int64_t)unit * (a.q_cap / kG) + first) * (kG / kBlkTok);
   auto block_index = [&](int j) -> int64_t {
-    return paged ? physical_group(a, unit, first + (j >> 2)) * (kG / kBlkTok) + (j & 3) : blk0 + j;
+    if constexpr (DYN) {   // j: 0..3 the current group, 4..7 the next, 8..11 the one after; none left: the last real one
+      const int sel = j >> 2;
+      int gi = gq[sel];
+      if (sel == 2 && gi < 0) gi = gq[1];
+      if (gi < 0) gi = gq[0];
+      return (paged ? physical_group(a, unit, gi) : (int64_t)unit * (a.q_cap / kG) + gi) * (kG / kBlkTok) + (j & 3);
+    } else {
+      return paged ? physical_group(a, unit, first + (j >> 2)) * (kG / kBlkTok) + (j & 3) : blk0 + j;
+    }
   };
   const int k_off = kOffK + rho * 64 + 16 * g;   // key rows rho and 16 + rho, channels 32g ..
   const int v_off = kOffV + 16 * lane;           // value tile, two halves of 1 KB
@@ -270,16 +387,21 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   };
   // loads of block j (chunk-local); past the end of the chunk the last block is re-read and never used
   auto load_block = [&](Blk& d, int j) {
-    const int jc = min(j, 4 * n_local - 1);
+    const int jc = DYN ? j : min(j, 4 * n_local - 1);
     const int64_t bj = block_index(jc);
     const uint8_t* u = a.upper + bj * kUpperBlk;
-    const uint8_t* un = a.upper + block_index(min((jc >> 2) + 1, n_local - 1) * 4 + (jc & 3)) * kUpperBlk;
+    const uint8_t* un = a.upper + block_index(DYN ? jc + 4 : min((jc >> 2) + 1, n_local - 1) * 4 + (jc & 3)) * kUpperBlk;
     d.kU[0] = ldg128(u + k_off);
     d.kU[1] = ldg128(u + k_off + 1024);
     d.vU[0] = ldg128(u + v_off);
     d.vU[1] = ldg128(u + v_off + 1024);
-    d.vS = ldg128(u + kOffVS + m_off);
-    d.vZ = ldg128(u + kOffVZ + m_off);
+    if (SINGLE) {   // this lane's own token only
+      d.vS[0] = *reinterpret_cast<const uint16_t*>(u + kOffVS + m_off + 2 * (rho & 7));
+      d.vZ[0] = *reinterpret_cast<const uint16_t*>(u + kOffVZ + m_off + 2 * (rho & 7));
+    } else {
+      d.vS = ldg128(u + kOffVS + m_off);
+      d.vZ = ldg128(u + kOffVZ + m_off);
+    }
     d.kS = ldg128(un + kOffKS + m_off);
     d.kZ = ldg128(un + kOffKZ + m_off);
     if (VERIFY) {
@@ -382,6 +504,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
       if (VERIFY) bias -= 0.5f * __builtin_fmaf(acc_sb[rt], 1.0f / kKeyPos, acc_sa[rt]);
       bias = group_sum(bias);
       cin[rt] = bias * (1.0f / kKeyRaw);   // added to the raw scores inside the softmax step
+      if (SINGLE) cin[rt] = __shfl(cin[rt], lane & 48);   // every lane works on the one row of column 0
 #pragma unroll
       for (int h = 0; h < NQB; ++h)
 #pragma unroll
@@ -415,31 +538,35 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
         }
     }
     prep_kstep(P, d.kS, d.kZ);   // one k-step of the next group's query operand
-    softmax_block<NRT>(st, raw, mul, cin);
-
-    // ---- probabilities x value scale -> B operand; zero-point term ----
-    const half8 vS = as_half8(d.vS), vZ = as_half8(d.vZ);
-    float sv[8];
-#pragma unroll
-    for (int jj = 0; jj < 8; ++jj) sv[jj] = (float)vS[jj];
-    raise_scale_reference<NRT>(st, raw, fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
-                                              fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7]))));
     half8 pb[NRT];
+    if constexpr (SINGLE) {
+      pb[0] = single_row_block<VERIFY>(st, raw[0], mul[0], cin[0], d.vS[0], d.vZ[0], rho, kPA, kPB);
+    } else {
+      softmax_block<NRT>(st, raw, mul, cin);
+
+      // ---- probabilities x value scale -> B operand; zero-point term ----
+      const half8 vS = as_half8(d.vS), vZ = as_half8(d.vZ);
+      float sv[8];
 #pragma unroll
-    for (int rt = 0; rt < NRT; ++rt) {
-      float zs = 0.f;
-      half8 ps;
+      for (int jj = 0; jj < 8; ++jj) sv[jj] = (float)vS[jj];
+      raise_scale_reference<NRT>(st, raw, fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
+                                                fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7]))));
 #pragma unroll
-      for (int jj = 0; jj < 8; ++jj) {
-        const float zeff = VERIFY ? __builtin_fmaf(-0.5f, sv[jj], (float)vZ[jj]) : (float)vZ[jj];
-        zs = __builtin_fmaf(raw[rt][jj], zeff, zs);
-        ps[jj] = (_Float16)(raw[rt][jj] * sv[jj]);
+      for (int rt = 0; rt < NRT; ++rt) {
+        float zs = 0.f;
+        half8 ps;
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+          const float zeff = VERIFY ? __builtin_fmaf(-0.5f, sv[jj], (float)vZ[jj]) : (float)vZ[jj];
+          zs = __builtin_fmaf(raw[rt][jj], zeff, zs);
+          ps[jj] = (_Float16)(raw[rt][jj] * sv[jj]);
+        }
+        st.z[rt] += zs;
+        u32x4 pw = as_u32x4(ps);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) pw[r] = as_u32(as_half2(pw[r]) * (_Float16)((r & 1) ? kPB : kPA));
+        pb[rt] = as_half8(pw);
       }
-      st.z[rt] += zs;
-      u32x4 pw = as_u32x4(ps);
-#pragma unroll
-      for (int r = 0; r < 4; ++r) pw[r] = as_u32(as_half2(pw[r]) * (_Float16)((r & 1) ? kPB : kPA));
-      pb[rt] = as_half8(pw);
     }
 
     // ---- O^T[channel, column] += codes^T x p ----
@@ -464,8 +591,8 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
              ldg128(ub + 3 * kUpperBlk + kOffKZ + m_off));
   prep_commit();
 
-  for (int lg = 0; lg < n_local; ++lg) {
-    const int j = 4 * lg;
+  for (int lg = 0; DYN ? gq[0] >= 0 : lg < n_local; ++lg) {
+    const int j = DYN ? 0 : 4 * lg;   // DYN: block numbers are relative to the current group
     if (kAhead == 2) {
       load_block(bufC, j + 2);
       compute_block(bufA, std::integral_constant<int, 0>{});
@@ -485,6 +612,15 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
       load_block(bufA, j + 4);
       compute_block(bufB, std::integral_constant<int, 3>{});
     }
+    if constexpr (DYN) {
+      gq[0] = gq[1];
+      gq[1] = gq[2];
+      gq[2] = gq[1] >= 0 ? draw() : -1;
+    }
+  }
+  if constexpr (SINGLE) {   // one token per lane: the row's sums are spread over eight lanes
+    st.l[0] = octet_sum(st.l[0]);
+    st.z[0] = octet_sum(st.z[0]);
   }
   write_partial<NRT, RPT>(a, st, b, kvh, row0, split, kOutRaw);
 }
@@ -497,13 +633,19 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
 // block's keys and values are in flight while the current one is computed.
 // ------------------------------------------------------------------------------------------------
 constexpr int kVtStride = 40;   // halfs per LDS row: 32 tokens + padding, keeps 8-byte reads aligned
+
+// A transpose tile is written and read by the lanes of ONE wave only.  The LDS executes a wave's
+// instructions in order, so all that is needed between its writes and its reads is that neither the
+// compiler nor the wave's own outstanding-operation counter lets them pass each other; a workgroup
+// barrier would be wrong where the waves of a workgroup work on unrelated items.
+__device__ __forceinline__ void wave_lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 constexpr float kBufP = 16384.0f;
 
 template <int NRT, bool KSPLIT>
 __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b, int kvh, int row0, int split,
                                              _Float16 (*vt)[kVtStride]) {
   constexpr int RPT = KSPLIT ? 16 : 8;
-  const int lane = threadIdx.x, rho = lane & 15, g = lane >> 4;
+  const int lane = threadIdx.x & 63, rho = lane & 15, g = lane >> 4;
   const bool lo_part = !KSPLIT && rho >= 8;   // the fp16 queries and keys need no remainder part
   const int nb = a.len.n_buf[b];
   // the buffer's 32-token blocks are dealt out evenly to its n_split_b chunks
@@ -584,7 +726,7 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
       }
     softmax_block<NRT>(st, raw, mulb, zero_bias);
 
-    __syncthreads();   // the previous block's LDS reads are done
+    wave_lds_sync();   // the previous block's LDS reads are done
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
       const int ch = 8 * (2 * it + cc);
@@ -592,7 +734,7 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
 #pragma unroll
       for (int i = 0; i < 8; ++i) vt[ch + i][tau] = v[i];
     }
-    __syncthreads();
+    wave_lds_sync();
     half8 pb[NRT];
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt)
@@ -620,7 +762,7 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
 
 // NRT 16-column tiles per wave; KSPLIT = 16 query rows per tile instead of 8 (see quant_chunk).  The
 // kernels that carry at most one tile of 8 rows run two waves per SIMD, the others one.
-template <int NRT, bool VERIFY, bool KSPLIT>
+template <int NRT, bool VERIFY, bool KSPLIT, bool SINGLE = false>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NRT == 1 && !KSPLIT ? 2 : 1))) void attn_kernel(AttnArgs a) {
   __shared__ _Float16 vt[kD][kVtStride];   // value-tile transpose of the buffer chunk
   // Dispatch order: unit fastest, the (short) buffer chunks of every unit before any quantized
@@ -631,9 +773,44 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NRT == 1 && 
   const int split = (int)blockIdx.y < a.n_split_b ? a.n_split_q + blockIdx.y : blockIdx.y - a.n_split_b;
   const int b = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   if (split < a.n_split_q)
-    quant_chunk<NRT, VERIFY, KSPLIT>(a, unit, b, kvh, row0, split);
+    quant_chunk<NRT, VERIFY, KSPLIT, SINGLE>(a, unit, b, kvh, row0, split);
   else
     buffer_chunk<NRT, KSPLIT>(a, unit, b, kvh, row0, split, vt);
+}
+
+// One workgroup per compute unit: eight waves (two per SIMD) share 1/W of a unit's quantized groups
+// (W = gridDim.y) and draw them one at a time from a counter in LDS, so a wave that the hardware
+// serves faster - the older of the two waves of a SIMD wins every issue conflict, and finishes a
+// fixed share tens of microseconds before the younger one - simply takes more groups, and the eight
+// finish together.  Buffer chunks w, w + W, ... of the unit are the first items of the same queue.
+// Each wave still writes one partial for its quantized groups (slot 8*w + wave).  For the kernels
+// with at most 8 query rows per kv-head; the planner guarantees at most four buffer items per
+// workgroup (one transpose tile each).
+constexpr int kCuWaves = 8, kCuBufItems = 4;
+template <bool VERIFY, bool SINGLE>
+__global__ __launch_bounds__(64 * kCuWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_kernel_cu(AttnArgs a) {
+  __shared__ _Float16 vt[kCuBufItems][kD][kVtStride];
+  __shared__ int queue;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int unit = blockIdx.x, w = blockIdx.y, n_wg = gridDim.y;
+  const int b = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
+  const int n_groups = a.len.n_quant[b] / kG;
+  const int g0 = (int)((int64_t)w * n_groups / n_wg), g1 = (int)((int64_t)(w + 1) * n_groups / n_wg);
+  const int n_buf_items = w < a.n_split_b ? (a.n_split_b - w + n_wg - 1) / n_wg : 0;
+  if (threadIdx.x == 0) queue = -n_buf_items;
+  __syncthreads();
+  auto draw = [&]() -> int {
+    int v = 0;
+    if (lane == 0) v = atomicAdd(&queue, 1);
+    return __builtin_amdgcn_readfirstlane(v);
+  };
+  int c = draw();
+  while (c < 0) {   // a buffer item: a partial of its own
+    const int item = -c - 1;
+    buffer_chunk<1, false>(a, unit, b, kvh, 0, a.n_split_q + w + n_wg * item, vt[item]);
+    c = draw();
+  }
+  quant_chunk<1, VERIFY, false, SINGLE, true>(a, unit, b, kvh, 0, kCuWaves * w + wave, &queue, g0, g1 - g0, c);
 }
 
 // Merge of the per-chunk partials (Appendix E): M = max m_i, L = sum l_i 2^(m_i - M),
@@ -716,6 +893,21 @@ hipError_t launch_attn_nrt(const AttnArgs& a, int batch, bool verify, hipStream_
 // up to 8 query rows per kv-head: one tile, remainder in columns 8-15; up to 16: one tile, remainder as a
 // second operand; more: two such tiles per wave (and row batches over grid.z beyond 32 rows)
 hipError_t launch_attn(const AttnArgs& a, int batch, bool verify, hipStream_t s) {
+  if (a.cu_wgs > 0) {   // at most 8 rows and enough groups: one workgroup per compute unit, groups drawn dynamically
+    dim3 grid(batch * a.n_kv_heads, a.cu_wgs, 1);
+    if (verify)
+      hipLaunchKernelGGL((attn_kernel_cu<true, false>), grid, dim3(64 * kCuWaves), 0, s, a);
+    else if (a.n_rows == 1)
+      hipLaunchKernelGGL((attn_kernel_cu<false, true>), grid, dim3(64 * kCuWaves), 0, s, a);
+    else
+      hipLaunchKernelGGL((attn_kernel_cu<false, false>), grid, dim3(64 * kCuWaves), 0, s, a);
+    return hipGetLastError();
+  }
+  if (a.n_rows == 1 && !verify) {   // one query row per kv-head: one token per lane in the softmax
+    dim3 grid(batch * a.n_kv_heads, a.n_split_q + a.n_split_b, 1);
+    hipLaunchKernelGGL((attn_kernel<1, false, false, true>), grid, dim3(64), 0, s, a);
+    return hipGetLastError();
+  }
   if (a.n_rows <= 8) return launch_attn_nrt<1, false>(a, batch, verify, s);
   if (a.n_rows <= 16) return launch_attn_nrt<1, true>(a, batch, verify, s);
   return launch_attn_nrt<2, true>(a, batch, verify, s);

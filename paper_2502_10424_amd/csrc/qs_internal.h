@@ -76,6 +76,7 @@ struct AttnArgs {
   float* ws_ml;            // [rows_total][n_split][2]   (running max in log2 units, sum)
   int32_t n_q_heads, n_kv_heads, rep, nq, q_cap, buf_cap;
   int32_t n_split_q, n_split_b, n_rows;   // n_rows = nq * rep query rows per unit
+  int32_t cu_wgs;          // > 0: eight-wave workgroups per unit that draw groups dynamically (n_split_q = 8 * cu_wgs)
   float c0;                // sm_scale * log2(e)
   SeqLens len;
 };

@@ -509,5 +509,6 @@ def test_split_count_invariance(env):
     cacheN = U.make_device_cache(np.repeat(k1, reps, 0), np.repeat(v1, reps, 0), 2, 64)
     o1, _ = _run_attn(env, cache1, q1, 0.09, True)
     oN, _ = _run_attn(env, cacheN, np.repeat(q1, reps, 0), 0.09, True)
-    assert np.abs(oN - oN[:1]).max() == 0.0
+    # identical sequences agree to rounding only: which wave takes which group is decided at run time
+    assert U.rel_err(oN, np.repeat(oN[:1], reps, 0).astype(np.float64)) <= 1e-3   # one fp16 step of the output
     assert U.rel_err(oN[:1], o1.astype(np.float64)) <= 1e-3
