@@ -418,8 +418,22 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   // buffers are live at any time).
   constexpr int kAhead = (!VERIFY && !KSPLIT) ? 2 : 1;
   Blk bufA, bufB, bufC, bufD;
-  load_block(bufA, 0);   // in flight while the queries and the first group's metadata arrive
-  if (kAhead == 2) load_block(bufB, 1);
+  // Everything the first group needs is requested before anything is waited for: its blocks (all
+  // four where the registers allow, so that the memory pipeline is full while the query operand is
+  // prepared) and its key metadata.
+  load_block(bufA, 0);
+  if (kAhead == 2) {
+    load_block(bufB, 1);
+    load_block(bufC, 2);
+    load_block(bufD, 3);
+  }
+  const uint8_t* ub = a.upper + block_index(0) * kUpperBlk;   // the four blocks of a group are adjacent
+  u32x4 ks0[4], kz0[4];
+#pragma unroll
+  for (int s4 = 0; s4 < 4; ++s4) {
+    ks0[s4] = ldg128(ub + s4 * kUpperBlk + kOffKS + m_off);
+    kz0[s4] = ldg128(ub + s4 * kUpperBlk + kOffKZ + m_off);
+  }
 
   // Queries of this lane's column: channels 32*g + 8*s + operand order.  Each row is scaled by a power
   // of two so that max|q| <= 1 (then |q*S| <= 8734 cannot overflow fp16 whatever the inputs are); the
@@ -580,23 +594,20 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
     if (p == 3) prep_commit();
   };
 
-  // the first group's query operand straight from global memory
+  // the first group's query operand from the metadata requested at the start
   prep_reset();
-  const uint8_t* ub = a.upper + block_index(0) * kUpperBlk;   // the four blocks of a group are adjacent
-  prep_kstep(std::integral_constant<int, 0>{}, ldg128(ub + kOffKS + m_off), ldg128(ub + kOffKZ + m_off));
-  prep_kstep(std::integral_constant<int, 1>{}, ldg128(ub + kUpperBlk + kOffKS + m_off), ldg128(ub + kUpperBlk + kOffKZ + m_off));
-  prep_kstep(std::integral_constant<int, 2>{}, ldg128(ub + 2 * kUpperBlk + kOffKS + m_off),
-             ldg128(ub + 2 * kUpperBlk + kOffKZ + m_off));
-  prep_kstep(std::integral_constant<int, 3>{}, ldg128(ub + 3 * kUpperBlk + kOffKS + m_off),
-             ldg128(ub + 3 * kUpperBlk + kOffKZ + m_off));
+  prep_kstep(std::integral_constant<int, 0>{}, ks0[0], kz0[0]);
+  prep_kstep(std::integral_constant<int, 1>{}, ks0[1], kz0[1]);
+  prep_kstep(std::integral_constant<int, 2>{}, ks0[2], kz0[2]);
+  prep_kstep(std::integral_constant<int, 3>{}, ks0[3], kz0[3]);
   prep_commit();
 
   for (int lg = 0; DYN ? gq[0] >= 0 : lg < n_local; ++lg) {
     const int j = DYN ? 0 : 4 * lg;   // DYN: block numbers are relative to the current group
     if (kAhead == 2) {
-      load_block(bufC, j + 2);
+      if (lg > 0) load_block(bufC, j + 2);   // the first group's blocks are already on their way
       compute_block(bufA, std::integral_constant<int, 0>{});
-      load_block(bufD, j + 3);
+      if (lg > 0) load_block(bufD, j + 3);
       compute_block(bufB, std::integral_constant<int, 1>{});
       load_block(bufA, j + 4);
       compute_block(bufC, std::integral_constant<int, 2>{});
