@@ -98,6 +98,22 @@ int qs_version(void);
 const char *qs_strerror(int code);
 
 /*
+ * Process-wide settings of the attention planner (host only, thread-safe, take effect from the next
+ * call on; after a change of QS_CFG_COMPUTE_UNITS qs_workspace_bytes() must be asked again).  Not part of the method: they
+ * select between equivalent ways of dealing the work of Appendix E's chunked decode out to the chip.
+ *   QS_CFG_DETERMINISTIC  value 0 (default): where it pays, the waves of a compute unit draw their
+ *                         128-token groups from a shared queue at run time, so which partial sum a
+ *                         group lands in - and with it the last bit of an fp16 output - can differ
+ *                         from call to call.  value 1: every wave gets a fixed range; results are
+ *                         bit-reproducible (about 5 % slower at 128k context).
+ *   QS_CFG_COMPUTE_UNITS  number of compute units to plan for (> 0), or 0 for the device's own count
+ *                         (default); e.g. when part of the GPU is reserved for other work.
+ * Returns QS_OK, or QS_ERR_RANGE for an unknown key or a value out of range.
+ */
+enum qs_config_key { QS_CFG_DETERMINISTIC = 1, QS_CFG_COMPUTE_UNITS = 2 };
+int qs_configure(int32_t key, int32_t value);
+
+/*
  * Bytes of device scratch the attention calls need for their split-K partial results
  * (Appendix E: per-chunk partials that are merged afterwards).  Depends only on the shapes and
  * capacities in `c` and on nq (1 for draft), not on the current lengths, so it can be sized once.

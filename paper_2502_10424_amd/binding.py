@@ -27,7 +27,7 @@ QS_OK = 0
 QS_ERR_NULL, QS_ERR_SHAPE, QS_ERR_UNSUPPORTED, QS_ERR_ALIGN = -1, -2, -3, -4
 QS_ERR_RANGE, QS_ERR_WORKSPACE, QS_ERR_HIP = -5, -6, -7
 
-EXPORTS = ("qs_version", "qs_strerror", "qs_workspace_bytes", "qs_quantize_flush", "qs_quantize_prefill",
+EXPORTS = ("qs_version", "qs_strerror", "qs_configure", "qs_workspace_bytes", "qs_quantize_flush", "qs_quantize_prefill",
            "qs_append", "qs_attn_draft", "qs_attn_verify", "qs_export_codes")
 
 
@@ -64,6 +64,7 @@ def lib() -> ctypes.CDLL:
         vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
         l.qs_version.restype, l.qs_version.argtypes = ctypes.c_int, []
         l.qs_strerror.restype, l.qs_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
+        l.qs_configure.restype, l.qs_configure.argtypes = ctypes.c_int, [i32, i32]
         l.qs_workspace_bytes.restype, l.qs_workspace_bytes.argtypes = sz, [P, i32]
         l.qs_quantize_flush.restype, l.qs_quantize_flush.argtypes = ctypes.c_int, [P, i32, vp]
         l.qs_quantize_prefill.restype, l.qs_quantize_prefill.argtypes = ctypes.c_int, [P, vp, vp, i64, i32, vp]
@@ -84,6 +85,13 @@ def qs_version() -> int:
 
 def qs_strerror(code: int) -> str:
     return lib().qs_strerror(code).decode()
+
+
+QS_CFG_DETERMINISTIC, QS_CFG_COMPUTE_UNITS = 1, 2
+
+
+def qs_configure(key: int, value: int) -> None:
+    _check(lib().qs_configure(key, value), "qs_configure")
 
 
 def _ptr(t) -> int | None:

@@ -16,10 +16,14 @@ constexpr int kWavesPerCU = 8;
 constexpr int kWavesPerCUMultiTile = 4;
 constexpr int kMinBufSplits = 8;   // a decode-time buffer (2G + gamma + 1 tokens) always gets its 64-token chunks
 
-std::atomic<int> g_cu_count{0};
+std::atomic<int> g_cu_count{0};        // the device's compute units, read once
+std::atomic<int> g_cu_override{0};     // QS_CFG_COMPUTE_UNITS
+std::atomic<int> g_deterministic{0};   // QS_CFG_DETERMINISTIC
 
 int cu_count() {
-  int n = g_cu_count.load(std::memory_order_relaxed);
+  int n = g_cu_override.load(std::memory_order_relaxed);
+  if (n > 0) return n;
+  n = g_cu_count.load(std::memory_order_relaxed);
   if (n > 0) return n;
   int dev = 0;
   hipDeviceProp_t prop;
@@ -67,6 +71,7 @@ int validate_cache(const qs_cache* c) {
 struct Plan {
   int n_split_q, n_split_b;
   int cu_wgs;   // > 0: workgroups of eight waves per unit, groups drawn dynamically (n_split_q = 8 * cu_wgs)
+  int ws_splits;   // partial slots per query row to size the workspace for: covers either way of dealing out
 };
 
 Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf) {
@@ -85,8 +90,10 @@ Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf) {
   // groups through a queue - when every wave still gets a group and the workgroup's share of the
   // buffer chunks fits its transpose tiles.
   p.cu_wgs = 0;
+  p.ws_splits = p.n_split_q + p.n_split_b;
   const int wgs = want / kWavesPerCU;
-  if (n_rows <= 8 && wgs >= 1 && groups >= kWavesPerCU * wgs && p.n_split_b <= 4 * wgs) {
+  if (g_deterministic.load(std::memory_order_relaxed) == 0 && n_rows <= 8 && wgs >= 1 &&
+      groups >= kWavesPerCU * wgs && p.n_split_b <= 4 * wgs) {
     p.cu_wgs = wgs;
     p.n_split_q = kWavesPerCU * wgs;
   }
@@ -194,11 +201,26 @@ const char* qs_strerror(int code) {
   }
 }
 
+int qs_configure(int32_t key, int32_t value) {
+  switch (key) {
+    case QS_CFG_DETERMINISTIC:
+      if (value != 0 && value != 1) return QS_ERR_RANGE;
+      g_deterministic.store(value, std::memory_order_relaxed);
+      return QS_OK;
+    case QS_CFG_COMPUTE_UNITS:
+      if (value < 0 || value > 65536) return QS_ERR_RANGE;
+      g_cu_override.store(value, std::memory_order_relaxed);
+      return QS_OK;
+    default:
+      return QS_ERR_RANGE;
+  }
+}
+
 size_t qs_workspace_bytes(const qs_cache* c, int32_t nq) {
   if (validate_shape(c) != QS_OK || nq < 1 || nq > QS_MAX_NQ) return 0;
   const Plan p = make_plan(c, nq, c->q_cap, c->buf_cap);
   const size_t rows_total = (size_t)c->batch * nq * c->n_q_heads;
-  return rows_total * (size_t)(p.n_split_q + p.n_split_b) * (kD + 2) * sizeof(float);
+  return rows_total * (size_t)p.ws_splits * (kD + 2) * sizeof(float);
 }
 
 int qs_quantize_flush(const qs_cache* c, int32_t n_tokens, void* stream) {

@@ -35,6 +35,25 @@ def test_header_symbols_are_exported(B):
     assert "unknown" in B.qs_strerror(-99)
 
 
+def test_configure_validates_keys_and_values(B):
+    lib = B.lib()
+    assert lib.qs_configure(99, 0) == B.QS_ERR_RANGE
+    assert lib.qs_configure(B.QS_CFG_DETERMINISTIC, 2) == B.QS_ERR_RANGE
+    assert lib.qs_configure(B.QS_CFG_COMPUTE_UNITS, -1) == B.QS_ERR_RANGE
+    try:
+        c = _fake_cache(B)
+        w_default = B.qs_workspace_bytes(c, 1)
+        assert lib.qs_configure(B.QS_CFG_COMPUTE_UNITS, 1) == B.QS_OK
+        w_small = B.qs_workspace_bytes(c, 1)
+        assert 0 < w_small < w_default                      # fewer compute units: fewer chunks per unit
+        assert lib.qs_configure(B.QS_CFG_DETERMINISTIC, 1) == B.QS_OK
+        assert B.qs_workspace_bytes(c, 1) == w_small        # the workspace covers either way of dealing out
+    finally:
+        assert lib.qs_configure(B.QS_CFG_COMPUTE_UNITS, 0) == B.QS_OK
+        assert lib.qs_configure(B.QS_CFG_DETERMINISTIC, 0) == B.QS_OK
+    assert B.qs_workspace_bytes(_fake_cache(B), 1) == w_default
+
+
 def _fake_cache(B, **over):
     """A descriptor with plausible, never-dereferenced device addresses (validation only)."""
     c = B.qs_cache()

@@ -1,0 +1,104 @@
+"""GPU parity of the attention kernels that deal 128-token groups out through a queue shared by the
+eight waves of a workgroup.  The planner takes them when a unit has at least eight groups per
+workgroup, i.e. at long contexts; here the library is told to plan for a handful of compute units
+(qs_configure), so that caches of a few thousand tokens run through exactly that code: with C compute
+units and U units the planner wants 8*C/U waves per unit, C/U workgroups of eight, and needs
+8*C/U groups or more and at most 4*C/U buffer chunks of 64 tokens."""
+import numpy as np
+import pytest
+
+from tests.test_gpu_parity import env, _check_attn, _random_case, _run_attn   # noqa: F401  (env is a fixture)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture()
+def few_compute_units(env):
+    B = env["B"]
+
+    def plan_for(n):
+        B.qs_configure(B.QS_CFG_COMPUTE_UNITS, n)
+
+    yield plan_for
+    B.qs_configure(B.QS_CFG_COMPUTE_UNITS, 0)
+    B.qs_configure(B.QS_CFG_DETERMINISTIC, 0)
+
+
+@pytest.mark.parametrize("bsz,hkv,rep,nq,cus", [
+    (2, 2, 1, 1, 4),    # one row per kv-head: one token per lane in the softmax; one workgroup per unit
+    (2, 2, 1, 5, 8),    # verify, 5 rows, two workgroups per unit
+    (1, 2, 4, 1, 2),    # grouped queries, 4 rows, draft
+    (1, 2, 4, 2, 4),    # 8 rows, verify, two workgroups per unit
+    (3, 1, 2, 3, 3),    # ragged batch, 6 rows
+    (1, 8, 1, 1, 24),   # three workgroups per unit
+])
+def test_queue_kernels_match_oracle(env, few_compute_units, bsz, hkv, rep, nq, cus):
+    rng = np.random.default_rng(31 * bsz + 7 * hkv + rep + nq)
+    few_compute_units(cus)
+    wgs = (8 * cus // (bsz * hkv)) // 8
+    assert wgs >= 1
+    checked = 0
+    for attempt in range(16):
+        # ragged lengths: some sequences hold far fewer groups than the planner cut the work for (even none)
+        cache, oc, q, tag = _random_case(env, rng, bsz, hkv, rep, nq, max_groups=40, max_buf=4 * 64 * wgs)
+        if int(cache.n_quant.max()) // 128 < 8 * wgs:
+            continue                       # this draw is too short for the queue kernels
+        _check_attn(env, cache, oc, q, 0.09, True, tag=f"queue verify {tag}")
+        _check_attn(env, cache, oc, q[:, -1:], 0.09, False, tag=f"queue draft {tag}")
+        checked += 1
+        if checked == 2:
+            break
+    assert checked == 2
+
+
+def test_queue_kernels_paged_and_flush(env, few_compute_units):
+    """Group-table mode under the queue kernels, before and after a flush."""
+    torch, O, U, B = env["torch"], env["O"], env["U"], env["B"]
+    rng = np.random.default_rng(77)
+    few_compute_units(4)
+    bsz, hkv, hq, nq = 2, 2, 4, 5
+    tq, nb, q_cap = 20 * 128, 128 + nq + 9, 24 * 128
+    n_logical = bsz * hkv * (q_cap // 128)
+    pool = n_logical + 5
+    cache = B.KVCache(bsz, hq, hkv, q_cap, nb + 8, pool_groups=pool)
+    table = rng.permutation(pool)[:n_logical].astype(np.int32).reshape(bsz, hkv, q_cap // 128)
+    cache.group_table.copy_(torch.from_numpy(table))
+    k = (rng.standard_normal((bsz, hkv, tq + nb, 128)) * 1.5).astype(np.float16)
+    v = rng.standard_normal((bsz, hkv, tq + nb, 128)).astype(np.float16)
+    kd, vd = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+    B.qs_quantize_prefill(cache, kd, vd, tq)
+    cache.n_quant[:] = tq
+    cache.k_buf[:, :, :nb] = kd[:, :, tq:]
+    cache.v_buf[:, :, :nb] = vd[:, :, tq:]
+    cache.n_buf[:] = nb
+    oc = O.build_cache(k, v, hq, 128, nb)
+    q = rng.standard_normal((bsz, nq, hq, 128)).astype(np.float16)
+    _check_attn(env, cache, oc, q, 0.1, True, tag="queue paged verify")
+    _check_attn(env, cache, oc, q[:, -1:], 0.1, False, tag="queue paged draft")
+    B.qs_quantize_flush(cache, 128)
+    cache.n_quant += 128
+    cache.n_buf -= 128
+    oc.flush(128)
+    _check_attn(env, cache, oc, q, 0.1, True, tag="queue paged verify after flush")
+
+
+def test_deterministic_setting_is_bit_reproducible(env, few_compute_units):
+    """With QS_CFG_DETERMINISTIC every wave gets a fixed range of groups: identical sequences of a batch
+    give identical bits, and so do repeated calls.  Without it they agree to one fp16 step."""
+    U, B = env["U"], env["B"]
+    rng = np.random.default_rng(9)
+    few_compute_units(16)
+    k1 = rng.standard_normal((1, 2, 128 * 40 + 64, 128)).astype(np.float16)
+    v1 = rng.standard_normal(k1.shape).astype(np.float16)
+    q1 = rng.standard_normal((1, 3, 2, 128)).astype(np.float16)
+    reps = 4
+    cache = U.make_device_cache(np.repeat(k1, reps, 0), np.repeat(v1, reps, 0), 2, 64)
+    qn = np.repeat(q1, reps, 0)
+    free, _ = _run_attn(env, cache, qn, 0.09, True)
+    assert U.rel_err(free, np.repeat(free[:1], reps, 0).astype(np.float64)) <= 1e-3
+    B.qs_configure(B.QS_CFG_DETERMINISTIC, 1)
+    fixed, _ = _run_attn(env, cache, qn, 0.09, True)
+    again, _ = _run_attn(env, cache, qn, 0.09, True)
+    assert np.array_equal(fixed.view(np.uint16), again.view(np.uint16))
+    assert np.abs(fixed.astype(np.float32) - fixed[:1].astype(np.float32)).max() == 0.0
+    assert U.rel_err(free, fixed.astype(np.float64)) <= 1e-3
