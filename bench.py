@@ -30,8 +30,8 @@ SPEC_GAMMAS = (1, 2, 4, 6)      # speculation lengths of the simulated decode lo
 # (calibrated against a plain copy kernel).  Filled from the summaries under profiles/; None = not measured.
 MEASURED_TRAFFIC_BYTES = {
     # profiles/attn_mha128k_hbm_traffic.md: (FETCH_SIZE x 1.99991 + WRITE_SIZE x 1.0) KiB per dispatch
-    ("mha128k", "draft"): int((280287.4 * 1.99991 + 1106.0) * 1024),
-    ("mha128k", "verify"): int((542234.9 * 1.99991 + 5554.9) * 1024),
+    ("mha128k", "draft"): int((283190.7 * 1.99991 + 1105.2) * 1024),
+    ("mha128k", "verify"): int((548462.9 * 1.99991 + 5563.6) * 1024),
 }
 
 
@@ -174,12 +174,12 @@ def main():
         "min_us": {k: round(float(v.min()), 2) for k, v in per_call.items()},
         "draft_GBps": round(gbps_d, 1), "verify_GBps": round(gbps_v, 1),
         "cycle_GBps": round(cycle_bytes / (ms_per_step * 1e-3) / 1e9, 1),
-        "roofline": {"bound": "hbm", "kernel": "draft call: attn_kernel<1,false> + merge_kernel (upper plane)",
+        "roofline": {"bound": "hbm", "kernel": "draft call: attn_kernel_cu<false,true> + merge_kernel (upper plane)",
                      "achieved": round(gbps_d, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gbps_d / HBM_PEAK_GBPS, 4),
                      "algorithmic_bytes_per_launch": bytes_d,
                      "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, "draft"))},
-        "roofline_verify": {"bound": "hbm", "kernel": "verify call: attn_kernel<1,true> + merge_kernel (both planes)",
+        "roofline_verify": {"bound": "hbm", "kernel": "verify call: attn_kernel_cu<true,false> + merge_kernel (both planes)",
                             "achieved": round(gbps_v, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                             "frac": round(gbps_v / HBM_PEAK_GBPS, 4),
                             "algorithmic_bytes_per_launch": bytes_v,
