@@ -6,8 +6,11 @@
 // split-K scheme (Appendix E), and every chunk's (max, sum, output) partial is merged afterwards.
 //
 // Design
-//  * One wave (a 64-thread workgroup) owns one chunk of one (sequence, kv-head) unit and all query
-//    rows that share that kv-head (grouped-query heads x query tokens), so the planes are read once.
+//  * One wave walks 128-token groups of one (sequence, kv-head) unit for all query rows that share
+//    that kv-head (grouped-query heads x query tokens), so the planes are read once, and writes one
+//    partial.  Either every wave is a workgroup with a fixed contiguous range (attn_kernel), or the
+//    eight waves of a compute unit form one workgroup and draw their groups from a queue in LDS
+//    (attn_kernel_cu: the two waves of a SIMD do not advance at the same pace).
 //    Every byte of the planes is loaded exactly once, by exactly one lane, with 128-bit loads that a
 //    wave issues as contiguous 1 KB requests, directly into the registers that feed the matrix cores;
 //    the cache is laid out in 32-token blocks so that these requests walk one array (draft) or two
