@@ -510,5 +510,5 @@ def test_split_count_invariance(env):
     o1, _ = _run_attn(env, cache1, q1, 0.09, True)
     oN, _ = _run_attn(env, cacheN, np.repeat(q1, reps, 0), 0.09, True)
     # identical sequences agree to rounding only: which wave takes which group is decided at run time
-    assert U.rel_err(oN, np.repeat(oN[:1], reps, 0).astype(np.float64)) <= 1e-3   # one fp16 step of the output
+    assert U.rel_err(oN, np.repeat(oN[:1], reps, 0).astype(np.float64)) <= 2e-3   # a step or two of the fp16 output
     assert U.rel_err(oN[:1], o1.astype(np.float64)) <= 1e-3

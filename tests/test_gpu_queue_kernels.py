@@ -84,7 +84,7 @@ def test_queue_kernels_paged_and_flush(env, few_compute_units):
 
 def test_deterministic_setting_is_bit_reproducible(env, few_compute_units):
     """With QS_CFG_DETERMINISTIC every wave gets a fixed range of groups: identical sequences of a batch
-    give identical bits, and so do repeated calls.  Without it they agree to one fp16 step."""
+    give identical bits, and so do repeated calls.  Without it two results agree to a step or two of the fp16 output."""
     U, B = env["U"], env["B"]
     rng = np.random.default_rng(9)
     few_compute_units(16)
@@ -95,10 +95,10 @@ def test_deterministic_setting_is_bit_reproducible(env, few_compute_units):
     cache = U.make_device_cache(np.repeat(k1, reps, 0), np.repeat(v1, reps, 0), 2, 64)
     qn = np.repeat(q1, reps, 0)
     free, _ = _run_attn(env, cache, qn, 0.09, True)
-    assert U.rel_err(free, np.repeat(free[:1], reps, 0).astype(np.float64)) <= 1e-3
+    assert U.rel_err(free, np.repeat(free[:1], reps, 0).astype(np.float64)) <= 2e-3
     B.qs_configure(B.QS_CFG_DETERMINISTIC, 1)
     fixed, _ = _run_attn(env, cache, qn, 0.09, True)
     again, _ = _run_attn(env, cache, qn, 0.09, True)
     assert np.array_equal(fixed.view(np.uint16), again.view(np.uint16))
     assert np.abs(fixed.astype(np.float32) - fixed[:1].astype(np.float32)).max() == 0.0
-    assert U.rel_err(free, fixed.astype(np.float64)) <= 1e-3
+    assert U.rel_err(free, fixed.astype(np.float64)) <= 2e-3
