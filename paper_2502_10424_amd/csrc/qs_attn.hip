@@ -829,13 +829,13 @@ __global__ __launch_bounds__(64 * kCuWaves) __attribute__((amdgpu_waves_per_eu(2
 
 // Merge of the per-chunk partials (Appendix E): M = max m_i, L = sum l_i 2^(m_i - M),
 // out = sum o_i 2^(m_i - M) / L.  One 256-thread workgroup per query row: thread (sl, c) folds chunks
-// sl, sl+8, ... for channels 4c..4c+3 into a running (m, l, o) of its own, eight chunks per step
-// with all their loads issued together, so a typical row is one memory round trip; the eight slices
-// are then combined through LDS.
+// sl, sl+8, ... for channels 4c..4c+3 into a running (m, l, o) of its own, nine chunks per step
+// with all their loads issued together, so a row of up to 72 chunks (64 quantized + a decode-time
+// buffer's) is one memory round trip; the eight slices are then combined through LDS.
 __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
   __shared__ float red_o[8][kD + 4];
   __shared__ float red_m[8], red_l[8];
-  constexpr int U = 8;
+  constexpr int U = 9;
   const int64_t row = blockIdx.x;
   const int tid = threadIdx.x, sl = tid >> 5, c = tid & 31;
   const float* __restrict__ ml = a.ws_ml + row * a.n_split * 2;
