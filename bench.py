@@ -30,8 +30,8 @@ SPEC_GAMMAS = (1, 2, 4, 6)      # speculation lengths of the simulated decode lo
 # (calibrated against a plain copy kernel).  Filled from the summaries under profiles/; None = not measured.
 MEASURED_TRAFFIC_BYTES = {
     # profiles/attn_mha128k_hbm_traffic.md: (FETCH_SIZE x 1.99991 + WRITE_SIZE x 1.0) KiB per dispatch
-    ("mha128k", "draft"): int((283190.7 * 1.99991 + 1105.2) * 1024),
-    ("mha128k", "verify"): int((548462.9 * 1.99991 + 5563.6) * 1024),
+    ("mha128k", "draft"): int((288598.1 * 1.99991 + 1105.1) * 1024),
+    ("mha128k", "verify"): int((550709.6 * 1.99991 + 5528.3) * 1024),
 }
 
 
