@@ -105,7 +105,7 @@ const char *qs_strerror(int code);
  *                         128-token groups from a shared queue at run time, so which partial sum a
  *                         group lands in - and with it the last bit of an fp16 output - can differ
  *                         from call to call.  value 1: every wave gets a fixed range; results are
- *                         bit-reproducible (about 5 % slower at 128k context).
+ *                         bit-reproducible (about 1 % slower at 128k context).
  *   QS_CFG_COMPUTE_UNITS  number of compute units to plan for (> 0), or 0 for the device's own count
  *                         (default); e.g. when part of the GPU is reserved for other work.
  * Returns QS_OK, or QS_ERR_RANGE for an unknown key or a value out of range.
