@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--workload", default="mha128k")
     ap.add_argument("--copies", type=int, default=4, help="independent cache copies to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--deterministic", action="store_true",
+                    help="time the bit-reproducible setting (qs_configure(QS_CFG_DETERMINISTIC, 1)) instead of the default")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the timed cycle: no prefill timing, fp16 baseline or speculation loop (for kernel traces)")
     args = ap.parse_args()
@@ -70,6 +72,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     B.lib()
+    if args.deterministic:
+        B.qs_configure(B.QS_CFG_DETERMINISTIC, 1)
     w = synth.WORKLOADS[args.workload]
     sm_scale = 1.0 / float(np.sqrt(w.head_dim))
     nqv = w.nq_verify
@@ -167,7 +171,8 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads} q-heads / {w.n_kv_heads} kv-heads x 128, "
                                f"ctx {w.ctx} = {w.n_quant} quantized + {w.n_buf} fp16 buffer, G=128, gamma=4",
-                   "cache_copies_rotated": len(caches), "flush_tokens_per_cycle": 128},
+                   "cache_copies_rotated": len(caches), "flush_tokens_per_cycle": 128,
+                   "deterministic": bool(args.deterministic)},
         "draft_us": round(avg_us["draft"], 2), "verify_us": round(avg_us["verify"], 2),
         "flush_us": round(avg_us["flush"], 2),
         "median_us": {k: round(float(np.median(v)), 2) for k, v in per_call.items()},
