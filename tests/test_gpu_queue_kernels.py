@@ -102,3 +102,40 @@ def test_deterministic_setting_is_bit_reproducible(env, few_compute_units):
     assert np.array_equal(fixed.view(np.uint16), again.view(np.uint16))
     assert np.abs(fixed.astype(np.float32) - fixed[:1].astype(np.float32)).max() == 0.0
     assert U.rel_err(free, fixed.astype(np.float64)) <= 2e-3
+
+
+def test_queue_kernels_in_a_hip_graph(env, few_compute_units):
+    """The queue lives in LDS and is set up by every launch itself, so a captured draft + verify pair can
+    be replayed any number of times: every replay agrees with the eager result to rounding."""
+    torch, U, B = env["torch"], env["U"], env["B"]
+    rng = np.random.default_rng(123)
+    few_compute_units(8)
+    bsz, hkv, hq = 2, 2, 4
+    t, nb = 24 * 128, 200
+    k = rng.standard_normal((bsz, hkv, t + nb, 128)).astype(np.float16)
+    v = rng.standard_normal((bsz, hkv, t + nb, 128)).astype(np.float16)
+    cache = U.make_device_cache(k, v, hq, nb, q_cap=t, buf_cap=nb + 8)
+    qd = torch.from_numpy(rng.standard_normal((bsz, 1, hq, 128)).astype(np.float16)).cuda()
+    qv = torch.from_numpy(rng.standard_normal((bsz, 5, hq, 128)).astype(np.float16)).cuda()
+    ws = torch.zeros(B.qs_workspace_bytes(cache, 5), dtype=torch.uint8, device="cuda")
+    e_d = B.qs_attn_draft(cache, qd, 0.1, workspace=ws).float().cpu().numpy()
+    e_v = B.qs_attn_verify(cache, qv, 0.1, workspace=ws).float().cpu().numpy()
+    o_d, o_v = torch.empty_like(qd), torch.empty_like(qv)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        B.qs_attn_draft(cache, qd, 0.1, out=o_d, workspace=ws, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        cs = torch.cuda.current_stream()
+        B.qs_attn_draft(cache, qd, 0.1, out=o_d, workspace=ws, stream=cs)
+        B.qs_attn_verify(cache, qv, 0.1, out=o_v, workspace=ws, stream=cs)
+    for rep in range(3):
+        o_d.zero_(); o_v.zero_(); ws.fill_(0xFF)
+        (torch.ones(1000, device="cuda") * rep).sum().item()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert U.rel_err(o_d.float().cpu().numpy(), e_d.astype(np.float64)) <= 2e-3, f"replay {rep}"
+        assert U.rel_err(o_v.float().cpu().numpy(), e_v.astype(np.float64)) <= 2e-3, f"replay {rep}"
