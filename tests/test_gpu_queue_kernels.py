@@ -139,3 +139,21 @@ def test_queue_kernels_in_a_hip_graph(env, few_compute_units):
         torch.cuda.synchronize()
         assert U.rel_err(o_d.float().cpu().numpy(), e_d.astype(np.float64)) <= 2e-3, f"replay {rep}"
         assert U.rel_err(o_v.float().cpu().numpy(), e_v.astype(np.float64)) <= 2e-3, f"replay {rep}"
+
+
+@pytest.mark.parametrize("cus", [1, 3, 8, 100, 1024])
+def test_random_shapes_under_other_planner_settings(env, few_compute_units, cus):
+    """The chunk counts, the kernel variant and the workspace layout all follow from the compute-unit count
+    the planner works with: seeded random caches under several counts, with queue and with fixed dealing."""
+    B = env["B"]
+    rng = np.random.default_rng(500 + cus)
+    few_compute_units(cus)
+    for det in (0, 1):
+        B.qs_configure(B.QS_CFG_DETERMINISTIC, det)
+        for case in range(2):
+            bsz, hkv = int(rng.integers(1, 4)), int(rng.choice([1, 2, 3, 8]))
+            rep, nq = int(rng.choice([1, 2, 4, 8])), int(rng.integers(1, 9))
+            cache, oc, q, tag = _random_case(env, rng, bsz, hkv, rep, nq, max_groups=int(rng.choice([3, 12, 40])),
+                                             max_buf=int(rng.choice([40, 140, 600])))
+            _check_attn(env, cache, oc, q, 0.09, True, tag=f"cus{cus} det{det} verify {tag}")
+            _check_attn(env, cache, oc, q[:, -1:], 0.09, False, tag=f"cus{cus} det{det} draft {tag}")
