@@ -62,7 +62,7 @@
 extern "C" {
 #endif
 
-#define QS_MAX_BATCH 64     /* per-sequence lengths travel by value in the kernel arguments      */
+#define QS_MAX_BATCH 256    /* per-sequence lengths travel by value in the kernel arguments      */
 #define QS_MAX_NQ 8         /* largest number of query tokens per sequence in one verify call    */
 
 typedef enum qs_status {

@@ -15,7 +15,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libquantspec.so")
 
-QS_MAX_BATCH = 64
+QS_MAX_BATCH = 256
 QS_MAX_NQ = 8
 HEAD_DIM = 128
 GROUP = 128

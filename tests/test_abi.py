@@ -97,7 +97,7 @@ def test_validation_errors_without_gpu(B):
     assert draft(_fake_cache(B, q_cap=1000)) == B.QS_ERR_SHAPE
     assert draft(_fake_cache(B, head_dim=64)) == B.QS_ERR_UNSUPPORTED
     assert draft(_fake_cache(B, group=64)) == B.QS_ERR_UNSUPPORTED
-    assert draft(_fake_cache(B, batch=65)) == B.QS_ERR_UNSUPPORTED
+    assert draft(_fake_cache(B, batch=257)) == B.QS_ERR_UNSUPPORTED
     assert draft(_fake_cache(B, lower=0x10008)) == B.QS_ERR_ALIGN
     assert draft(_fake_cache(B), q=0x200004) == B.QS_ERR_ALIGN
     assert draft(_fake_cache(B), wsp=None) == B.QS_ERR_WORKSPACE

@@ -328,11 +328,12 @@ def test_attention_random_shapes(env):
 
 
 def test_attention_maximum_batch(env):
-    """64 sequences (the most the by-value length arrays hold), different lengths each: 128 units."""
+    """256 sequences (the most the by-value length arrays hold), different lengths each: 512 units."""
+    B = env["B"]
     rng = np.random.default_rng(64)
-    cache, oc, q, tag = _random_case(env, rng, 64, 2, 2, 2, max_groups=2, max_buf=40)
-    _check_attn(env, cache, oc, q, 0.09, True, tag=f"batch 64 verify {tag[:40]}")
-    _check_attn(env, cache, oc, q[:, -1:], 0.09, False, tag=f"batch 64 draft {tag[:40]}")
+    cache, oc, q, tag = _random_case(env, rng, B.QS_MAX_BATCH, 2, 2, 2, max_groups=2, max_buf=40)
+    _check_attn(env, cache, oc, q, 0.09, True, tag=f"batch {B.QS_MAX_BATCH} verify {tag[:40]}")
+    _check_attn(env, cache, oc, q[:, -1:], 0.09, False, tag=f"batch {B.QS_MAX_BATCH} draft {tag[:40]}")
 
 
 @pytest.mark.parametrize("hq,hkv,nq", [(4, 2, 1), (8, 2, 5), (16, 2, 5)])
