@@ -63,7 +63,7 @@ extern "C" {
 #endif
 
 #define QS_MAX_BATCH 256    /* per-sequence lengths travel by value in the kernel arguments      */
-#define QS_MAX_NQ 8         /* largest number of query tokens per sequence in one verify call    */
+#define QS_MAX_NQ 16        /* largest number of query tokens per sequence in one verify call    */
 
 typedef enum qs_status {
   QS_OK = 0,

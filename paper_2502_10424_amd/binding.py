@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libquantspec.so")
 
 QS_MAX_BATCH = 256
-QS_MAX_NQ = 8
+QS_MAX_NQ = 16
 HEAD_DIM = 128
 GROUP = 128
 UPPER_BLOCK_BYTES = 4352     # per 32 tokens: key codes, value codes, value S/Z, a quarter of the group's key S/Z

@@ -192,7 +192,7 @@ const char* qs_strerror(int code) {
     case QS_OK: return "ok";
     case QS_ERR_NULL: return "a required pointer is NULL";
     case QS_ERR_SHAPE: return "inconsistent batch / head counts / capacities";
-    case QS_ERR_UNSUPPORTED: return "unsupported configuration (head_dim and group must be 128, batch <= 256, nq <= 8)";
+    case QS_ERR_UNSUPPORTED: return "unsupported configuration (head_dim and group must be 128, batch <= 256, nq <= 16)";
     case QS_ERR_ALIGN: return "a device pointer is not 16-byte aligned";
     case QS_ERR_RANGE: return "a length is out of range for its capacity or not a multiple of the group size";
     case QS_ERR_WORKSPACE: return "workspace is missing or smaller than qs_workspace_bytes()";

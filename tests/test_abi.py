@@ -76,7 +76,7 @@ def test_workspace_bytes(B):
     w1, w5 = B.qs_workspace_bytes(c, 1), B.qs_workspace_bytes(c, 5)
     assert w1 > 0 and w5 == 5 * w1 and w1 % (130 * 4) == 0
     assert B.qs_workspace_bytes(_fake_cache(B, head_dim=64), 1) == 0
-    assert B.qs_workspace_bytes(c, 0) == 0 and B.qs_workspace_bytes(c, 9) == 0
+    assert B.qs_workspace_bytes(c, 0) == 0 and B.qs_workspace_bytes(c, 17) == 0
 
 
 def test_validation_errors_without_gpu(B):
@@ -105,7 +105,7 @@ def test_validation_errors_without_gpu(B):
     for bad in (0.0, -0.1, float("inf"), float("nan")):
         assert lib.qs_attn_draft(ctypes.byref(_fake_cache(B)), 0x200000, 0x300000, bad, 0x400000, ws, None, None) == B.QS_ERR_RANGE
     assert verify(_fake_cache(B), 0) == B.QS_ERR_UNSUPPORTED
-    assert verify(_fake_cache(B), 9) == B.QS_ERR_UNSUPPORTED
+    assert verify(_fake_cache(B), 17) == B.QS_ERR_UNSUPPORTED
     c = _fake_cache(B); c._keep[0][0] = 100            # n_quant not a multiple of 128
     assert draft(c) == B.QS_ERR_RANGE
     c = _fake_cache(B); c._keep[0][1] = 2048           # n_quant > q_cap

@@ -217,7 +217,7 @@ def test_attention_tiny_workload(env, verify):
     _check_attn(env, cache, oc, q, 1.0 / np.sqrt(128), verify, tag=f"tiny {'verify' if verify else 'draft'}")
 
 
-@pytest.mark.parametrize("hq,hkv,nq", [(2, 2, 1), (4, 1, 2), (8, 2, 3), (16, 2, 5), (8, 1, 8), (16, 2, 7), (3, 3, 4)])
+@pytest.mark.parametrize("hq,hkv,nq", [(2, 2, 1), (4, 1, 2), (8, 2, 3), (16, 2, 5), (8, 1, 8), (16, 2, 7), (3, 3, 4), (2, 2, 12), (8, 2, 16)])
 def test_attention_row_shapes(env, hq, hkv, nq):
     """1..64 query rows per kv-head (one to several 8-row MFMA tiles and row batches), ragged lengths,
     buffer lengths that end inside a 16-token tile."""
