@@ -157,3 +157,37 @@ def test_random_shapes_under_other_planner_settings(env, few_compute_units, cus)
                                              max_buf=int(rng.choice([40, 140, 600])))
             _check_attn(env, cache, oc, q, 0.09, True, tag=f"cus{cus} det{det} verify {tag}")
             _check_attn(env, cache, oc, q[:, -1:], 0.09, False, tag=f"cus{cus} det{det} draft {tag}")
+
+
+@pytest.mark.parametrize("bsz,hkv,rep,nq,tq,nb,cus", [
+    (1, 1, 1, 1, [8 * 128], [1], 1),                                  # one group per wave, one buffer token
+    (1, 1, 1, 1, [9 * 128], [256], 1),                                # nine groups for eight waves, four buffer items
+    (2, 1, 1, 1, [8 * 128, 0], [1, 5], 2),                            # a sequence without quantized tokens
+    (2, 1, 2, 4, [16 * 128, 128], [4, 200], 2),                       # one group against sixteen
+    (1, 2, 1, 5, [24 * 128], [5], 6),                                 # three workgroups, the buffer holds just the queries
+    (3, 1, 1, 1, [40 * 128, 17 * 128, 3 * 128], [64, 65, 63], 3),     # buffers that end at tile edges
+    (1, 1, 8, 1, [8 * 128], [256], 1),                                # eight rows
+])
+def test_queue_kernels_edge_lengths(env, few_compute_units, bsz, hkv, rep, nq, tq, nb, cus):
+    torch, O, U, B = env["torch"], env["O"], env["U"], env["B"]
+    rng = np.random.default_rng(7 + sum(tq) // 128 + sum(nb))
+    few_compute_units(cus)
+    hq = hkv * rep
+    cache = B.KVCache(bsz, hq, hkv, max(max(tq), 128), max(nb) + 3)
+    oc = O.CacheOracle(bsz, hq, hkv, 128, 128)
+    for b in range(bsz):
+        n = tq[b] + nb[b]
+        k = rng.standard_normal((1, hkv, n, 128)).astype(np.float16)
+        v = rng.standard_normal((1, hkv, n, 128)).astype(np.float16)
+        kd, vd = torch.from_numpy(k).cuda(), torch.from_numpy(v).cuda()
+        if tq[b]:
+            B.qs_quantize_prefill(U._seq_view(cache, b), kd, vd, tq[b])
+        cache.n_quant[b], cache.n_buf[b] = tq[b], nb[b]
+        cache.k_buf[b, :, :nb[b]] = kd[0, :, tq[b]:]
+        cache.v_buf[b, :, :nb[b]] = vd[0, :, tq[b]:]
+        ob = O.build_cache(k, v, hq, 128, nb[b])
+        for name in ("ku", "kl", "ks", "kz", "vu", "vl", "vs", "vz", "kbuf", "vbuf"):
+            getattr(oc, name)[b] = getattr(ob, name)[0]
+    q = rng.standard_normal((bsz, nq, hq, 128)).astype(np.float16)
+    _check_attn(env, cache, oc, q, 0.09, True, tag=f"edge verify tq{tq} nb{nb}")
+    _check_attn(env, cache, oc, q[:, -1:], 0.09, False, tag=f"edge draft tq{tq} nb{nb}")
