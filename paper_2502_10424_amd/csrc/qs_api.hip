@@ -12,7 +12,7 @@ constexpr int kVersion = 100;   // 0.1.0
 constexpr int kDefaultCUs = 256;
 // resident chunk waves per compute unit the split planner aims for: the single-row-tile kernels run two
 // waves per SIMD, the multi-row-tile kernels (more than 8 query rows per kv-head) one
-constexpr int kWavesPerCU = 8;
+constexpr int kWavesPerCU = kCuWaves;
 constexpr int kWavesPerCUMultiTile = 4;
 constexpr int kMinBufSplits = 8;   // a decode-time buffer (2G + gamma + 1 tokens) always gets its 64-token chunks
 
@@ -93,9 +93,9 @@ Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf) {
   p.ws_splits = p.n_split_q + p.n_split_b;
   const int wgs = want / kWavesPerCU;
   if (g_deterministic.load(std::memory_order_relaxed) == 0 && n_rows <= 8 && wgs >= 1 &&
-      groups >= kWavesPerCU * wgs && p.n_split_b <= 4 * wgs) {
+      groups >= kCuWaves * wgs && p.n_split_b <= kCuBufItems * wgs) {
     p.cu_wgs = wgs;
-    p.n_split_q = kWavesPerCU * wgs;
+    p.n_split_q = kCuWaves * wgs;
   }
   return p;
 }

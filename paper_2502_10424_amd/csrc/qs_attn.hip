@@ -829,7 +829,6 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NRT == 1 && 
 // Each wave still writes one partial for its quantized groups (slot 8*w + wave).  For the kernels
 // with at most 8 query rows per kv-head; the planner guarantees at most four buffer items per
 // workgroup (one transpose tile each).
-constexpr int kCuWaves = 8, kCuBufItems = 4;
 template <bool VERIFY, bool SINGLE>
 __global__ __launch_bounds__(64 * kCuWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_kernel_cu(AttnArgs a) {
   __shared__ _Float16 vt[kCuBufItems][kD][kVtStride];

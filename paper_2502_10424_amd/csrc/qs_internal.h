@@ -21,6 +21,9 @@ constexpr int kOffKZ = 4288;       // key zero, likewise
 constexpr int kUpperBlk = 4352;    // bytes per block of the upper array
 // ... and of the lower array: key codes at 0, value codes at 2048
 constexpr int kLowerBlk = 4096;
+// queue-dealt attention kernel: waves of a workgroup (two per SIMD of a compute unit) and the buffer chunks
+// one workgroup can take (one transpose tile each)
+constexpr int kCuWaves = 8, kCuBufItems = 4;
 constexpr int kBulkGroups = 512;   // from this many (group, unit) pairs on, quantization takes the bulk kernel
 constexpr int kBufSplitTok = 64;   // buffer tokens handled by one wave of the attention kernel
 
