@@ -114,11 +114,6 @@ __device__ __forceinline__ half8 to_operand_order(half8 c) {
   return r;
 }
 
-__device__ __forceinline__ float xor8_in_row(float x) {   // value of lane (l ^ 8); stays inside a 16-lane row
-  const int v = __builtin_bit_cast(int, x);
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, 0x128, 0xF, 0xF, true));
-}
-
 __device__ __forceinline__ float group_max(float x) {     // over the four 16-lane groups of the wave
   x = fmaxf(x, __shfl_xor(x, 16));
   return fmaxf(x, __shfl_xor(x, 32));
@@ -151,69 +146,151 @@ __device__ __forceinline__ uint32_t row_shl_zero(uint32_t src) {
 }
 
 
+// ------------------------------------------------------------------------------------------------
+// Query rows on the 16 columns of an MFMA tile.  A tile carries 16 or 8 query rows (its mode M):
+//   M = 16  column c = row c.  The remainder of q*S (see the file header) is a second operand that is
+//           accumulated into the same result.
+//   M = 8   columns c and c + 8 = row c: q*S in the first, its remainder in the second; one DPP add
+//           recombines the scores, after which both columns hold the same and do the same work.
+// Either way a lane owns the 8 tokens of its lane group for the query row of its column.
+// ------------------------------------------------------------------------------------------------
+struct Lane {
+  int rho, g;   // MFMA column and lane group
+  __device__ __forceinline__ Lane() {
+    const int lane = threadIdx.x & 63;
+    rho = lane & 15;
+    g = lane >> 4;
+  }
+  template <int M>
+  __device__ __forceinline__ int row() const { return rho & (M - 1); }          // row of the tile this column serves
+  template <int M>
+  __device__ __forceinline__ bool remainder() const { return M == 8 && rho >= 8; }   // column holds the remainder of q*S
+};
+
+template <int K>
+__device__ __forceinline__ float ror_in_row(float x) {   // value of lane (l + K) mod 16 of the same 16-lane row
+  const int v = __builtin_bit_cast(int, x);
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(v, v, 0x120 + K, 0xF, 0xF, true));
+}
+
+// The scores of this lane's eight tokens from the two MFMA results of a block (a0: tokens 0..15,
+// a1: 16..31; element jj of either is token 4g + jj of that half).
+template <int M>
+__device__ __forceinline__ void tile_scores(const float4v& a0, const float4v& a1, float (&x)[8]) {
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) {
+    x[jj] = M == 16 ? a0[jj] : a0[jj] + ror_in_row<8>(a0[jj]);
+    x[4 + jj] = M == 16 ? a1[jj] : a1[jj] + ror_in_row<8>(a1[jj]);
+  }
+}
+
+// Eight fp16 values (two per 32-bit word) as floats.
+__device__ __forceinline__ void meta_floats(const u32x4& d, float (&f)[8]) {
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const half2v h = as_half2(d[r]);
+    f[2 * r] = (float)h[0], f[2 * r + 1] = (float)h[1];
+  }
+}
+
+// p * S of this lane's tokens -> the lane's operand of the value contraction.  The draft pass scales
+// the words whose codes sit four bits higher in their half (odd words) by 2^-4; see the constants in
+// quant_chunk.
+template <bool VERIFY>
+__device__ __forceinline__ half8 p_operand(const float (&ps)[8]) {
+  u32x4 pw;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    half2v h;
+    h[0] = (_Float16)ps[2 * r], h[1] = (_Float16)ps[2 * r + 1];
+    if (!VERIFY && (r & 1)) h = h * (_Float16)0.0625f;
+    pw[r] = as_u32(h);
+  }
+  return as_half8(pw);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Online softmax with a reference that moves rarely.  A row keeps a reference exponent m (log2 units)
+// and everything it accumulates - sum l, zero-point term z, output o - is relative to it:
+// p = 2^(score - m).  m does not have to be the largest score: any reference works as long as p fits
+// its formats, and the merge of the partials is indifferent to it.  So m is only raised when a score
+// of the wave exceeds it by more than kTau (p > 2^kTau), and is then put kLift below the largest score
+// of the row.  (m also carries the exponent e of the value scales, see raise_scale_reference: the bounds
+// here are on p * 2^e.)  After the first blocks of a chunk that practically never happens again, so the main
+// path of a block has no cross-lane reduction and no rescaling of the accumulators - with 20 query
+// rows per wave the classic running maximum took the rescaling path in nearly every second block.
+// p <= 2^kTau = 256 and p * S <= 512 (S: see raise_scale_reference) stay far inside fp16.
+// ------------------------------------------------------------------------------------------------
+constexpr float kTau = 8.0f;
+constexpr float kLift = 2.0f;
+
 template <int NRT>
 struct RowState {
-  float m[NRT];        // reference exponent of the row: running max of the scaled scores (log2 units) plus e
+  float m[NRT];        // reference exponent of the row (includes e)
   float e;             // floor(log2) of the largest value scale met so far by the wave; 0 in the buffer chunk
   float s_limit;       // 2^(e + 1): a larger value scale raises e
   float l[NRT];        // running sum of p over this lane's tokens
   float z[NRT];        // running sum of p * zero-point over this lane's tokens
   float4v o[NRT][8];   // O^T accumulators: tile n, element jj -> channel 8*(4*g + jj) + n
-};
-
-// Online-softmax update for one 32-token block.  raw[rt][j] are this lane's eight scores (query
-// column rho, tokens tile_token(g, j)) before scaling, each still short of the additive term
-// bias[rt] (the zero-point part of the score, the same for every token of a group); on return they
-// hold the probabilities relative to the row's reference exponent m = (largest score so far) + e
-// (e: see raise_scale_reference).  The reference only moves when some score of the wave exceeds it;
-// otherwise the cross-lane reduction and the rescaling of the accumulators are skipped altogether.
-template <int NRT>
-__device__ __forceinline__ void softmax_block(RowState<NRT>& st, float (&raw)[NRT][8], const float (&mul)[NRT],
-                                              const float (&bias)[NRT]) {
-  float mx[NRT];
-  bool grow = false;
-#pragma unroll
-  for (int rt = 0; rt < NRT; ++rt) {
-    const float top = fmaxf(fmaxf(fmaxf(raw[rt][0], raw[rt][1]), fmaxf(raw[rt][2], raw[rt][3])),
-                            fmaxf(fmaxf(raw[rt][4], raw[rt][5]), fmaxf(raw[rt][6], raw[rt][7])));
-    mx[rt] = __builtin_fmaf(top + bias[rt], mul[rt], st.e);   // mul > 0
-    grow |= mx[rt] > st.m[rt];
-  }
-  if (__any(grow)) {
+  __device__ __forceinline__ void reset(float e0, float limit0) {
+    e = e0;
+    s_limit = limit0;
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt) {
-      const float m_new = fmaxf(st.m[rt], group_max(mx[rt]));
-      const float alpha = __builtin_amdgcn_exp2f(st.m[rt] - m_new);
-      st.m[rt] = m_new;
-      st.l[rt] *= alpha;
-      st.z[rt] *= alpha;
+      m[rt] = kNegBig, l[rt] = 0.f, z[rt] = 0.f;
 #pragma unroll
-      for (int n = 0; n < 8; ++n) st.o[rt][n] *= alpha;
+      for (int n = 0; n < 8; ++n) o[rt][n] = (float4v){0.f, 0.f, 0.f, 0.f};
     }
   }
-#pragma unroll
-  for (int rt = 0; rt < NRT; ++rt) {
-    const float shift = __builtin_fmaf(bias[rt], mul[rt], -st.m[rt]);
-    float sum = 0.f;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      raw[rt][j] = __builtin_amdgcn_exp2f(__builtin_fmaf(raw[rt][j], mul[rt], shift));
-      sum += raw[rt][j];
-    }
-    st.l[rt] += sum;
-  }
+};
+
+// Rescaling of an output accumulator on one of the rare paths.  PIN: the kernel keeps its accumulators
+// in the accumulation registers, where the matrix cores update them in place; the empty statement
+// says that the value is there when the rare path begins, so the copy to the arithmetic registers
+// that the multiplication needs is made here and not ahead of the branch, in every block.
+template <bool PIN>
+__device__ __forceinline__ void scale_acc(float4v& o, float alpha) {
+  if constexpr (PIN) asm volatile("" : "+a"(o));
+  o *= alpha;
 }
 
-// The row reference carries, on top of the largest score, the exponent e of the largest value scale S
-// met so far, so that p * S, which enters the second contraction as fp16, is at most 2 for the
-// largest S and keeps its bits however small or large the values are.  A reference is only a
-// convention between the accumulators and the partial written at the end: sum, zero-point term and
-// output all carry it and the merge of the partials is indifferent to it.  Called with this lane's
-// largest scale of the block after the block's probabilities exist and before they are used: when a
-// scale of the wave exceeds 2^(e+1), e is raised and everything that carries the old reference,
-// the block's probabilities included, is scaled down by the same power of two.
+__device__ __forceinline__ float max_of(const float (&v)[8]) {
+  return fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+}
+
+// The rare path of a tile.  arg: the exponents score - m of this lane's tokens, relative to the row's
+// present reference m = (score level) + e.  Raises the score level to kLift below the row's largest
+// score if that is higher than the present one, rescales what the row has accumulated and rebases the
+// exponents.
+template <bool PIN, int NRT>
+__device__ __forceinline__ void raise_reference(RowState<NRT>& st, int rt, float (&arg)[8]) {
+  const float top = group_max(max_of(arg));
+  const float delta = fmaxf(top + st.e - kLift, 0.f);
+  const float alpha = __builtin_amdgcn_exp2f(-delta);
+  st.m[rt] += delta;
+  st.l[rt] *= alpha;
+  st.z[rt] *= alpha;
+#pragma unroll
+  for (int n = 0; n < 8; ++n) scale_acc<PIN>(st.o[rt][n], alpha);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) arg[j] -= delta;
+}
+
+// The first reference of a row, from the scaled scores s of the first block the wave sees (nothing
+// has been accumulated yet).  A row whose tokens are all masked keeps "no reference".
 template <int NRT>
-__device__ __forceinline__ void raise_scale_reference(RowState<NRT>& st, float (&p)[NRT][8], float smax) {
+__device__ __forceinline__ void first_reference(RowState<NRT>& st, int rt, const float (&s)[8]) {
+  st.m[rt] = fmaxf(group_max(max_of(s)) - kLift + st.e, kNegBig);
+}
+
+// The row reference carries, on top of the score part, the exponent e of the largest value scale S
+// met so far, so that p * S, which enters the second contraction as fp16, keeps its bits however
+// small or large the values are (S / 2^e < 2 for the largest S).  Called with this lane group's largest
+// scale of the block after the block's probabilities exist and before they are used: when a scale of
+// the wave exceeds 2^(e+1), e is raised and everything that carries the old reference, the block's
+// probabilities included, is scaled down by the same power of two.
+template <bool PIN, int NRT, typename ScaleP>
+__device__ __forceinline__ void raise_scale_reference(RowState<NRT>& st, float smax, ScaleP&& scale_p) {
   if (__any(smax > st.s_limit)) {
     const float s_all = group_max(smax);   // the same in every lane: lanes of one group share their tokens
     const uint32_t ebits = __builtin_bit_cast(uint32_t, s_all) & 0x7f800000u;   // 2^floor(log2 s_all)
@@ -228,11 +305,18 @@ __device__ __forceinline__ void raise_scale_reference(RowState<NRT>& st, float (
       st.l[rt] *= alpha;
       st.z[rt] *= alpha;
 #pragma unroll
-      for (int n = 0; n < 8; ++n) st.o[rt][n] *= alpha;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) p[rt][j] *= alpha;
+      for (int n = 0; n < 8; ++n) scale_acc<PIN>(st.o[rt][n], alpha);
     }
+    scale_p(alpha);
   }
+}
+
+// Largest of the eight fp16 value scales of a lane group (positive numbers; packed maxima).
+__device__ __forceinline__ float max_scale(const u32x4& d) {
+  const half2v a = __builtin_elementwise_max(as_half2(d[0]), as_half2(d[1]));
+  const half2v b = __builtin_elementwise_max(as_half2(d[2]), as_half2(d[3]));
+  const half2v c = __builtin_elementwise_max(a, b);
+  return (float)__builtin_elementwise_max(c[0], c[1]);
 }
 
 // One 32-token block of a kv-head with a single query row (multi-head attention, one decode query).
@@ -244,10 +328,10 @@ __device__ __forceinline__ void raise_scale_reference(RowState<NRT>& st, float (
 // complete in lane (0, g) - the only column whose result is kept.  Sums (l, z) stay per lane and are
 // folded over the eight lanes once, before the partial is written.
 // raw: this lane's eight combined scores (meaningful in column 0); s_bits, z_bits: fp16 scale and
-// zero-point of token tile_token(g, rho & 7).  Returns the lane's operand of the value contraction.
+// zero-point of token tile_token(g, rho & 7); first: the wave's first block.  Returns the lane's operand of the value contraction.
 template <bool VERIFY>
 __device__ __forceinline__ half8 single_row_block(RowState<1>& st, const float (&raw)[8], float mul, float bias,
-                                                  uint32_t s_bits, uint32_t z_bits, int rho, float pos_a, float pos_b) {
+                                                  uint32_t s_bits, uint32_t z_bits, int rho, bool first) {
   auto bits = [](float f) { return __builtin_bit_cast(uint32_t, f); };
   uint32_t w = bits(raw[0]);
   w = row_shr_keep<1>(w, bits(raw[1]));
@@ -260,69 +344,73 @@ __device__ __forceinline__ half8 single_row_block(RowState<1>& st, const float (
   w = (uint32_t)__builtin_amdgcn_update_dpp((int)w, (int)w, 0x118, 0xF, 0xC, false);   // lanes 8..15 <- lanes 0..7
   const float x = __builtin_bit_cast(float, w);
 
-  const float s = __builtin_fmaf(x + bias, mul, st.e);
-  if (__any(s > st.m[0])) {
-    const float m_new = fmaxf(st.m[0], group_max(octet_max(s)));
-    const float alpha = __builtin_amdgcn_exp2f(st.m[0] - m_new);
-    st.m[0] = m_new;
-    st.l[0] *= alpha;
-    st.z[0] *= alpha;
-#pragma unroll
-    for (int n = 0; n < 8; ++n) st.o[0][n] *= alpha;
-  }
-  float p = __builtin_amdgcn_exp2f(__builtin_fmaf(x, mul, __builtin_fmaf(bias, mul, -st.m[0])));
-
-  const float sv = (float)__builtin_bit_cast(_Float16, (uint16_t)s_bits);
-  const float zv = (float)__builtin_bit_cast(_Float16, (uint16_t)z_bits);
-  if (__any(sv > st.s_limit)) {   // see raise_scale_reference
-    const float s_all = group_max(octet_max(sv));
-    const uint32_t ebits = bits(s_all) & 0x7f800000u;
-    const float e_new = (float)((int)(ebits >> 23) - 127);
-    const float delta = e_new - st.e;
+  const float base = bias * mul;
+  if (first) st.m[0] = group_max(octet_max(__builtin_fmaf(x, mul, base))) - kLift + st.e;   // see first_reference
+  float arg = __builtin_fmaf(x, mul, base - st.m[0]);
+  if (__any(arg > kTau - st.e)) {   // see raise_reference
+    const float delta = fmaxf(group_max(octet_max(arg)) + st.e - kLift, 0.f);
     const float alpha = __builtin_amdgcn_exp2f(-delta);
-    st.e = e_new;
-    st.s_limit = 2.0f * __builtin_bit_cast(float, ebits);
     st.m[0] += delta;
     st.l[0] *= alpha;
     st.z[0] *= alpha;
 #pragma unroll
     for (int n = 0; n < 8; ++n) st.o[0][n] *= alpha;
-    p *= alpha;
+    arg -= delta;
   }
+  float p = __builtin_amdgcn_exp2f(arg);
+
+  const float sv = (float)__builtin_bit_cast(_Float16, (uint16_t)s_bits);
+  const float zv = (float)__builtin_bit_cast(_Float16, (uint16_t)z_bits);
+  raise_scale_reference<false>(st, octet_max(sv), [&](float alpha) { p *= alpha; });
   st.l[0] += p;
   st.z[0] = __builtin_fmaf(p, VERIFY ? __builtin_fmaf(-0.5f, sv, zv) : zv, st.z[0]);
   _Float16 h = (_Float16)(p * sv);
-  h = h * (_Float16)((rho & 2) ? pos_b : pos_a);   // elements 2,3,6,7 of the operand: see the value unpacking
+  if (!VERIFY) h = h * (_Float16)((rho & 2) ? 0.0625f : 1.0f);   // elements 2,3,6,7 of the operand: see the value unpacking
   const uint32_t hb = __builtin_bit_cast(uint16_t, h);
   const uint32_t pair = hb | (row_shl_zero<1>(hb) << 16);
   const u32x4 pw = {pair, row_shl_zero<2>(pair), row_shl_zero<4>(pair), row_shl_zero<6>(pair)};
   return as_half8(pw);
 }
 
-template <int NRT, int RPT>
+// Tile rt of a wave that carries NRT tiles: all but the last are full (16 rows), the last has mode TAIL.
+template <int NRT, int TAIL>
+constexpr int mode_of(int rt) { return rt == NRT - 1 ? TAIL : 16; }
+
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (N > 0) {
+    static_for<N - 1>(f);
+    f(std::integral_constant<int, N - 1>{});
+  }
+}
+
+// Writes the partial (m, l, o) of every row of the wave.  o_scale: factor on the raw accumulators.
+template <int NRT, int TAIL>
 __device__ __forceinline__ void write_partial(const AttnArgs& a, RowState<NRT>& st, int b, int kvh, int row0,
                                               int split, float o_scale) {
-  const int lane = threadIdx.x & 63, rho = lane & 15, g = lane >> 4;
+  const Lane L;
   const int n_split = a.n_split_q + a.n_split_b;
-#pragma unroll
-  for (int rt = 0; rt < NRT; ++rt) {
+  static_for<NRT>([&](auto RT) {
+    constexpr int rt = decltype(RT)::value;
+    constexpr int M = mode_of<NRT, TAIL>(rt);
     const float l = group_sum(st.l[rt]);
     const float z = group_sum(st.z[rt]);
-    const int row = row0 + rt * RPT + (rho & (RPT - 1));
-    if (rho < RPT && row < a.n_rows) {
-      const int qi = row / a.rep, head = kvh * a.rep + row % a.rep;
-      const int64_t r = (((int64_t)b * a.nq + qi) * a.n_q_heads + head) * n_split + split;
-      float* po = a.ws_o + r * kD;
+    const int row = row0 + 16 * rt + L.row<M>();
+    const bool writer = L.rho < M && row < a.n_rows;
+    const int qi = row / a.rep, head = kvh * a.rep + row % a.rep;
+    const int64_t r = (((int64_t)b * a.nq + qi) * a.n_q_heads + head) * n_split + split;
+    float* po = a.ws_o + r * kD;
+    if (writer) {
 #pragma unroll
       for (int n = 0; n < 8; ++n)
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) po[8 * (4 * g + jj) + n] = __builtin_fmaf(st.o[rt][n][jj], o_scale, z);
-      if (g == 0) {
-        a.ws_ml[2 * r] = st.m[rt];
-        a.ws_ml[2 * r + 1] = l;
-      }
+        for (int jj = 0; jj < 4; ++jj) po[8 * (4 * L.g + jj) + n] = __builtin_fmaf(st.o[rt][n][jj], o_scale, z);
     }
-  }
+    if (writer && L.g == 0) {
+      a.ws_ml[2 * r] = st.m[rt];
+      a.ws_ml[2 * r + 1] = l;
+    }
+  });
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -340,13 +428,14 @@ __device__ __forceinline__ void write_partial(const AttnArgs& a, RowState<NRT>& 
 // the waves of a workgroup share in LDS (first_claim: the value this wave already drew).  The
 // pipeline looks two groups ahead (block prefetch, key metadata of the next group), so the wave
 // always holds the group it computes and the next two it has drawn.
-template <int NRT, bool VERIFY, bool KSPLIT, bool SINGLE, bool DYN = false>
+template <int NRT, int TAIL, bool VERIFY, bool SINGLE, bool DYN = false>
 __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, int kvh, int row0, int split,
                                             int* queue = nullptr, int g_base = 0, int g_count = 0, int first_claim = 0) {
-  static_assert(!SINGLE || (NRT == 1 && !KSPLIT), "the single-row path is a variant of the one-tile kernel");
-  constexpr int RPT = KSPLIT ? 16 : 8;   // query rows per 16-column MFMA tile
-  const int lane = threadIdx.x & 63, rho = lane & 15, g = lane >> 4;
-  const bool lo_part = !KSPLIT && rho >= 8;
+  static_assert(!SINGLE || (NRT == 1 && TAIL == 8), "the single-row path is a variant of the one-tile kernel");
+  constexpr bool kTwoWaves = NRT == 1 && TAIL != 16;   // two waves per SIMD: at most 256 registers, none of them accumulation registers
+  constexpr bool PIN = !kTwoWaves;
+  const Lane L;
+  const int lane = threadIdx.x & 63, rho = L.rho, g = L.g;
   const int n_groups = a.len.n_quant[b] / kG;
   int first = 0, n_local = 0;
   int gq[3] = {-1, -1, -1};   // DYN: the group being computed and the two drawn after it (-1: none left)
@@ -367,27 +456,17 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   }
 
   // Powers of two folded out of the operands (see file header).
-  //   draft : code operand carries 2^-24 (elements 0,1,4,5) or 2^-20 (elements 2,3,6,7)
+  //   draft : code operand carries 2^-24 (elements 0,1,4,5) or 2^-20 (elements 2,3,6,7); the other
+  //           operand of either contraction takes 2^-4 at the latter
   //   verify: code operand carries 2^-24 and the codes are 16*C_U + C_L + 8 in units of S/16
   constexpr float kKeyPos = VERIFY ? 1.0f : 0.0625f;             // factor on q at elements 2,3,6,7
   constexpr float kKeyRaw = VERIFY ? 1048576.0f : 16777216.0f;   // score = raw * kKeyRaw * c0
-  // p*S (at most 2, see raise_scale_reference) takes a factor 4 or 1/4 that evens out the two bit
-  // positions a code can sit at.
-  constexpr float kPA = 4.0f;                                    // factor on p*S at elements 0,1,4,5
-  constexpr float kPB = VERIFY ? 4.0f : 0.25f;                   // factor on p*S at elements 2,3,6,7
-  constexpr float kOutRaw = VERIFY ? 262144.0f : 4194304.0f;     // out = rawO * kOutRaw + sum p*Zeff
+  constexpr float kOutRaw = VERIFY ? 1048576.0f : 16777216.0f;   // out = rawO * kOutRaw + sum p*Zeff
 
   RowState<NRT> st;
-  st.e = -40.f;   // below every value scale (>= 2^-24): the first block raises it
-  st.s_limit = 0x1p-39f;
-#pragma unroll
-  for (int rt = 0; rt < NRT; ++rt) {
-    st.m[rt] = kNegBig; st.l[rt] = 0.f; st.z[rt] = 0.f;
-#pragma unroll
-    for (int n = 0; n < 8; ++n) st.o[rt][n] = (float4v){0.f, 0.f, 0.f, 0.f};
-  }
+  st.reset(-40.f, 0x1p-39f);   // e below every value scale (>= 2^-24): the first block raises it
   if (n_local <= 0) {
-    write_partial<NRT, RPT>(a, st, b, kvh, row0, split, kOutRaw);
+    write_partial<NRT, TAIL>(a, st, b, kvh, row0, split, kOutRaw);
     return;
   }
 
@@ -448,7 +527,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   // keeps in flight, divided by the memory latency under load, cap the bandwidth below what the
   // memory delivers; the draft kernel has the registers for a second one (three of the four named
   // buffers are live at any time).
-  constexpr int kAhead = (!VERIFY && !KSPLIT) ? 2 : 1;
+  constexpr int kAhead = (!VERIFY && kTwoWaves) ? 2 : 1;
   Blk bufA, bufB, bufC, bufD;
   // Everything the first group needs is requested before anything is waited for: its blocks (all
   // four where the registers allow, so that the memory pipeline is full while the query operand is
@@ -472,9 +551,10 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   // power goes into the row's score multiplier.  Elements 2,3,6,7 also take the code operand's 2^-4.
   half2v qv[NRT][16];
   float mul[NRT];
-#pragma unroll
-  for (int rt = 0; rt < NRT; ++rt) {
-    const int row = row0 + rt * RPT + (rho & (RPT - 1));
+  static_for<NRT>([&](auto RT) {
+    constexpr int rt = decltype(RT)::value;
+    constexpr int M = mode_of<NRT, TAIL>(rt);
+    const int row = row0 + 16 * rt + L.row<M>();
     const bool valid = row < a.n_rows;
     const int rowc = valid ? row : 0;
     const int qi = rowc / a.rep, head = kvh * a.rep + rowc % a.rep;
@@ -501,15 +581,12 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
         h = h * (_Float16)(down * ((r & 1) ? kKeyPos : 1.0f));
         qv[rt][4 * s + r] = h;
       }
-  }
+  });
 
   // Query operand of the current group (qb, cin) and, built one k-step per block, of the next one.
-  // q*S is split exactly into fp16(q*S) and the fp16 remainder q*S - fp16(q*S).  With up to 8 query
-  // rows per tile the two parts sit in columns 0-7 and 8-15 of one operand and a DPP add recombines the
-  // scores; with up to 16 rows per tile (KSPLIT) every column is a query row and the remainder is a
-  // second operand accumulated into the same MFMA result.
-  constexpr int NQB = KSPLIT ? 2 : 1;
-  half8 qb[NRT][NQB][4], qbn[NRT][NQB][4];
+  // q*S is split exactly into fp16(q*S) and the fp16 remainder q*S - fp16(q*S): two operands
+  // accumulated into the same MFMA result for a tile of 16 rows, two columns of one operand otherwise.
+  half8 qb[NRT][2][4], qbn[NRT][2][4];
   float cin[NRT], acc_a[NRT], acc_b[NRT], acc_sa[NRT], acc_sb[NRT];
   auto prep_reset = [&]() {
 #pragma unroll
@@ -517,19 +594,20 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   };
   auto prep_kstep = [&](auto S, u32x4 sw, u32x4 zw) {   // sw, zw: key S / Z of channels 32g + 8s.., operand order
     constexpr int s = decltype(S)::value;
-#pragma unroll
-    for (int rt = 0; rt < NRT; ++rt) {
+    static_for<NRT>([&](auto RT) {
+      constexpr int rt = decltype(RT)::value;
+      constexpr int M = mode_of<NRT, TAIL>(rt);
       u32x4 out, out_lo;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const half2v qh = qv[rt][4 * s + r], sh = as_half2(sw[r]), zh = as_half2(zw[r]);
         const half2v hi = qh * sh;
         const half2v lo = __builtin_elementwise_fma(qh, sh, -hi);
-        if (KSPLIT) {
+        if (M == 16) {
           out[r] = as_u32(hi);
           out_lo[r] = as_u32(lo);
         } else {
-          out[r] = lo_part ? as_u32(lo) : as_u32(hi);
+          out[r] = L.remainder<M>() ? as_u32(lo) : as_u32(hi);
         }
         if (r & 1) {
           acc_b[rt] = __builtin_amdgcn_fdot2(qh, zh, acc_b[rt], false);
@@ -540,78 +618,119 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
         }
       }
       qbn[rt][0][s] = as_half8(out);
-      if (KSPLIT) qbn[rt][1][s] = as_half8(out_lo);
-    }
+      if (M == 16) qbn[rt][1][s] = as_half8(out_lo);
+    });
   };
   auto prep_commit = [&]() {   // sum_d q_d * Zeff_d, Zeff = Z (draft) or Z - S/2 (verify: codes carry +8 lower steps)
-#pragma unroll
-    for (int rt = 0; rt < NRT; ++rt) {
+    static_for<NRT>([&](auto RT) {
+      constexpr int rt = decltype(RT)::value;
+      constexpr int M = mode_of<NRT, TAIL>(rt);
       float bias = __builtin_fmaf(acc_b[rt], 1.0f / kKeyPos, acc_a[rt]);
       if (VERIFY) bias -= 0.5f * __builtin_fmaf(acc_sb[rt], 1.0f / kKeyPos, acc_sa[rt]);
       bias = group_sum(bias);
       cin[rt] = bias * (1.0f / kKeyRaw);   // added to the raw scores inside the softmax step
       if (SINGLE) cin[rt] = __shfl(cin[rt], lane & 48);   // every lane works on the one row of column 0
 #pragma unroll
-      for (int h = 0; h < NQB; ++h)
+      for (int h = 0; h < (M == 16 ? 2 : 1); ++h)
 #pragma unroll
         for (int s = 0; s < 4; ++s) qb[rt][h][s] = qbn[rt][h][s];
-    }
+    });
     prep_reset();
   };
 
+  bool fresh = true;   // the wave's first block sets the rows' references
   auto compute_block = [&](const Blk& d, auto P) {
     constexpr int p = decltype(P)::value;
     // ---- scores: S^T[token, column] = codes x q ----
-    float raw[NRT][8];
+    float x[NRT][8];   // raw scores of this lane's eight tokens; later their exponents, then their probabilities
     {
       half8 ka[2][4];
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int s = 0; s < 4; ++s) ka[t][s] = VERIFY ? unpack8(d.kU[t][s], d.kL[t][s]) : unpack4(d.kU[t][s]);
-#pragma unroll
-      for (int rt = 0; rt < NRT; ++rt)
+      static_for<NRT>([&](auto RT) {
+        constexpr int rt = decltype(RT)::value;
+        constexpr int M = mode_of<NRT, TAIL>(rt);
+        float4v acc[2];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-          float4v acc = {0.f, 0.f, 0.f, 0.f};
+          acc[t] = (float4v){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int s = 0; s < 4; ++s) {
-            acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qb[rt][0][s], acc, 0, 0, 0);
-            if (KSPLIT) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qb[rt][1][s], acc, 0, 0, 0);
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qb[rt][0][s], acc[t], 0, 0, 0);
+            if (M == 16) acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t][s], qb[rt][1][s], acc[t], 0, 0, 0);
           }
-#pragma unroll
-          for (int jj = 0; jj < 4; ++jj) raw[rt][4 * t + jj] = KSPLIT ? acc[jj] : acc[jj] + xor8_in_row(acc[jj]);
         }
+        tile_scores<M>(acc[0], acc[1], x[rt]);
+      });
     }
     prep_kstep(P, d.kS, d.kZ);   // one k-step of the next group's query operand
     half8 pb[NRT];
     if constexpr (SINGLE) {
-      pb[0] = single_row_block<VERIFY>(st, raw[0], mul[0], cin[0], d.vS[0], d.vZ[0], rho, kPA, kPB);
+      pb[0] = single_row_block<VERIFY>(st, x[0], mul[0], cin[0], d.vS[0], d.vZ[0], rho, p == 0 && fresh);
     } else {
-      softmax_block<NRT>(st, raw, mul, cin);
-
-      // ---- probabilities x value scale -> B operand; zero-point term ----
-      const half8 vS = as_half8(d.vS), vZ = as_half8(d.vZ);
-      float sv[8];
+      // ---- probabilities relative to the rows' references (see above) ----
+      float base[NRT];
 #pragma unroll
-      for (int jj = 0; jj < 8; ++jj) sv[jj] = (float)vS[jj];
-      raise_scale_reference<NRT>(st, raw, fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])),
-                                                fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7]))));
+      for (int rt = 0; rt < NRT; ++rt) base[rt] = cin[rt] * mul[rt];
+      if (p == 0 && fresh) {
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) {
+          float s[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) s[j] = __builtin_fmaf(x[rt][j], mul[rt], base[rt]);
+          first_reference(st, rt, s);
+        }
+      }
+      const float limit = kTau - st.e;   // exponents are short of the scores by e
+      bool high = false;
 #pragma unroll
       for (int rt = 0; rt < NRT; ++rt) {
-        float zs = 0.f;
-        half8 ps;
+        const float shift = base[rt] - st.m[rt];
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
-          const float zeff = VERIFY ? __builtin_fmaf(-0.5f, sv[jj], (float)vZ[jj]) : (float)vZ[jj];
-          zs = __builtin_fmaf(raw[rt][jj], zeff, zs);
-          ps[jj] = (_Float16)(raw[rt][jj] * sv[jj]);
+        for (int j = 0; j < 8; ++j) x[rt][j] = __builtin_fmaf(x[rt][j], mul[rt], shift);   // the exponent score - m
+        high |= max_of(x[rt]) > limit;
+      }
+      if (__any(high)) {
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt) raise_reference<PIN>(st, rt, x[rt]);
+      }
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) {
+        float sum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          x[rt][j] = __builtin_amdgcn_exp2f(x[rt][j]);   // the probability
+          sum += x[rt][j];
+        }
+        st.l[rt] += sum;
+      }
+
+      // ---- probabilities x value scale -> B operand; zero-point term ----
+      raise_scale_reference<PIN>(st, max_scale(d.vS), [&](float alpha) {
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) x[rt][j] *= alpha;
+      });
+      float sv[8], zeff[8];
+      meta_floats(d.vS, sv);
+      meta_floats(d.vZ, zeff);
+      if (VERIFY) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) zeff[j] = __builtin_fmaf(-0.5f, sv[j], zeff[j]);
+      }
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) {
+        float zs = 0.f, ps[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          zs = __builtin_fmaf(x[rt][j], zeff[j], zs);
+          ps[j] = x[rt][j] * sv[j];
         }
         st.z[rt] += zs;
-        u32x4 pw = as_u32x4(ps);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) pw[r] = as_u32(as_half2(pw[r]) * (_Float16)((r & 1) ? kPB : kPA));
-        pb[rt] = as_half8(pw);
+        pb[rt] = p_operand<VERIFY>(ps);
       }
     }
 
@@ -624,6 +743,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
         st.o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(va, pb[rt], st.o[rt][n], 0, 0, 0);
     }
     if (p == 3) prep_commit();
+    if (p == 0) fresh = false;
   };
 
   // the first group's query operand from the metadata requested at the start
@@ -664,8 +784,10 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   if constexpr (SINGLE) {   // one token per lane: the row's sums are spread over eight lanes
     st.l[0] = octet_sum(st.l[0]);
     st.z[0] = octet_sum(st.z[0]);
+    write_partial<1, 16>(a, st, b, kvh, row0, split, kOutRaw);   // column 0 alone holds the row: nothing to add up
+    return;
   }
-  write_partial<NRT, RPT>(a, st, b, kvh, row0, split, kOutRaw);
+  write_partial<NRT, TAIL>(a, st, b, kvh, row0, split, kOutRaw);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -673,7 +795,8 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
 // buffer, many when the buffer is long, e.g. a cache that keeps every token in fp16).  Keys are read
 // straight into the A operand; the value rows are transposed through LDS because the matrix cores
 // need eight tokens of one channel per lane while the buffer is stored token-major.  The next
-// block's keys and values are in flight while the current one is computed.
+// block's keys and values are in flight while the current one is computed.  fp16 queries and keys
+// need no remainder part, so every column of a tile is a query row here (NRT tiles of 16 rows).
 // ------------------------------------------------------------------------------------------------
 constexpr int kVtStride = 40;   // halfs per LDS row: 32 tokens + padding, keeps 8-byte reads aligned
 
@@ -682,14 +805,12 @@ constexpr int kVtStride = 40;   // halfs per LDS row: 32 tokens + padding, keeps
 // compiler nor the wave's own outstanding-operation counter lets them pass each other; a workgroup
 // barrier would be wrong where the waves of a workgroup work on unrelated items.
 __device__ __forceinline__ void wave_lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-constexpr float kBufP = 16384.0f;
+constexpr float kBufP = 128.0f;   // p <= 2^kTau: p * kBufP stays inside fp16
 
-template <int NRT, bool KSPLIT>
+template <int NRT>
 __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b, int kvh, int row0, int split,
                                              _Float16 (*vt)[kVtStride]) {
-  constexpr int RPT = KSPLIT ? 16 : 8;
   const int lane = threadIdx.x & 63, rho = lane & 15, g = lane >> 4;
-  const bool lo_part = !KSPLIT && rho >= 8;   // the fp16 queries and keys need no remainder part
   const int nb = a.len.n_buf[b];
   // the buffer's 32-token blocks are dealt out evenly to its n_split_b chunks
   const int n_blk = (nb + 31) >> 5, piece = split - a.n_split_q;
@@ -700,7 +821,7 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
   int vis[NRT];   // buffer tokens [0, vis) are visible to this lane's query (causal among the nq queries)
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
-    const int row = row0 + rt * RPT + (rho & (RPT - 1));
+    const int row = row0 + 16 * rt + rho;
     const bool valid = row < a.n_rows;
     const int rowc = valid ? row : 0;
     const int qi = rowc / a.rep, head = kvh * a.rep + rowc % a.rep;
@@ -709,22 +830,12 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       u32x4 w = ldg128(qp + 32 * s);
-      if (!valid || lo_part) w = (u32x4){0u, 0u, 0u, 0u};
+      if (!valid) w = (u32x4){0u, 0u, 0u, 0u};
       qb[rt][s] = as_half8(w);
     }
   }
   RowState<NRT> st;
-  st.e = 0.f;   // no value scales here: the reference is the largest score itself
-  st.s_limit = __builtin_inff();
-#pragma unroll
-  for (int rt = 0; rt < NRT; ++rt) {
-    st.m[rt] = kNegBig; st.l[rt] = 0.f; st.z[rt] = 0.f;
-#pragma unroll
-    for (int n = 0; n < 8; ++n) st.o[rt][n] = (float4v){0.f, 0.f, 0.f, 0.f};
-  }
-  float mulb[NRT], zero_bias[NRT];
-#pragma unroll
-  for (int rt = 0; rt < NRT; ++rt) mulb[rt] = a.c0, zero_bias[rt] = 0.f;
+  st.reset(0.f, __builtin_inff());   // no value scales here: the reference follows the scores alone
   const _Float16* kb = a.k_buf + (int64_t)unit * a.buf_cap * kD;
   const _Float16* vb = a.v_buf + (int64_t)unit * a.buf_cap * kD;
   const int tau = lane & 31, cc = lane >> 5;   // value rows: this lane's token of the block, channel half
@@ -751,9 +862,10 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
     const int t0 = 32 * blk;
     u32x4 kn[2][4] = {}, vn[8] = {};
     if (blk + 1 < blk1) load_block(blk + 1, kn, vn);
-    float raw[NRT][8];
+    float x[NRT][8];   // raw scores, then exponents, then probabilities of this lane's eight tokens
+    bool high = false;
 #pragma unroll
-    for (int rt = 0; rt < NRT; ++rt)
+    for (int rt = 0; rt < NRT; ++rt) {
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         float4v acc = {0.f, 0.f, 0.f, 0.f};
@@ -763,11 +875,41 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
           const int tok = t0 + 16 * t + 4 * g + jj;
-          const float sc = KSPLIT ? acc[jj] : acc[jj] + xor8_in_row(acc[jj]);
-          raw[rt][4 * t + jj] = tok < vis[rt] ? sc : -__builtin_inff();
+          x[rt][4 * t + jj] = tok < vis[rt] ? acc[jj] : -__builtin_inff();
         }
       }
-    softmax_block<NRT>(st, raw, mulb, zero_bias);
+      if (blk == blk0) {
+        float s[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s[j] = x[rt][j] * a.c0;
+        first_reference(st, rt, s);
+      }
+      // masked tokens follow the visible ones, so a row either has its reference by now or sees nothing here
+      const float shift = -st.m[rt];
+      float top = -__builtin_inff();
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        x[rt][j] = __builtin_fmaf(x[rt][j], a.c0, shift);
+        top = fmaxf(top, x[rt][j]);
+      }
+      high |= top > kTau;
+    }
+    if (__any(high)) {
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) raise_reference<false>(st, rt, x[rt]);
+    }
+    half8 pb[NRT];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      float sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float p = __builtin_amdgcn_exp2f(x[rt][j]);
+        sum += p;
+        pb[rt][j] = (_Float16)(p * kBufP);
+      }
+      st.l[rt] += sum;
+    }
 
     wave_lds_sync();   // the previous block's LDS reads are done
 #pragma unroll
@@ -778,11 +920,6 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
       for (int i = 0; i < 8; ++i) vt[ch + i][tau] = v[i];
     }
     wave_lds_sync();
-    half8 pb[NRT];
-#pragma unroll
-    for (int rt = 0; rt < NRT; ++rt)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) pb[rt][j] = (_Float16)(raw[rt][j] * kBufP);
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
       const _Float16* rowp = &vt[8 * rho + n][0];
@@ -800,25 +937,25 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
 #pragma unroll
     for (int it = 0; it < 8; ++it) va[it] = vn[it];
   }
-  write_partial<NRT, RPT>(a, st, b, kvh, row0, split, 1.0f / kBufP);
+  write_partial<NRT, 16>(a, st, b, kvh, row0, split, 1.0f / kBufP);
 }
 
-// NRT 16-column tiles per wave; KSPLIT = 16 query rows per tile instead of 8 (see quant_chunk).  The
-// kernels that carry at most one tile of 8 rows run two waves per SIMD, the others one.
-template <int NRT, bool VERIFY, bool KSPLIT, bool SINGLE = false>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NRT == 1 && !KSPLIT ? 2 : 1))) void attn_kernel(AttnArgs a) {
+// A wave carries NRT tiles of query rows: 16 in each but the last, TAIL (16 or 8) in the last.
+// The kernels with one tile of at most 8 rows run two waves per SIMD, the others one.
+template <int NRT, int TAIL, bool VERIFY, bool SINGLE = false>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NRT == 1 && TAIL != 16 ? 2 : 1))) void attn_kernel(AttnArgs a) {
   __shared__ _Float16 vt[kD][kVtStride];   // value-tile transpose of the buffer chunk
   // Dispatch order: unit fastest, every quantized chunk before any buffer chunk.  The planner makes
   // no more quantized chunks than there are resident wave slots, so all of them start at once; the
   // short buffer chunks take the slots of the first waves to finish and end long before the last
   // quantized chunk does.  (Buffer chunks first cost the last 128 quantized chunks a 10 us late start.)
-  const int unit = blockIdx.x, row0 = blockIdx.z * (KSPLIT ? 16 : 8) * NRT;
+  const int unit = blockIdx.x, row0 = blockIdx.z * (16 * (NRT - 1) + TAIL);
   const int split = blockIdx.y;
   const int b = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   if (split < a.n_split_q)
-    quant_chunk<NRT, VERIFY, KSPLIT, SINGLE>(a, unit, b, kvh, row0, split);
+    quant_chunk<NRT, TAIL, VERIFY, SINGLE>(a, unit, b, kvh, row0, split);
   else
-    buffer_chunk<NRT, KSPLIT>(a, unit, b, kvh, row0, split, vt);
+    buffer_chunk<NRT>(a, unit, b, kvh, row0, split, vt);
 }
 
 // One workgroup per compute unit: eight waves (two per SIMD) share 1/W of a unit's quantized groups
@@ -849,10 +986,10 @@ __global__ __launch_bounds__(64 * kCuWaves) __attribute__((amdgpu_waves_per_eu(2
   int c = draw();
   while (c < 0) {   // a buffer item: a partial of its own
     const int item = -c - 1;
-    buffer_chunk<1, false>(a, unit, b, kvh, 0, a.n_split_q + w + n_wg * item, vt[item]);
+    buffer_chunk<1>(a, unit, b, kvh, 0, a.n_split_q + w + n_wg * item, vt[item]);
     c = draw();
   }
-  quant_chunk<1, VERIFY, false, SINGLE, true>(a, unit, b, kvh, 0, kCuWaves * w + wave, &queue, g0, g1 - g0, c);
+  quant_chunk<1, 8, VERIFY, SINGLE, true>(a, unit, b, kvh, 0, kCuWaves * w + wave, &queue, g0, g1 - g0, c);
 }
 
 // Merge of the per-chunk partials (Appendix E): M = max m_i, L = sum l_i 2^(m_i - M),
@@ -919,45 +1056,38 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
   }
 }
 
-template <int NRT, bool KSPLIT>
-hipError_t launch_attn_nrt(const AttnArgs& a, int batch, bool verify, hipStream_t s) {
-  constexpr int rows = (KSPLIT ? 16 : 8) * NRT;
+template <int NRT, int TAIL>
+hipError_t launch_attn_tiles(const AttnArgs& a, int batch, bool verify, hipStream_t s) {
+  constexpr int rows = 16 * (NRT - 1) + TAIL;
   dim3 grid(batch * a.n_kv_heads, a.n_split_q + a.n_split_b, (a.n_rows + rows - 1) / rows);
-  if (verify)
-    hipLaunchKernelGGL((attn_kernel<NRT, true, KSPLIT>), grid, dim3(64), 0, s, a);
-  else
-    hipLaunchKernelGGL((attn_kernel<NRT, false, KSPLIT>), grid, dim3(64), 0, s, a);
-  return hipGetLastError();
+  return verify ? launch(attn_kernel<NRT, TAIL, true>, grid, dim3(64), s, a)
+                : launch(attn_kernel<NRT, TAIL, false>, grid, dim3(64), s, a);
 }
 
 }  // namespace
 
-// up to 8 query rows per kv-head: one tile, remainder in columns 8-15; up to 16: one tile, remainder as a
-// second operand; more: two such tiles per wave (and row batches over grid.z beyond 32 rows)
+// Query rows per kv-head -> tiles of the wave: up to 8 rows one tile with the remainders in its other
+// columns; up to 16 one full tile; up to 24 a full tile and one of 8; up to 32 two full tiles; more: row
+// batches of 32 over grid.z.
 hipError_t launch_attn(const AttnArgs& a, int batch, bool verify, hipStream_t s) {
   if (a.cu_wgs > 0) {   // at most 8 rows and enough groups: one workgroup per compute unit, groups drawn dynamically
-    dim3 grid(batch * a.n_kv_heads, a.cu_wgs, 1);
-    if (verify)
-      hipLaunchKernelGGL((attn_kernel_cu<true, false>), grid, dim3(64 * kCuWaves), 0, s, a);
-    else if (a.n_rows == 1)
-      hipLaunchKernelGGL((attn_kernel_cu<false, true>), grid, dim3(64 * kCuWaves), 0, s, a);
-    else
-      hipLaunchKernelGGL((attn_kernel_cu<false, false>), grid, dim3(64 * kCuWaves), 0, s, a);
-    return hipGetLastError();
+    dim3 grid(batch * a.n_kv_heads, a.cu_wgs, 1), block(64 * kCuWaves);
+    if (verify) return launch(attn_kernel_cu<true, false>, grid, block, s, a);
+    if (a.n_rows == 1) return launch(attn_kernel_cu<false, true>, grid, block, s, a);
+    return launch(attn_kernel_cu<false, false>, grid, block, s, a);
   }
   if (a.n_rows == 1 && !verify) {   // one query row per kv-head: one token per lane in the softmax
     dim3 grid(batch * a.n_kv_heads, a.n_split_q + a.n_split_b, 1);
-    hipLaunchKernelGGL((attn_kernel<1, false, false, true>), grid, dim3(64), 0, s, a);
-    return hipGetLastError();
+    return launch(attn_kernel<1, 8, false, true>, grid, dim3(64), s, a);
   }
-  if (a.n_rows <= 8) return launch_attn_nrt<1, false>(a, batch, verify, s);
-  if (a.n_rows <= 16) return launch_attn_nrt<1, true>(a, batch, verify, s);
-  return launch_attn_nrt<2, true>(a, batch, verify, s);
+  if (a.n_rows <= 8) return launch_attn_tiles<1, 8>(a, batch, verify, s);
+  if (a.n_rows <= 16) return launch_attn_tiles<1, 16>(a, batch, verify, s);
+  if (a.n_rows <= 24) return launch_attn_tiles<2, 8>(a, batch, verify, s);
+  return launch_attn_tiles<2, 16>(a, batch, verify, s);
 }
 
 hipError_t launch_merge(const MergeArgs& a, int rows_total, hipStream_t s) {
-  hipLaunchKernelGGL(merge_kernel, dim3(rows_total), dim3(256), 0, s, a);
-  return hipGetLastError();
+  return launch(merge_kernel, dim3(rows_total), dim3(256), s, a);
 }
 
 }  // namespace qs

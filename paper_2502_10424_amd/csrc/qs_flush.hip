@@ -537,31 +537,25 @@ bool flush_moves_buffer(int n_groups, int units) { return n_groups == 1 && units
 hipError_t launch_flush(const FlushArgs& a, int batch, hipStream_t s) {
   if (a.n_groups <= 0) return hipSuccess;
   const int units = batch * a.n_kv_heads;
-  if ((int64_t)a.n_groups * units >= kBulkGroups) {
-    hipLaunchKernelGGL(quantize_group_kernel, dim3(a.n_groups, units), dim3(256), 0, s, a);
-  } else {
-    hipLaunchKernelGGL(flush_kernel, dim3(4 * a.n_groups, units), dim3(256), 0, s, a);
-  }
-  return hipGetLastError();
+  if ((int64_t)a.n_groups * units >= kBulkGroups)
+    return launch(quantize_group_kernel, dim3(a.n_groups, units), dim3(256), s, a);
+  return launch(flush_kernel, dim3(4 * a.n_groups, units), dim3(256), s, a);
 }
 
 hipError_t launch_shift(const ShiftArgs& a, int batch, hipStream_t s) {
   dim3 grid(batch * a.n_kv_heads, 2);
-  hipLaunchKernelGGL(shift_kernel, grid, dim3(1024), 0, s, a);
-  return hipGetLastError();
+  return launch(shift_kernel, grid, dim3(1024), s, a);
 }
 
 hipError_t launch_append(const AppendArgs& a, int batch, hipStream_t s) {
   const int chunks = a.n_new * a.n_kv_heads * 16;
-  hipLaunchKernelGGL(append_kernel, dim3((chunks + 255) / 256, batch), dim3(256), 0, s, a);
-  return hipGetLastError();
+  return launch(append_kernel, dim3((chunks + 255) / 256, batch), dim3(256), s, a);
 }
 
 hipError_t launch_export(const ExportArgs& a, hipStream_t s) {
   if (a.n_tokens <= 0) return hipSuccess;
   const int words = a.n_tokens * kRowDw;
-  hipLaunchKernelGGL(export_kernel, dim3((words + 255) / 256), dim3(256), 0, s, a);
-  return hipGetLastError();
+  return launch(export_kernel, dim3((words + 255) / 256), dim3(256), s, a);
 }
 
 }  // namespace qs

@@ -98,6 +98,15 @@ __device__ __forceinline__ int64_t physical_group(const Args& a, int unit, int g
   return a.group_table != nullptr ? (int64_t)a.group_table[logical] : logical;
 }
 
+// Launches a kernel that takes one argument struct and returns the status of that launch alone: an
+// error that an earlier call of the application left behind on this thread is neither reported nor
+// consumed (hipGetLastError() would do both).
+template <typename K, typename A>
+hipError_t launch(K kernel, dim3 grid, dim3 block, hipStream_t s, A args) {
+  void* kargs[] = {&args};
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, kargs, 0, s);
+}
+
 // True if a flush of n_groups groups of `units` units takes the kernel that can also move the buffer.
 bool flush_moves_buffer(int n_groups, int units);
 hipError_t launch_flush(const FlushArgs& a, int batch, hipStream_t s);
