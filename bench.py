@@ -56,7 +56,7 @@ def main():
     ap.add_argument("--copies", type=int, default=4, help="independent cache copies to rotate over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--deterministic", action="store_true",
-                    help="time the bit-reproducible setting (qs_configure(QS_CFG_DETERMINISTIC, 1)) instead of the default")
+                    help="time the bit-reproducible setting (QS_FLAG_FIXED_RANGES) instead of the default")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the timed cycle: no prefill timing, fp16 baseline or speculation loop (for kernel traces)")
     args = ap.parse_args()
@@ -73,7 +73,7 @@ def main():
         sys.exit(1)
     B.lib()
     if args.deterministic:
-        B.qs_configure(B.QS_CFG_DETERMINISTIC, 1)
+        B.KVCache.default_flags = B.QS_FLAG_FIXED_RANGES
     w = synth.WORKLOADS[args.workload]
     sm_scale = 1.0 / float(np.sqrt(w.head_dim))
     nqv = w.nq_verify

@@ -14,7 +14,8 @@
  *     kernel arguments, so they may change as soon as the call returns).
  *   - The library never allocates, frees or synchronizes.  Every call enqueues its kernels on
  *     `stream` (a hipStream_t passed as void*; NULL = the default stream) and returns.
- *   - Return value: QS_OK, or a negative qs_status; on error nothing has been enqueued.
+ *   - Return value: QS_OK, or a negative qs_status; on error nothing has been enqueued.  There is no
+ *     process-wide state: what a call does depends on its arguments (and the current device) alone.
  *   - head_dim and group must both be 128 (the paper's evaluation setting, Section 5.1).
  *   - All device pointers must be 16-byte aligned.
  *
@@ -65,13 +66,23 @@ extern "C" {
 #define QS_MAX_BATCH 256    /* per-sequence lengths travel by value in the kernel arguments      */
 #define QS_MAX_NQ 16        /* largest number of query tokens per sequence in one verify call    */
 
+/* qs_cache.flags.  Not part of the method: they select between equivalent ways of dealing the work of
+ * Appendix E's chunked decode out to the chip.
+ *   QS_FLAG_FIXED_RANGES  every wave of the attention kernels gets a fixed range of 128-token groups, so
+ *                         results are bit-reproducible from call to call.  Without it (default), where it
+ *                         pays, the waves of a compute unit draw their groups from a shared queue at run
+ *                         time: about 2 % faster at 128k context, but which partial sum a group lands in -
+ *                         and with it the last bit of an fp16 output - can differ between calls.        */
+#define QS_FLAG_FIXED_RANGES 1u
+
 typedef enum qs_status {
   QS_OK = 0,
   QS_ERR_NULL = -1,         /* a required pointer is NULL                                         */
   QS_ERR_SHAPE = -2,        /* batch / head counts / capacities are inconsistent                  */
   QS_ERR_UNSUPPORTED = -3,  /* head_dim or group != 128, batch > QS_MAX_BATCH, nq > QS_MAX_NQ      */
   QS_ERR_ALIGN = -4,        /* a device pointer is not 16-byte aligned                            */
-  QS_ERR_RANGE = -5,        /* a length exceeds its capacity, is not a multiple of 128, n_buf < nq */
+  QS_ERR_RANGE = -5,        /* a length exceeds its capacity, is not a multiple of 128, n_buf < nq;
+                               compute_units or flags out of range                                  */
   QS_ERR_WORKSPACE = -6,    /* workspace missing or smaller than qs_workspace_bytes()              */
   QS_ERR_HIP = -7           /* a HIP runtime call failed (no device, launch failure)               */
 } qs_status;
@@ -89,6 +100,9 @@ typedef struct qs_cache {
                                              Entries must lie in [0, pool_groups) and be distinct where the
                                              groups are live; the library cannot check device memory        */
   int32_t pool_groups;                    /* groups held by upper / lower when group_table is given        */
+  int32_t compute_units;                  /* compute units the attention calls are planned for, e.g. when part
+                                             of the GPU is reserved for other work; 0 = all of the current device's */
+  uint32_t flags;                         /* QS_FLAG_*; 0 = defaults                                        */
 } qs_cache;
 
 /* Library version: major*10000 + minor*100 + patch. */
@@ -98,26 +112,10 @@ int qs_version(void);
 const char *qs_strerror(int code);
 
 /*
- * Process-wide settings of the attention planner (host only, thread-safe, take effect from the next
- * call on; after a change of QS_CFG_COMPUTE_UNITS qs_workspace_bytes() must be asked again).  Not part of the method: they
- * select between equivalent ways of dealing the work of Appendix E's chunked decode out to the chip.
- *   QS_CFG_DETERMINISTIC  value 0 (default): where it pays, the waves of a compute unit draw their
- *                         128-token groups from a shared queue at run time, so which partial sum a
- *                         group lands in - and with it the last bit of an fp16 output - can differ
- *                         from call to call.  value 1: every wave gets a fixed range; results are
- *                         bit-reproducible (about 1 % slower at 128k context).
- *   QS_CFG_COMPUTE_UNITS  number of compute units to plan for (> 0), or 0 for the device's own count
- *                         (default); e.g. when part of the GPU is reserved for other work.
- * Returns QS_OK, or QS_ERR_RANGE for an unknown key or a value out of range.
- */
-enum qs_config_key { QS_CFG_DETERMINISTIC = 1, QS_CFG_COMPUTE_UNITS = 2 };
-int qs_configure(int32_t key, int32_t value);
-
-/*
  * Bytes of device scratch the attention calls need for their split-K partial results
- * (Appendix E: per-chunk partials that are merged afterwards).  Depends only on the shapes and
- * capacities in `c` and on nq (1 for draft), not on the current lengths, so it can be sized once.
- * Returns 0 if `c` is invalid.
+ * (Appendix E: per-chunk partials that are merged afterwards).  Depends only on the descriptor
+ * (shapes, capacities, compute_units, flags; with compute_units == 0 also on the current device) and
+ * on nq (1 for draft), not on the current lengths, so it can be sized once.  Returns 0 if `c` is invalid.
  */
 size_t qs_workspace_bytes(const qs_cache *c, int32_t nq);
 

@@ -27,7 +27,7 @@ QS_OK = 0
 QS_ERR_NULL, QS_ERR_SHAPE, QS_ERR_UNSUPPORTED, QS_ERR_ALIGN = -1, -2, -3, -4
 QS_ERR_RANGE, QS_ERR_WORKSPACE, QS_ERR_HIP = -5, -6, -7
 
-EXPORTS = ("qs_version", "qs_strerror", "qs_configure", "qs_workspace_bytes", "qs_quantize_flush", "qs_quantize_prefill",
+EXPORTS = ("qs_version", "qs_strerror", "qs_workspace_bytes", "qs_quantize_flush", "qs_quantize_prefill",
            "qs_append", "qs_attn_draft", "qs_attn_verify", "qs_export_codes")
 
 
@@ -40,6 +40,7 @@ class qs_cache(ctypes.Structure):
         ("k_buf", ctypes.c_void_p), ("v_buf", ctypes.c_void_p),
         ("n_quant", ctypes.POINTER(ctypes.c_int32)), ("n_buf", ctypes.POINTER(ctypes.c_int32)),
         ("group_table", ctypes.c_void_p), ("pool_groups", ctypes.c_int32),
+        ("compute_units", ctypes.c_int32), ("flags", ctypes.c_uint32),
     ]
 
 
@@ -64,7 +65,6 @@ def lib() -> ctypes.CDLL:
         vp, i32, i64, f32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_size_t
         l.qs_version.restype, l.qs_version.argtypes = ctypes.c_int, []
         l.qs_strerror.restype, l.qs_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
-        l.qs_configure.restype, l.qs_configure.argtypes = ctypes.c_int, [i32, i32]
         l.qs_workspace_bytes.restype, l.qs_workspace_bytes.argtypes = sz, [P, i32]
         l.qs_quantize_flush.restype, l.qs_quantize_flush.argtypes = ctypes.c_int, [P, i32, vp]
         l.qs_quantize_prefill.restype, l.qs_quantize_prefill.argtypes = ctypes.c_int, [P, vp, vp, i64, i32, vp]
@@ -87,11 +87,7 @@ def qs_strerror(code: int) -> str:
     return lib().qs_strerror(code).decode()
 
 
-QS_CFG_DETERMINISTIC, QS_CFG_COMPUTE_UNITS = 1, 2
-
-
-def qs_configure(key: int, value: int) -> None:
-    _check(lib().qs_configure(key, value), "qs_configure")
+QS_FLAG_FIXED_RANGES = 1
 
 
 def _ptr(t) -> int | None:
@@ -109,6 +105,10 @@ class KVCache:
 
     Pure storage: allocation through torch, layout as documented in include/quantspec.h.
     """
+
+    # what a new cache's planner settings (qs_cache.compute_units, qs_cache.flags) start as
+    default_compute_units = 0
+    default_flags = 0
 
     def __init__(self, batch: int, n_q_heads: int, n_kv_heads: int, q_cap: int, buf_cap: int,
                  device="cuda", head_dim: int = HEAD_DIM, group: int = GROUP, pool_groups: int | None = None):
@@ -132,6 +132,7 @@ class KVCache:
         self.v_buf = torch.zeros((batch, n_kv_heads, buf_cap, 128), **f16)
         self.n_quant = np.zeros(batch, np.int32)
         self.n_buf = np.zeros(batch, np.int32)
+        self.compute_units, self.flags = KVCache.default_compute_units, KVCache.default_flags
 
     def struct(self) -> qs_cache:
         c = qs_cache()
@@ -144,6 +145,7 @@ class KVCache:
         c.n_buf = self.n_buf.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
         if self.group_table is not None:
             c.group_table, c.pool_groups = self.group_table.data_ptr(), self.pool_groups
+        c.compute_units, c.flags = self.compute_units, self.flags
         return c
 
     def plane_bytes(self) -> int:

@@ -8,7 +8,7 @@
 namespace qs {
 namespace {
 
-constexpr int kVersion = 100;   // 0.1.0
+constexpr int kVersion = 200;   // 0.2.0
 constexpr int kDefaultCUs = 256;
 // resident chunk waves per compute unit the split planner aims for: the single-row-tile kernels run two
 // waves per SIMD, the multi-row-tile kernels (more than 8 query rows per kv-head) one
@@ -16,22 +16,20 @@ constexpr int kWavesPerCU = kCuWaves;
 constexpr int kWavesPerCUMultiTile = 4;
 constexpr int kMinBufSplits = 8;   // a decode-time buffer (2G + gamma + 1 tokens) always gets its 64-token chunks
 
-std::atomic<int> g_cu_count{0};        // the device's compute units, read once
-std::atomic<int> g_cu_override{0};     // QS_CFG_COMPUTE_UNITS
-std::atomic<int> g_deterministic{0};   // QS_CFG_DETERMINISTIC
+constexpr int kMaxDevices = 64;
+std::atomic<int> g_cu_count[kMaxDevices];   // compute units of each device, read once (0: not read yet)
 
-int cu_count() {
-  int n = g_cu_override.load(std::memory_order_relaxed);
-  if (n > 0) return n;
-  n = g_cu_count.load(std::memory_order_relaxed);
-  if (n > 0) return n;
+// Compute units to plan for: the caller's figure, else those of the current device.
+int cu_count(const qs_cache* c) {
+  if (c->compute_units > 0) return c->compute_units;
   int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return kDefaultCUs;
+  int n = g_cu_count[dev].load(std::memory_order_relaxed);
+  if (n > 0) return n;
   hipDeviceProp_t prop;
   n = kDefaultCUs;
-  if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
-      prop.multiProcessorCount > 0)
-    n = prop.multiProcessorCount;
-  g_cu_count.store(n, std::memory_order_relaxed);
+  if (hipGetDeviceProperties(&prop, dev) == hipSuccess && prop.multiProcessorCount > 0) n = prop.multiProcessorCount;
+  g_cu_count[dev].store(n, std::memory_order_relaxed);
   return n;
 }
 
@@ -43,6 +41,8 @@ int validate_shape(const qs_cache* c) {
     return QS_ERR_SHAPE;
   if (c->q_cap < 0 || c->q_cap % kG != 0 || c->buf_cap <= 0) return QS_ERR_SHAPE;
   if (c->group_table != nullptr && c->pool_groups <= 0) return QS_ERR_SHAPE;
+  if (c->compute_units < 0 || c->compute_units > 65536 || (c->flags & ~(uint32_t)QS_FLAG_FIXED_RANGES) != 0)
+    return QS_ERR_RANGE;
   if (c->head_dim != kD || c->group != kG || c->batch > QS_MAX_BATCH) return QS_ERR_UNSUPPORTED;
   return QS_OK;
 }
@@ -67,7 +67,7 @@ int validate_cache(const qs_cache* c) {
 // Number of chunks per unit.  The quantized region is cut so that about kWavesPerCU waves per
 // compute unit are resident; the buffer is cut into 64-token chunks, or, when it is so long that
 // these would exceed that budget too, into as many equal chunks as the budget allows.  Depends on
-// shapes and on the given maximum lengths only.
+// the descriptor (shapes, compute units, flags) and on the given maximum lengths only.
 struct Plan {
   int n_split_q, n_split_b;
   int cu_wgs;   // > 0: workgroups of eight waves per unit, groups drawn dynamically (n_split_q = 8 * cu_wgs)
@@ -80,7 +80,7 @@ Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf) {
   const int n_rows = nq * (c->n_q_heads / c->n_kv_heads);
   const int wpc = n_rows <= 8 ? kWavesPerCU : kWavesPerCUMultiTile;
   // never more long chunks than resident slots: a chunk that starts late doubles the launch time
-  const int want = std::max(1, cu_count() * wpc / units);
+  const int want = std::max(1, cu_count(c) * wpc / units);
   Plan p;
   p.n_split_q = std::max(1, std::min(want, groups));
   // the buffer: 64-token chunks while they fit the same budget of resident waves, longer ones beyond
@@ -92,7 +92,7 @@ Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf) {
   p.cu_wgs = 0;
   p.ws_splits = p.n_split_q + p.n_split_b;
   const int wgs = want / kWavesPerCU;
-  if (g_deterministic.load(std::memory_order_relaxed) == 0 && n_rows <= 8 && wgs >= 1 &&
+  if ((c->flags & QS_FLAG_FIXED_RANGES) == 0 && n_rows <= 8 && wgs >= 1 &&
       groups >= kCuWaves * wgs && p.n_split_b <= kCuBufItems * wgs) {
     p.cu_wgs = wgs;
     p.n_split_q = kCuWaves * wgs;
@@ -194,25 +194,10 @@ const char* qs_strerror(int code) {
     case QS_ERR_SHAPE: return "inconsistent batch / head counts / capacities";
     case QS_ERR_UNSUPPORTED: return "unsupported configuration (head_dim and group must be 128, batch <= 256, nq <= 16)";
     case QS_ERR_ALIGN: return "a device pointer is not 16-byte aligned";
-    case QS_ERR_RANGE: return "a length is out of range for its capacity or not a multiple of the group size";
+    case QS_ERR_RANGE: return "a length, count or flag is out of range (lengths: within capacity, multiples of the group size)";
     case QS_ERR_WORKSPACE: return "workspace is missing or smaller than qs_workspace_bytes()";
     case QS_ERR_HIP: return "a HIP runtime call failed";
     default: return "unknown status code";
-  }
-}
-
-int qs_configure(int32_t key, int32_t value) {
-  switch (key) {
-    case QS_CFG_DETERMINISTIC:
-      if (value != 0 && value != 1) return QS_ERR_RANGE;
-      g_deterministic.store(value, std::memory_order_relaxed);
-      return QS_OK;
-    case QS_CFG_COMPUTE_UNITS:
-      if (value < 0 || value > 65536) return QS_ERR_RANGE;
-      g_cu_override.store(value, std::memory_order_relaxed);
-      return QS_OK;
-    default:
-      return QS_ERR_RANGE;
   }
 }
 

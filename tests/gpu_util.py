@@ -44,6 +44,7 @@ def _seq_view(cache, b):
     for name in B.PLANES + ("k_buf", "v_buf"):
         setattr(sub, name, getattr(cache, name)[b:b + 1])
     sub.pool_groups, sub.group_table = cache.pool_groups, None
+    sub.compute_units, sub.flags = cache.compute_units, cache.flags
     if cache.group_table is not None:      # paged: the pools are shared, the view selects the table rows
         sub.upper, sub.lower = cache.upper, cache.lower
         sub.group_table = cache.group_table[b:b + 1]

@@ -35,23 +35,21 @@ def test_header_symbols_are_exported(B):
     assert "unknown" in B.qs_strerror(-99)
 
 
-def test_configure_validates_keys_and_values(B):
-    lib = B.lib()
-    assert lib.qs_configure(99, 0) == B.QS_ERR_RANGE
-    assert lib.qs_configure(B.QS_CFG_DETERMINISTIC, 2) == B.QS_ERR_RANGE
-    assert lib.qs_configure(B.QS_CFG_COMPUTE_UNITS, -1) == B.QS_ERR_RANGE
-    try:
-        c = _fake_cache(B)
-        w_default = B.qs_workspace_bytes(c, 1)
-        assert lib.qs_configure(B.QS_CFG_COMPUTE_UNITS, 1) == B.QS_OK
-        w_small = B.qs_workspace_bytes(c, 1)
-        assert 0 < w_small < w_default                      # fewer compute units: fewer chunks per unit
-        assert lib.qs_configure(B.QS_CFG_DETERMINISTIC, 1) == B.QS_OK
-        assert B.qs_workspace_bytes(c, 1) == w_small        # the workspace covers either way of dealing out
-    finally:
-        assert lib.qs_configure(B.QS_CFG_COMPUTE_UNITS, 0) == B.QS_OK
-        assert lib.qs_configure(B.QS_CFG_DETERMINISTIC, 0) == B.QS_OK
+def test_planner_settings_travel_in_the_descriptor(B):
+    """compute_units and flags are validated like any other field, and the workspace size follows from the
+    descriptor alone (the library keeps no settings of its own)."""
+    w_default = B.qs_workspace_bytes(_fake_cache(B), 1)
+    w_small = B.qs_workspace_bytes(_fake_cache(B, compute_units=1), 1)
+    assert 0 < w_small < w_default                          # fewer compute units: fewer chunks per unit
+    # the workspace covers either way of dealing the groups out
+    assert B.qs_workspace_bytes(_fake_cache(B, compute_units=1, flags=B.QS_FLAG_FIXED_RANGES), 1) == w_small
     assert B.qs_workspace_bytes(_fake_cache(B), 1) == w_default
+    assert B.qs_workspace_bytes(_fake_cache(B, compute_units=-1), 1) == 0
+    assert B.qs_workspace_bytes(_fake_cache(B, flags=2), 1) == 0
+    lib = B.lib()
+    for bad in (dict(compute_units=-1), dict(compute_units=1 << 20), dict(flags=0x10)):
+        c = _fake_cache(B, **bad)
+        assert lib.qs_quantize_flush(ctypes.byref(c), 128, None) == B.QS_ERR_RANGE
 
 
 def _fake_cache(B, **over):

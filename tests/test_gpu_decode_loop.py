@@ -140,11 +140,11 @@ def test_hip_graph_replay_matches_eager(env):
     """Draft, verify and flush captured in one HIP graph; replayed three times with eager work and
     synchronizations in between; every replay must reproduce the eager results exactly."""
     torch, B, U = env["torch"], env["B"], env["U"]
-    B.qs_configure(B.QS_CFG_DETERMINISTIC, 1)   # exact comparison below: fixed ranges whatever the planner would pick
+    B.KVCache.default_flags = B.QS_FLAG_FIXED_RANGES   # exact comparison below: fixed ranges whatever the planner would pick
     try:
         _graph_replay_case(torch, B, U)
     finally:
-        B.qs_configure(B.QS_CFG_DETERMINISTIC, 0)
+        B.KVCache.default_flags = 0
 
 
 def _graph_replay_case(torch, B, U):

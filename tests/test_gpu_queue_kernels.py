@@ -1,7 +1,7 @@
 """GPU parity of the attention kernels that deal 128-token groups out through a queue shared by the
 eight waves of a workgroup.  The planner takes them when a unit has at least eight groups per
-workgroup, i.e. at long contexts; here the library is told to plan for a handful of compute units
-(qs_configure), so that caches of a few thousand tokens run through exactly that code: with C compute
+workgroup, i.e. at long contexts; here the caches tell the library to plan for a handful of compute units
+(qs_cache.compute_units), so that caches of a few thousand tokens run through exactly that code: with C compute
 units and U units the planner wants 8*C/U waves per unit, C/U workgroups of eight, and needs
 8*C/U groups or more and at most 4*C/U buffer chunks of 64 tokens."""
 import numpy as np
@@ -17,11 +17,11 @@ def few_compute_units(env):
     B = env["B"]
 
     def plan_for(n):
-        B.qs_configure(B.QS_CFG_COMPUTE_UNITS, n)
+        B.KVCache.default_compute_units = n      # every cache made from here on carries it
 
     yield plan_for
-    B.qs_configure(B.QS_CFG_COMPUTE_UNITS, 0)
-    B.qs_configure(B.QS_CFG_DETERMINISTIC, 0)
+    B.KVCache.default_compute_units = 0
+    B.KVCache.default_flags = 0
 
 
 @pytest.mark.parametrize("bsz,hkv,rep,nq,cus", [
@@ -83,7 +83,7 @@ def test_queue_kernels_paged_and_flush(env, few_compute_units):
 
 
 def test_deterministic_setting_is_bit_reproducible(env, few_compute_units):
-    """With QS_CFG_DETERMINISTIC every wave gets a fixed range of groups: identical sequences of a batch
+    """With QS_FLAG_FIXED_RANGES every wave gets a fixed range of groups: identical sequences of a batch
     give identical bits, and so do repeated calls.  Without it two results agree to a step or two of the fp16 output."""
     U, B = env["U"], env["B"]
     rng = np.random.default_rng(9)
@@ -96,7 +96,7 @@ def test_deterministic_setting_is_bit_reproducible(env, few_compute_units):
     qn = np.repeat(q1, reps, 0)
     free, _ = _run_attn(env, cache, qn, 0.09, True)
     assert U.rel_err(free, np.repeat(free[:1], reps, 0).astype(np.float64)) <= 2e-3
-    B.qs_configure(B.QS_CFG_DETERMINISTIC, 1)
+    cache.flags = B.QS_FLAG_FIXED_RANGES
     fixed, _ = _run_attn(env, cache, qn, 0.09, True)
     again, _ = _run_attn(env, cache, qn, 0.09, True)
     assert np.array_equal(fixed.view(np.uint16), again.view(np.uint16))
@@ -149,7 +149,7 @@ def test_random_shapes_under_other_planner_settings(env, few_compute_units, cus)
     rng = np.random.default_rng(500 + cus)
     few_compute_units(cus)
     for det in (0, 1):
-        B.qs_configure(B.QS_CFG_DETERMINISTIC, det)
+        B.KVCache.default_flags = B.QS_FLAG_FIXED_RANGES if det else 0
         for case in range(2):
             bsz, hkv = int(rng.integers(1, 4)), int(rng.choice([1, 2, 3, 8]))
             rep, nq = int(rng.choice([1, 2, 4, 8])), int(rng.integers(1, 9))
