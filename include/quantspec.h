@@ -65,6 +65,7 @@ extern "C" {
 
 #define QS_MAX_BATCH 256    /* per-sequence lengths travel by value in the kernel arguments      */
 #define QS_MAX_NQ 16        /* largest number of query tokens per sequence in one verify call    */
+#define QS_STATIC_WS_BYTES (32u << 20)   /* device scratch built into the library, see qs_attn_static  */
 
 /* qs_cache.flags.  Not part of the method: they select between equivalent ways of dealing the work of
  * Appendix E's chunked decode out to the chip.
@@ -171,6 +172,22 @@ int qs_attn_draft(const qs_cache *c, const void *q, void *out, float sm_scale,
  */
 int qs_attn_verify(const qs_cache *c, const void *q, int32_t nq, void *out, float sm_scale,
                    void *workspace, size_t workspace_bytes, float *lse, void *stream);
+
+/*
+ * The two attention calls above for callers that can neither allocate device memory nor be handed a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * verify == 0: exactly qs_attn_draft (nq must be 1); verify == 1: exactly qs_attn_verify.  The split-K
+ * partials go to an array of QS_STATIC_WS_BYTES that is part of the library's code object; every GPU the
+ * library runs on holds its own copy from the first call on it until the process ends.  The call
+ * allocates nothing and frees nothing.  Its first call on a device looks the array's address up
+ * (hipGetSymbolAddress) and should therefore happen outside a stream capture.
+ *   - QS_ERR_WORKSPACE if qs_workspace_bytes(c, nq) exceeds QS_STATIC_WS_BYTES (nothing is enqueued).
+ *   - Every call on one GPU uses that GPU's one array: calls that overlap in time on the same GPU (two
+ *     streams, two threads) race on it and corrupt each other's results; calls on one stream are ordered.
+ *   - Nothing in the array has to start at zero: each call writes every partial before it reads it.
+ */
+int qs_attn_static(const qs_cache *c, const void *q, int32_t nq, int32_t verify, void *out,
+                   float sm_scale, float *lse, void *stream);
 
 /*
  * Inspection helper: expand the packed planes and metadata of tokens [0, n_tokens) of one unit

@@ -27,7 +27,7 @@ QS_OK = 0
 QS_ERR_NULL, QS_ERR_SHAPE, QS_ERR_UNSUPPORTED, QS_ERR_ALIGN = -1, -2, -3, -4
 QS_ERR_RANGE, QS_ERR_WORKSPACE, QS_ERR_HIP = -5, -6, -7
 
-EXPORTS = ("qs_version", "qs_strerror", "qs_workspace_bytes", "qs_quantize_flush", "qs_quantize_prefill",
+EXPORTS = ("qs_version", "qs_strerror", "qs_workspace_bytes", "qs_attn_static", "qs_quantize_flush", "qs_quantize_prefill",
            "qs_append", "qs_attn_draft", "qs_attn_verify", "qs_export_codes")
 
 
@@ -73,6 +73,8 @@ def lib() -> ctypes.CDLL:
         l.qs_attn_draft.argtypes = [P, vp, vp, f32, vp, sz, vp, vp]
         l.qs_attn_verify.restype = ctypes.c_int
         l.qs_attn_verify.argtypes = [P, vp, i32, vp, f32, vp, sz, vp, vp]
+        l.qs_attn_static.restype = ctypes.c_int
+        l.qs_attn_static.argtypes = [P, vp, i32, i32, vp, f32, vp, vp]
         l.qs_export_codes.restype = ctypes.c_int
         l.qs_export_codes.argtypes = [P, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         _lib = l
@@ -88,6 +90,7 @@ def qs_strerror(code: int) -> str:
 
 
 QS_FLAG_FIXED_RANGES = 1
+QS_STATIC_WS_BYTES = 32 << 20
 
 
 def _ptr(t) -> int | None:
@@ -219,6 +222,19 @@ def qs_attn_draft(cache, q, sm_scale: float, out=None, workspace=None, lse=None,
 def qs_attn_verify(cache, q, sm_scale: float, out=None, workspace=None, lse=None, stream=None):
     """q: fp16 device tensor [B, nq, Hq, 128], nq = gamma + 1.  Returns out (same shape)."""
     return _attn("qs_attn_verify", cache, q, q.shape[1], out, sm_scale, workspace, lse, stream)
+
+
+def qs_attn_static(cache, q, sm_scale: float, verify: bool, out=None, lse=None, stream=None):
+    """qs_attn_draft (verify=False, one query) or qs_attn_verify (verify=True) with the split-K partials in
+    the library's built-in scratch array: no workspace argument, nothing allocated by the call itself
+    (pass `out`; without it the binding allocates the result tensor, the library does not)."""
+    c = _as_struct(cache)
+    assert q.dtype == torch.float16 and q.is_contiguous()
+    if out is None:
+        out = torch.empty_like(q)
+    _check(lib().qs_attn_static(ctypes.byref(c), q.data_ptr(), q.shape[1], int(bool(verify)), out.data_ptr(), sm_scale,
+                                _ptr(lse), _stream(stream)), "qs_attn_static")
+    return out
 
 
 def qs_export_codes(cache: KVCache, b: int, kv_head: int, n_tokens: int, stream=None):

@@ -33,6 +33,25 @@ int cu_count(const qs_cache* c) {
   return n;
 }
 
+// Split-K partials of qs_attn_static: one array per device, part of the library's code object, so a
+// caller that must not allocate needs no workspace of its own.  In host code the array's name only
+// stands for the symbol; its address on a device comes from hipGetSymbolAddress() with that device
+// current, once, and that pointer is what the kernels get.
+static __device__ __align__(256) unsigned char scratch[QS_STATIC_WS_BYTES];
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+int static_scratch(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return QS_ERR_HIP;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (ptr == nullptr) {
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return QS_ERR_HIP;
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // two threads racing here store the same address
+  }
+  *out = ptr;
+  return QS_OK;
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int validate_shape(const qs_cache* c) {
@@ -100,8 +119,9 @@ Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf) {
   return p;
 }
 
+// dry_run: validate everything but the workspace and launch nothing.
 int attn_common(const qs_cache* c, const void* q, int32_t nq, void* out, float sm_scale, void* workspace,
-                size_t workspace_bytes, float* lse, void* stream, bool verify) {
+                size_t workspace_bytes, float* lse, void* stream, bool verify, bool dry_run = false) {
   int rc = validate_cache(c);
   if (rc != QS_OK) return rc;
   if (q == nullptr || out == nullptr) return QS_ERR_NULL;
@@ -114,6 +134,7 @@ int attn_common(const qs_cache* c, const void* q, int32_t nq, void* out, float s
     max_quant = std::max(max_quant, c->n_quant[b]);
     max_buf = std::max(max_buf, c->n_buf[b]);
   }
+  if (dry_run) return QS_OK;
   if (workspace == nullptr || workspace_bytes < qs_workspace_bytes(c, nq)) return QS_ERR_WORKSPACE;
 
   const Plan p = make_plan(c, nq, max_quant, max_buf);
@@ -195,7 +216,7 @@ const char* qs_strerror(int code) {
     case QS_ERR_UNSUPPORTED: return "unsupported configuration (head_dim and group must be 128, batch <= 256, nq <= 16)";
     case QS_ERR_ALIGN: return "a device pointer is not 16-byte aligned";
     case QS_ERR_RANGE: return "a length, count or flag is out of range (lengths: within capacity, multiples of the group size)";
-    case QS_ERR_WORKSPACE: return "workspace is missing or smaller than qs_workspace_bytes()";
+    case QS_ERR_WORKSPACE: return "workspace is missing or smaller than qs_workspace_bytes(), or (qs_attn_static) that size exceeds QS_STATIC_WS_BYTES";
     case QS_ERR_HIP: return "a HIP runtime call failed";
     default: return "unknown status code";
   }
@@ -279,6 +300,21 @@ int qs_attn_draft(const qs_cache* c, const void* q, void* out, float sm_scale, v
 int qs_attn_verify(const qs_cache* c, const void* q, int32_t nq, void* out, float sm_scale, void* workspace,
                    size_t workspace_bytes, float* lse, void* stream) {
   return attn_common(c, q, nq, out, sm_scale, workspace, workspace_bytes, lse, stream, true);
+}
+
+int qs_attn_static(const qs_cache* c, const void* q, int32_t nq, int32_t verify, void* out, float sm_scale, float* lse,
+                   void* stream) {
+  if (verify != 0 && verify != 1) return QS_ERR_RANGE;
+  if (!verify && nq != 1) return QS_ERR_UNSUPPORTED;
+  const size_t need = qs_workspace_bytes(c, nq);   // 0 for a descriptor that attn_common rejects anyway
+  if (need > QS_STATIC_WS_BYTES) return QS_ERR_WORKSPACE;
+  // everything else is checked before the first HIP call: a dry run against a stand-in address
+  int rc = attn_common(c, q, nq, out, sm_scale, nullptr, 0, lse, stream, verify != 0, /*dry_run=*/true);
+  if (rc != QS_OK) return rc;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != QS_OK) return rc;
+  return attn_common(c, q, nq, out, sm_scale, ws, QS_STATIC_WS_BYTES, lse, stream, verify != 0);
 }
 
 int qs_export_codes(const qs_cache* c, int32_t b, int32_t kv_head, int32_t n_tokens, void* k_u, void* k_l,

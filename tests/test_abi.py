@@ -52,6 +52,22 @@ def test_planner_settings_travel_in_the_descriptor(B):
         assert lib.qs_quantize_flush(ctypes.byref(c), 128, None) == B.QS_ERR_RANGE
 
 
+def test_static_scratch_entry_validates_before_touching_the_gpu(B):
+    lib = B.lib()
+    c = _fake_cache(B)
+    q, out = 0x50000, 0x60000
+    assert lib.qs_attn_static(ctypes.byref(c), q, 1, 2, out, 0.1, None, None) == B.QS_ERR_RANGE        # verify flag
+    assert lib.qs_attn_static(ctypes.byref(c), q, 2, 0, out, 0.1, None, None) == B.QS_ERR_UNSUPPORTED  # draft: one query
+    assert lib.qs_attn_static(ctypes.byref(c), None, 1, 0, out, 0.1, None, None) == B.QS_ERR_NULL
+    assert lib.qs_attn_static(ctypes.byref(c), q, 17, 1, out, 0.1, None, None) == B.QS_ERR_UNSUPPORTED
+    big = _fake_cache(B, batch=256, n_q_heads=64, n_kv_heads=8)
+    nq, nb = np.full(256, 512, np.int32), np.full(256, 256, np.int32)
+    big.n_quant = nq.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    big.n_buf = nb.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    assert B.qs_workspace_bytes(big, 16) > B.QS_STATIC_WS_BYTES
+    assert lib.qs_attn_static(ctypes.byref(big), q, 16, 1, out, 0.1, None, None) == B.QS_ERR_WORKSPACE
+
+
 def _fake_cache(B, **over):
     """A descriptor with plausible, never-dereferenced device addresses (validation only)."""
     c = B.qs_cache()
