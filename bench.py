@@ -1,12 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the QuantSpec decode-attention hot path on one MI355X.
 
-One "step" is one speculation cycle of Algorithm 1 over one layer's cache, every stage of the hot
-path included: gamma = 4 draft attention calls (1 query, upper plane + buffer), one verify call
-(gamma + 1 = 5 causal queries, both planes + buffer) and one quantize-on-flush of G = 128 buffered
-tokens (quantize, append, buffer move).  Inputs are resident in HBM before the timed region.  The
-cycle rotates over several independent cache copies so the 256 MB last-level cache cannot serve the
-planes.  Prints ONE JSON line.
+One "step" is one speculation cycle of Algorithm 1, every stage of the hot path included: gamma = 4
+draft attention calls (1 query, upper plane + buffer), one verify call (gamma + 1 = 5 causal queries,
+both planes + buffer) and one quantize-on-flush of buffered tokens (quantize, append, buffer move),
+each issued once per layer (one layer, except for the 32-layer stack workload).  Inputs are resident
+in HBM before the timed region.  Single-layer workloads rotate over several independent cache copies
+so the 256 MB last-level cache cannot serve the planes; the stack's 32 layer caches are distinct
+allocations anyway.
+
+The headline keys of the JSON line are those of the 128k-context multi-head workload (`mha128k`); the
+`workloads` object carries the same figures for every workload of the baseline description, the stack
+as a whole-stack step.  Every workload is timed three ways: eager calls through the C ABI (the headline),
+the same cycle captured in a HIP graph and replayed, and eager with bit-reproducible dealing
+(QS_FLAG_FIXED_RANGES).  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -25,20 +32,25 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0
 GAMMA = 4
 SPEC_GAMMAS = (1, 2, 4, 6)      # speculation lengths of the simulated decode loop (Table 6)
+ALL_WORKLOADS = ("mha128k", "tiny", "mha32k", "gqa128k_b4", "stack64k_b8")
+# tokens flushed per cycle: the baseline description names 256 for the tiny and the stack workload;
+# the others take the paper's cadence (G = 128 tokens once 2G are buffered, Section 4.3.2)
+FLUSH_TOKENS = {"tiny": 256, "stack64k_b8": 256}
+PRECONDITION_S = 1.0            # untimed run of the cycle before the warm-up steps (see precondition())
 
-# HBM traffic per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (calibrated against a plain copy kernel).  Filled from the summaries under profiles/; None = not measured.
+# HBM traffic per launch of the attention kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (calibrated against a plain copy kernel: FETCH_SIZE x 1.99991, WRITE_SIZE x 1.0, KiB per dispatch).
+# Filled from profiles/attn_hbm_traffic.md; a workload without an entry reports null.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/attn_mha128k_hbm_traffic.md: (FETCH_SIZE x 1.99991 + WRITE_SIZE x 1.0) KiB per dispatch
     ("mha128k", "draft"): int((288598.1 * 1.99991 + 1105.1) * 1024),
     ("mha128k", "verify"): int((550709.6 * 1.99991 + 5528.3) * 1024),
 }
 
 
 def algorithmic_bytes(w, nq, verify):
-    """Bytes one attention call must move (fp16 metadata): per quantized token and unit 64 (K upper)
-    + 64 (V upper) + 4 (K scale/zero, amortised over the group) + 4 (V scale/zero); twice the plane
-    bytes for verify; plus the fp16 buffer and q / out."""
+    """Bytes one attention call on one layer must move (fp16 metadata): per quantized token and unit
+    64 (K upper) + 64 (V upper) + 4 (K scale/zero, amortised over the group) + 4 (V scale/zero); twice
+    the plane bytes for verify; plus the fp16 buffer and q / out."""
     per_tok = (128 + 128 + 8) if verify else (64 + 64 + 8)
     return w.units * (w.n_quant * per_tok + w.n_buf * 128 * 2 * 2) + w.batch * w.n_q_heads * nq * 128 * 2 * 2
 
@@ -47,18 +59,231 @@ def flush_bytes(w, n):
     return w.units * n * (128 * 2 * 2 + (128 + 128 + 4 + 4))
 
 
+class Bench:
+    """One workload resident on the GPU: `groups` is the list of cache groups a cycle may run on - one
+    cache per group for a single-layer workload (the cycle rotates over the groups), all 32 layer caches
+    in one group for the stack."""
+
+    def __init__(self, torch, B, synth, w, copies, keep_fp16=False):
+        self.torch, self.B, self.w = torch, B, w
+        self.sm_scale = 1.0 / float(np.sqrt(w.head_dim))
+        self.n_flush = FLUSH_TOKENS.get(w.name, 128)
+        dev = "cuda"
+        t0 = time.time()
+        self.k_host, self.v_host = synth.gen_layer_kv(w, workers=min(16, os.cpu_count() or 8))
+        self.q_draft = torch.from_numpy(synth.gen_layer_q(w, 1)).to(dev)
+        self.q_verify = torch.from_numpy(synth.gen_layer_q(w, w.nq_verify)).to(dev)
+        kd, vd = torch.from_numpy(self.k_host).to(dev), torch.from_numpy(self.v_host).to(dev)
+        n_caches = w.n_layers if w.n_layers > 1 else copies
+        q_cap = w.n_quant + 640            # room for the groups flushed during the run
+        caches = []
+        self.prefill = None
+        for i in range(n_caches):
+            c = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, q_cap, w.n_buf + 8)
+            if i == 0:
+                B.qs_quantize_prefill(c, kd, vd, w.n_quant)
+                if keep_fp16:
+                    self.prefill = time_prefill(torch, B, c, kd, vd, w)
+            else:      # further copies / layers: the same codes in memory of their own
+                for name in B.PLANES:
+                    getattr(c, name).copy_(getattr(caches[0], name))
+            c.k_buf[:, :, :w.n_buf] = kd[:, :, w.n_quant:]
+            c.v_buf[:, :, :w.n_buf] = vd[:, :, w.n_quant:]
+            c.n_quant[:] = w.n_quant
+            c.n_buf[:] = w.n_buf
+            caches.append(c)
+        self.caches = caches
+        self.groups = [caches] if w.n_layers > 1 else [[c] for c in caches]
+        self.fp16 = (kd, vd) if keep_fp16 else None
+        del kd, vd
+        self.ws = torch.empty(max(B.qs_workspace_bytes(caches[0], n) for n in (1, w.nq_verify, max(SPEC_GAMMAS) + 1)),
+                              dtype=torch.uint8, device=dev)
+        self.out_d = torch.empty_like(self.q_draft)
+        self.out_v = torch.empty_like(self.q_verify)
+        self.set_flags(0)
+        torch.cuda.synchronize()
+        self.setup_s = time.time() - t0
+
+    def set_flags(self, flags):
+        for c in self.caches:
+            c.flags = flags
+        # descriptors are built once per setting: the host lengths do not move during the timed cycles
+        self.structs = [[c.struct() for c in g] for g in self.groups]
+
+    def cycle(self, i, events=None):
+        """One speculation cycle on cache group i: per layer gamma draft calls, then per layer the verify
+        call, then per layer the flush (host lengths stay put: the same group slots are rewritten each
+        cycle).  events: four HIP events to record around the three phases."""
+        B, s = self.B, self.structs[i % len(self.structs)]
+        if events:
+            events[0].record()
+        for _ in range(GAMMA):
+            for c in s:
+                B.qs_attn_draft(c, self.q_draft, self.sm_scale, out=self.out_d, workspace=self.ws)
+        if events:
+            events[1].record()
+        for c in s:
+            B.qs_attn_verify(c, self.q_verify, self.sm_scale, out=self.out_v, workspace=self.ws)
+        if events:
+            events[2].record()
+        for c in s:
+            B.qs_quantize_flush(c, self.n_flush)
+        if events:
+            events[3].record()
+
+    def precondition(self, seconds):
+        """Runs the cycle untimed for `seconds`.  The chip's power management needs about half a second
+        of a steady load to settle: the first ~20 ms of a 128k-context loop run at boost clocks (the
+        20-row verify call: 176 us), the next few hundred ms below the steady state (up to 275 us), then
+        it stays put (184 us) at the 1400 W board limit.  Figures taken inside that transient depend on
+        what ran before; the steady state is what a decoder lives in."""
+        torch = self.torch
+        t0, i = time.perf_counter(), 0
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(4):
+                self.cycle(i)
+                i += 1
+            torch.cuda.synchronize()
+        return i
+
+    def run_eager(self, steps, warmup):
+        """`warmup` untimed cycles, then exactly `steps` timed ones.  Returns seconds per cycle (host clock
+        around the timed cycles, synchronized on both sides) and per-call microseconds of each phase
+        from HIP events on the launch stream."""
+        torch = self.torch
+        layers = len(self.groups[0])
+        for i in range(warmup):
+            self.cycle(i)
+        torch.cuda.synchronize()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+        gc.collect()
+        gc.disable()                      # no collector pause inside the timed region
+        t_start = time.perf_counter()
+        for i in range(steps):
+            self.cycle(warmup + i, ev[i])
+            if i >= 2:
+                # stay at most two cycles ahead of the GPU (a decoder reads each cycle's outcome anyway);
+                # letting the host queue hundreds of launches ahead has stalled the runtime for tens of ms
+                ev[i - 2][3].synchronize()
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t_start
+        gc.enable()
+        calls = {"draft": GAMMA * layers, "verify": layers, "flush": layers}
+        per_call = {k: np.array([1e3 * e[j].elapsed_time(e[j + 1]) / calls[k] for e in ev])
+                    for j, k in enumerate(("draft", "verify", "flush"))}
+        return elapsed / steps, per_call
+
+    def run_graph(self, steps, warmup):
+        """The same cycles captured once into a HIP graph (one cycle per cache group) and replayed: no
+        host work between the launches.  Returns seconds per cycle."""
+        torch = self.torch
+        n = len(self.groups)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):     # the library's first launches on the capture stream happen before capture
+            self.cycle(0)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(n):
+                self.cycle(i)
+        replays, warm = max(1, -(-steps // n)), max(1, -(-warmup // n))
+        for _ in range(warm):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(replays):
+            graph.replay()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / (replays * n)
+        del graph
+        return dt
+
+    def time_flush(self, n_tokens, reps=40):
+        """A flush of n_tokens on one layer, alone: microseconds per call (HIP events around `reps` calls)."""
+        torch, B = self.torch, self.B
+        s = [g[0] for g in self.structs]
+        for i in range(4):
+            B.qs_quantize_flush(s[i % len(s)], n_tokens)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            B.qs_quantize_flush(s[i % len(s)], n_tokens)
+        e1.record()
+        torch.cuda.synchronize()
+        return 1e3 * e0.elapsed_time(e1) / reps
+
+
+def pick_counts(cycle_s, timed_s=0.6, warm_s=0.2, lo=20, hi=4000):
+    """Timed and warm-up cycle counts for a workload whose cycle takes cycle_s seconds."""
+    steps = int(min(hi, max(lo, timed_s / cycle_s)))
+    return steps, int(min(hi, max(5, warm_s / cycle_s)))
+
+
+def measure(bench, steps=None, warmup=None, graph=True, fixed=True):
+    """All figures of one workload.  steps / warmup: given for the headline workload, chosen from the
+    cycle time otherwise."""
+    w, layers = bench.w, len(bench.groups[0])
+    n_pre = bench.precondition(PRECONDITION_S)
+    if steps is None:
+        est, _ = bench.run_eager(8, 2)
+        steps, warmup = pick_counts(est)
+    cyc_s, per_call = bench.run_eager(steps, warmup)
+    avg = {k: float(v.mean()) for k, v in per_call.items()}
+    bytes_d, bytes_v = algorithmic_bytes(w, 1, False), algorithmic_bytes(w, w.nq_verify, True)
+    cycle_bytes = layers * (GAMMA * bytes_d + bytes_v + flush_bytes(w, bench.n_flush))
+    gb = lambda nbytes, us: nbytes / (us * 1e-6) / 1e9
+    res = {
+        "workload": f"{w.name}: {w.n_layers} layer(s) x batch {w.batch}, {w.n_q_heads} q-heads / {w.n_kv_heads} kv-heads x 128, "
+                    f"ctx {w.ctx} = {w.n_quant} quantized + {w.n_buf} fp16 buffer, G=128, gamma=4",
+        "layers": layers, "steps": steps, "warmup": warmup, "precondition_cycles": n_pre,
+        "flush_tokens_per_cycle": bench.n_flush,
+        "us_per_decode_step": round(cyc_s * 1e6 / (GAMMA + 1), 3),
+        "ms_per_cycle": round(cyc_s * 1e3, 5),
+        "cycle_GBps": round(cycle_bytes / cyc_s / 1e9, 1),
+        "cycle_bytes": cycle_bytes,
+        "draft_us": round(avg["draft"], 2), "verify_us": round(avg["verify"], 2), "flush_us": round(avg["flush"], 2),
+        "median_us": {k: round(float(np.median(v)), 2) for k, v in per_call.items()},
+        "min_us": {k: round(float(v.min()), 2) for k, v in per_call.items()},
+        "draft_GBps": round(gb(bytes_d, avg["draft"]), 1), "verify_GBps": round(gb(bytes_v, avg["verify"]), 1),
+        "draft_frac": round(gb(bytes_d, avg["draft"]) / HBM_PEAK_GBPS, 4),
+        "verify_frac": round(gb(bytes_v, avg["verify"]) / HBM_PEAK_GBPS, 4),
+        "draft_bytes": bytes_d, "verify_bytes": bytes_v,
+        "flush128_us": round(bench.time_flush(128), 2), "flush256_us": round(bench.time_flush(256), 2),
+    }
+    if layers > 1:
+        res["whole_stack"] = {
+            "draft_pass_us": round(avg["draft"] * layers, 1), "verify_pass_us": round(avg["verify"] * layers, 1),
+            "flush_pass_us": round(avg["flush"] * layers, 1),
+            "us_per_decode_step": res["us_per_decode_step"], "GBps": res["cycle_GBps"],
+            "bytes_per_cycle": cycle_bytes, "resident_plane_bytes": sum(c.plane_bytes() for c in bench.caches)}
+    if graph:
+        g_s = bench.run_graph(steps, warmup)
+        res["graph"] = {"us_per_decode_step": round(g_s * 1e6 / (GAMMA + 1), 3), "ms_per_cycle": round(g_s * 1e3, 5),
+                        "cycle_GBps": round(cycle_bytes / g_s / 1e9, 1)}
+    if fixed:
+        bench.set_flags(bench.B.QS_FLAG_FIXED_RANGES)
+        f_s, f_call = bench.run_eager(max(20, steps // 2), max(5, warmup // 2))
+        bench.set_flags(0)
+        res["fixed_ranges"] = {"us_per_decode_step": round(f_s * 1e6 / (GAMMA + 1), 3),
+                               "draft_us": round(float(f_call["draft"].mean()), 2),
+                               "verify_us": round(float(f_call["verify"].mean()), 2)}
+    return res, avg
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=60)
-    ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="mha128k")
-    ap.add_argument("--copies", type=int, default=4, help="independent cache copies to rotate over")
+    ap.add_argument("--steps", type=int, default=1000, help="timed cycles of the headline workload")
+    ap.add_argument("--warmup", type=int, default=200, help="untimed cycles of the headline workload before them")
+    ap.add_argument("--workload", default="all",
+                    help="'all' (headline mha128k, then the other baseline workloads) or one workload's name")
+    ap.add_argument("--copies", type=int, default=4, help="independent cache copies a single-layer workload rotates over")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--deterministic", action="store_true",
-                    help="time the bit-reproducible setting (QS_FLAG_FIXED_RANGES) instead of the default")
     ap.add_argument("--no-extras", action="store_true",
-                    help="only the timed cycle: no prefill timing, fp16 baseline or speculation loop (for kernel traces)")
+                    help="only the eager timed cycle of the chosen workload(s): no graph / fixed-range timing, prefill, "
+                         "fp16 baseline or speculation loop (for kernel traces)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; every figure is the one GPU's throughput. "
@@ -72,140 +297,76 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     B.lib()
-    if args.deterministic:
-        B.KVCache.default_flags = B.QS_FLAG_FIXED_RANGES
-    w = synth.WORKLOADS[args.workload]
-    sm_scale = 1.0 / float(np.sqrt(w.head_dim))
-    nqv = w.nq_verify
-    dev = "cuda"
+    names = ALL_WORKLOADS if args.workload == "all" else (args.workload,)
+    extras = not args.no_extras
+    t_all = time.time()
 
-    # ---- synthetic inputs, resident in HBM ------------------------------------------------------
-    t0 = time.time()
-    workers = min(16, os.cpu_count() or 8)
-    k_host, v_host = synth.gen_layer_kv(w, workers=workers)
-    q_draft = torch.from_numpy(synth.gen_layer_q(w, 1)).to(dev)
-    q_verify = torch.from_numpy(synth.gen_layer_q(w, nqv)).to(dev)
-    q_cap = w.n_quant + 640            # room for the groups flushed during the run
-    caches = []
-    kd, vd = torch.from_numpy(k_host).to(dev), torch.from_numpy(v_host).to(dev)
-    for i in range(args.copies):
-        c = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, q_cap, w.n_buf + 8)
-        if i == 0:
-            B.qs_quantize_prefill(c, kd, vd, w.n_quant)
-            prefill = None if args.no_extras else time_prefill(torch, B, c, kd, vd, w)
-        else:
-            for name in B.PLANES:
-                getattr(c, name).copy_(getattr(caches[0], name))
-        c.k_buf[:, :, :w.n_buf] = kd[:, :, w.n_quant:]
-        c.v_buf[:, :, :w.n_buf] = vd[:, :, w.n_quant:]
-        c.n_quant[:] = w.n_quant
-        c.n_buf[:] = w.n_buf
-        caches.append(c)
-    # the same tokens as a plain fp16 cache (no quantized region): the baseline of Table 4
-    fp16_cache = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, 0, w.ctx)
-    fp16_cache.k_buf, fp16_cache.v_buf = kd, vd
-    fp16_cache.n_buf[:] = w.ctx
-    del kd, vd
-    ws = torch.empty(max(B.qs_workspace_bytes(caches[0], n) for n in (1, nqv, max(SPEC_GAMMAS) + 1)),
-                     dtype=torch.uint8, device=dev)
-    out_d = torch.empty_like(q_draft)
-    out_v = torch.empty_like(q_verify)
-    torch.cuda.synchronize()
-    setup_s = time.time() - t0
-
-    ev = lambda: torch.cuda.Event(enable_timing=True)
-    timed = {"draft": [], "verify": [], "flush": []}
-
-    def cycle(i, record):
-        """One speculation cycle on cache copy i.  With record=True four events bracket the three
-        phases (the draft figure is the mean of the gamma back-to-back calls)."""
-        c = caches[i % len(caches)]
-        if record:
-            e = [ev() for _ in range(4)]
-            e[0].record()
-        for _ in range(GAMMA):
-            B.qs_attn_draft(c, q_draft, sm_scale, out=out_d, workspace=ws)
-        if record:
-            e[1].record()
-        B.qs_attn_verify(c, q_verify, sm_scale, out=out_v, workspace=ws)
-        if record:
-            e[2].record()
-        B.qs_quantize_flush(c, 128)     # host lengths stay put: the same group slot is rewritten each cycle
-        if record:
-            e[3].record()
-            timed["draft"].append((e[0], e[1], GAMMA))
-            timed["verify"].append((e[1], e[2], 1))
-            timed["flush"].append((e[2], e[3], 1))
-
-    for i in range(args.warmup):
-        cycle(i, False)
-    torch.cuda.synchronize()
-    gc.collect()
-    gc.disable()                      # no collector pause inside the timed region
-    t_start = time.perf_counter()
-    for i in range(args.steps):
-        cycle(args.warmup + i, True)
-        if i >= 2:
-            # stay at most two cycles ahead of the GPU (a decoder reads each cycle's outcome anyway);
-            # letting the host queue hundreds of launches ahead has stalled the runtime for tens of ms
-            timed["flush"][i - 2][1].synchronize()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_start
-    gc.enable()
-
-    ms_per_step = elapsed * 1e3 / args.steps
-    per_call = {k: np.array([1e3 * a.elapsed_time(b) / n for a, b, n in v]) for k, v in timed.items()}
-    avg_us = {k: float(v.mean()) for k, v in per_call.items()}
-    bytes_d, bytes_v = algorithmic_bytes(w, 1, False), algorithmic_bytes(w, nqv, True)
-    gbps_d = bytes_d / (avg_us["draft"] * 1e-6) / 1e9
-    gbps_v = bytes_v / (avg_us["verify"] * 1e-6) / 1e9
-    cycle_bytes = GAMMA * bytes_d + bytes_v + flush_bytes(w, 128)
-
+    # ---- headline workload ------------------------------------------------------------------------
+    w = synth.WORKLOADS[names[0]]
+    bench = Bench(torch, B, synth, w, args.copies, keep_fp16=extras and w.n_layers == 1)
+    head, avg = measure(bench, args.steps, args.warmup, graph=extras, fixed=extras)
+    kern = {"draft": "attn_kernel_cu<false,true>" if w.n_q_heads == w.n_kv_heads else "attn_kernel_cu<false,false>",
+            "verify": "attn_kernel_cu<true,false>" if w.nq_verify * w.n_q_heads // w.n_kv_heads <= 8 else "attn_kernel<2,8,true>"}
+    roof = lambda what, plane: {
+        "bound": "hbm", "kernel": f"{what} call: {kern[what]} + merge_kernel ({plane})",
+        "achieved": head[f"{what}_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": head[f"{what}_frac"],
+        "algorithmic_bytes_per_launch": head[f"{what}_bytes"],
+        "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, what))}
     result = {
         "metric": "draft/verify attention us per decode step + achieved HBM GB/s at 128k ctx",
-        "value": round(ms_per_step * 1e3 / (GAMMA + 1), 3),
-        "unit": "us/decode-step (mean over a cycle of 4 draft + 1 verify call, flush included)",
+        "value": head["us_per_decode_step"],
+        "unit": "us/decode-step (mean over a cycle of 4 draft + 1 verify call per layer, flush included)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 5),
+        "ms_per_step": head["ms_per_cycle"],
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16", "data": "synthetic",
-        "config": {"workload": f"{w.name}: batch {w.batch}, {w.n_q_heads} q-heads / {w.n_kv_heads} kv-heads x 128, "
-                               f"ctx {w.ctx} = {w.n_quant} quantized + {w.n_buf} fp16 buffer, G=128, gamma=4",
-                   "cache_copies_rotated": len(caches), "flush_tokens_per_cycle": 128,
-                   "deterministic": bool(args.deterministic)},
-        "draft_us": round(avg_us["draft"], 2), "verify_us": round(avg_us["verify"], 2),
-        "flush_us": round(avg_us["flush"], 2),
-        "median_us": {k: round(float(np.median(v)), 2) for k, v in per_call.items()},
-        "min_us": {k: round(float(v.min()), 2) for k, v in per_call.items()},
-        "draft_GBps": round(gbps_d, 1), "verify_GBps": round(gbps_v, 1),
-        "cycle_GBps": round(cycle_bytes / (ms_per_step * 1e-3) / 1e9, 1),
-        "roofline": {"bound": "hbm", "kernel": "draft call: attn_kernel_cu<false,true> + merge_kernel (upper plane)",
-                     "achieved": round(gbps_d, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(gbps_d / HBM_PEAK_GBPS, 4),
-                     "algorithmic_bytes_per_launch": bytes_d,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, "draft"))},
-        "roofline_verify": {"bound": "hbm", "kernel": "verify call: attn_kernel_cu<true,false> + merge_kernel (both planes)",
-                            "achieved": round(gbps_v, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                            "frac": round(gbps_v / HBM_PEAK_GBPS, 4),
-                            "algorithmic_bytes_per_launch": bytes_v,
-                            "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, "verify"))},
-        "setup_s": round(setup_s, 1),
+        "config": {"workload": head["workload"], "cache_copies_rotated": len(bench.groups),
+                   "flush_tokens_per_cycle": bench.n_flush, "fixed_ranges": False,
+                   "precondition_s": PRECONDITION_S},
+        "draft_us": head["draft_us"], "verify_us": head["verify_us"], "flush_us": head["flush_us"],
+        "median_us": head["median_us"], "min_us": head["min_us"],
+        "draft_GBps": head["draft_GBps"], "verify_GBps": head["verify_GBps"], "cycle_GBps": head["cycle_GBps"],
+        "roofline": roof("draft", "upper plane"),
+        "roofline_verify": roof("verify", "both planes"),
+        "setup_s": round(bench.setup_s, 1),
     }
+    if "graph" in head:
+        result["graph"] = head["graph"]
+    if "fixed_ranges" in head:
+        result["fixed_ranges"] = head["fixed_ranges"]
+    if extras and bench.fp16 is not None:
+        kd, vd = bench.fp16
+        fp16_cache = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, 0, w.ctx)
+        fp16_cache.k_buf, fp16_cache.v_buf = kd, vd
+        fp16_cache.n_buf[:] = w.ctx
+        result["prefill_quantize"] = bench.prefill
+        result["fp16_baseline"] = fp16_baseline(torch, B, fp16_cache, w, bench.sm_scale, bench.q_draft, bench.q_verify,
+                                                avg["draft"], avg["verify"])
+        result["speculation"] = speculation_loop(torch, B, bench.caches[0], w, bench.sm_scale, bench.ws)
+        del fp16_cache, kd, vd
+    k_host, v_host, sm_scale = bench.k_host, bench.v_host, bench.sm_scale
+    workloads = {w.name: head}
+    del bench
+    torch.cuda.empty_cache()
 
-    if not args.no_extras:
-        result["prefill_quantize"] = prefill
-        result["fp16_baseline"] = fp16_baseline(torch, B, fp16_cache, w, sm_scale, q_draft, q_verify,
-                                                avg_us["draft"], avg_us["verify"])
-        result["speculation"] = speculation_loop(torch, B, caches[0], w, sm_scale, ws)
-    del fp16_cache
+    # ---- the other workloads ------------------------------------------------------------------------
+    for name in names[1:]:
+        b = Bench(torch, B, synth, synth.WORKLOADS[name], args.copies)
+        workloads[name], _ = measure(b, graph=extras, fixed=extras)
+        workloads[name]["setup_s"] = round(b.setup_s, 1)
+        del b
+        gc.collect()
+        torch.cuda.empty_cache()
+    result["workloads"] = workloads
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, k_host, v_host, sm_scale)
+    result["wall_s"] = round(time.time() - t_all, 1)
     print(json.dumps(result), flush=True)
 
 
 def time_prefill(torch, B, cache, kd, vd, w, reps=3):
     """Bulk quantization of the whole prompt (Algorithm 1, prefill stage): fp16 K/V read once, both
-    planes and the metadata written once.  The kernel is bound by the quantizer's vector arithmetic."""
+    planes and the metadata written once."""
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
     for i in range(reps):
         ev[i].record()
@@ -219,6 +380,8 @@ def time_prefill(torch, B, cache, kd, vd, w, reps=3):
     lane_ops = 24.3 * w.units * w.n_quant * 128 * 2
     return {"us": round(us, 1), "GBps_read_plus_write": round(nbytes / us / 1e3, 1), "bytes": nbytes,
             "tokens_per_unit": w.n_quant,
+            "roofline_hbm": {"bound": "hbm", "achieved": round(nbytes / us / 1e3, 1), "peak": HBM_PEAK_GBPS,
+                             "unit": "GB/s", "frac": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 4)},
             "roofline": {"bound": "alu", "achieved": round(lane_ops / us / 1e6, 2), "peak": 39.32,
                          "unit": "T lane-ops/s", "frac": round(lane_ops / us / 1e6 / 39.32, 4)}}
 
@@ -306,6 +469,7 @@ def cpu_baseline(w, k_host, v_host, sm_scale, sample_units=6):
     except Exception:
         threads = 1
     rep = w.n_q_heads // w.n_kv_heads
+    sample_units = min(sample_units, w.n_kv_heads)
     ks, vs = k_host[:1, :sample_units], v_host[:1, :sample_units]
     oc = O.build_cache(ks, vs, rep * sample_units, w.group, w.n_buf)      # prefill quantize: not timed
     qd = synth.gen_layer_q(w, 1)[:1, :, :rep * sample_units]
@@ -319,12 +483,12 @@ def cpu_baseline(w, k_host, v_host, sm_scale, sample_units=6):
     t0 = time.perf_counter()
     oc.flush(128)
     t_flush = time.perf_counter() - t0
-    scale = w.units / sample_units
+    scale = w.units * w.n_layers / sample_units
     cyc = (GAMMA * t_draft + t_verify + t_flush) * scale
     return {"value": round(cyc * 1e6 / (GAMMA + 1), 1), "unit": "us/decode-step (same cycle, scaled to all units)",
             "cores": threads, "kind": "oracle",
-            "sample": f"{sample_units} of {w.units} units: 1 draft call (x{GAMMA}), 1 verify call, 1 flush of 128 "
-                      f"tokens; {t_draft:.2f}s + {t_verify:.2f}s + {t_flush:.3f}s measured, scaled x{scale:.0f}",
+            "sample": f"{sample_units} of {w.units * w.n_layers} units of {w.name}: 1 draft call (x{GAMMA}), 1 verify call, "
+                      f"1 flush of 128 tokens; {t_draft:.2f}s + {t_verify:.2f}s + {t_flush:.3f}s measured, scaled x{scale:.0f}",
             "draft_us": round(t_draft * scale * 1e6, 1), "verify_us": round(t_verify * scale * 1e6, 1)}
 
 
