@@ -19,9 +19,11 @@ from __future__ import annotations
 
 import argparse
 import gc
+import glob
 import json
 import os
 import sys
+import threading
 import time
 
 import numpy as np
@@ -42,9 +44,49 @@ PRECONDITION_S = 1.0            # untimed run of the cycle before the warm-up st
 # (calibrated against a plain copy kernel: FETCH_SIZE x 1.99991, WRITE_SIZE x 1.0, KiB per dispatch).
 # Filled from profiles/attn_hbm_traffic.md; a workload without an entry reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("mha128k", "draft"): int((288598.1 * 1.99991 + 1105.1) * 1024),
-    ("mha128k", "verify"): int((550709.6 * 1.99991 + 5528.3) * 1024),
+    ("mha128k", "draft"): int((288661.0 * 1.99991 + 1105.1) * 1024),
+    ("mha128k", "verify"): int((550411.9 * 1.99991 + 5528.0) * 1024),
+    ("gqa128k_b4", "draft"): int((288777.1 * 1.99991 + 4420.5) * 1024),
+    ("gqa128k_b4", "verify"): int((545104.6 * 1.99991 + 11701.1) * 1024),
 }
+
+
+class PowerSampler:
+    """Board power (hwmon, microwatts) read every 20 ms while a timed region runs: the long-context
+    kernels sit at the board's power limit, which is what bounds them (see precondition())."""
+
+    def __init__(self):
+        hits = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") +
+                      glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average"))
+        self.path = hits[0] if hits else None
+        self.samples = []
+
+    def __enter__(self):
+        self.samples, self._stop = [], False
+        if self.path:
+            self._thread = threading.Thread(target=self._run, daemon=True)
+            self._thread.start()
+        return self
+
+    def _run(self):
+        while not self._stop:
+            try:
+                with open(self.path) as f:
+                    self.samples.append(int(f.read()) / 1e6)
+            except (OSError, ValueError):
+                pass
+            time.sleep(0.02)
+
+    def __exit__(self, *exc):
+        self._stop = True
+        if self.path:
+            self._thread.join()
+
+    def summary(self):
+        if not self.samples:
+            return None
+        return {"mean": round(float(np.mean(self.samples)), 1), "max": round(float(np.max(self.samples)), 1),
+                "samples": len(self.samples)}
 
 
 def algorithmic_bytes(w, nq, verify):
@@ -221,15 +263,16 @@ def pick_counts(cycle_s, timed_s=0.6, warm_s=0.2, lo=20, hi=4000):
     return steps, int(min(hi, max(5, warm_s / cycle_s)))
 
 
-def measure(bench, steps=None, warmup=None, graph=True, fixed=True):
+def measure(bench, steps=None, warmup=None, graph=True, fixed=True, precondition_s=PRECONDITION_S):
     """All figures of one workload.  steps / warmup: given for the headline workload, chosen from the
     cycle time otherwise."""
     w, layers = bench.w, len(bench.groups[0])
-    n_pre = bench.precondition(PRECONDITION_S)
+    n_pre = bench.precondition(precondition_s) if precondition_s > 0 else 0
     if steps is None:
         est, _ = bench.run_eager(8, 2)
         steps, warmup = pick_counts(est)
-    cyc_s, per_call = bench.run_eager(steps, warmup)
+    with PowerSampler() as power:
+        cyc_s, per_call = bench.run_eager(steps, warmup)
     avg = {k: float(v.mean()) for k, v in per_call.items()}
     bytes_d, bytes_v = algorithmic_bytes(w, 1, False), algorithmic_bytes(w, w.nq_verify, True)
     cycle_bytes = layers * (GAMMA * bytes_d + bytes_v + flush_bytes(w, bench.n_flush))
@@ -251,6 +294,8 @@ def measure(bench, steps=None, warmup=None, graph=True, fixed=True):
         "verify_frac": round(gb(bytes_v, avg["verify"]) / HBM_PEAK_GBPS, 4),
         "draft_bytes": bytes_d, "verify_bytes": bytes_v,
         "flush128_us": round(bench.time_flush(128), 2), "flush256_us": round(bench.time_flush(256), 2),
+        "board_power_W": power.summary(),
+        "traffic": {k: MEASURED_TRAFFIC_BYTES.get((w.name, k)) for k in ("draft", "verify")},
     }
     if layers > 1:
         res["whole_stack"] = {
@@ -280,6 +325,8 @@ def main():
     ap.add_argument("--workload", default="all",
                     help="'all' (headline mha128k, then the other baseline workloads) or one workload's name")
     ap.add_argument("--copies", type=int, default=4, help="independent cache copies a single-layer workload rotates over")
+    ap.add_argument("--precondition", type=float, default=PRECONDITION_S,
+                    help="seconds of the cycle run untimed before the warm-up steps (0 for counter collection runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the eager timed cycle of the chosen workload(s): no graph / fixed-range timing, prefill, "
@@ -304,7 +351,7 @@ def main():
     # ---- headline workload ------------------------------------------------------------------------
     w = synth.WORKLOADS[names[0]]
     bench = Bench(torch, B, synth, w, args.copies, keep_fp16=extras and w.n_layers == 1)
-    head, avg = measure(bench, args.steps, args.warmup, graph=extras, fixed=extras)
+    head, avg = measure(bench, args.steps, args.warmup, graph=extras, fixed=extras, precondition_s=args.precondition)
     kern = {"draft": "attn_kernel_cu<false,true>" if w.n_q_heads == w.n_kv_heads else "attn_kernel_cu<false,false>",
             "verify": "attn_kernel_cu<true,false>" if w.nq_verify * w.n_q_heads // w.n_kv_heads <= 8 else "attn_kernel<2,8,true>"}
     roof = lambda what, plane: {
@@ -322,7 +369,7 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": head["workload"], "cache_copies_rotated": len(bench.groups),
                    "flush_tokens_per_cycle": bench.n_flush, "fixed_ranges": False,
-                   "precondition_s": PRECONDITION_S},
+                   "precondition_s": args.precondition},
         "draft_us": head["draft_us"], "verify_us": head["verify_us"], "flush_us": head["flush_us"],
         "median_us": head["median_us"], "min_us": head["min_us"],
         "draft_GBps": head["draft_GBps"], "verify_GBps": head["verify_GBps"], "cycle_GBps": head["cycle_GBps"],
@@ -352,7 +399,7 @@ def main():
     # ---- the other workloads ------------------------------------------------------------------------
     for name in names[1:]:
         b = Bench(torch, B, synth, synth.WORKLOADS[name], args.copies)
-        workloads[name], _ = measure(b, graph=extras, fixed=extras)
+        workloads[name], _ = measure(b, graph=extras, fixed=extras, precondition_s=args.precondition)
         workloads[name]["setup_s"] = round(b.setup_s, 1)
         del b
         gc.collect()
