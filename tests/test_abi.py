@@ -165,6 +165,40 @@ def test_header_is_plain_c_and_library_works_without_python(B, tmp_path):
     assert out.stdout.strip() == "ok"
 
 
+def test_validation_paths_under_sanitizers(B, tmp_path):
+    """The host side of the API layer (argument validation, planning, sizing) built with AddressSanitizer
+    and UndefinedBehaviorSanitizer - host code only, the device code objects are the ordinary ones - and
+    driven by the same C program."""
+    import shutil
+    import subprocess
+    from paper_2502_10424_amd import build
+    hipcc = build.hipcc()
+    clang = os.path.join(os.path.dirname(os.path.realpath(hipcc)), "..", "lib", "llvm", "bin", "clang")
+    if not os.path.exists(clang):
+        clang = shutil.which("amdclang") or shutil.which("clang")
+    if clang is None:
+        pytest.skip("no clang for the sanitizer runtime")
+    objs = [os.path.join(build.CSRC, n) for n in ("qs_attn.o", "qs_flush.o")]
+    if not all(os.path.exists(o) for o in objs):
+        build.build()
+    san = ["-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined"]
+    host_san = [x for f in san for x in ("-Xarch_host", f)]
+    api_o, lib, exe = str(tmp_path / "qs_api_san.o"), str(tmp_path / "libquantspec_san.so"), str(tmp_path / "abi_check_san")
+    subprocess.run([hipcc, *build.COMMON, "-O1", "-g", *host_san, "-c", os.path.join(build.CSRC, "qs_api.hip"), "-o", api_o],
+                   check=True, capture_output=True)
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined",
+                    "-shared-libsan", "-o", lib, api_o, *objs], check=True, capture_output=True)
+    subprocess.run([clang, "-std=c99", "-g", *san, "-shared-libsan", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "c_abi", "abi_check.c"), "-o", exe, "-ldl"], check=True, capture_output=True)
+    rt = subprocess.run([clang, "-print-file-name=libclang_rt.asan-x86_64.so"], check=True, capture_output=True, text=True)
+    env = dict(os.environ)
+    env["LD_LIBRARY_PATH"] = os.pathsep.join([os.path.dirname(rt.stdout.strip()), "/opt/rocm/lib", env.get("LD_LIBRARY_PATH", "")])
+    # the HIP runtime's own allocations at load time are not ours to judge; link order: a preloaded library may come first
+    env["ASAN_OPTIONS"] = "detect_leaks=0:verify_asan_link_order=0"
+    out = subprocess.run([exe, lib], env=env, capture_output=True, text=True)
+    assert out.returncode == 0 and out.stdout.strip() == "ok", out.stderr[-2000:]
+
+
 def test_missing_library_fails_loudly(B, monkeypatch):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libquantspec.so")

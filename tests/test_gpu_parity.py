@@ -44,10 +44,11 @@ def _run_attn(env, cache, q, sm_scale, verify):
     return out.cpu().numpy(), lse.cpu().numpy()
 
 
-def _check_attn(env, cache, oc, q, sm_scale, verify, rows=None, tag=""):
+def _check_attn(env, cache, oc, q, sm_scale, verify, rows=None, tag="", ref_sm=None):
+    """ref_sm: softmax scale the oracle uses, if not sm_scale (a caller that rescaled its keys)."""
     U = env["U"]
     out, lse = _run_attn(env, cache, q, sm_scale, verify)
-    ref, ref_lse = (oc.attn_verify if verify else oc.attn_draft)(q, sm_scale, rows=rows)
+    ref, ref_lse = (oc.attn_verify if verify else oc.attn_draft)(q, sm_scale if ref_sm is None else ref_sm, rows=rows)
     if rows is not None:
         sel = np.zeros(ref.shape[:1] + ref.shape[2:3], bool)
         for b, h in rows:
@@ -442,7 +443,7 @@ def test_attention_key_magnitudes(env, kmag):
     """Keys four orders of magnitude apart with a softmax scale that keeps the scores at O(1), flat and
     peaked.  q * S_K travels as two fp16 numbers with q normalised to at most 1 per row, so key scales
     down to about 1e-2 (key spread 0.1) are safe; much smaller ones push q * S_K into fp16 subnormals
-    and are out of range (the quantized keys of a model are O(1))."""
+    and are outside the documented domain (see the next test for what a caller does then)."""
     O, U = env["O"], env["U"]
     rng = np.random.default_rng(int(kmag * 10) + 11)
     t, nb = 1024, 19
@@ -455,6 +456,30 @@ def test_attention_key_magnitudes(env, kmag):
         oc = O.build_cache(k, v, 4, 128, nb)
         _check_attn(env, cache, oc, q, sm, True, tag=f"verify |k|~{kmag:g} peak {peak}")
         _check_attn(env, cache, oc, q[:, :1].copy(), sm, False, tag=f"draft |k|~{kmag:g} peak {peak}")
+
+
+@pytest.mark.parametrize("kmag", [1e-2, 1e-3])
+def test_attention_tiny_keys_through_the_documented_rescaling(env, kmag):
+    """Key spreads below the documented domain of the attention calls (every channel's max - min under
+    about 0.1) are handled by the caller as the header says: keys enter the cache multiplied by a power
+    of two and sm_scale is divided by it.  Scaling fp16 keys by a power of two scales S and Z by the same
+    and leaves the codes alone, so the result is that of the unscaled problem, which is what the oracle
+    computes here."""
+    O, U = env["O"], env["U"]
+    rng = np.random.default_rng(int(1e4 * kmag) + 3)
+    t, nb = 1024, 19
+    lift = 2.0 ** np.ceil(np.log2(1.0 / kmag))
+    for peak in (0.5, 3.0):
+        k = (rng.standard_normal((1, 2, t + nb, 128)) * kmag).astype(np.float16)
+        v = rng.standard_normal((1, 2, t + nb, 128)).astype(np.float16)
+        q = rng.standard_normal((1, 3, 4, 128)).astype(np.float16)
+        sm = peak / (kmag * np.sqrt(128))
+        k_lifted = (k.astype(np.float32) * np.float32(lift)).astype(np.float16)
+        assert np.array_equal(k_lifted.astype(np.float32), k.astype(np.float32) * np.float32(lift))   # exact
+        cache = U.make_device_cache(k_lifted, v, 4, nb, buf_cap=32)
+        oc = O.build_cache(k, v, 4, 128, nb)                   # the problem as posed
+        _check_attn(env, cache, oc, q, sm / lift, True, ref_sm=sm, tag=f"verify |k|~{kmag:g} x {lift:g}, peak {peak}")
+        _check_attn(env, cache, oc, q[:, :1].copy(), sm / lift, False, ref_sm=sm, tag=f"draft |k|~{kmag:g} x {lift:g}, peak {peak}")
 
 
 def test_attention_value_scale_jumps(env):
