@@ -327,6 +327,10 @@ def main():
     ap.add_argument("--copies", type=int, default=4, help="independent cache copies a single-layer workload rotates over")
     ap.add_argument("--precondition", type=float, default=PRECONDITION_S,
                     help="seconds of the cycle run untimed before the warm-up steps (0 for counter collection runs)")
+    ap.add_argument("--trace-transient", choices=("cycle", "draft", "verify"), default=None,
+                    help="instead of the benchmark: start the chosen workload's cycle (or its draft / verify call alone, "
+                         "back to back) on an idle chip and print, as one JSON line, the call times and the board power "
+                         "over the first seconds")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the eager timed cycle of the chosen workload(s): no graph / fixed-range timing, prefill, "
@@ -345,6 +349,9 @@ def main():
         sys.exit(1)
     B.lib()
     names = ALL_WORKLOADS if args.workload == "all" else (args.workload,)
+    if args.trace_transient:
+        print(json.dumps(trace_transient(torch, B, synth, synth.WORKLOADS[names[0]], args.copies, args.trace_transient)), flush=True)
+        return
     extras = not args.no_extras
     t_all = time.time()
 
@@ -409,6 +416,49 @@ def main():
         result["cpu_baseline"] = cpu_baseline(w, k_host, v_host, sm_scale)
     result["wall_s"] = round(time.time() - t_all, 1)
     print(json.dumps(result), flush=True)
+
+
+def trace_transient(torch, B, synth, w, copies, what, seconds=3.0, idle_s=3.0):
+    """How the call times and the board power move when work starts on an idle chip.  what = "cycle":
+    batches of four cycles, each batch's mean draft and verify call time (HIP events) next to the power
+    read after it; "draft" / "verify": that call alone, back to back, in batches of twenty."""
+    bench = Bench(torch, B, synth, w, copies)
+    bench.run_eager(4, 2)                 # first launches (code objects, descriptors) are not part of the trace
+    time.sleep(idle_s)
+    power = PowerSampler()
+    layers = len(bench.groups[0])
+    rows, i, t0 = [], 0, time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        if what == "cycle":
+            ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(4)]
+            for e in ev:
+                bench.cycle(i, e)
+                i += 1
+            torch.cuda.synchronize()
+            times = [float(np.mean([e[0].elapsed_time(e[1]) for e in ev])) * 1e3 / (GAMMA * layers),
+                     float(np.mean([e[1].elapsed_time(e[2]) for e in ev])) * 1e3 / layers]
+        else:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                for c in bench.structs[i % len(bench.structs)]:
+                    if what == "draft":
+                        B.qs_attn_draft(c, bench.q_draft, bench.sm_scale, out=bench.out_d, workspace=bench.ws)
+                    else:
+                        B.qs_attn_verify(c, bench.q_verify, bench.sm_scale, out=bench.out_v, workspace=bench.ws)
+                i += 1
+            e1.record()
+            torch.cuda.synchronize()
+            times = [e0.elapsed_time(e1) * 1e3 / (20 * layers)]
+        watts = None
+        if power.path:
+            with open(power.path) as f:
+                watts = round(int(f.read()) / 1e6)
+        rows.append((round(time.perf_counter() - t0, 3), *[round(t, 1) for t in times], watts))
+    pick = sorted(set(list(range(0, min(12, len(rows)))) + list(range(12, len(rows), max(1, len(rows) // 30)))))
+    cols = ["draft call us", "verify call us"] if what == "cycle" else [f"{what} call us"]
+    return {"workload": w.name, "traced": what, "columns": ["seconds since start", *cols, "board power W"],
+            "batches": len(rows), "rows": [rows[j] for j in pick]}
 
 
 def time_prefill(torch, B, cache, kd, vd, w, reps=3):
