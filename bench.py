@@ -412,6 +412,8 @@ def main():
         gc.collect()
         torch.cuda.empty_cache()
     result["workloads"] = workloads
+    if extras and args.workload == "all":
+        result["other_shapes"] = other_shapes(torch, B)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, k_host, v_host, sm_scale)
     result["wall_s"] = round(time.time() - t_all, 1)
@@ -552,6 +554,60 @@ def speculation_loop(torch, B, cache, w, sm_scale, ws, gammas=SPEC_GAMMAS, accep
         dt = time.perf_counter() - t0
         out["per_gamma"][str(gamma)] = {"us_per_token": round(dt * 1e6 / tokens, 2),
                                         "tokens_per_cycle": round(tokens / cycles, 3), "flushes": flushes}
+    return out
+
+
+OTHER_SHAPES = ((64, 32), (64, 64), (128, 32), (128, 64), (256, 32), (256, 64), (256, 128))
+
+
+def other_shapes(torch, B, ctx=32768, n_buf=256, heads=32, nq_verify=5, seconds=0.25):
+    """The other (head_dim, group) shapes on one layer of `heads` kv-heads (no grouped queries) at a 32k
+    context: call times of draft and verify with the kernels these shapes share, against the same HBM
+    roofline.  Seeded normal K / V; parity of these shapes is the tests' business."""
+    out = {}
+    gen = torch.Generator(device="cuda").manual_seed(7)
+    for d, g in OTHER_SHAPES:
+        n_quant = ctx - n_buf
+        cache = B.KVCache(1, heads, heads, n_quant, n_buf + 8, head_dim=d, group=g)
+        k = torch.randn((1, heads, ctx, d), generator=gen, device="cuda", dtype=torch.float16)
+        v = torch.randn((1, heads, ctx, d), generator=gen, device="cuda", dtype=torch.float16)
+        B.qs_quantize_prefill(cache, k, v, n_quant)
+        cache.k_buf[:, :, :n_buf] = k[:, :, n_quant:]
+        cache.v_buf[:, :, :n_buf] = v[:, :, n_quant:]
+        cache.n_quant[:], cache.n_buf[:] = n_quant, n_buf
+        del k, v
+        c = cache.struct()
+        ws = torch.empty(B.qs_workspace_bytes(c, nq_verify), dtype=torch.uint8, device="cuda")
+        sm = 1.0 / float(np.sqrt(d))
+        entry = {"heads": heads, "ctx": ctx}
+        for what, nq in (("draft", 1), ("verify", nq_verify)):
+            q = torch.randn((1, nq, heads, d), generator=gen, device="cuda", dtype=torch.float16)
+            o = torch.empty_like(q)
+            call = (lambda: B.qs_attn_verify(c, q, sm, out=o, workspace=ws)) if what == "verify" else \
+                   (lambda: B.qs_attn_draft(c, q, sm, out=o, workspace=ws))
+            for _ in range(5):
+                call()
+            torch.cuda.synchronize()
+            t0 = time.time()
+            call()
+            torch.cuda.synchronize()
+            reps = int(min(2000, max(10, seconds / max(time.time() - t0, 1e-5))))
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                call()
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1000.0 / reps
+            codes = (2 * d) if what == "verify" else d          # K and V codes of one token, bytes
+            meta = 4 * (d // g) + 4.0 * d / g                    # value (S, Z) + the token's share of the key (S, Z)
+            nbytes = heads * (n_quant * (codes + meta) + n_buf * d * 4) + heads * nq * d * 4
+            entry[f"{what}_us"] = round(us, 2)
+            entry[f"{what}_GBps"] = round(nbytes / us / 1e3, 1)
+            entry[f"{what}_frac"] = round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 3)
+        out[f"d{d}_g{g}"] = entry
+        del cache, ws
+        torch.cuda.empty_cache()
     return out
 
 

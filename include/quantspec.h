@@ -16,7 +16,11 @@
  *     `stream` (a hipStream_t passed as void*; NULL = the default stream) and returns.
  *   - Return value: QS_OK, or a negative qs_status; on error nothing has been enqueued.  There is no
  *     process-wide state: what a call does depends on its arguments (and the current device) alone.
- *   - head_dim and group must both be 128 (the paper's evaluation setting, Section 5.1).
+ *   - Shapes: head_dim D in {64, 128, 256} and group G in {32, 64, 128} with G dividing D (Section
+ *     4.3.1 leaves both open).  D = G = 128, the paper's evaluation setting (Section 5.1), has its own
+ *     layout and kernels, tuned to the memory roofline; the other shapes share a plain layout and one
+ *     simpler, slower set of kernels with the same arithmetic and the same accuracy.  Wherever this header
+ *     writes 128 for a channel count or a group of tokens in a signature, read D or G.
  *   - All device pointers must be 16-byte aligned.
  *
  * Cache layout (B = batch, Hkv = n_kv_heads, "unit" = one (sequence, kv-head) pair)
@@ -39,16 +43,26 @@
  *     lower : uint8 [B][Hkv][q_cap/32][4096]   per block
  *               [   0, 2048)  key codes C_L + 8 (0..15), same arrangement as in the upper array
  *               [2048, 4096)  value codes C_L + 8, likewise
- *   Paging: by default unit u = b*Hkv + kv_head owns the q_cap/128 consecutive 128-token groups (of
- *   four blocks each) that start at group u*(q_cap/128) of both arrays.  With a group table
+ *   Other shapes (D, G) than (128, 128): both arrays are cut into rows of 128 tokens, VG = D/G value groups
+ *   per token, 128/G key groups per row:
+ *     upper : uint8 [B][Hkv][q_cap/128][128*D + 1024*VG]   per row
+ *               [0, 64*D)             key codes C_U, 128 token rows of D/2 bytes: byte j of a row holds channel
+ *                                     2j in bits 0-3 and channel 2j+1 in bits 4-7
+ *               [64*D, 128*D)         value codes C_U, same arrangement
+ *               then, each fp16:      value scale S [128][VG], value zero Z [128][VG],
+ *                                     key scale S [128/G][D], key zero Z [128/G][D], all in plain order
+ *     lower : uint8 [B][Hkv][q_cap/128][128*D]             per row: key codes C_L + 8, then value codes C_L + 8
+ *   Paging: by default unit u = b*Hkv + kv_head owns the q_cap/128 consecutive 128-token groups (four
+ *   blocks, or one row of the other shapes' layout, each; the unit of paging whatever G is) that start at
+ *   group u*(q_cap/128) of both arrays.  With a group table
  *   (group_table != NULL) entry [b][kv_head][g] is instead the index, counted in groups, of the place
  *   in upper / lower that holds logical group g of that unit: upper and lower are then pools of
  *   pool_groups groups in any order, and q_cap is only the longest a sequence may get.
- *   Keys are grouped per channel over 128 consecutive tokens, values per token over the 128 channels
+ *   Keys are grouped per channel over G consecutive tokens, values per token over G consecutive channels
  *   (Section 4.3.1); both planes share S and Z.  qs_quantize_flush / qs_quantize_prefill are the only
  *   writers of these arrays; qs_export_codes returns plain [token][channel] codes and metadata.
  *   Full-precision buffer (Section 4.3.2), plain row-major, written by the caller or by qs_append:
- *     k_buf, v_buf     : fp16  [B][Hkv][buf_cap][128]   tokens [0, n_buf[b]) are valid.
+ *     k_buf, v_buf     : fp16  [B][Hkv][buf_cap][D]     tokens [0, n_buf[b]) are valid.
  *   A cache may have no quantized region at all: q_cap == 0, n_quant[b] == 0, and upper / lower may
  *   then be NULL.  The attention calls are then plain fp16 attention over the
  *   buffer, of any length up to buf_cap (the full-precision baseline of the paper's Table 4).
@@ -80,9 +94,9 @@ typedef enum qs_status {
   QS_OK = 0,
   QS_ERR_NULL = -1,         /* a required pointer is NULL                                         */
   QS_ERR_SHAPE = -2,        /* batch / head counts / capacities are inconsistent                  */
-  QS_ERR_UNSUPPORTED = -3,  /* head_dim or group != 128, batch > QS_MAX_BATCH, nq > QS_MAX_NQ      */
+  QS_ERR_UNSUPPORTED = -3,  /* (head_dim, group) not listed above, batch > QS_MAX_BATCH, nq > QS_MAX_NQ */
   QS_ERR_ALIGN = -4,        /* a device pointer is not 16-byte aligned                            */
-  QS_ERR_RANGE = -5,        /* a length exceeds its capacity, is not a multiple of 128, n_buf < nq;
+  QS_ERR_RANGE = -5,        /* a length exceeds its capacity, is not a multiple of the group, n_buf < nq;
                                compute_units or flags out of range                                  */
   QS_ERR_WORKSPACE = -6,    /* workspace missing or smaller than qs_workspace_bytes()              */
   QS_ERR_HIP = -7           /* a HIP runtime call failed (no device, launch failure)               */
@@ -90,12 +104,12 @@ typedef enum qs_status {
 
 typedef struct qs_cache {
   int32_t batch, n_q_heads, n_kv_heads;   /* n_q_heads % n_kv_heads == 0 (grouped-query attention)   */
-  int32_t head_dim, group;                /* both 128                                                 */
+  int32_t head_dim, group;                /* D and G, see "Shapes" above                              */
   int32_t q_cap;                          /* capacity of the quantized region in tokens, multiple of 128 */
   int32_t buf_cap;                        /* capacity of the fp16 buffer in tokens                    */
   void *upper, *lower;                    /* device, C_U and C_L, see layout above                    */
   void *k_buf, *v_buf;
-  const int32_t *n_quant;                 /* HOST int32[batch]: valid quantized tokens (multiple of 128) */
+  const int32_t *n_quant;                 /* HOST int32[batch]: valid quantized tokens (multiple of group) */
   const int32_t *n_buf;                   /* HOST int32[batch]: valid buffer tokens                   */
   const int32_t *group_table;             /* DEVICE int32 [batch][n_kv_heads][q_cap/128], or NULL = contiguous.
                                              Entries must lie in [0, pool_groups) and be distinct where the
@@ -125,7 +139,7 @@ size_t qs_workspace_bytes(const qs_cache *c, int32_t nq);
  * the older half of the full-precision buffer once it is full): for every sequence b, quantize buffer tokens [0, n_tokens) into both
  * 4-bit planes with one shared fp16 (S, Z) per group, write them at token offset n_quant[b], then
  * move buffer tokens [n_tokens, n_buf[b]) to the front of the buffer.
- *   n_tokens: multiple of 128, <= every n_buf[b]; n_quant[b] + n_tokens <= q_cap.
+ *   n_tokens: multiple of group, <= every n_buf[b]; n_quant[b] + n_tokens <= q_cap.
  * The host arrays are not modified: afterwards the caller adds n_tokens to n_quant[b] and
  * subtracts it from n_buf[b].
  */
@@ -134,7 +148,7 @@ int qs_quantize_flush(const qs_cache *c, int32_t n_tokens, void *stream);
 /*
  * QUANTIZE at prefill (Algorithm 1, prefill stage, where the two planes are first built): quantize
  * n_tokens tokens of caller-provided fp16 K / V, device [B][Hkv][src_stride_tokens][128], into the
- * planes at token offset n_quant[b].  n_tokens is a multiple of 128.  The buffer is not touched.
+ * planes at token offset n_quant[b].  n_tokens is a multiple of group.  The buffer is not touched.
  */
 int qs_quantize_prefill(const qs_cache *c, const void *k_src, const void *v_src,
                         int64_t src_stride_tokens, int32_t n_tokens, void *stream);
@@ -158,7 +172,7 @@ int qs_append(const qs_cache *c, const void *k_new, const void *v_new, int32_t n
  * out = softmax(sm_scale * q K^T) V, sm_scale > 0 and finite (QS_ERR_RANGE otherwise).
  * Numerical domain (both attention calls): any fp16 q and V; keys whose quantization groups are not
  * all tiny - the 2e-3 accuracy of the outputs holds while the per-channel spread max - min of the keys
- * of a 128-token group reaches about 0.1 in at least the channels that carry the scores (keys of a
+ * of a group reaches about 0.1 in at least the channels that carry the scores (keys of a
  * transformer are O(1); spreads up to the fp16 maximum are fine).  Uniformly smaller keys lose bits in
  * q * S, which enters the matrix cores as two fp16 numbers (spread 0.03: up to 3e-3; 0.003: 2.5e-2),
  * and the library cannot see that from its arguments.  A caller with such keys multiplies them by a
@@ -201,9 +215,9 @@ int qs_attn_static(const qs_cache *c, const void *q, int32_t nq, int32_t verify,
  * Inspection helper: expand the packed planes and metadata of tokens [0, n_tokens) of one unit
  * into plain arrays (device pointers, any may be NULL to skip):
  *   k_u, v_u : uint8 [n_tokens][128]      C_U       k_l, v_l : int8 [n_tokens][128]  C_L
- *   k_s, k_z : fp16  [n_tokens/128][128]  per-(group, channel) S, Z in channel order
- *   v_s, v_z : fp16  [n_tokens]           per-token S, Z in token order
- * n_tokens is a multiple of 128.
+ *   k_s, k_z : fp16  [n_tokens/G][D]      per-(group, channel) S, Z in channel order
+ *   v_s, v_z : fp16  [n_tokens][D/G]      per-(token, value group) S, Z in token order
+ * n_tokens is a multiple of group.
  */
 int qs_export_codes(const qs_cache *c, int32_t b, int32_t kv_head, int32_t n_tokens,
                     void *k_u, void *k_l, void *k_s, void *k_z,

@@ -103,6 +103,12 @@ def _stream(stream) -> int | None:
     return getattr(stream, "cuda_stream", stream) or None
 
 
+def plain_group_bytes(head_dim: int, group: int) -> tuple[int, int]:
+    """Bytes of one 128-token group of the upper and of the lower array for shapes other than
+    head_dim = group = 128 (the plain layout of include/quantspec.h)."""
+    return 128 * head_dim + 1024 * (head_dim // group), 128 * head_dim
+
+
 class KVCache:
     """Device tensors of one layer's hierarchical cache plus the host-side lengths.
 
@@ -124,15 +130,19 @@ class KVCache:
         f16 = dict(dtype=torch.float16, device=device)
         qc = max(q_cap, 0)
         self.pool_groups, self.group_table = pool_groups, None
+        if head_dim == HEAD_DIM and group == GROUP:    # 32-token blocks, four to a 128-token group
+            rows, ub, lb = 4, UPPER_BLOCK_BYTES, LOWER_BLOCK_BYTES
+        else:                                          # plain layout: one row per 128-token group
+            rows, (ub, lb) = 1, plain_group_bytes(head_dim, group)
         if pool_groups is None:
-            self.upper = torch.zeros((batch, n_kv_heads, qc // 32, UPPER_BLOCK_BYTES), **u8)
-            self.lower = torch.zeros((batch, n_kv_heads, qc // 32, LOWER_BLOCK_BYTES), **u8)
+            self.upper = torch.zeros((batch, n_kv_heads, qc // 128 * rows, ub), **u8)
+            self.lower = torch.zeros((batch, n_kv_heads, qc // 128 * rows, lb), **u8)
         else:
-            self.upper = torch.zeros((pool_groups * 4, UPPER_BLOCK_BYTES), **u8)
-            self.lower = torch.zeros((pool_groups * 4, LOWER_BLOCK_BYTES), **u8)
+            self.upper = torch.zeros((pool_groups * rows, ub), **u8)
+            self.lower = torch.zeros((pool_groups * rows, lb), **u8)
             self.group_table = torch.zeros((batch, n_kv_heads, qc // 128), dtype=torch.int32, device=device)
-        self.k_buf = torch.zeros((batch, n_kv_heads, buf_cap, 128), **f16)
-        self.v_buf = torch.zeros((batch, n_kv_heads, buf_cap, 128), **f16)
+        self.k_buf = torch.zeros((batch, n_kv_heads, buf_cap, head_dim), **f16)
+        self.v_buf = torch.zeros((batch, n_kv_heads, buf_cap, head_dim), **f16)
         self.n_quant = np.zeros(batch, np.int32)
         self.n_buf = np.zeros(batch, np.int32)
         self.compute_units, self.flags = KVCache.default_compute_units, KVCache.default_flags
@@ -178,7 +188,7 @@ def qs_quantize_flush(cache, n_tokens: int, stream=None) -> None:
 
 
 def qs_quantize_prefill(cache, k_src, v_src, n_tokens: int, stream=None) -> None:
-    """k_src, v_src: fp16 device tensors [B, Hkv, T_src, 128] (contiguous); quantizes their first n_tokens."""
+    """k_src, v_src: fp16 device tensors [B, Hkv, T_src, head_dim] (contiguous); quantizes their first n_tokens."""
     c = _as_struct(cache)
     assert k_src.is_contiguous() and v_src.is_contiguous() and k_src.dtype == torch.float16
     _check(lib().qs_quantize_prefill(ctypes.byref(c), k_src.data_ptr(), v_src.data_ptr(), k_src.shape[2],
@@ -186,7 +196,7 @@ def qs_quantize_prefill(cache, k_src, v_src, n_tokens: int, stream=None) -> None
 
 
 def qs_append(cache, k_new, v_new, stream=None) -> None:
-    """k_new, v_new: fp16 device tensors [B, n_new, Hkv, 128] written to buffer rows n_buf[b].. of every
+    """k_new, v_new: fp16 device tensors [B, n_new, Hkv, head_dim] written to buffer rows n_buf[b].. of every
     sequence.  Like the C call it leaves the host lengths alone: the caller adds n_new to n_buf."""
     c = _as_struct(cache)
     assert k_new.dtype == torch.float16 and k_new.is_contiguous() and v_new.is_contiguous()
@@ -214,13 +224,13 @@ def _attn(fn_name, cache, q, nq, out, sm_scale, workspace, lse, stream):
 
 
 def qs_attn_draft(cache, q, sm_scale: float, out=None, workspace=None, lse=None, stream=None):
-    """q: fp16 device tensor [B, 1, Hq, 128].  Returns out (same shape)."""
+    """q: fp16 device tensor [B, 1, Hq, head_dim].  Returns out (same shape)."""
     assert q.shape[1] == 1
     return _attn("qs_attn_draft", cache, q, 1, out, sm_scale, workspace, lse, stream)
 
 
 def qs_attn_verify(cache, q, sm_scale: float, out=None, workspace=None, lse=None, stream=None):
-    """q: fp16 device tensor [B, nq, Hq, 128], nq = gamma + 1.  Returns out (same shape)."""
+    """q: fp16 device tensor [B, nq, Hq, head_dim], nq = gamma + 1.  Returns out (same shape)."""
     return _attn("qs_attn_verify", cache, q, q.shape[1], out, sm_scale, workspace, lse, stream)
 
 
@@ -238,17 +248,18 @@ def qs_attn_static(cache, q, sm_scale: float, verify: bool, out=None, lse=None, 
 
 
 def qs_export_codes(cache: KVCache, b: int, kv_head: int, n_tokens: int, stream=None):
-    """Plain-order codes and metadata of one unit, as a dict of device tensors:
-    k_u, v_u uint8 [T,128]; k_l, v_l int8 [T,128]; k_s, k_z fp16 [T/128,128]; v_s, v_z fp16 [T]."""
+    """Plain-order codes and metadata of one unit, as a dict of device tensors (D = head_dim, G = group):
+    k_u, v_u uint8 [T,D]; k_l, v_l int8 [T,D]; k_s, k_z fp16 [T/G,D]; v_s, v_z fp16 [T,D/G] ([T] when G = D)."""
     c = cache.struct()
     dev = cache.k_buf.device
-    k_u = torch.empty((n_tokens, 128), dtype=torch.uint8, device=dev)
+    d, g = cache.head_dim, cache.group
+    k_u = torch.empty((n_tokens, d), dtype=torch.uint8, device=dev)
     v_u = torch.empty_like(k_u)
-    k_l = torch.empty((n_tokens, 128), dtype=torch.int8, device=dev)
+    k_l = torch.empty((n_tokens, d), dtype=torch.int8, device=dev)
     v_l = torch.empty_like(k_l)
-    v_s = torch.empty(n_tokens, dtype=torch.float16, device=dev)
+    v_s = torch.empty(n_tokens if g == d else (n_tokens, d // g), dtype=torch.float16, device=dev)
     v_z = torch.empty_like(v_s)
-    k_s = torch.empty((n_tokens // 128, 128), dtype=torch.float16, device=dev)
+    k_s = torch.empty((n_tokens // g, d), dtype=torch.float16, device=dev)
     k_z = torch.empty_like(k_s)
     _check(lib().qs_export_codes(ctypes.byref(c), b, kv_head, n_tokens, k_u.data_ptr(), k_l.data_ptr(),
                                  k_s.data_ptr(), k_z.data_ptr(), v_u.data_ptr(), v_l.data_ptr(),

@@ -8,7 +8,7 @@
 namespace qs {
 namespace {
 
-constexpr int kVersion = 200;   // 0.2.0
+constexpr int kVersion = 210;   // 0.2.1
 constexpr int kDefaultCUs = 256;
 // resident chunk waves per compute unit the split planner aims for: the single-row-tile kernels run two
 // waves per SIMD, the multi-row-tile kernels (more than 8 query rows per kv-head) one
@@ -52,6 +52,11 @@ int static_scratch(void** out) {
   return QS_OK;
 }
 
+// head_dim in {64, 128, 256}, group in {32, 64, 128}, whole groups per token row
+bool shape_built(int d, int g) {
+  return (d == 64 || d == 128 || d == 256) && (g == 32 || g == 64 || g == 128) && d % g == 0;
+}
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int validate_shape(const qs_cache* c) {
@@ -62,9 +67,11 @@ int validate_shape(const qs_cache* c) {
   if (c->group_table != nullptr && c->pool_groups <= 0) return QS_ERR_SHAPE;
   if (c->compute_units < 0 || c->compute_units > 65536 || (c->flags & ~(uint32_t)QS_FLAG_FIXED_RANGES) != 0)
     return QS_ERR_RANGE;
-  if (c->head_dim != kD || c->group != kG || c->batch > QS_MAX_BATCH) return QS_ERR_UNSUPPORTED;
+  if (!shape_built(c->head_dim, c->group) || c->batch > QS_MAX_BATCH) return QS_ERR_UNSUPPORTED;
   return QS_OK;
 }
+
+bool tuned_shape(const qs_cache* c) { return c->head_dim == kD && c->group == kG; }
 
 int validate_cache(const qs_cache* c) {
   int rc = validate_shape(c);
@@ -77,7 +84,7 @@ int validate_cache(const qs_cache* c) {
   for (const void* p : ptrs)
     if (!aligned16(p)) return QS_ERR_ALIGN;
   for (int b = 0; b < c->batch; ++b) {
-    if (c->n_quant[b] < 0 || c->n_quant[b] > c->q_cap || c->n_quant[b] % kG != 0) return QS_ERR_RANGE;
+    if (c->n_quant[b] < 0 || c->n_quant[b] > c->q_cap || c->n_quant[b] % c->group != 0) return QS_ERR_RANGE;
     if (c->n_buf[b] < 0 || c->n_buf[b] > c->buf_cap) return QS_ERR_RANGE;
   }
   return QS_OK;
@@ -101,6 +108,15 @@ Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf) {
   // never more long chunks than resident slots: a chunk that starts late doubles the launch time
   const int want = std::max(1, cu_count(c) * wpc / units);
   Plan p;
+  if (!tuned_shape(c)) {   // one-wave workgroups over ranges of 32-token blocks, fixed ranges only
+    const int blocks = max_quant / kBlkTok;
+    const int want_plain = std::max(1, cu_count(c) * (c->head_dim == 256 ? 4 : 8) / units);
+    p.n_split_q = std::max(1, std::min(want_plain, blocks));
+    p.n_split_b = std::max(1, std::min((max_buf + kBufSplitTok - 1) / kBufSplitTok, std::max(want_plain, kMinBufSplits)));
+    p.cu_wgs = 0;
+    p.ws_splits = p.n_split_q + p.n_split_b;
+    return p;
+  }
   p.n_split_q = std::max(1, std::min(want, groups));
   // the buffer: 64-token chunks while they fit the same budget of resident waves, longer ones beyond
   p.n_split_b = std::max(1, std::min((max_buf + kBufSplitTok - 1) / kBufSplitTok, std::max(want, kMinBufSplits)));
@@ -142,6 +158,8 @@ int attn_common(const qs_cache* c, const void* q, int32_t nq, void* out, float s
   const int64_t rows_total = (int64_t)c->batch * nq * c->n_q_heads;
 
   AttnArgs a;
+  a.head_dim = c->head_dim;
+  a.group = c->group;
   a.upper = static_cast<const uint8_t*>(c->upper);
   a.lower = static_cast<const uint8_t*>(c->lower);
   a.group_table = c->group_table;
@@ -149,7 +167,7 @@ int attn_common(const qs_cache* c, const void* q, int32_t nq, void* out, float s
   a.v_buf = static_cast<const _Float16*>(c->v_buf);
   a.q = static_cast<const _Float16*>(q);
   a.ws_o = static_cast<float*>(workspace);
-  a.ws_ml = a.ws_o + rows_total * n_split * kD;
+  a.ws_ml = a.ws_o + rows_total * n_split * c->head_dim;
   a.n_q_heads = c->n_q_heads;
   a.n_kv_heads = c->n_kv_heads;
   a.rep = c->n_q_heads / c->n_kv_heads;
@@ -169,6 +187,7 @@ int attn_common(const qs_cache* c, const void* q, int32_t nq, void* out, float s
   if (launch_attn(a, c->batch, verify, s) != hipSuccess) return QS_ERR_HIP;
 
   MergeArgs m;
+  m.head_dim = c->head_dim;
   m.ws_o = a.ws_o;
   m.ws_ml = a.ws_ml;
   m.out = static_cast<_Float16*>(out);
@@ -181,6 +200,8 @@ int attn_common(const qs_cache* c, const void* q, int32_t nq, void* out, float s
 int quantize_common(const qs_cache* c, const _Float16* k_src, const _Float16* v_src, int64_t src_stride,
                     int32_t n_tokens, bool move_buffer, hipStream_t s) {
   FlushArgs f;
+  f.head_dim = c->head_dim;
+  f.group = c->group;
   f.k_src = k_src;
   f.v_src = v_src;
   f.src_stride = src_stride;
@@ -189,7 +210,7 @@ int quantize_common(const qs_cache* c, const _Float16* k_src, const _Float16* v_
   f.group_table = c->group_table;
   f.n_kv_heads = c->n_kv_heads;
   f.q_cap = c->q_cap;
-  f.n_groups = n_tokens / kG;
+  f.n_groups = n_tokens / c->group;
   f.k_move = move_buffer ? static_cast<_Float16*>(c->k_buf) : nullptr;
   f.v_move = move_buffer ? static_cast<_Float16*>(c->v_buf) : nullptr;
   for (int b = 0; b < QS_MAX_BATCH; ++b) {
@@ -213,7 +234,7 @@ const char* qs_strerror(int code) {
     case QS_OK: return "ok";
     case QS_ERR_NULL: return "a required pointer is NULL";
     case QS_ERR_SHAPE: return "inconsistent batch / head counts / capacities";
-    case QS_ERR_UNSUPPORTED: return "unsupported configuration (head_dim and group must be 128, batch <= 256, nq <= 16)";
+    case QS_ERR_UNSUPPORTED: return "unsupported configuration (head_dim 64/128/256, group 32/64/128 dividing head_dim, batch <= 256, nq <= 16)";
     case QS_ERR_ALIGN: return "a device pointer is not 16-byte aligned";
     case QS_ERR_RANGE: return "a length, count or flag is out of range (lengths: within capacity, multiples of the group size)";
     case QS_ERR_WORKSPACE: return "workspace is missing or smaller than qs_workspace_bytes(), or (qs_attn_static) that size exceeds QS_STATIC_WS_BYTES";
@@ -226,23 +247,24 @@ size_t qs_workspace_bytes(const qs_cache* c, int32_t nq) {
   if (validate_shape(c) != QS_OK || nq < 1 || nq > QS_MAX_NQ) return 0;
   const Plan p = make_plan(c, nq, c->q_cap, c->buf_cap);
   const size_t rows_total = (size_t)c->batch * nq * c->n_q_heads;
-  return rows_total * (size_t)p.ws_splits * (kD + 2) * sizeof(float);
+  return rows_total * (size_t)p.ws_splits * (c->head_dim + 2) * sizeof(float);
 }
 
 int qs_quantize_flush(const qs_cache* c, int32_t n_tokens, void* stream) {
   int rc = validate_cache(c);
   if (rc != QS_OK) return rc;
-  if (n_tokens < 0 || n_tokens % kG != 0) return QS_ERR_RANGE;
+  if (n_tokens < 0 || n_tokens % c->group != 0) return QS_ERR_RANGE;
   for (int b = 0; b < c->batch; ++b)
     if (n_tokens > c->n_buf[b] || c->n_quant[b] + n_tokens > c->q_cap) return QS_ERR_RANGE;
   if (n_tokens == 0) return QS_OK;
   hipStream_t s = static_cast<hipStream_t>(stream);
   // one group: the flush kernel moves the rest of the buffer itself; more: a second kernel does
-  const bool fused = flush_moves_buffer(n_tokens / kG, c->batch * c->n_kv_heads);
+  const bool fused = flush_moves_buffer(c->head_dim, c->group, n_tokens / c->group, c->batch * c->n_kv_heads);
   rc = quantize_common(c, static_cast<const _Float16*>(c->k_buf), static_cast<const _Float16*>(c->v_buf),
                        c->buf_cap, n_tokens, fused, s);
   if (rc != QS_OK || fused) return rc;
   ShiftArgs sh;
+  sh.head_dim = c->head_dim;
   sh.k_buf = static_cast<_Float16*>(c->k_buf);
   sh.v_buf = static_cast<_Float16*>(c->v_buf);
   sh.n_kv_heads = c->n_kv_heads;
@@ -263,7 +285,7 @@ int qs_quantize_prefill(const qs_cache* c, const void* k_src, const void* v_src,
   if (rc != QS_OK) return rc;
   if (k_src == nullptr || v_src == nullptr) return QS_ERR_NULL;
   if (!aligned16(k_src) || !aligned16(v_src)) return QS_ERR_ALIGN;
-  if (n_tokens < 0 || n_tokens % kG != 0 || src_stride_tokens < n_tokens) return QS_ERR_RANGE;
+  if (n_tokens < 0 || n_tokens % c->group != 0 || src_stride_tokens < n_tokens) return QS_ERR_RANGE;
   for (int b = 0; b < c->batch; ++b)
     if (c->n_quant[b] + n_tokens > c->q_cap) return QS_ERR_RANGE;
   if (n_tokens == 0) return QS_OK;
@@ -281,6 +303,7 @@ int qs_append(const qs_cache* c, const void* k_new, const void* v_new, int32_t n
     if (c->n_buf[b] + n_new > c->buf_cap) return QS_ERR_RANGE;
   if (n_new == 0) return QS_OK;
   AppendArgs a;
+  a.head_dim = c->head_dim;
   a.k_new = static_cast<const _Float16*>(k_new);
   a.v_new = static_cast<const _Float16*>(v_new);
   a.k_buf = static_cast<_Float16*>(c->k_buf);
@@ -322,9 +345,11 @@ int qs_export_codes(const qs_cache* c, int32_t b, int32_t kv_head, int32_t n_tok
   int rc = validate_cache(c);
   if (rc != QS_OK) return rc;
   if (b < 0 || b >= c->batch || kv_head < 0 || kv_head >= c->n_kv_heads) return QS_ERR_RANGE;
-  if (n_tokens < 0 || n_tokens % kG != 0 || n_tokens > c->q_cap) return QS_ERR_RANGE;
+  if (n_tokens < 0 || n_tokens % c->group != 0 || n_tokens > c->q_cap) return QS_ERR_RANGE;
   const int64_t unit = (int64_t)b * c->n_kv_heads + kv_head;
   ExportArgs e;
+  e.head_dim = c->head_dim;
+  e.group = c->group;
   e.upper = static_cast<const uint8_t*>(c->upper);
   e.lower = static_cast<const uint8_t*>(c->lower);
   e.group_table = c->group_table;

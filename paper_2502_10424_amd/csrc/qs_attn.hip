@@ -1056,6 +1056,396 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Other shapes than head_dim = group = 128 (plain layout, see quantspec.h).  One wave per workgroup, NRT
+// tiles of 16 query rows, chunks are ranges of 32-token blocks.  The arithmetic is that of the kernels
+// above without their tuning:
+//  * a code c (4 or 8 bits), zero-extended to 16 bits, is the fp16 subnormal c * 2^-24: codes go to LDS
+//    as they are and serve as the A operand of both contractions, exactly;
+//  * keys: score = sum_c q_c (mul_c code_c + add_c) with (mul, add) = (S, Z) for the upper plane alone and
+//    (S/16, Z - S/2) for the 8-bit code 16 C_U + C_L + 8.  Once per group of G tokens the products
+//    q_c mul_c (exact in binary32: 11 x 11 bits) are scaled by a power of two per query row and split
+//    into two fp16 operands hi + lo, again exactly, and sum_c q_c add_c becomes a per-row bias;
+//  * values: out_c = sum_t (p_t mul_t) code_tc + sum_t p_t add_t per value group of the channel: the P operand
+//    carries the value scale (and a power of two that follows the largest scale seen, so that it stays
+//    inside fp16), the second sum is kept in binary32 beside the accumulators;
+//  * the full-precision buffer is the same block step with the fp16 rows as "codes", q itself as the
+//    operand and no scales.
+// ------------------------------------------------------------------------------------------------
+using half4 = _Float16 __attribute__((ext_vector_type(4)));
+
+// Row `row` (of the n_rows that share kv-head kvh of sequence b) in the [B][nq][Hq] order of q and out.
+__device__ __forceinline__ int64_t global_row(const AttnArgs& a, int b, int kvh, int row) {
+  const int qi = row / a.rep, head = kvh * a.rep + row % a.rep;
+  return ((int64_t)b * a.nq + qi) * a.n_q_heads + head;
+}
+
+__device__ __forceinline__ float pow2(int e) { return __builtin_bit_cast(float, (uint32_t)(127 + e) << 23); }   // -126 <= e <= 127
+__device__ __forceinline__ int exponent_of(float x) { return (int)((__builtin_bit_cast(uint32_t, x) >> 23) & 255u) - 127; }
+
+template <int D, int G, bool VERIFY, int NRT>
+__global__ __launch_bounds__(64) void attn_plain_kernel(AttnArgs a) {
+  constexpr int KS = D / 32, NT = D / 16, VG = D / G;
+  constexpr int KSTRIDE = D + 8, VSTRIDE = 40;        // 16-bit elements per LDS row (padding keeps 16- / 8-byte accesses aligned)
+  constexpr int kEvFloor = -40;                       // below every value scale that is not zero (2^-24 / 16)
+  __shared__ uint16_t kt[32][KSTRIDE];                // keys of the block, [token][channel]
+  __shared__ uint16_t vt[D][VSTRIDE];                 // values of the block, [channel][token]
+  const ShapeLayout lay{D, G};
+  const int lane = threadIdx.x & 63, rho = lane & 15, g = lane >> 4;
+  const int unit = blockIdx.x, split = blockIdx.y, row0 = blockIdx.z * 16 * NRT;
+  const int b = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
+  const int nb = a.len.n_buf[b];
+  const bool quantized = split < a.n_split_q;
+  // this wave's range of 32-token blocks, of the quantized region or of the buffer
+  const int n_blk = quantized ? a.len.n_quant[b] / 32 : (nb + 31) >> 5;
+  const int piece = quantized ? split : split - a.n_split_q, pieces = quantized ? a.n_split_q : a.n_split_b;
+  const int blk0 = (int)((int64_t)piece * n_blk / pieces), blk1 = (int)((int64_t)(piece + 1) * n_blk / pieces);
+
+  const _Float16* qp[NRT];
+  bool valid[NRT];
+  int vis[NRT];   // buffer tokens [0, vis) are visible to this lane's query (causal among the nq queries)
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    const int row = row0 + 16 * rt + rho;
+    valid[rt] = row < a.n_rows;
+    const int rowc = valid[rt] ? row : 0;
+    const int qi = rowc / a.rep, head = kvh * a.rep + rowc % a.rep;
+    qp[rt] = a.q + (((int64_t)b * a.nq + qi) * a.n_q_heads + head) * D + 8 * g;
+    vis[rt] = valid[rt] ? nb - a.nq + qi + 1 : 0;
+  }
+  // operands of the query rows for the current group of keys, see above
+  half8 qhi[NRT][KS], qlo[NRT][KS];
+  float sc[NRT], bias[NRT];
+  auto load_q = [&](int rt, int s) {
+    u32x4 w = ldg128(qp[rt] + 32 * s);
+    if (!valid[rt]) w = (u32x4){0u, 0u, 0u, 0u};
+    return as_half8(w);
+  };
+  auto plain_q = [&]() {
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+#pragma unroll
+      for (int s = 0; s < KS; ++s) qhi[rt][s] = load_q(rt, s);
+      sc[rt] = a.c0, bias[rt] = 0.f;
+    }
+  };
+  auto scaled_q = [&](const uint8_t* ub, int key_group) {
+    half8 sh[KS], zh[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      sh[s] = as_half8(ldg128(ub + lay.off_ks() + (key_group * D + 32 * s + 8 * g) * 2));
+      zh[s] = as_half8(ldg128(ub + lay.off_kz() + (key_group * D + 32 * s + 8 * g) * 2));
+    }
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      float t[KS][8];
+      float amax = 0.f, bsum = 0.f;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const half8 qv = load_q(rt, s);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float sf = (float)sh[s][i], zf = (float)zh[s][i], qf = (float)qv[i];
+          const float mul = VERIFY ? sf * 0.0625f : sf;
+          const float add = VERIFY ? __builtin_fmaf(-0.5f, sf, zf) : zf;
+          t[s][i] = qf * mul;
+          amax = fmaxf(amax, __builtin_fabsf(t[s][i]));
+          bsum = __builtin_fmaf(qf, add, bsum);
+        }
+      }
+      // 2^up brings the row's largest product into [2^13, 2^14); a row of zeros keeps any scale
+      const int ea = max(exponent_of(group_max(amax)), -100);
+      const float up = pow2(13 - ea);
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float th = t[s][i] * up;
+          const _Float16 hi = (_Float16)th;
+          qhi[rt][s][i] = hi;
+          qlo[rt][s][i] = (_Float16)(th - (float)hi);
+        }
+      sc[rt] = a.c0 * pow2(ea - 13 + 24);   // undoes 2^up and the 2^-24 of a code read as a subnormal
+      bias[rt] = a.c0 * group_sum(bsum);
+    }
+  };
+
+  float m[NRT], l[NRT], zs[NRT][VG];
+  float4v o[NRT][NT];   // O^T accumulators: tile n, element jj -> channel 16*n + 4*g + jj
+  int ev = quantized ? kEvFloor : 0;   // the P operand is p * mul * 2^(14 - ev)
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    m[rt] = kNegBig, l[rt] = 0.f;
+#pragma unroll
+    for (int k = 0; k < VG; ++k) zs[rt][k] = 0.f;
+#pragma unroll
+    for (int n = 0; n < NT; ++n) o[rt][n] = (float4v){0.f, 0.f, 0.f, 0.f};
+  }
+
+  // ---- filling the tiles ----
+  // keys: lane (cg, tg) takes channels 8*cg .. of tokens tg*TPL .. (one 32-bit word of eight codes per token)
+  constexpr int CGS = D / 8, TPL = 32 * CGS / 64;
+  const int cg = lane % CGS, tg = lane / CGS;
+  // values: lane (tok, half) takes D/2 channels of one token
+  const int vtok = lane & 31, vhalf = lane >> 5;
+  // the eight codes of a word (C_U, or 16*C_U + C_L + 8) as 16-bit numbers, two to a word, in channel order
+  auto eight = [](uint32_t u, uint32_t lw, uint32_t (&w)[4]) {
+    uint32_t even, odd;   // byte k: the code of channel 2k / 2k+1
+    if (VERIFY) {
+      even = ((u << 4) & 0xF0F0F0F0u) | (lw & 0x0F0F0F0Fu);
+      odd = (u & 0xF0F0F0F0u) | ((lw >> 4) & 0x0F0F0F0Fu);
+    } else {
+      even = u & 0x0F0F0F0Fu;
+      odd = (u >> 4) & 0x0F0F0F0Fu;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) w[k] = ((even >> (8 * k)) & 0xFFu) | (((odd >> (8 * k)) & 0xFFu) << 16);
+  };
+  auto fill_quantized = [&](const uint8_t* ub, const uint8_t* lb, int st0) {
+#pragma unroll
+    for (int i = 0; i < TPL; ++i) {   // keys
+      const int t = tg * TPL + i, off = (st0 + t) * (D / 2) + 4 * cg;
+      const uint32_t u = *reinterpret_cast<const uint32_t*>(ub + off);
+      const uint32_t lw = VERIFY ? *reinterpret_cast<const uint32_t*>(lb + off) : 0u;
+      uint32_t w[4];
+      eight(u, lw, w);
+      *reinterpret_cast<u32x4*>(&kt[t][8 * cg]) = (u32x4){w[0], w[1], w[2], w[3]};
+    }
+    const int off = lay.off_v() + (st0 + vtok) * (D / 2) + vhalf * (D / 4);
+#pragma unroll
+    for (int k = 0; k < D / 16; ++k) {   // values: word k of this lane's half row = channels ch0 ..
+      const int ch0 = vhalf * (D / 2) + 8 * k;
+      const uint32_t u = *reinterpret_cast<const uint32_t*>(ub + off + 4 * k);
+      const uint32_t lw = VERIFY ? *reinterpret_cast<const uint32_t*>(lb + off + 4 * k) : 0u;
+      uint32_t w[4];
+      eight(u, lw, w);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        vt[ch0 + 2 * e][vtok] = (uint16_t)(w[e] & 0xFFFFu);
+        vt[ch0 + 2 * e + 1][vtok] = (uint16_t)(w[e] >> 16);
+      }
+    }
+  };
+  const uint16_t* kb = reinterpret_cast<const uint16_t*>(a.k_buf) + (int64_t)unit * a.buf_cap * D;
+  const uint16_t* vb = reinterpret_cast<const uint16_t*>(a.v_buf) + (int64_t)unit * a.buf_cap * D;
+  auto fill_buffer = [&](int blk) {   // rows past the end are clamped here and masked below
+    const int t0 = 32 * blk;
+#pragma unroll
+    for (int i = 0; i < TPL; ++i) {
+      const int t = tg * TPL + i, tok = min(t0 + t, nb - 1);
+      *reinterpret_cast<u32x4*>(&kt[t][8 * cg]) = ldg128(kb + (int64_t)tok * D + 8 * cg);
+    }
+    const int tok = min(t0 + vtok, nb - 1);
+#pragma unroll
+    for (int k = 0; k < D / 16; ++k) {
+      const int ch0 = vhalf * (D / 2) + 8 * k;
+      const u32x4 x = ldg128(vb + (int64_t)tok * D + ch0);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        vt[ch0 + 2 * e][vtok] = (uint16_t)(x[e] & 0xFFFFu);
+        vt[ch0 + 2 * e + 1][vtok] = (uint16_t)(x[e] >> 16);
+      }
+    }
+  };
+
+  if (!quantized) plain_q();
+  for (int blk = blk0; blk < blk1; ++blk) {
+    const int st0 = (32 * blk) % kSuper;   // first token of the block inside its 128-token row of the layout
+    const uint8_t* ub = nullptr;
+    wave_lds_sync();   // the previous block's LDS reads are done
+    if (quantized) {
+      const int64_t pg = physical_group(a, unit, (32 * blk) / kSuper);
+      ub = a.upper + pg * lay.upper_bytes();
+      if (blk == blk0 || st0 % G == 0) scaled_q(ub, st0 / G);
+      fill_quantized(ub, a.lower + pg * lay.lower_bytes(), st0);
+    } else {
+      fill_buffer(blk);
+    }
+    wave_lds_sync();
+    // ---- scores, in log2 units ----
+    float x[NRT][8], mx[NRT];
+    bool grow = false;
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          const half8 ka = as_half8(*reinterpret_cast<const u32x4*>(&kt[16 * t + rho][32 * s + 8 * g]));
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qhi[rt][s], acc, 0, 0, 0);
+          if (quantized) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qlo[rt][s], acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const int tok = 32 * blk + 16 * t + 4 * g + jj;
+          x[rt][4 * t + jj] = (quantized || tok < vis[rt]) ? __builtin_fmaf(acc[jj], sc[rt], bias[rt]) : -__builtin_inff();
+        }
+      }
+      mx[rt] = group_max(max_of(x[rt]));
+      grow |= mx[rt] > m[rt];
+    }
+    // ---- value scales of this lane's eight tokens (16*t + 4*g + jj), per value group ----
+    float vmul[8][VG], vadd[8][VG];
+    int eb = ev;
+    if (quantized) {
+      float smax = 0.f;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const int tok = st0 + 16 * t + 4 * g;
+        const _Float16* vs = reinterpret_cast<const _Float16*>(ub + lay.off_vs()) + tok * VG;
+        const _Float16* vz = reinterpret_cast<const _Float16*>(ub + lay.off_vz()) + tok * VG;
+#pragma unroll
+        for (int c = 0; c < VG; ++c) {   // 4 tokens x VG groups = VG chunks of four fp16
+          const uint2 ws = *reinterpret_cast<const uint2*>(vs + 4 * c);
+          const uint2 wz = *reinterpret_cast<const uint2*>(vz + 4 * c);
+          const half4 s4 = __builtin_bit_cast(half4, ws), z4 = __builtin_bit_cast(half4, wz);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int idx = 4 * c + e, jj = idx / VG, k = idx % VG;
+            const float sf = (float)s4[e], zf = (float)z4[e];
+            vmul[4 * t + jj][k] = VERIFY ? sf * 0.0625f : sf;
+            vadd[4 * t + jj][k] = VERIFY ? __builtin_fmaf(-0.5f, sf, zf) : zf;
+            smax = fmaxf(smax, vmul[4 * t + jj][k]);
+          }
+        }
+      }
+      eb = max(exponent_of(group_max(smax)), ev);   // the same in every lane: all lanes of a group of 16 share their tokens
+    }
+    if (__any(grow) || eb > ev) {   // a running maximum or the scale exponent moves: rescale what is accumulated
+      const float alpha_e = pow2(max(ev - eb, -120));
+      ev = eb;
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) {
+        const float m_new = fmaxf(m[rt], mx[rt]);
+        const float alpha = __builtin_amdgcn_exp2f(m[rt] - m_new);
+        m[rt] = m_new;
+        l[rt] *= alpha;
+#pragma unroll
+        for (int k = 0; k < VG; ++k) zs[rt][k] *= alpha;
+        const float both = alpha * alpha_e;
+#pragma unroll
+        for (int n = 0; n < NT; ++n) o[rt][n] *= both;
+      }
+    }
+    const float pscale = pow2(14 - ev);
+    half8 pb[NRT][VG];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      float sum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float p = __builtin_amdgcn_exp2f(x[rt][j] - m[rt]);
+        sum += p;
+        if (quantized) {
+#pragma unroll
+          for (int k = 0; k < VG; ++k) {
+            zs[rt][k] = __builtin_fmaf(p, vadd[j][k], zs[rt][k]);
+            pb[rt][k][j] = (_Float16)(p * vmul[j][k] * pscale);
+          }
+        } else {
+          pb[rt][0][j] = (_Float16)(p * pscale);
+        }
+      }
+      l[rt] += sum;
+    }
+    // ---- O^T[channel, column] += V^T x p ----
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+      const uint16_t* rowp = &vt[16 * n + rho][0];
+      const uint2 lo = *reinterpret_cast<const uint2*>(rowp + 4 * g);
+      const uint2 hi = *reinterpret_cast<const uint2*>(rowp + 16 + 4 * g);
+      const half8 vop = as_half8((u32x4){lo.x, lo.y, hi.x, hi.y});
+      const int k = quantized ? (16 * n) / G : 0;
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt)
+        o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vop, pb[rt][k], o[rt][n], 0, 0, 0);
+    }
+  }
+  // ---- partial: (m, l) and the unnormalised output row ----
+  const int n_split = a.n_split_q + a.n_split_b;
+  const float back = quantized ? pow2(ev + 10) : pow2(-14);   // 2^(ev - 14), and 2^24 for codes read as subnormals
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    const float lsum = group_sum(l[rt]);
+    float zsum[VG];
+#pragma unroll
+    for (int k = 0; k < VG; ++k) zsum[k] = group_sum(zs[rt][k]);
+    const int row = row0 + 16 * rt + rho;
+    if (row < a.n_rows) {
+      const int64_t r = global_row(a, b, kvh, row) * n_split + split;
+      float* po = a.ws_o + r * D;
+#pragma unroll
+      for (int n = 0; n < NT; ++n) {
+        float4v y;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) y[jj] = __builtin_fmaf(o[rt][n][jj], back, zsum[(16 * n) / G]);
+        *reinterpret_cast<float4v*>(po + 16 * n + 4 * g) = y;
+      }
+      if (g == 0) {
+        a.ws_ml[2 * r] = m[rt];
+        a.ws_ml[2 * r + 1] = lsum;
+      }
+    }
+  }
+}
+
+// Merge for any head_dim: thread (sl, c) folds chunks sl, sl + SL, ... for channels 4c .. 4c+3; the SL
+// slices are then combined through LDS (see merge_kernel).
+template <int D>
+__global__ __launch_bounds__(256) void merge_plain_kernel(MergeArgs a) {
+  constexpr int CL = D / 4, SL = 256 / CL;
+  __shared__ float red_o[SL][D + 4];
+  __shared__ float red_m[SL], red_l[SL];
+  const int64_t row = blockIdx.x;
+  const int tid = threadIdx.x, sl = tid / CL, c = tid % CL;
+  const float* ml = a.ws_ml + row * a.n_split * 2;
+  const float* po = a.ws_o + row * a.n_split * D + 4 * c;
+  float m = kNegBig, l = 0.f;
+  float4v o = {0.f, 0.f, 0.f, 0.f};
+  for (int s = sl; s < a.n_split; s += SL) {
+    const float2 p = *reinterpret_cast<const float2*>(ml + 2 * s);
+    const float4v x = *reinterpret_cast<const float4v*>(po + (int64_t)s * D);
+    const float mb = fmaxf(m, p.x);
+    const float down = __builtin_amdgcn_exp2f(m - mb), w = __builtin_amdgcn_exp2f(p.x - mb);
+    l = __builtin_fmaf(w, p.y, l * down);
+    o = o * down + w * x;
+    m = mb;
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) red_o[sl][4 * c + i] = o[i];
+  if (c == 0) red_m[sl] = m, red_l[sl] = l;
+  __syncthreads();
+  if (tid < D) {
+    float mm = red_m[0];
+#pragma unroll
+    for (int k = 1; k < SL; ++k) mm = fmaxf(mm, red_m[k]);
+    float os = 0.f, lsum = 0.f;
+#pragma unroll
+    for (int k = 0; k < SL; ++k) {
+      const float w = __builtin_amdgcn_exp2f(red_m[k] - mm);
+      os = __builtin_fmaf(w, red_o[k][tid], os);
+      lsum = __builtin_fmaf(w, red_l[k], lsum);
+    }
+    a.out[row * D + tid] = (_Float16)(os / lsum);
+    if (a.lse != nullptr && tid == 0) a.lse[row] = (mm + __builtin_log2f(lsum)) * 0.6931471805599453f;
+  }
+}
+
+template <int D, int G>
+hipError_t launch_attn_plain(const AttnArgs& a, int batch, bool verify, hipStream_t s) {
+  // two row tiles per wave where their accumulators fit the register file (head_dim 256: 128 of them per tile)
+  const int nrt = (D == 256 || a.n_rows <= 16) ? 1 : 2;
+  dim3 grid(batch * a.n_kv_heads, a.n_split_q + a.n_split_b, (a.n_rows + 16 * nrt - 1) / (16 * nrt));
+  if constexpr (D != 256) {
+    if (nrt == 2)
+      return verify ? launch(attn_plain_kernel<D, G, true, 2>, grid, dim3(64), s, a)
+                    : launch(attn_plain_kernel<D, G, false, 2>, grid, dim3(64), s, a);
+  }
+  return verify ? launch(attn_plain_kernel<D, G, true, 1>, grid, dim3(64), s, a)
+                : launch(attn_plain_kernel<D, G, false, 1>, grid, dim3(64), s, a);
+}
+
 template <int NRT, int TAIL>
 hipError_t launch_attn_tiles(const AttnArgs& a, int batch, bool verify, hipStream_t s) {
   constexpr int rows = 16 * (NRT - 1) + TAIL;
@@ -1070,6 +1460,13 @@ hipError_t launch_attn_tiles(const AttnArgs& a, int batch, bool verify, hipStrea
 // columns; up to 16 one full tile; up to 24 a full tile and one of 8; up to 32 two full tiles; more: row
 // batches of 32 over grid.z.
 hipError_t launch_attn(const AttnArgs& a, int batch, bool verify, hipStream_t s) {
+  if (a.head_dim != kD || a.group != kG) {
+#define QS_SHAPE(DD, GG) \
+  if (a.head_dim == DD && a.group == GG) return launch_attn_plain<DD, GG>(a, batch, verify, s);
+    QS_SHAPE(64, 32) QS_SHAPE(64, 64) QS_SHAPE(128, 32) QS_SHAPE(128, 64) QS_SHAPE(256, 32) QS_SHAPE(256, 64) QS_SHAPE(256, 128)
+#undef QS_SHAPE
+    return hipErrorInvalidValue;
+  }
   if (a.cu_wgs > 0) {   // at most 8 rows and enough groups: one workgroup per compute unit, groups drawn dynamically
     dim3 grid(batch * a.n_kv_heads, a.cu_wgs, 1), block(64 * kCuWaves);
     if (verify) return launch(attn_kernel_cu<true, false>, grid, block, s, a);
@@ -1087,6 +1484,8 @@ hipError_t launch_attn(const AttnArgs& a, int batch, bool verify, hipStream_t s)
 }
 
 hipError_t launch_merge(const MergeArgs& a, int rows_total, hipStream_t s) {
+  if (a.head_dim == 64) return launch(merge_plain_kernel<64>, dim3(rows_total), dim3(256), s, a);
+  if (a.head_dim == 256) return launch(merge_plain_kernel<256>, dim3(rows_total), dim3(256), s, a);
   return launch(merge_kernel, dim3(rows_total), dim3(256), s, a);
 }
 

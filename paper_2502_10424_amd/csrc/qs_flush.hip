@@ -8,6 +8,8 @@
 //
 // Every thread owns a few channels of the eight tokens that share one 32-bit word of the value-plane
 // tile, so value words are assembled in registers and each plane is written exactly once.
+#include <type_traits>
+
 #include "qs_internal.h"
 
 namespace qs {
@@ -475,15 +477,16 @@ __global__ __launch_bounds__(1024) void shift_kernel(ShiftArgs a) {
   }
 }
 
-// Append: one 16-byte chunk per thread, [B][n_new][Hkv][128] -> buffer rows n_buf[b] .. of every unit.
+// Append: one 16-byte chunk per thread, [B][n_new][Hkv][head_dim] -> buffer rows n_buf[b] .. of every unit.
 __global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
   const int b = blockIdx.y;
   const int idx = blockIdx.x * 256 + threadIdx.x;           // (token, kv-head, 16-byte chunk)
-  const int per_tok = a.n_kv_heads * 16;
+  const int d = a.head_dim, cpr = d / 8;                    // chunks per row
+  const int per_tok = a.n_kv_heads * cpr;
   if (idx >= a.n_new * per_tok) return;
-  const int tok = idx / per_tok, h = (idx % per_tok) >> 4, c = idx & 15;
-  const int64_t src = (((int64_t)b * a.n_new + tok) * a.n_kv_heads + h) * kD + 8 * c;
-  const int64_t dst = (((int64_t)b * a.n_kv_heads + h) * a.buf_cap + a.n_buf[b] + tok) * kD + 8 * c;
+  const int tok = idx / per_tok, h = (idx % per_tok) / cpr, c = idx % cpr;
+  const int64_t src = (((int64_t)b * a.n_new + tok) * a.n_kv_heads + h) * d + 8 * c;
+  const int64_t dst = (((int64_t)b * a.n_kv_heads + h) * a.buf_cap + a.n_buf[b] + tok) * d + 8 * c;
   *reinterpret_cast<uint4*>(a.k_buf + dst) = *reinterpret_cast<const uint4*>(a.k_new + src);
   *reinterpret_cast<uint4*>(a.v_buf + dst) = *reinterpret_cast<const uint4*>(a.v_new + src);
 }
@@ -530,13 +533,183 @@ __global__ __launch_bounds__(256) void export_kernel(ExportArgs a) {
   }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Other shapes than head_dim = group = 128: the plain layout (superblocks of 128 tokens, see
+// quantspec.h).  One workgroup per (unit, G-token key group); the same encoding, written for clarity
+// rather than speed: codes are staged one per byte in LDS and packed from there.
+//   keys:   thread (c = tid % D, slice = tid / D) walks the group's tokens slice, slice + 256/D, ...
+//           of channel c twice - statistics, then codes with the group's (S, Z)
+//   values: one thread per (token, value group of G channels): D of them for G tokens
+// ------------------------------------------------------------------------------------------------
+template <int D, int G>
+__global__ __launch_bounds__(256) void quantize_plain_kernel(FlushArgs a) {
+  constexpr int NSL = 256 / D;    // token slices of the key pass
+  constexpr int VG = D / G;       // value groups per token
+  __shared__ uint8_t cb[G][D];   // staged codes, one element per byte: C_U in the low nibble, C_L + 8 in the high one
+  __shared__ float red[2][NSL][D];
+  const ShapeLayout lay{D, G};
+  const int grp = blockIdx.x, unit = blockIdx.y;
+  const int b = unit / a.n_kv_heads;
+  const int tid = threadIdx.x;
+  const int tq0 = a.n_quant[b] + grp * G;          // destination token offset inside the unit (multiple of G)
+  const int64_t src0 = ((int64_t)unit * a.src_stride + (int64_t)grp * G) * D;
+  const int sb_tok = tq0 % kSuper;                 // first token of the group inside its superblock
+  uint8_t* ub = a.upper + physical_group(a, unit, tq0 / kSuper) * lay.upper_bytes();
+  uint8_t* lb = a.lower + physical_group(a, unit, tq0 / kSuper) * lay.lower_bytes();
+
+  auto pack_rows = [&](int code_off) {   // staged codes -> plane rows of D/2 bytes, 8 codes per 32-bit word
+    for (int w = tid; w < G * D / 8; w += 256) {
+      const int t = w / (D / 8), c0 = 8 * (w % (D / 8));
+      uint32_t wu = 0, wl = 0;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) wu |= (uint32_t)(cb[t][c0 + i] & 15) << (4 * i), wl |= (uint32_t)(cb[t][c0 + i] >> 4) << (4 * i);
+      const int off = code_off + (sb_tok + t) * (D / 2) + c0 / 2;
+      *reinterpret_cast<uint32_t*>(ub + off) = wu;
+      *reinterpret_cast<uint32_t*>(lb + off) = wl;
+    }
+  };
+
+  // ---- keys: per channel over the G tokens ----
+  {
+    const int c = tid % D, sl = tid / D;
+    float lo = __builtin_inff(), hi = -__builtin_inff();
+    for (int t = sl; t < G; t += NSL) {
+      const float x = (float)a.k_src[src0 + (int64_t)t * D + c];
+      lo = fminf(lo, x), hi = fmaxf(hi, x);
+    }
+    red[0][sl][c] = lo, red[1][sl][c] = hi;
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < NSL; ++k) lo = fminf(lo, red[0][k][c]), hi = fmaxf(hi, red[1][k][c]);
+    const _Float16 sh = make_scale(lo, hi);
+    const GroupScale gs = group_scale((float)sh, lo);
+    if (sl == 0) {
+      reinterpret_cast<_Float16*>(ub + lay.off_ks())[(sb_tok / G) * D + c] = sh;
+      reinterpret_cast<_Float16*>(ub + lay.off_kz())[(sb_tok / G) * D + c] = (_Float16)lo;
+    }
+    for (int t = sl; t < G; t += NSL) {
+      const Codes cd = encode_fast((float)a.k_src[src0 + (int64_t)t * D + c], gs);
+      cb[t][c] = (uint8_t)((int)cd.u | ((int)(cd.l + 8.0f) << 4));
+    }
+  }
+  __syncthreads();
+  pack_rows(0);
+  __syncthreads();
+  // ---- values: per token over each group of G channels ----
+  if (tid < G * VG) {
+    const int t = tid / VG, vg = tid % VG;
+    const _Float16* xp = a.v_src + src0 + (int64_t)t * D + vg * G;
+    float lo = __builtin_inff(), hi = -__builtin_inff();
+    for (int i = 0; i < G; ++i) {
+      const float x = (float)xp[i];
+      lo = fminf(lo, x), hi = fmaxf(hi, x);
+    }
+    const _Float16 sh = make_scale(lo, hi);
+    const GroupScale gs = group_scale((float)sh, lo);
+    reinterpret_cast<_Float16*>(ub + lay.off_vs())[(sb_tok + t) * VG + vg] = sh;
+    reinterpret_cast<_Float16*>(ub + lay.off_vz())[(sb_tok + t) * VG + vg] = (_Float16)lo;
+    for (int i = 0; i < G; ++i) {
+      const Codes cd = encode_fast((float)xp[i], gs);
+      cb[t][vg * G + i] = (uint8_t)((int)cd.u | ((int)(cd.l + 8.0f) << 4));
+    }
+  }
+  __syncthreads();
+  pack_rows(lay.off_v());
+}
+
+// Buffer move for any head_dim: rows [n_tokens, n_buf) become rows [0, n_buf - n_tokens).  Thread
+// (rl = tid / (D/8), c) moves rows rl, rl + 32, ... of its 16-byte column, four at a time; n_tokens is a
+// multiple of 32, so a row is only overwritten by the thread that read it as a source before.
+template <int D>
+__global__ __launch_bounds__(4 * D) void shift_plain_kernel(ShiftArgs a) {
+  constexpr int COLS = D / 8;
+  const int unit = blockIdx.x;
+  const int b = unit / a.n_kv_heads;
+  _Float16* buf = (blockIdx.y == 0 ? a.k_buf : a.v_buf) + (int64_t)unit * a.buf_cap * D;
+  const int n_keep = a.n_buf[b] - a.n_tokens;
+  const int c = threadIdx.x % COLS, rl = threadIdx.x / COLS;
+  for (int base = rl; base < n_keep; base += 128) {
+    uint4 x[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int r = min(base + 32 * k, n_keep - 1);
+      x[k] = *reinterpret_cast<const uint4*>(buf + (int64_t)(r + a.n_tokens) * D + 8 * c);
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (base + 32 * k < n_keep) *reinterpret_cast<uint4*>(buf + (int64_t)(base + 32 * k) * D + 8 * c) = x[k];
+  }
+}
+
+// Plain layout -> one code per byte and metadata in [token][channel] order (see export_kernel).
+template <int D, int G>
+__global__ __launch_bounds__(256) void export_plain_kernel(ExportArgs a) {
+  constexpr int VG = D / G;
+  const ShapeLayout lay{D, G};
+  const int idx = blockIdx.x * 256 + threadIdx.x;      // one 32-bit word of key codes and one of value codes
+  if (idx >= a.n_tokens * (D / 8)) return;
+  const int tok = idx / (D / 8), c0 = 8 * (idx % (D / 8));
+  const uint8_t* ub = a.upper + physical_group(a, a.unit, tok / kSuper) * lay.upper_bytes();
+  const uint8_t* lb = a.lower + physical_group(a, a.unit, tok / kSuper) * lay.lower_bytes();
+  const int row = (tok % kSuper) * (D / 2) + c0 / 2;
+#pragma unroll
+  for (int kv = 0; kv < 2; ++kv) {
+    const uint32_t wu = *reinterpret_cast<const uint32_t*>(ub + (kv ? lay.off_v() : 0) + row);
+    const uint32_t wl = *reinterpret_cast<const uint32_t*>(lb + (kv ? lay.off_v() : 0) + row);
+    uint8_t* pu = kv ? a.v_u : a.k_u;
+    int8_t* pl = kv ? a.v_l : a.k_l;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (pu) pu[(int64_t)tok * D + c0 + i] = (uint8_t)((wu >> (4 * i)) & 15u);
+      if (pl) pl[(int64_t)tok * D + c0 + i] = (int8_t)((int)((wl >> (4 * i)) & 15u) - 8);
+    }
+  }
+  if (tok % G == 0) {   // key metadata of the token's group: this thread's eight channels
+    const _Float16* ks = reinterpret_cast<const _Float16*>(ub + lay.off_ks()) + ((tok % kSuper) / G) * D;
+    const _Float16* kz = reinterpret_cast<const _Float16*>(ub + lay.off_kz()) + ((tok % kSuper) / G) * D;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if (a.k_s) a.k_s[(int64_t)(tok / G) * D + c0 + i] = ks[c0 + i];
+      if (a.k_z) a.k_z[(int64_t)(tok / G) * D + c0 + i] = kz[c0 + i];
+    }
+  }
+  if (c0 % G == 0) {    // value metadata of the group that starts at this thread's first channel
+    const int vg = c0 / G;
+    if (a.v_s) a.v_s[(int64_t)tok * VG + vg] = reinterpret_cast<const _Float16*>(ub + lay.off_vs())[(tok % kSuper) * VG + vg];
+    if (a.v_z) a.v_z[(int64_t)tok * VG + vg] = reinterpret_cast<const _Float16*>(ub + lay.off_vz())[(tok % kSuper) * VG + vg];
+  }
+}
+
+// Calls f with the compile-time shape that matches (d, g); false if the shape is not built.
+template <typename F>
+bool with_shape(int d, int g, F&& f) {
+#define QS_SHAPE(DD, GG)                                                          \
+  if (d == DD && g == GG) {                                                       \
+    f(std::integral_constant<int, DD>{}, std::integral_constant<int, GG>{});     \
+    return true;                                                                  \
+  }
+  QS_SHAPE(64, 32) QS_SHAPE(64, 64) QS_SHAPE(128, 32) QS_SHAPE(128, 64) QS_SHAPE(256, 32) QS_SHAPE(256, 64) QS_SHAPE(256, 128)
+#undef QS_SHAPE
+  return false;
+}
+
 }  // namespace
 
-bool flush_moves_buffer(int n_groups, int units) { return n_groups == 1 && units < kBulkGroups; }
+bool flush_moves_buffer(int head_dim, int group, int n_groups, int units) {
+  return head_dim == kD && group == kG && n_groups == 1 && units < kBulkGroups;
+}
 
 hipError_t launch_flush(const FlushArgs& a, int batch, hipStream_t s) {
   if (a.n_groups <= 0) return hipSuccess;
   const int units = batch * a.n_kv_heads;
+  if (a.head_dim != kD || a.group != kG) {   // n_groups counts groups of a.group tokens here
+    hipError_t rc = hipErrorInvalidValue;
+    with_shape(a.head_dim, a.group, [&](auto DD, auto GG) {
+      rc = launch(quantize_plain_kernel<decltype(DD)::value, decltype(GG)::value>, dim3(a.n_groups, units), dim3(256), s, a);
+    });
+    return rc;
+  }
   if ((int64_t)a.n_groups * units >= kBulkGroups)
     return launch(quantize_group_kernel, dim3(a.n_groups, units), dim3(256), s, a);
   return launch(flush_kernel, dim3(4 * a.n_groups, units), dim3(256), s, a);
@@ -544,16 +717,27 @@ hipError_t launch_flush(const FlushArgs& a, int batch, hipStream_t s) {
 
 hipError_t launch_shift(const ShiftArgs& a, int batch, hipStream_t s) {
   dim3 grid(batch * a.n_kv_heads, 2);
+  if (a.head_dim == 64) return launch(shift_plain_kernel<64>, grid, dim3(256), s, a);
+  if (a.head_dim == 256) return launch(shift_plain_kernel<256>, grid, dim3(1024), s, a);
+  if (a.n_tokens % 64 != 0) return launch(shift_plain_kernel<128>, grid, dim3(512), s, a);   // groups of 32 tokens
   return launch(shift_kernel, grid, dim3(1024), s, a);
 }
 
 hipError_t launch_append(const AppendArgs& a, int batch, hipStream_t s) {
-  const int chunks = a.n_new * a.n_kv_heads * 16;
+  const int chunks = a.n_new * a.n_kv_heads * (a.head_dim / 8);
   return launch(append_kernel, dim3((chunks + 255) / 256, batch), dim3(256), s, a);
 }
 
 hipError_t launch_export(const ExportArgs& a, hipStream_t s) {
   if (a.n_tokens <= 0) return hipSuccess;
+  if (a.head_dim != kD || a.group != kG) {
+    hipError_t rc = hipErrorInvalidValue;
+    with_shape(a.head_dim, a.group, [&](auto DD, auto GG) {
+      constexpr int D = decltype(DD)::value;
+      rc = launch(export_plain_kernel<D, decltype(GG)::value>, dim3((a.n_tokens * (D / 8) + 255) / 256), dim3(256), s, a);
+    });
+    return rc;
+  }
   const int words = a.n_tokens * kRowDw;
   return launch(export_kernel, dim3((words + 255) / 256), dim3(256), s, a);
 }

@@ -27,6 +27,23 @@ constexpr int kCuWaves = 8, kCuBufItems = 4;
 constexpr int kBulkGroups = 512;   // from this many (group, unit) pairs on, quantization takes the bulk kernel
 constexpr int kBufSplitTok = 64;   // buffer tokens handled by one wave of the attention kernel
 
+// Other shapes than head_dim = group = 128 (head_dim 64 / 128 / 256, group 32 / 64 / 128 with group <=
+// head_dim) keep the quantized region in plain order, cut into "superblocks" of 128 tokens (see
+// quantspec.h).  Byte offsets inside a superblock of the upper array; the lower array holds the key
+// codes at 0 and the value codes at 64 * head_dim.
+constexpr int kSuper = 128;
+struct ShapeLayout {
+  int32_t d, g;
+  __host__ __device__ int vg() const { return d / g; }                       // value groups per token
+  __host__ __device__ int off_v() const { return 64 * d; }                   // value codes
+  __host__ __device__ int off_vs() const { return 128 * d; }                 // value scale, fp16 [128][vg]
+  __host__ __device__ int off_vz() const { return 128 * d + 256 * vg(); }    // value zero
+  __host__ __device__ int off_ks() const { return 128 * d + 512 * vg(); }    // key scale, fp16 [128 / g][d]
+  __host__ __device__ int off_kz() const { return off_ks() + (kSuper / g) * d * 2; }
+  __host__ __device__ int upper_bytes() const { return off_kz() + (kSuper / g) * d * 2; }   // = 128 d + 1024 d / g
+  __host__ __device__ int lower_bytes() const { return 128 * d; }
+};
+
 // Per-sequence lengths travel inside the kernel arguments.
 struct SeqLens {
   int32_t n_quant[QS_MAX_BATCH];
@@ -34,7 +51,8 @@ struct SeqLens {
 };
 
 struct FlushArgs {
-  const _Float16* k_src;   // [B][Hkv][src_stride][128]
+  int32_t head_dim, group;   // 128, 128: the blocked layout and its kernels; else the plain layout
+  const _Float16* k_src;   // [B][Hkv][src_stride][head_dim]
   const _Float16* v_src;
   int64_t src_stride;      // tokens between consecutive units of the source
   uint8_t *upper, *lower;
@@ -48,19 +66,22 @@ struct FlushArgs {
 };
 
 struct ShiftArgs {
+  int32_t head_dim;
   _Float16 *k_buf, *v_buf;
   int32_t n_kv_heads, buf_cap, n_tokens;
   int32_t n_buf[QS_MAX_BATCH];
 };
 
 struct AppendArgs {
-  const _Float16 *k_new, *v_new;   // [B][n_new][Hkv][128]
+  int32_t head_dim;
+  const _Float16 *k_new, *v_new;   // [B][n_new][Hkv][head_dim]
   _Float16 *k_buf, *v_buf;
   int32_t n_kv_heads, buf_cap, n_new;
   int32_t n_buf[QS_MAX_BATCH];
 };
 
 struct ExportArgs {
+  int32_t head_dim, group;
   const uint8_t *upper, *lower;
   const int32_t* group_table;     // see FlushArgs
   int32_t unit, q_cap;
@@ -71,6 +92,7 @@ struct ExportArgs {
 };
 
 struct AttnArgs {
+  int32_t head_dim, group;
   const uint8_t *upper, *lower;
   const int32_t* group_table;     // see FlushArgs
   const _Float16 *k_buf, *v_buf;
@@ -85,8 +107,9 @@ struct AttnArgs {
 };
 
 struct MergeArgs {
+  int32_t head_dim;
   const float *ws_o, *ws_ml;
-  _Float16* out;           // [rows_total][128]
+  _Float16* out;           // [rows_total][head_dim]
   float* lse;              // [rows_total] or null
   int32_t n_split;
 };
@@ -108,7 +131,7 @@ hipError_t launch(K kernel, dim3 grid, dim3 block, hipStream_t s, A args) {
 }
 
 // True if a flush of n_groups groups of `units` units takes the kernel that can also move the buffer.
-bool flush_moves_buffer(int n_groups, int units);
+bool flush_moves_buffer(int head_dim, int group, int n_groups, int units);
 hipError_t launch_flush(const FlushArgs& a, int batch, hipStream_t s);
 hipError_t launch_shift(const ShiftArgs& a, int batch, hipStream_t s);
 hipError_t launch_export(const ExportArgs& a, hipStream_t s);

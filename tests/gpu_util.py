@@ -7,15 +7,18 @@ from oracle import quantspec_oracle as O
 from paper_2502_10424_amd import binding as B
 
 
-def make_device_cache(k, v, n_q_heads, n_buf, q_cap=None, buf_cap=None):
-    """k, v: host fp16 [B, Hkv, T, 128]; the last n_buf[b] tokens go to the buffer, the rest is quantized
-    on the device with qs_quantize_prefill.  n_buf: int or per-sequence list (T - n_buf[b] multiple of 128)."""
+def make_device_cache(k, v, n_q_heads, n_buf, q_cap=None, buf_cap=None, group=128, pool_groups=None):
+    """k, v: host fp16 [B, Hkv, T, D]; the last n_buf[b] tokens go to the buffer, the rest is quantized
+    on the device with qs_quantize_prefill.  n_buf: int or per-sequence list (T - n_buf[b] multiple of group)."""
     bsz, hkv, t, d = k.shape
     nb = [n_buf] * bsz if np.isscalar(n_buf) else list(n_buf)
     tq = [t - x for x in nb]
-    q_cap = max(tq) if q_cap is None else q_cap
+    q_cap = -(-max(tq) // 128) * 128 if q_cap is None else q_cap
     buf_cap = max(max(nb), 1) if buf_cap is None else buf_cap
-    cache = B.KVCache(bsz, n_q_heads, hkv, q_cap, buf_cap)
+    cache = B.KVCache(bsz, n_q_heads, hkv, q_cap, buf_cap, head_dim=d, group=group, pool_groups=pool_groups)
+    if pool_groups is not None:      # a seeded permutation of the pool: every logical group somewhere else
+        perm = np.random.default_rng(pool_groups).permutation(pool_groups)[:cache.group_table.numel()]
+        cache.group_table.copy_(torch.from_numpy(perm.astype(np.int32)).view_as(cache.group_table))
     kd = torch.from_numpy(k).cuda()
     vd = torch.from_numpy(v).cuda()
     if len(set(tq)) == 1:
@@ -68,8 +71,8 @@ def assert_unit_equals_oracle(cache, oc: O.CacheOracle, b, h):
         e = export_unit(cache, b, h, tq)
         for name, ref in (("ku", oc.ku[b][h]), ("kl", oc.kl[b][h]), ("vu", oc.vu[b][h]), ("vl", oc.vl[b][h])):
             assert np.array_equal(e[name], ref), f"{name} differs for unit ({b},{h})"
-        for name, ref in (("ks", oc.ks[b][h]), ("kz", oc.kz[b][h]), ("vs", oc.vs[b][h][:, 0]), ("vz", oc.vz[b][h][:, 0])):
-            assert np.array_equal(e[name].view(np.uint16), ref.view(np.uint16)), f"{name} differs for unit ({b},{h})"
+        for name, ref in (("ks", oc.ks[b][h]), ("kz", oc.kz[b][h]), ("vs", oc.vs[b][h]), ("vz", oc.vz[b][h])):
+            assert np.array_equal(e[name].view(np.uint16).reshape(ref.shape), ref.view(np.uint16)), f"{name} differs for unit ({b},{h})"
     nb = oc.n_buf(b)
     assert np.array_equal(cache.k_buf[b, h, :nb].cpu().numpy().view(np.uint16), oc.kbuf[b][h].view(np.uint16))
     assert np.array_equal(cache.v_buf[b, h, :nb].cpu().numpy().view(np.uint16), oc.vbuf[b][h].view(np.uint16))

@@ -89,7 +89,11 @@ def test_workspace_bytes(B):
     c = _fake_cache(B)
     w1, w5 = B.qs_workspace_bytes(c, 1), B.qs_workspace_bytes(c, 5)
     assert w1 > 0 and w5 == 5 * w1 and w1 % (130 * 4) == 0
-    assert B.qs_workspace_bytes(_fake_cache(B, head_dim=64), 1) == 0
+    assert B.qs_workspace_bytes(_fake_cache(B, head_dim=64), 1) == 0          # group 128 does not divide 64
+    assert B.qs_workspace_bytes(_fake_cache(B, head_dim=96, group=32), 1) == 0
+    w64 = B.qs_workspace_bytes(_fake_cache(B, head_dim=64, group=32), 1)
+    assert w64 > 0 and w64 % (66 * 4) == 0
+    assert B.qs_workspace_bytes(_fake_cache(B, head_dim=256, group=64), 1) % (258 * 4) == 0
     assert B.qs_workspace_bytes(c, 0) == 0 and B.qs_workspace_bytes(c, 17) == 0
 
 
@@ -109,8 +113,14 @@ def test_validation_errors_without_gpu(B):
     assert draft(_fake_cache(B), q=None) == B.QS_ERR_NULL
     assert draft(_fake_cache(B, n_q_heads=7)) == B.QS_ERR_SHAPE
     assert draft(_fake_cache(B, q_cap=1000)) == B.QS_ERR_SHAPE
-    assert draft(_fake_cache(B, head_dim=64)) == B.QS_ERR_UNSUPPORTED
-    assert draft(_fake_cache(B, group=64)) == B.QS_ERR_UNSUPPORTED
+    assert draft(_fake_cache(B, head_dim=64)) == B.QS_ERR_UNSUPPORTED          # whole groups per token row only
+    assert draft(_fake_cache(B, head_dim=96, group=32)) == B.QS_ERR_UNSUPPORTED
+    assert draft(_fake_cache(B, group=16)) == B.QS_ERR_UNSUPPORTED
+    assert draft(_fake_cache(B, head_dim=256, group=256)) == B.QS_ERR_UNSUPPORTED
+    c = _fake_cache(B, head_dim=64, group=32); c._keep[0][0] = 96            # a multiple of the group of 32
+    assert draft(c, wsb=0) == B.QS_ERR_WORKSPACE                                 # i.e. everything else was accepted
+    c = _fake_cache(B, head_dim=64, group=64); c._keep[0][0] = 96
+    assert draft(c) == B.QS_ERR_RANGE
     assert draft(_fake_cache(B, batch=257)) == B.QS_ERR_UNSUPPORTED
     assert draft(_fake_cache(B, lower=0x10008)) == B.QS_ERR_ALIGN
     assert draft(_fake_cache(B), q=0x200004) == B.QS_ERR_ALIGN
