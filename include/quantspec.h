@@ -43,15 +43,18 @@
  *     lower : uint8 [B][Hkv][q_cap/32][4096]   per block
  *               [   0, 2048)  key codes C_L + 8 (0..15), same arrangement as in the upper array
  *               [2048, 4096)  value codes C_L + 8, likewise
- *   Other shapes (D, G) than (128, 128): both arrays are cut into rows of 128 tokens, VG = D/G value groups
- *   per token, 128/G key groups per row:
+ *   Other shapes (D, G) than (128, 128): both arrays are cut into rows of 128 tokens (four blocks of 32), VG = D/G
+ *   value groups per token, 128/G key groups per row.  Codes are packed eight to a 32-bit word (nibble i in bits
+ *   4i .. 4i+3), one word per lane of a 64-lane wave (lane = 16*g + r, g < 4, r < 16) and matrix-core step:
  *     upper : uint8 [B][Hkv][q_cap/128][128*D + 1024*VG]   per row
- *               [0, 64*D)             key codes C_U, 128 token rows of D/2 bytes: byte j of a row holds channel
- *                                     2j in bits 0-3 and channel 2j+1 in bits 4-7
- *               [64*D, 128*D)         value codes C_U, same arrangement
- *               then, each fp16:      value scale S [128][VG], value zero Z [128][VG],
- *                                     key scale S [128/G][D], key zero Z [128/G][D], all in plain order
- *     lower : uint8 [B][Hkv][q_cap/128][128*D]             per row: key codes C_L + 8, then value codes C_L + 8
+ *               block p (p < 4) at 32*D*p:
+ *                 [0, 16*D)           key codes C_U: with KW = min(D/32, 4), word ((t*(D/32/KW) + s/KW)*64 + lane)*KW
+ *                                     + s%KW (t < 2, s < D/32) holds channels 32*s + 8*g + i of token 32*p + 16*t + r
+ *                 [16*D, 32*D)        value codes C_U: word ((n/4)*64 + lane)*4 + n%4 (n < D/16) holds channel
+ *                                     16*n + r of tokens 32*p + 16*(i/4) + 4*g + i%4
+ *               [128*D, ...)          fp16, plain order: value scale S [128][VG], value zero Z [128][VG],
+ *                                     key scale S [128/G][D], key zero Z [128/G][D]
+ *     lower : uint8 [B][Hkv][q_cap/128][128*D]             per row: the codes C_L + 8, arranged as in upper
  *   Paging: by default unit u = b*Hkv + kv_head owns the q_cap/128 consecutive 128-token groups (four
  *   blocks, or one row of the other shapes' layout, each; the unit of paging whatever G is) that start at
  *   group u*(q_cap/128) of both arrays.  With a group table

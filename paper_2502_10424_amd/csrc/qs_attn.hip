@@ -1060,8 +1060,10 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
 // Other shapes than head_dim = group = 128 (plain layout, see quantspec.h).  One wave per workgroup, NRT
 // tiles of 16 query rows, chunks are ranges of 32-token blocks.  The arithmetic is that of the kernels
 // above without their tuning:
-//  * a code c (4 or 8 bits), zero-extended to 16 bits, is the fp16 subnormal c * 2^-24: codes go to LDS
-//    as they are and serve as the A operand of both contractions, exactly;
+//  * the codes lie in memory in the order the lanes of a wave take them as matrix-core operands: a
+//    32-bit word holds the eight codes of one lane for one key step (eight channels of a token) or
+//    one value tile (eight tokens of a channel).  A code c (4 or 8 bits), zero-extended to 16 bits,
+//    is the fp16 subnormal c * 2^-24 and serves as the A operand of both contractions, exactly;
 //  * keys: score = sum_c q_c (mul_c code_c + add_c) with (mul, add) = (S, Z) for the upper plane alone and
 //    (S/16, Z - S/2) for the 8-bit code 16 C_U + C_L + 8.  Once per group of G tokens the products
 //    q_c mul_c (exact in binary32: 11 x 11 bits) are scaled by a power of two per query row and split
@@ -1069,8 +1071,9 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
 //  * values: out_c = sum_t (p_t mul_t) code_tc + sum_t p_t add_t per value group of the channel: the P operand
 //    carries the value scale (and a power of two that follows the largest scale seen, so that it stays
 //    inside fp16), the second sum is kept in binary32 beside the accumulators;
-//  * the full-precision buffer is the same block step with the fp16 rows as "codes", q itself as the
-//    operand and no scales.
+//  * the full-precision buffer is the same block step with the fp16 rows as "codes" (keys straight from
+//    memory, values transposed through LDS), q itself as the operand and no scales.
+// The next block's words are requested before the current block is worked on.
 // ------------------------------------------------------------------------------------------------
 using half4 = _Float16 __attribute__((ext_vector_type(4)));
 
@@ -1083,15 +1086,41 @@ __device__ __forceinline__ int64_t global_row(const AttnArgs& a, int b, int kvh,
 __device__ __forceinline__ float pow2(int e) { return __builtin_bit_cast(float, (uint32_t)(127 + e) << 23); }   // -126 <= e <= 127
 __device__ __forceinline__ int exponent_of(float x) { return (int)((__builtin_bit_cast(uint32_t, x) >> 23) & 255u) - 127; }
 
+// The eight codes of a word (C_U, or 16*C_U + C_L + 8 from the words of both planes) as 16-bit numbers in
+// nibble order: the matrix-core operand of the lane.
+template <bool VERIFY>
+__device__ __forceinline__ half8 code_operand(uint32_t u, uint32_t lw) {
+  uint32_t even, odd;   // byte k: the code in nibble 2k / 2k+1
+  if (VERIFY) {
+    even = ((u << 4) & 0xF0F0F0F0u) | (lw & 0x0F0F0F0Fu);
+    odd = (u & 0xF0F0F0F0u) | ((lw >> 4) & 0x0F0F0F0Fu);
+  } else {
+    even = u & 0x0F0F0F0Fu;
+    odd = (u >> 4) & 0x0F0F0F0Fu;
+  }
+  u32x4 w;   // bytes (even.k, 0, odd.k, 0)
+  w[0] = __builtin_amdgcn_perm(odd, even, 0x0c040c00u);
+  w[1] = __builtin_amdgcn_perm(odd, even, 0x0c050c01u);
+  w[2] = __builtin_amdgcn_perm(odd, even, 0x0c060c02u);
+  w[3] = __builtin_amdgcn_perm(odd, even, 0x0c070c03u);
+  return as_half8(w);
+}
+
 template <int D, int G, bool VERIFY, int NRT>
-__global__ __launch_bounds__(64) void attn_plain_kernel(AttnArgs a) {
+__global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnArgs a) {
   constexpr int KS = D / 32, NT = D / 16, VG = D / G;
-  constexpr int KSTRIDE = D + 8, VSTRIDE = 40;        // 16-bit elements per LDS row (padding keeps 16- / 8-byte accesses aligned)
+  constexpr int KW = KS < 4 ? KS : 4, KQ = KS / KW;   // key words a lane holds side by side, and how many such runs
+  constexpr int PL = VERIFY ? 2 : 1;                  // planes read
+  constexpr int VSTRIDE = 40;                         // 16-bit elements per LDS row (keeps 8-byte reads aligned)
   constexpr int kEvFloor = -40;                       // below every value scale that is not zero (2^-24 / 16)
-  __shared__ uint16_t kt[32][KSTRIDE];                // keys of the block, [token][channel]
-  __shared__ uint16_t vt[D][VSTRIDE];                 // values of the block, [channel][token]
+  // LDS of the one wave: the two operands hi, lo of every (row tile, key step) for the quantized region, one
+  // 16-byte slot per lane (a lane reads back what it wrote itself); or the values of a buffer block, [channel][token]
+  constexpr int kQBytes = 2 * NRT * KS * 64 * 16, kVtBytes = D * VSTRIDE * 2;
+  __shared__ __attribute__((aligned(16))) uint8_t lds[kQBytes > kVtBytes ? kQBytes : kVtBytes];
+  uint16_t (*vt)[VSTRIDE] = reinterpret_cast<uint16_t (*)[VSTRIDE]>(lds);
   const ShapeLayout lay{D, G};
   const int lane = threadIdx.x & 63, rho = lane & 15, g = lane >> 4;
+  half8* q_lds = reinterpret_cast<half8*>(lds) + lane;   // operand (part, rt, s) at [((part * NRT + rt) * KS + s) * 64]
   const int unit = blockIdx.x, split = blockIdx.y, row0 = blockIdx.z * 16 * NRT;
   const int b = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   const int nb = a.len.n_buf[b];
@@ -1113,8 +1142,8 @@ __global__ __launch_bounds__(64) void attn_plain_kernel(AttnArgs a) {
     qp[rt] = a.q + (((int64_t)b * a.nq + qi) * a.n_q_heads + head) * D + 8 * g;
     vis[rt] = valid[rt] ? nb - a.nq + qi + 1 : 0;
   }
-  // operands of the query rows for the current group of keys, see above
-  half8 qhi[NRT][KS], qlo[NRT][KS];
+  // operands of the query rows: q itself for the buffer (registers), hi and lo for the current group of keys (LDS)
+  half8 qhi[NRT][KS];
   float sc[NRT], bias[NRT];
   auto load_q = [&](int rt, int s) {
     u32x4 w = ldg128(qp[rt] + 32 * s);
@@ -1129,43 +1158,56 @@ __global__ __launch_bounds__(64) void attn_plain_kernel(AttnArgs a) {
       sc[rt] = a.c0, bias[rt] = 0.f;
     }
   };
-  auto scaled_q = [&](const uint8_t* ub, int key_group) {
-    half8 sh[KS], zh[KS];
+  // |q| of a row never exceeds 2^(eq + 1)
+  int eq[NRT];
+#pragma unroll
+  for (int rt = 0; rt < NRT; ++rt) {
+    float qmax = 0.f;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-      sh[s] = as_half8(ldg128(ub + lay.off_ks() + (key_group * D + 32 * s + 8 * g) * 2));
-      zh[s] = as_half8(ldg128(ub + lay.off_kz() + (key_group * D + 32 * s + 8 * g) * 2));
+      const half8 qv = load_q(rt, s);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) qmax = fmaxf(qmax, __builtin_fabsf((float)qv[i]));
     }
+    eq[rt] = max(exponent_of(group_max(qmax)), -40);
+  }
+  auto scaled_q = [&](const uint8_t* row, int key_group) {
+    const uint8_t* sp = row + lay.off_ks() + (key_group * D + 8 * g) * 2;
+    const uint8_t* zp = row + lay.off_kz() + (key_group * D + 8 * g) * 2;
+    half8 sh[KS];
+    float smax = 0.f;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      sh[s] = as_half8(ldg128(sp + 64 * s));
+#pragma unroll
+      for (int i = 0; i < 8; ++i) smax = fmaxf(smax, (float)sh[s][i]);
+    }
+    // the largest key scale of the group, over all channels: the lanes of a row of 16 hold the same channels
+    const int es = max(exponent_of(group_max(smax)), -40) - (VERIFY ? 4 : 0);
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt) {
-      float t[KS][8];
-      float amax = 0.f, bsum = 0.f;
+      // every product q * mul is below 2^(eq + es + 2): 2^up brings that bound to 2^14
+      const int e = eq[rt] + es;
+      const float up = pow2(12 - e) * (VERIFY ? 0.0625f : 1.0f);
+      float bsum = 0.f;
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
-        const half8 qv = load_q(rt, s);
+        const half8 zh = as_half8(ldg128(zp + 64 * s)), qv = load_q(rt, s);
+        half8 h8, l8;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          const float sf = (float)sh[s][i], zf = (float)zh[s][i], qf = (float)qv[i];
-          const float mul = VERIFY ? sf * 0.0625f : sf;
-          const float add = VERIFY ? __builtin_fmaf(-0.5f, sf, zf) : zf;
-          t[s][i] = qf * mul;
-          amax = fmaxf(amax, __builtin_fabsf(t[s][i]));
+          const float sf = (float)sh[s][i], qf = (float)qv[i];
+          const float add = VERIFY ? __builtin_fmaf(-0.5f, sf, (float)zh[i]) : (float)zh[i];
           bsum = __builtin_fmaf(qf, add, bsum);
-        }
-      }
-      // 2^up brings the row's largest product into [2^13, 2^14); a row of zeros keeps any scale
-      const int ea = max(exponent_of(group_max(amax)), -100);
-      const float up = pow2(13 - ea);
-#pragma unroll
-      for (int s = 0; s < KS; ++s)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const float th = t[s][i] * up;
+          const float th = qf * (sf * up);          // both products exact: 11 x 11 bits and a power of two
           const _Float16 hi = (_Float16)th;
-          qhi[rt][s][i] = hi;
-          qlo[rt][s][i] = (_Float16)(th - (float)hi);
+          h8[i] = hi;
+          l8[i] = (_Float16)(th - (float)hi);
         }
-      sc[rt] = a.c0 * pow2(ea - 13 + 24);   // undoes 2^up and the 2^-24 of a code read as a subnormal
+        q_lds[((0 * NRT + rt) * KS + s) * 64] = h8;
+        q_lds[((1 * NRT + rt) * KS + s) * 64] = l8;
+      }
+      sc[rt] = a.c0 * pow2(e - 12 + 24);   // undoes 2^up and the 2^-24 of a code read as a subnormal
       bias[rt] = a.c0 * group_sum(bsum);
     }
   };
@@ -1182,60 +1224,48 @@ __global__ __launch_bounds__(64) void attn_plain_kernel(AttnArgs a) {
     for (int n = 0; n < NT; ++n) o[rt][n] = (float4v){0.f, 0.f, 0.f, 0.f};
   }
 
-  // ---- filling the tiles ----
-  // keys: lane (cg, tg) takes channels 8*cg .. of tokens tg*TPL .. (one 32-bit word of eight codes per token)
-  constexpr int CGS = D / 8, TPL = 32 * CGS / 64;
-  const int cg = lane % CGS, tg = lane / CGS;
-  // values: lane (tok, half) takes D/2 channels of one token
-  const int vtok = lane & 31, vhalf = lane >> 5;
-  // the eight codes of a word (C_U, or 16*C_U + C_L + 8) as 16-bit numbers, two to a word, in channel order
-  auto eight = [](uint32_t u, uint32_t lw, uint32_t (&w)[4]) {
-    uint32_t even, odd;   // byte k: the code of channel 2k / 2k+1
-    if (VERIFY) {
-      even = ((u << 4) & 0xF0F0F0F0u) | (lw & 0x0F0F0F0Fu);
-      odd = (u & 0xF0F0F0F0u) | ((lw >> 4) & 0x0F0F0F0Fu);
-    } else {
-      even = u & 0x0F0F0F0Fu;
-      odd = (u >> 4) & 0x0F0F0F0Fu;
-    }
-#pragma unroll
-    for (int k = 0; k < 4; ++k) w[k] = ((even >> (8 * k)) & 0xFFu) | (((odd >> (8 * k)) & 0xFFu) << 16);
+  // ---- a block of the quantized region as it comes from memory ----
+  struct Raw {
+    uint32_t k[PL][2][KS];      // key words of the two 16-token tiles
+    uint32_t v[PL][NT];         // value words
   };
-  auto fill_quantized = [&](const uint8_t* ub, const uint8_t* lb, int st0) {
+  auto load_raw = [&](int blk, Raw& r) {
+    const int64_t pg = physical_group(a, unit, (32 * blk) / kSuper);
+    const int st0 = (32 * blk) % kSuper;
+    const uint8_t* row = a.upper + pg * lay.upper_bytes();
 #pragma unroll
-    for (int i = 0; i < TPL; ++i) {   // keys
-      const int t = tg * TPL + i, off = (st0 + t) * (D / 2) + 4 * cg;
-      const uint32_t u = *reinterpret_cast<const uint32_t*>(ub + off);
-      const uint32_t lw = VERIFY ? *reinterpret_cast<const uint32_t*>(lb + off) : 0u;
-      uint32_t w[4];
-      eight(u, lw, w);
-      *reinterpret_cast<u32x4*>(&kt[t][8 * cg]) = (u32x4){w[0], w[1], w[2], w[3]};
-    }
-    const int off = lay.off_v() + (st0 + vtok) * (D / 2) + vhalf * (D / 4);
+    for (int pl = 0; pl < PL; ++pl) {
+      const uint8_t* base = pl == 0 ? row : a.lower + pg * lay.lower_bytes();
+      const uint8_t* kp = base + lay.off_k(st0 / 32);
+      const uint8_t* vp = base + lay.off_v(st0 / 32);
 #pragma unroll
-    for (int k = 0; k < D / 16; ++k) {   // values: word k of this lane's half row = channels ch0 ..
-      const int ch0 = vhalf * (D / 2) + 8 * k;
-      const uint32_t u = *reinterpret_cast<const uint32_t*>(ub + off + 4 * k);
-      const uint32_t lw = VERIFY ? *reinterpret_cast<const uint32_t*>(lb + off + 4 * k) : 0u;
-      uint32_t w[4];
-      eight(u, lw, w);
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        vt[ch0 + 2 * e][vtok] = (uint16_t)(w[e] & 0xFFFFu);
-        vt[ch0 + 2 * e + 1][vtok] = (uint16_t)(w[e] >> 16);
+        for (int sq = 0; sq < KQ; ++sq) {
+          const uint8_t* src = kp + (((t * KQ + sq) * 64 + lane) * KW) * 4;
+          if constexpr (KW == 4) {
+            const u32x4 w = ldg128_stream(src);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r.k[pl][t][4 * sq + i] = w[i];
+          } else {
+            const uint2 w = *reinterpret_cast<const uint2*>(src);
+            r.k[pl][t][0] = w.x, r.k[pl][t][1] = w.y;
+          }
+        }
+#pragma unroll
+      for (int nq = 0; nq < NT / 4; ++nq) {
+        const u32x4 w = ldg128_stream(vp + (nq * 64 + lane) * 16);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r.v[pl][4 * nq + i] = w[i];
       }
     }
   };
+
   const uint16_t* kb = reinterpret_cast<const uint16_t*>(a.k_buf) + (int64_t)unit * a.buf_cap * D;
   const uint16_t* vb = reinterpret_cast<const uint16_t*>(a.v_buf) + (int64_t)unit * a.buf_cap * D;
-  auto fill_buffer = [&](int blk) {   // rows past the end are clamped here and masked below
-    const int t0 = 32 * blk;
-#pragma unroll
-    for (int i = 0; i < TPL; ++i) {
-      const int t = tg * TPL + i, tok = min(t0 + t, nb - 1);
-      *reinterpret_cast<u32x4*>(&kt[t][8 * cg]) = ldg128(kb + (int64_t)tok * D + 8 * cg);
-    }
-    const int tok = min(t0 + vtok, nb - 1);
+  const int vtok = lane & 31, vhalf = lane >> 5;   // buffer values: lane (token, half) takes D/2 channels of one token
+  auto fill_values = [&](int blk) {   // rows past the end are clamped here and masked below
+    const int tok = min(32 * blk + vtok, nb - 1);
 #pragma unroll
     for (int k = 0; k < D / 16; ++k) {
       const int ch0 = vhalf * (D / 2) + 8 * k;
@@ -1248,68 +1278,88 @@ __global__ __launch_bounds__(64) void attn_plain_kernel(AttnArgs a) {
     }
   };
 
-  if (!quantized) plain_q();
-  for (int blk = blk0; blk < blk1; ++blk) {
+  // one 32-token block; QUANT (a std::bool_constant): of the quantized region (its words in cur, those of the
+  // next block requested into nxt), else of the buffer
+  auto block_step = [&](int blk, auto QUANT, Raw& cur, Raw& nxt) {
+    constexpr bool quantized = decltype(QUANT)::value;
     const int st0 = (32 * blk) % kSuper;   // first token of the block inside its 128-token row of the layout
-    const uint8_t* ub = nullptr;
-    wave_lds_sync();   // the previous block's LDS reads are done
-    if (quantized) {
-      const int64_t pg = physical_group(a, unit, (32 * blk) / kSuper);
-      ub = a.upper + pg * lay.upper_bytes();
-      if (blk == blk0 || st0 % G == 0) scaled_q(ub, st0 / G);
-      fill_quantized(ub, a.lower + pg * lay.lower_bytes(), st0);
-    } else {
-      fill_buffer(blk);
-    }
-    wave_lds_sync();
-    // ---- scores, in log2 units ----
-    float x[NRT][8], mx[NRT];
-    bool grow = false;
-#pragma unroll
-    for (int rt = 0; rt < NRT; ++rt) {
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        float4v acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-          const half8 ka = as_half8(*reinterpret_cast<const u32x4*>(&kt[16 * t + rho][32 * s + 8 * g]));
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qhi[rt][s], acc, 0, 0, 0);
-          if (quantized) acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qlo[rt][s], acc, 0, 0, 0);
-        }
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-          const int tok = 32 * blk + 16 * t + 4 * g + jj;
-          x[rt][4 * t + jj] = (quantized || tok < vis[rt]) ? __builtin_fmaf(acc[jj], sc[rt], bias[rt]) : -__builtin_inff();
-        }
-      }
-      mx[rt] = group_max(max_of(x[rt]));
-      grow |= mx[rt] > m[rt];
-    }
-    // ---- value scales of this lane's eight tokens (16*t + 4*g + jj), per value group ----
-    float vmul[8][VG], vadd[8][VG];
-    int eb = ev;
-    if (quantized) {
-      float smax = 0.f;
+    uint2 vs[2][VG], vz[2][VG];   // value scale / zero of this lane's tokens 16 t + 4 g .. + 3: four tokens x VG groups
+    if constexpr (quantized) {
+      const uint8_t* row = a.upper + physical_group(a, unit, (32 * blk) / kSuper) * lay.upper_bytes();
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const int tok = st0 + 16 * t + 4 * g;
-        const _Float16* vs = reinterpret_cast<const _Float16*>(ub + lay.off_vs()) + tok * VG;
-        const _Float16* vz = reinterpret_cast<const _Float16*>(ub + lay.off_vz()) + tok * VG;
 #pragma unroll
-        for (int c = 0; c < VG; ++c) {   // 4 tokens x VG groups = VG chunks of four fp16
-          const uint2 ws = *reinterpret_cast<const uint2*>(vs + 4 * c);
-          const uint2 wz = *reinterpret_cast<const uint2*>(vz + 4 * c);
-          const half4 s4 = __builtin_bit_cast(half4, ws), z4 = __builtin_bit_cast(half4, wz);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int idx = 4 * c + e, jj = idx / VG, k = idx % VG;
-            const float sf = (float)s4[e], zf = (float)z4[e];
-            vmul[4 * t + jj][k] = VERIFY ? sf * 0.0625f : sf;
-            vadd[4 * t + jj][k] = VERIFY ? __builtin_fmaf(-0.5f, sf, zf) : zf;
-            smax = fmaxf(smax, vmul[4 * t + jj][k]);
-          }
+        for (int c = 0; c < VG; ++c) {
+          vs[t][c] = *reinterpret_cast<const uint2*>(row + lay.off_vs() + (tok * VG + 4 * c) * 2);
+          vz[t][c] = *reinterpret_cast<const uint2*>(row + lay.off_vz() + (tok * VG + 4 * c) * 2);
         }
       }
+      if (blk + 1 < blk1) load_raw(blk + 1, nxt);
+      if (blk == blk0 || st0 % G == 0) scaled_q(row, st0 / G);
+    } else {
+      wave_lds_sync();   // the previous block's LDS reads are done
+      fill_values(blk);
+      wave_lds_sync();
+    }
+    // ---- scores, in log2 units ----
+    float x[NRT][8], mx[NRT];
+    bool grow = false;
+    float4v acc[NRT][2];
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) acc[rt][0] = acc[rt][1] = (float4v){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      half8 ka[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        if constexpr (quantized)
+          ka[t] = code_operand<VERIFY>(cur.k[0][t][s], cur.k[PL - 1][t][s]);
+        else
+          ka[t] = as_half8(ldg128(kb + (int64_t)min(32 * blk + 16 * t + rho, nb - 1) * D + 32 * s + 8 * g));
+      }
+#pragma unroll
+      for (int rt = 0; rt < NRT; ++rt) {
+        if constexpr (quantized) {
+          const half8 bh = q_lds[((0 * NRT + rt) * KS + s) * 64], bl = q_lds[((1 * NRT + rt) * KS + s) * 64];
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            acc[rt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t], bh, acc[rt][t], 0, 0, 0);
+            acc[rt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t], bl, acc[rt][t], 0, 0, 0);
+          }
+        } else {
+#pragma unroll
+          for (int t = 0; t < 2; ++t) acc[rt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t], qhi[rt][s], acc[rt][t], 0, 0, 0);
+        }
+      }
+    }
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+          const int tok = 32 * blk + 16 * t + 4 * g + jj;
+          x[rt][4 * t + jj] = (quantized || tok < vis[rt]) ? __builtin_fmaf(acc[rt][t][jj], sc[rt], bias[rt]) : -__builtin_inff();
+        }
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      mx[rt] = group_max(max_of(x[rt]));
+      grow |= mx[rt] > m[rt];
+    }
+    // ---- largest value scale of the block ----
+    int eb = ev;
+    if constexpr (quantized) {
+      float smax = 0.f;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int c = 0; c < VG; ++c) {
+          const half4 s4 = __builtin_bit_cast(half4, vs[t][c]);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) smax = fmaxf(smax, (float)s4[e]);
+        }
+      if (VERIFY) smax *= 0.0625f;
       eb = max(exponent_of(group_max(smax)), ev);   // the same in every lane: all lanes of a group of 16 share their tokens
     }
     if (__any(grow) || eb > ev) {   // a running maximum or the scale exponent moves: rescale what is accumulated
@@ -1329,38 +1379,74 @@ __global__ __launch_bounds__(64) void attn_plain_kernel(AttnArgs a) {
       }
     }
     const float pscale = pow2(14 - ev);
-    half8 pb[NRT][VG];
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt) {
       float sum = 0.f;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const float p = __builtin_amdgcn_exp2f(x[rt][j] - m[rt]);
-        sum += p;
-        if (quantized) {
-#pragma unroll
-          for (int k = 0; k < VG; ++k) {
-            zs[rt][k] = __builtin_fmaf(p, vadd[j][k], zs[rt][k]);
-            pb[rt][k][j] = (_Float16)(p * vmul[j][k] * pscale);
-          }
-        } else {
-          pb[rt][0][j] = (_Float16)(p * pscale);
-        }
+        x[rt][j] = __builtin_amdgcn_exp2f(x[rt][j] - m[rt]);
+        sum += x[rt][j];
       }
       l[rt] += sum;
     }
-    // ---- O^T[channel, column] += V^T x p ----
+    // ---- O^T[channel, column] += V^T x p, value group by value group ----
 #pragma unroll
-    for (int n = 0; n < NT; ++n) {
-      const uint16_t* rowp = &vt[16 * n + rho][0];
-      const uint2 lo = *reinterpret_cast<const uint2*>(rowp + 4 * g);
-      const uint2 hi = *reinterpret_cast<const uint2*>(rowp + 16 + 4 * g);
-      const half8 vop = as_half8((u32x4){lo.x, lo.y, hi.x, hi.y});
-      const int k = quantized ? (16 * n) / G : 0;
+    for (int k = 0; k < (quantized ? VG : 1); ++k) {
+      half8 pb[NRT];
+      if constexpr (quantized) {
+        float vmul[8], vadd[8];   // of token j = 4 t + jj of this lane: element (jj * VG + k) of the four-token run
 #pragma unroll
-      for (int rt = 0; rt < NRT; ++rt)
-        o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vop, pb[rt][k], o[rt][n], 0, 0, 0);
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) {
+            const int idx = jj * VG + k;
+            const half4 s4 = __builtin_bit_cast(half4, vs[t][idx / 4]), z4 = __builtin_bit_cast(half4, vz[t][idx / 4]);
+            const float sf = (float)s4[idx % 4], zf = (float)z4[idx % 4];
+            vmul[4 * t + jj] = (VERIFY ? sf * 0.0625f : sf) * pscale;
+            vadd[4 * t + jj] = VERIFY ? __builtin_fmaf(-0.5f, sf, zf) : zf;
+          }
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            zs[rt][k] = __builtin_fmaf(x[rt][j], vadd[j], zs[rt][k]);
+            pb[rt][j] = (_Float16)(x[rt][j] * vmul[j]);
+          }
+      } else {
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt)
+#pragma unroll
+          for (int j = 0; j < 8; ++j) pb[rt][j] = (_Float16)(x[rt][j] * pscale);
+      }
+      constexpr int TILES = NT / VG;   // value tiles per value group (all of them for the buffer)
+#pragma unroll
+      for (int i = 0; i < (quantized ? TILES : NT); ++i) {
+        const int n = quantized ? k * TILES + i : i;
+        half8 vop;
+        if constexpr (quantized) {
+          vop = code_operand<VERIFY>(cur.v[0][n], cur.v[PL - 1][n]);
+        } else {
+          const uint16_t* rowp = &vt[16 * n + rho][0];
+          const uint2 lo = *reinterpret_cast<const uint2*>(rowp + 4 * g);
+          const uint2 hi = *reinterpret_cast<const uint2*>(rowp + 16 + 4 * g);
+          vop = as_half8((u32x4){lo.x, lo.y, hi.x, hi.y});
+        }
+#pragma unroll
+        for (int rt = 0; rt < NRT; ++rt)
+          o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vop, pb[rt], o[rt][n], 0, 0, 0);
+      }
     }
+  };
+  Raw ra, rb;
+  if (quantized) {
+    if (blk0 < blk1) load_raw(blk0, ra);
+    for (int blk = blk0; blk < blk1; blk += 2) {   // the two sets of registers swap roles from block to block
+      block_step(blk, std::true_type{}, ra, rb);
+      if (blk + 1 < blk1) block_step(blk + 1, std::true_type{}, rb, ra);
+    }
+  } else {
+    plain_q();
+    for (int blk = blk0; blk < blk1; ++blk) block_step(blk, std::false_type{}, ra, rb);
   }
   // ---- partial: (m, l) and the unnormalised output row ----
   const int n_split = a.n_split_q + a.n_split_b;

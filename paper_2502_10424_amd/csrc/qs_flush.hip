@@ -558,13 +558,30 @@ __global__ __launch_bounds__(256) void quantize_plain_kernel(FlushArgs a) {
   uint8_t* ub = a.upper + physical_group(a, unit, tq0 / kSuper) * lay.upper_bytes();
   uint8_t* lb = a.lower + physical_group(a, unit, tq0 / kSuper) * lay.lower_bytes();
 
-  auto pack_rows = [&](int code_off) {   // staged codes -> plane rows of D/2 bytes, 8 codes per 32-bit word
-    for (int w = tid; w < G * D / 8; w += 256) {
-      const int t = w / (D / 8), c0 = 8 * (w % (D / 8));
+  // staged codes -> the words of the group's 32-token blocks, in the order the attention kernel's lanes load
+  // them (see ShapeLayout): consecutive threads write consecutive words
+  auto pack = [&](bool values) {
+    constexpr int WPB = 4 * D;   // words per block and kind
+    for (int w = tid; w < (G / 32) * WPB; w += 256) {
+      const int bl = w / WPB, r = w % WPB;
       uint32_t wu = 0, wl = 0;
+      if (!values) {
+        constexpr int KS = D / 32, KW = KS < 4 ? KS : 4, KQ = KS / KW;
+        const int lane = (r / KW) % 64, tsq = r / (KW * 64);
+        const int s = (tsq % KQ) * KW + r % KW, t = tsq / KQ;
+        const int tok = 32 * bl + 16 * t + (lane & 15), c0 = 32 * s + 8 * (lane >> 4);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) wu |= (uint32_t)(cb[t][c0 + i] & 15) << (4 * i), wl |= (uint32_t)(cb[t][c0 + i] >> 4) << (4 * i);
-      const int off = code_off + (sb_tok + t) * (D / 2) + c0 / 2;
+        for (int i = 0; i < 8; ++i) wu |= (uint32_t)(cb[tok][c0 + i] & 15) << (4 * i), wl |= (uint32_t)(cb[tok][c0 + i] >> 4) << (4 * i);
+      } else {
+        const int lane = (r / 4) % 64, n = 4 * (r / 256) + r % 4;
+        const int c = 16 * n + (lane & 15), tok0 = 32 * bl + 4 * (lane >> 4);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const uint32_t code = cb[tok0 + 16 * (j >> 2) + (j & 3)][c];
+          wu |= (code & 15u) << (4 * j), wl |= (code >> 4) << (4 * j);
+        }
+      }
+      const int off = (values ? lay.off_v(sb_tok / 32 + bl) : lay.off_k(sb_tok / 32 + bl)) + 4 * r;
       *reinterpret_cast<uint32_t*>(ub + off) = wu;
       *reinterpret_cast<uint32_t*>(lb + off) = wl;
     }
@@ -594,7 +611,7 @@ __global__ __launch_bounds__(256) void quantize_plain_kernel(FlushArgs a) {
     }
   }
   __syncthreads();
-  pack_rows(0);
+  pack(false);
   __syncthreads();
   // ---- values: per token over each group of G channels ----
   if (tid < G * VG) {
@@ -615,7 +632,7 @@ __global__ __launch_bounds__(256) void quantize_plain_kernel(FlushArgs a) {
     }
   }
   __syncthreads();
-  pack_rows(lay.off_v());
+  pack(true);
 }
 
 // Buffer move for any head_dim: rows [n_tokens, n_buf) become rows [0, n_buf - n_tokens).  Thread
@@ -647,23 +664,30 @@ template <int D, int G>
 __global__ __launch_bounds__(256) void export_plain_kernel(ExportArgs a) {
   constexpr int VG = D / G;
   const ShapeLayout lay{D, G};
-  const int idx = blockIdx.x * 256 + threadIdx.x;      // one 32-bit word of key codes and one of value codes
+  const int idx = blockIdx.x * 256 + threadIdx.x;      // eight channels of one token
   if (idx >= a.n_tokens * (D / 8)) return;
   const int tok = idx / (D / 8), c0 = 8 * (idx % (D / 8));
   const uint8_t* ub = a.upper + physical_group(a, a.unit, tok / kSuper) * lay.upper_bytes();
   const uint8_t* lb = a.lower + physical_group(a, a.unit, tok / kSuper) * lay.lower_bytes();
-  const int row = (tok % kSuper) * (D / 2) + c0 / 2;
-#pragma unroll
-  for (int kv = 0; kv < 2; ++kv) {
-    const uint32_t wu = *reinterpret_cast<const uint32_t*>(ub + (kv ? lay.off_v() : 0) + row);
-    const uint32_t wl = *reinterpret_cast<const uint32_t*>(lb + (kv ? lay.off_v() : 0) + row);
-    uint8_t* pu = kv ? a.v_u : a.k_u;
-    int8_t* pl = kv ? a.v_l : a.k_l;
+  const int p = (tok % kSuper) / 32, tl = tok % 32, t = tl / 16;
+  {   // keys: the eight channels are the eight nibbles of one word
+    const int off = lay.off_k(p) + 4 * lay.k_word(t, 16 * ((c0 / 8) % 4) + tl % 16, c0 / 32);
+    const uint32_t wu = *reinterpret_cast<const uint32_t*>(ub + off);
+    const uint32_t wl = *reinterpret_cast<const uint32_t*>(lb + off);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      if (pu) pu[(int64_t)tok * D + c0 + i] = (uint8_t)((wu >> (4 * i)) & 15u);
-      if (pl) pl[(int64_t)tok * D + c0 + i] = (int8_t)((int)((wl >> (4 * i)) & 15u) - 8);
+      if (a.k_u) a.k_u[(int64_t)tok * D + c0 + i] = (uint8_t)((wu >> (4 * i)) & 15u);
+      if (a.k_l) a.k_l[(int64_t)tok * D + c0 + i] = (int8_t)((int)((wl >> (4 * i)) & 15u) - 8);
     }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {   // values: one word per channel, the token picks the nibble
+    const int c = c0 + i, j = 4 * t + tl % 4;
+    const int off = lay.off_v(p) + 4 * lay.v_word(c / 16, 16 * ((tl % 16) / 4) + c % 16);
+    const uint32_t wu = *reinterpret_cast<const uint32_t*>(ub + off);
+    const uint32_t wl = *reinterpret_cast<const uint32_t*>(lb + off);
+    if (a.v_u) a.v_u[(int64_t)tok * D + c] = (uint8_t)((wu >> (4 * j)) & 15u);
+    if (a.v_l) a.v_l[(int64_t)tok * D + c] = (int8_t)((int)((wl >> (4 * j)) & 15u) - 8);
   }
   if (tok % G == 0) {   // key metadata of the token's group: this thread's eight channels
     const _Float16* ks = reinterpret_cast<const _Float16*>(ub + lay.off_ks()) + ((tok % kSuper) / G) * D;

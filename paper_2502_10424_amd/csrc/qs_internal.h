@@ -29,13 +29,23 @@ constexpr int kBufSplitTok = 64;   // buffer tokens handled by one wave of the a
 
 // Other shapes than head_dim = group = 128 (head_dim 64 / 128 / 256, group 32 / 64 / 128 with group <=
 // head_dim) keep the quantized region in plain order, cut into "superblocks" of 128 tokens (see
-// quantspec.h).  Byte offsets inside a superblock of the upper array; the lower array holds the key
-// codes at 0 and the value codes at 64 * head_dim.
+// quantspec.h).  Byte offsets inside a 128-token row of the upper array; the lower array holds its codes
+// at the same offsets and no metadata.
 constexpr int kSuper = 128;
 struct ShapeLayout {
   int32_t d, g;
   __host__ __device__ int vg() const { return d / g; }                       // value groups per token
-  __host__ __device__ int off_v() const { return 64 * d; }                   // value codes
+  __host__ __device__ int ks() const { return d / 32; }                      // 32-channel steps of a key row
+  __host__ __device__ int kw() const { return ks() < 4 ? ks() : 4; }         // key words a lane holds side by side
+  // codes: four 32-token blocks per row, each 16 d bytes of key codes, then 16 d bytes of value codes
+  __host__ __device__ int off_k(int p) const { return p * 32 * d; }
+  __host__ __device__ int off_v(int p) const { return p * 32 * d + 16 * d; }
+  // 32-bit word of a key block with channels 32 s + 8 g + i (nibble i) of token 16 t + rho, lane = 16 g + rho
+  __host__ __device__ int k_word(int t, int lane, int s) const {
+    return ((t * (ks() / kw()) + s / kw()) * 64 + lane) * kw() + s % kw();
+  }
+  // 32-bit word of a value block with channel 16 n + rho of tokens 16 (j >> 2) + 4 g + (j & 3) (nibble j)
+  __host__ __device__ int v_word(int n, int lane) const { return ((n >> 2) * 64 + lane) * 4 + (n & 3); }
   __host__ __device__ int off_vs() const { return 128 * d; }                 // value scale, fp16 [128][vg]
   __host__ __device__ int off_vz() const { return 128 * d + 256 * vg(); }    // value zero
   __host__ __device__ int off_ks() const { return 128 * d + 512 * vg(); }    // key scale, fp16 [128 / g][d]
