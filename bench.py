@@ -323,7 +323,8 @@ def main():
     ap.add_argument("--steps", type=int, default=1000, help="timed cycles of the headline workload")
     ap.add_argument("--warmup", type=int, default=200, help="untimed cycles of the headline workload before them")
     ap.add_argument("--workload", default="all",
-                    help="'all' (headline mha128k, then the other baseline workloads) or one workload's name")
+                    help="'all' (headline mha128k, then the other baseline workloads), one workload's name, or 'other_shapes' "
+                         "(only the call times of the other (head_dim, group) shapes, for kernel traces)")
     ap.add_argument("--copies", type=int, default=4, help="independent cache copies a single-layer workload rotates over")
     ap.add_argument("--precondition", type=float, default=PRECONDITION_S,
                     help="seconds of the cycle run untimed before the warm-up steps (0 for counter collection runs)")
@@ -348,6 +349,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     B.lib()
+    if args.workload == "other_shapes":
+        print(json.dumps({"other_shapes": other_shapes(torch, B)}), flush=True)
+        return
     names = ALL_WORKLOADS if args.workload == "all" else (args.workload,)
     if args.trace_transient:
         print(json.dumps(trace_transient(torch, B, synth, synth.WORKLOADS[names[0]], args.copies, args.trace_transient)), flush=True)

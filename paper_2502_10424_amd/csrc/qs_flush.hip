@@ -544,19 +544,30 @@ __global__ __launch_bounds__(256) void export_kernel(ExportArgs a) {
 // ------------------------------------------------------------------------------------------------
 template <int D, int G>
 __global__ __launch_bounds__(256) void quantize_plain_kernel(FlushArgs a) {
-  constexpr int NSL = 256 / D;    // token slices of the key pass
+  constexpr int C8 = D / 8;       // 16-byte pieces (eight channels) of a token row
+  constexpr int RPP = 256 / C8;   // token rows the 256 threads cover at a time (at most 32, so never more than G)
   constexpr int VG = D / G;       // value groups per token
-  __shared__ uint8_t cb[G][D];   // staged codes, one element per byte: C_U in the low nibble, C_L + 8 in the high one
-  __shared__ float red[2][NSL][D];
+  constexpr int LPG = G / 8;      // threads that share a value group: consecutive lanes of one wave
+  __shared__ uint8_t cb[G][D];    // staged codes, one element per byte: C_U in the low nibble, C_L + 8 in the high one
+  __shared__ float red[2][RPP][D];
+  __shared__ float kmeta[2][D];   // key scale and zero of the group, per channel
   const ShapeLayout lay{D, G};
   const int grp = blockIdx.x, unit = blockIdx.y;
   const int b = unit / a.n_kv_heads;
   const int tid = threadIdx.x;
+  const int c8 = tid % C8, r0 = tid / C8;          // this thread's piece of the rows r0, r0 + RPP, ...
   const int tq0 = a.n_quant[b] + grp * G;          // destination token offset inside the unit (multiple of G)
-  const int64_t src0 = ((int64_t)unit * a.src_stride + (int64_t)grp * G) * D;
-  const int sb_tok = tq0 % kSuper;                 // first token of the group inside its superblock
+  const int64_t src0 = ((int64_t)unit * a.src_stride + (int64_t)grp * G) * D + 8 * c8;
+  const int sb_tok = tq0 % kSuper;                 // first token of the group inside its 128-token row of the layout
   uint8_t* ub = a.upper + physical_group(a, unit, tq0 / kSuper) * lay.upper_bytes();
   uint8_t* lb = a.lower + physical_group(a, unit, tq0 / kSuper) * lay.lower_bytes();
+  using half8v = _Float16 __attribute__((ext_vector_type(8)));
+  auto stage = [&](int t, const Codes (&cd)[8]) {   // eight codes of row t -> eight staging bytes
+    uint32_t w[2] = {0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w[i >> 2] |= ((uint32_t)cd[i].u | ((uint32_t)(cd[i].l + 8.0f) << 4)) << (8 * (i & 3));
+    *reinterpret_cast<uint2*>(&cb[t][8 * c8]) = make_uint2(w[0], w[1]);
+  };
 
   // staged codes -> the words of the group's 32-token blocks, in the order the attention kernel's lanes load
   // them (see ShapeLayout): consecutive threads write consecutive words
@@ -589,47 +600,59 @@ __global__ __launch_bounds__(256) void quantize_plain_kernel(FlushArgs a) {
 
   // ---- keys: per channel over the G tokens ----
   {
-    const int c = tid % D, sl = tid / D;
-    float lo = __builtin_inff(), hi = -__builtin_inff();
-    for (int t = sl; t < G; t += NSL) {
-      const float x = (float)a.k_src[src0 + (int64_t)t * D + c];
-      lo = fminf(lo, x), hi = fmaxf(hi, x);
-    }
-    red[0][sl][c] = lo, red[1][sl][c] = hi;
-    __syncthreads();
+    float lo[8], hi[8];
 #pragma unroll
-    for (int k = 0; k < NSL; ++k) lo = fminf(lo, red[0][k][c]), hi = fmaxf(hi, red[1][k][c]);
-    const _Float16 sh = make_scale(lo, hi);
-    const GroupScale gs = group_scale((float)sh, lo);
-    if (sl == 0) {
-      reinterpret_cast<_Float16*>(ub + lay.off_ks())[(sb_tok / G) * D + c] = sh;
-      reinterpret_cast<_Float16*>(ub + lay.off_kz())[(sb_tok / G) * D + c] = (_Float16)lo;
+    for (int i = 0; i < 8; ++i) lo[i] = __builtin_inff(), hi[i] = -__builtin_inff();
+    for (int t = r0; t < G; t += RPP) {
+      const half8v x = *reinterpret_cast<const half8v*>(a.k_src + src0 + (int64_t)t * D);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) lo[i] = fminf(lo[i], (float)x[i]), hi[i] = fmaxf(hi[i], (float)x[i]);
     }
-    for (int t = sl; t < G; t += NSL) {
-      const Codes cd = encode_fast((float)a.k_src[src0 + (int64_t)t * D + c], gs);
-      cb[t][c] = (uint8_t)((int)cd.u | ((int)(cd.l + 8.0f) << 4));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) red[0][r0][8 * c8 + i] = lo[i], red[1][r0][8 * c8 + i] = hi[i];
+    __syncthreads();
+    if (tid < D) {
+      float l = red[0][0][tid], h = red[1][0][tid];
+#pragma unroll
+      for (int k = 1; k < RPP; ++k) l = fminf(l, red[0][k][tid]), h = fmaxf(h, red[1][k][tid]);
+      const _Float16 sh = make_scale(l, h);
+      kmeta[0][tid] = (float)sh, kmeta[1][tid] = l;
+      reinterpret_cast<_Float16*>(ub + lay.off_ks())[(sb_tok / G) * D + tid] = sh;
+      reinterpret_cast<_Float16*>(ub + lay.off_kz())[(sb_tok / G) * D + tid] = (_Float16)l;
+    }
+    __syncthreads();
+    GroupScale gs[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) gs[i] = group_scale(kmeta[0][8 * c8 + i], kmeta[1][8 * c8 + i]);
+    for (int t = r0; t < G; t += RPP) {
+      const half8v x = *reinterpret_cast<const half8v*>(a.k_src + src0 + (int64_t)t * D);
+      Codes cd[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) cd[i] = encode_fast((float)x[i], gs[i]);
+      stage(t, cd);
     }
   }
   __syncthreads();
   pack(false);
   __syncthreads();
-  // ---- values: per token over each group of G channels ----
-  if (tid < G * VG) {
-    const int t = tid / VG, vg = tid % VG;
-    const _Float16* xp = a.v_src + src0 + (int64_t)t * D + vg * G;
-    float lo = __builtin_inff(), hi = -__builtin_inff();
-    for (int i = 0; i < G; ++i) {
-      const float x = (float)xp[i];
-      lo = fminf(lo, x), hi = fmaxf(hi, x);
-    }
+  // ---- values: per token over each group of G channels, LPG threads to a group ----
+  for (int t = r0; t < G; t += RPP) {   // the same number of rounds for every thread
+    const half8v x = *reinterpret_cast<const half8v*>(a.v_src + src0 + (int64_t)t * D);
+    float lo = (float)x[0], hi = lo;
+#pragma unroll
+    for (int i = 1; i < 8; ++i) lo = fminf(lo, (float)x[i]), hi = fmaxf(hi, (float)x[i]);
+#pragma unroll
+    for (int m = 1; m < LPG; m <<= 1) lo = fminf(lo, __shfl_xor(lo, m)), hi = fmaxf(hi, __shfl_xor(hi, m));
     const _Float16 sh = make_scale(lo, hi);
     const GroupScale gs = group_scale((float)sh, lo);
-    reinterpret_cast<_Float16*>(ub + lay.off_vs())[(sb_tok + t) * VG + vg] = sh;
-    reinterpret_cast<_Float16*>(ub + lay.off_vz())[(sb_tok + t) * VG + vg] = (_Float16)lo;
-    for (int i = 0; i < G; ++i) {
-      const Codes cd = encode_fast((float)xp[i], gs);
-      cb[t][vg * G + i] = (uint8_t)((int)cd.u | ((int)(cd.l + 8.0f) << 4));
+    if (c8 % LPG == 0) {
+      reinterpret_cast<_Float16*>(ub + lay.off_vs())[(sb_tok + t) * VG + c8 / LPG] = sh;
+      reinterpret_cast<_Float16*>(ub + lay.off_vz())[(sb_tok + t) * VG + c8 / LPG] = (_Float16)lo;
     }
+    Codes cd[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) cd[i] = encode_fast((float)x[i], gs);
+    stage(t, cd);
   }
   __syncthreads();
   pack(true);
