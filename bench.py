@@ -350,7 +350,8 @@ def main():
         sys.exit(1)
     B.lib()
     if args.workload == "other_shapes":
-        print(json.dumps({"other_shapes": other_shapes(torch, B)}), flush=True)
+        # --steps below 100: a few launches per kernel only (counter collection)
+        print(json.dumps({"other_shapes": other_shapes(torch, B, seconds=0.25 if args.steps >= 100 else 0.002)}), flush=True)
         return
     names = ALL_WORKLOADS if args.workload == "all" else (args.workload,)
     if args.trace_transient:

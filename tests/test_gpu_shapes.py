@@ -84,11 +84,11 @@ def test_quantize_and_flush_bit_exact(env, d, g):
 
 
 @pytest.mark.parametrize("d,g", SHAPES)
-@pytest.mark.parametrize("hq,hkv,nq", [(4, 4, 1), (8, 2, 5), (16, 2, 4)])
+@pytest.mark.parametrize("hq,hkv,nq", [(4, 4, 1), (8, 2, 5), (16, 2, 4), (24, 2, 3)])
 def test_attention_parity(env, d, g, hq, hkv, nq):
-    """Draft (upper plane) and verify (both planes, nq causal queries) against the oracle: 1, 20 and 32 query
-    rows per kv-head (one and two row tiles, the second partly empty), ragged lengths, a buffer whose last
-    32-token block is partly filled, several chunks per unit."""
+    """Draft (upper plane) and verify (both planes, nq causal queries) against the oracle: 1, 20, 32 and 36 query
+    rows per kv-head (one and two row tiles, the second partly empty; more than 32 rows: several passes over the
+    unit's blocks), ragged lengths, a buffer whose last 32-token block is partly filled, several chunks per unit."""
     O, U = env["O"], env["U"]
     rng = np.random.default_rng(7 * d + g + hq + nq)
     bsz = 2
@@ -116,6 +116,11 @@ def test_buffer_only_and_paged(env, d, g):
     oc = O.build_cache(k, v, hq, g, 77)
     q = rng.standard_normal((1, nq, hq, d)).astype(np.float16)
     _attn(env, cache, oc, q, 0.11, True, f"({d},{g}) buffer only")
+    k, v = _kv(rng, 2, hkv, 1003, d)      # a long full-precision buffer: many 32-token blocks per chunk, ragged end
+    cache = U.make_device_cache(k, v, hq, 1003, q_cap=0, group=g)
+    oc = O.build_cache(k, v, hq, g, 1003)
+    q = rng.standard_normal((2, nq, hq, d)).astype(np.float16)
+    _attn(env, cache, oc, q, 0.11, True, f"({d},{g}) long buffer only")
     t = 6 * 128 + 50
     k, v = _kv(rng, 2, hkv, t, d)
     nb = [50, 50 + 128]
