@@ -402,6 +402,7 @@ def main():
         result["fp16_baseline"] = fp16_baseline(torch, B, fp16_cache, w, bench.sm_scale, bench.q_draft, bench.q_verify,
                                                 avg["draft"], avg["verify"])
         result["speculation"] = speculation_loop(torch, B, bench.caches[0], w, bench.sm_scale, bench.ws)
+        result["paged_cache"] = paged_cache(torch, B, w, kd, vd, bench.sm_scale, bench.q_draft, bench.q_verify)
         del fp16_cache, kd, vd
     k_host, v_host, sm_scale = bench.k_host, bench.v_host, bench.sm_scale
     workloads = {w.name: head}
@@ -511,6 +512,34 @@ def fp16_baseline(torch, B, cache, w, sm_scale, q_draft, q_verify, draft_us, ver
     res["bytes"] = nbytes
     res["draft_speedup_vs_fp16"] = round(res["1_query"]["us"] / draft_us, 3)
     res["verify_speedup_vs_fp16"] = round(res[f"{q_verify.shape[1]}_queries"]["us"] / verify_us, 3)
+    return res
+
+
+def paged_cache(torch, B, w, kd, vd, sm_scale, q_draft, q_verify, reps=60):
+    """The headline workload once more as a paged cache: the same codes, every 128-token group at a random
+    place of shared pools, found through the group table.  Call times of draft and verify."""
+    groups = w.n_quant // 128
+    pool = w.units * groups
+    c = B.KVCache(w.batch, w.n_q_heads, w.n_kv_heads, w.n_quant, w.n_buf + 8, pool_groups=pool)
+    perm = np.random.default_rng(11).permutation(pool).astype(np.int32)
+    c.group_table.copy_(torch.from_numpy(perm).view_as(c.group_table))
+    B.qs_quantize_prefill(c, kd, vd, w.n_quant)
+    c.k_buf[:, :, :w.n_buf] = kd[:, :, w.n_quant:]
+    c.v_buf[:, :, :w.n_buf] = vd[:, :, w.n_quant:]
+    c.n_quant[:], c.n_buf[:] = w.n_quant, w.n_buf
+    ws = torch.empty(B.qs_workspace_bytes(c, q_verify.shape[1]), dtype=torch.uint8, device=q_draft.device)
+    st, res = c.struct(), {"pool_groups": pool}
+    for tag, fn, q in (("draft_us", B.qs_attn_draft, q_draft), ("verify_us", B.qs_attn_verify, q_verify)):
+        out = torch.empty_like(q)
+        for _ in range(10):
+            fn(st, q, sm_scale, out=out, workspace=ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn(st, q, sm_scale, out=out, workspace=ws)
+        e1.record()
+        torch.cuda.synchronize()
+        res[tag] = round(e0.elapsed_time(e1) * 1e3 / reps, 2)
     return res
 
 

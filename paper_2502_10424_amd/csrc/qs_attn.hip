@@ -472,19 +472,39 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
 
   // Start of chunk-local block j in the upper / lower array.  Contiguous units: blocks follow each
   // other; with a group table every 128-token group (four blocks) is looked up.
+  // The table entries of the three groups the pipeline holds (the one being computed, the next, the one
+  // after) are asked for when a group enters the pipeline, a whole group before its first address is
+  // formed, and are only waited for there: a lookup at the point of use would stop the wave for a trip to
+  // memory eight times per group.
   const bool paged = a.group_table != nullptr;
   const int64_t blk0 = ((int64_t)unit * (a.q_cap / kG) + first) * (kG / kBlkTok);
+  int place[3] = {0, 0, 0};   // paged: where those three groups lie (the same in every lane)
+  int cur_lg = 0;             // fixed ranges: chunk-local number of the group being computed
+  auto look_up = [&](int gi) -> int { return a.group_table[(int64_t)unit * (a.q_cap / kG) + gi]; };
+  auto held = [&](int k) -> int64_t {   // place[k], k in 0..2
+    const int v = k == 0 ? place[0] : k == 1 ? place[1] : place[2];
+    return (int64_t)__builtin_amdgcn_readfirstlane(v);
+  };
   auto block_index = [&](int j) -> int64_t {
     if constexpr (DYN) {   // j: 0..3 the current group, 4..7 the next, 8..11 the one after; none left: the last real one
-      const int sel = j >> 2;
-      int gi = gq[sel];
-      if (sel == 2 && gi < 0) gi = gq[1];
-      if (gi < 0) gi = gq[0];
-      return (paged ? physical_group(a, unit, gi) : (int64_t)unit * (a.q_cap / kG) + gi) * (kG / kBlkTok) + (j & 3);
+      int sel = j >> 2;
+      if (sel == 2 && gq[2] < 0) sel = 1;
+      if (gq[sel] < 0) sel = 0;
+      return (paged ? held(sel) : (int64_t)unit * (a.q_cap / kG) + gq[sel]) * (kG / kBlkTok) + (j & 3);
     } else {
-      return paged ? physical_group(a, unit, first + (j >> 2)) * (kG / kBlkTok) + (j & 3) : blk0 + j;
+      return paged ? held((j >> 2) - cur_lg) * (kG / kBlkTok) + (j & 3) : blk0 + j;
     }
   };
+  if (paged) {
+    if constexpr (DYN) {
+#pragma unroll
+      for (int k = 0; k < 3; ++k)
+        if (gq[k] >= 0) place[k] = look_up(gq[k]);
+    } else {
+#pragma unroll
+      for (int k = 0; k < 3; ++k) place[k] = look_up(first + min(k, n_local - 1));
+    }
+  }
   const int k_off = kOffK + rho * 64 + 16 * g;   // key rows rho and 16 + rho, channels 32g ..
   const int v_off = kOffV + 16 * lane;           // value tile, two halves of 1 KB
   const int m_off = 16 * g;                      // metadata: eight fp16 of lane group g
@@ -777,6 +797,16 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
       gq[0] = gq[1];
       gq[1] = gq[2];
       gq[2] = gq[1] >= 0 ? draw() : -1;
+    }
+    cur_lg = lg + 1;
+    if (paged) {
+      place[0] = place[1];
+      place[1] = place[2];
+      if constexpr (DYN) {
+        if (gq[2] >= 0) place[2] = look_up(gq[2]);
+      } else {
+        place[2] = look_up(first + min(lg + 3, n_local - 1));
+      }
     }
   }
   if constexpr (SINGLE) {   // one token per lane: the row's sums are spread over eight lanes
