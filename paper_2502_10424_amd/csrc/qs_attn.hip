@@ -1257,8 +1257,15 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
     uint32_t k[PL][2][KS];      // key words of the two 16-token tiles
     uint32_t v[PL][NT];         // value words
   };
-  auto load_raw = [&](int blk, Raw& r) {
-    const int64_t pg = physical_group(a, unit, (32 * blk) / kSuper);
+  // Where the 128-token rows of the current block, the next and the one after lie (the same in every lane).
+  // Paged caches: the table entry is asked for two blocks before the block's words are, and waited for there.
+  int place_cur = 0, place_nxt = 0, place_aft = 0;
+  auto look_up = [&](int blk) -> int {
+    const int logical = unit * (a.q_cap / kG) + (32 * min(blk, blk1 - 1)) / kSuper;
+    return a.group_table != nullptr ? a.group_table[logical] : logical;
+  };
+  auto load_raw = [&](int blk, Raw& r, int place) {
+    const int64_t pg = __builtin_amdgcn_readfirstlane(place);
     const int st0 = (32 * blk) % kSuper;
     const uint8_t* row = a.upper + pg * lay.upper_bytes();
 #pragma unroll
@@ -1313,7 +1320,7 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
     const int st0 = (32 * blk) % kSuper;   // first token of the block inside its 128-token row of the layout
     uint2 vs[2][VG], vz[2][VG];   // value scale / zero of this lane's tokens 16 t + 4 g .. + 3: four tokens x VG groups
     if constexpr (quantized) {
-      const uint8_t* row = a.upper + physical_group(a, unit, (32 * blk) / kSuper) * lay.upper_bytes();
+      const uint8_t* row = a.upper + (int64_t)__builtin_amdgcn_readfirstlane(place_cur) * lay.upper_bytes();
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const int tok = st0 + 16 * t + 4 * g;
@@ -1323,7 +1330,7 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
           vz[t][c] = *reinterpret_cast<const uint2*>(row + lay.off_vz() + (tok * VG + 4 * c) * 2);
         }
       }
-      if (blk + 1 < blk1) load_raw(blk + 1, nxt);
+      if (blk + 1 < blk1) load_raw(blk + 1, nxt, place_nxt);
       if (blk == blk0 || st0 % G == 0) scaled_q(row, st0 / G);
     } else {
       wave_lds_sync();   // the previous block's LDS reads are done
@@ -1464,10 +1471,14 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
           o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vop, pb[rt], o[rt][n], 0, 0, 0);
       }
     }
+    if constexpr (quantized) place_cur = place_nxt, place_nxt = place_aft, place_aft = look_up(blk + 3);
   };
   Raw ra, rb;
   if (quantized) {
-    if (blk0 < blk1) load_raw(blk0, ra);
+    if (blk0 < blk1) {
+      place_cur = look_up(blk0), place_nxt = look_up(blk0 + 1), place_aft = look_up(blk0 + 2);
+      load_raw(blk0, ra, place_cur);
+    }
     for (int blk = blk0; blk < blk1; blk += 2) {   // the two sets of registers swap roles from block to block
       block_step(blk, std::true_type{}, ra, rb);
       if (blk + 1 < blk1) block_step(blk + 1, std::true_type{}, rb, ra);
