@@ -428,7 +428,7 @@ __device__ __forceinline__ void write_partial(const AttnArgs& a, RowState<NRT>& 
 // the waves of a workgroup share in LDS (first_claim: the value this wave already drew).  The
 // pipeline looks two groups ahead (block prefetch, key metadata of the next group), so the wave
 // always holds the group it computes and the next two it has drawn.
-template <int NRT, int TAIL, bool VERIFY, bool SINGLE, bool DYN = false>
+template <int NRT, int TAIL, bool VERIFY, bool SINGLE, bool PAGED, bool DYN = false>
 __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, int kvh, int row0, int split,
                                             int* queue = nullptr, int g_base = 0, int g_count = 0, int first_claim = 0) {
   static_assert(!SINGLE || (NRT == 1 && TAIL == 8), "the single-row path is a variant of the one-tile kernel");
@@ -476,7 +476,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   // after) are asked for when a group enters the pipeline, a whole group before its first address is
   // formed, and are only waited for there: a lookup at the point of use would stop the wave for a trip to
   // memory eight times per group.
-  const bool paged = a.group_table != nullptr;
+  constexpr bool paged = PAGED;   // (a kernel of its own: the table entries carried from round to round cost the others a wait)
   const int64_t blk0 = ((int64_t)unit * (a.q_cap / kG) + first) * (kG / kBlkTok);
   int place[3] = {0, 0, 0};   // paged: where those three groups lie (the same in every lane)
   int cur_lg = 0;             // fixed ranges: chunk-local number of the group being computed
@@ -513,15 +513,12 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   struct Blk {
     u32x4 kU[2], kL[2], vU[2], vL[2];   // two 16-token key tiles, two halves of the value tile
     u32x4 vS, vZ;                       // value S / Z of this lane group's eight tokens
-    u32x4 kS, kZ;                       // key S / Z of k-step (block mod 4) of the NEXT group
   };
   // loads of block j (chunk-local); past the end of the chunk the last block is re-read and never used
   auto load_block = [&](Blk& d, int j) {
     const int jc = DYN ? j : min(j, 4 * n_local - 1);
     const int64_t bj = block_index(jc);
     const __amdgpu_buffer_rsrc_t u = block_resource(a.upper + bj * kUpperBlk, kUpperBlk);
-    const __amdgpu_buffer_rsrc_t un = block_resource(
-        a.upper + block_index(DYN ? jc + 4 : min((jc >> 2) + 1, n_local - 1) * 4 + (jc & 3)) * kUpperBlk, kUpperBlk);
     d.kU[0] = ldb128_stream(u, k_off);
     d.kU[1] = ldb128_stream(u, k_off + 1024);
     d.vU[0] = ldb128_stream(u, v_off);
@@ -533,8 +530,6 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
       d.vS = ldb128_stream(u, kOffVS + m_off);
       d.vZ = ldb128_stream(u, kOffVZ + m_off);
     }
-    d.kS = ldb128_stream(un, kOffKS + m_off);
-    d.kZ = ldb128_stream(un, kOffKZ + m_off);
     if (VERIFY) {
       const __amdgpu_buffer_rsrc_t l = block_resource(a.lower + bj * kLowerBlk, kLowerBlk);
       d.kL[0] = ldb128_stream(l, k_off);
@@ -549,6 +544,19 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   // buffers are live at any time).
   constexpr int kAhead = (!VERIFY && kTwoWaves) ? 2 : 1;
   Blk bufA, bufB, bufC, bufD;
+  // Key S / Z of the four k-steps of the NEXT group, asked for at the top of a round and used from its
+  // second block on.  (Fetched with the blocks instead, two of the four crossed the end of the round in
+  // registers that the compiler would not keep in place: it copied them there, behind a wait for every
+  // load in flight, once per group.)
+  u32x4 nkS[4], nkZ[4];
+  auto load_next_meta = [&](int lg) {
+    const uint8_t* nb = a.upper + block_index(DYN ? 4 : min(lg + 1, n_local - 1) * 4) * kUpperBlk;
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+      nkS[s4] = ldg128_stream(nb + s4 * kUpperBlk + kOffKS + m_off);
+      nkZ[s4] = ldg128_stream(nb + s4 * kUpperBlk + kOffKZ + m_off);
+    }
+  };
   // Everything the first group needs first is requested before anything is waited for: as many of its
   // blocks as the loop keeps in flight, and its key metadata.  (All four blocks at once, where the
   // registers allow it, put 35 MB of requests in front of the memory at the start of a 128k-context
@@ -683,7 +691,13 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
         tile_scores<M>(acc[0], acc[1], x[rt]);
       });
     }
-    prep_kstep(P, d.kS, d.kZ);   // one k-step of the next group's query operand
+    // the next group's query operand, spread over the blocks that follow the arrival of its metadata
+    if constexpr (p == 1) prep_kstep(std::integral_constant<int, 0>{}, nkS[0], nkZ[0]);
+    if constexpr (p == 2) {
+      prep_kstep(std::integral_constant<int, 1>{}, nkS[1], nkZ[1]);
+      prep_kstep(std::integral_constant<int, 2>{}, nkS[2], nkZ[2]);
+    }
+    if constexpr (p == 3) prep_kstep(std::integral_constant<int, 3>{}, nkS[3], nkZ[3]);
     half8 pb[NRT];
     if constexpr (SINGLE) {
       pb[0] = single_row_block<VERIFY>(st, x[0], mul[0], cin[0], d.vS[0], d.vZ[0], rho, p == 0 && fresh);
@@ -774,6 +788,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
 
   for (int lg = 0; DYN ? gq[0] >= 0 : lg < n_local; ++lg) {
     const int j = DYN ? 0 : 4 * lg;   // DYN: block numbers are relative to the current group
+    load_next_meta(lg);
     if (kAhead == 2) {
       load_block(bufC, j + 2);
       compute_block(bufA, std::integral_constant<int, 0>{});
@@ -970,7 +985,7 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
 
 // A wave carries NRT tiles of query rows: 16 in each but the last, TAIL (16 or 8) in the last.
 // The kernels with one tile of at most 8 rows run two waves per SIMD, the others one.
-template <int NRT, int TAIL, bool VERIFY, bool SINGLE = false>
+template <int NRT, int TAIL, bool VERIFY, bool SINGLE, bool PAGED>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NRT == 1 && TAIL != 16 ? 2 : 1))) void attn_kernel(AttnArgs a) {
   __shared__ _Float16 vt[kD][kVtStride];   // value-tile transpose of the buffer chunk
   // Dispatch order: unit fastest, every quantized chunk before any buffer chunk.  The planner makes
@@ -981,7 +996,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NRT == 1 && 
   const int split = blockIdx.y;
   const int b = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   if (split < a.n_split_q)
-    quant_chunk<NRT, TAIL, VERIFY, SINGLE>(a, unit, b, kvh, row0, split);
+    quant_chunk<NRT, TAIL, VERIFY, SINGLE, PAGED>(a, unit, b, kvh, row0, split);
   else
     buffer_chunk<NRT>(a, unit, b, kvh, row0, split, vt);
 }
@@ -994,7 +1009,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NRT == 1 && 
 // Each wave still writes one partial for its quantized groups (slot 8*w + wave).  For the kernels
 // with at most 8 query rows per kv-head; the planner guarantees at most four buffer items per
 // workgroup (one transpose tile each).
-template <bool VERIFY, bool SINGLE>
+template <bool VERIFY, bool SINGLE, bool PAGED>
 __global__ __launch_bounds__(64 * kCuWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_kernel_cu(AttnArgs a) {
   __shared__ _Float16 vt[kCuBufItems][kD][kVtStride];
   __shared__ int queue;
@@ -1017,7 +1032,7 @@ __global__ __launch_bounds__(64 * kCuWaves) __attribute__((amdgpu_waves_per_eu(2
     buffer_chunk<1>(a, unit, b, kvh, 0, a.n_split_q + w + n_wg * item, vt[item]);
     c = draw();
   }
-  quant_chunk<1, 8, VERIFY, SINGLE, true>(a, unit, b, kvh, 0, kCuWaves * w + wave, &queue, g0, g1 - g0, c);
+  quant_chunk<1, 8, VERIFY, SINGLE, PAGED, true>(a, unit, b, kvh, 0, kCuWaves * w + wave, &queue, g0, g1 - g0, c);
 }
 
 // Merge of the per-chunk partials (Appendix E): M = max m_i, L = sum l_i 2^(m_i - M),
@@ -1571,12 +1586,23 @@ hipError_t launch_attn_plain(const AttnArgs& a, int batch, bool verify, hipStrea
                 : launch(attn_plain_kernel<D, G, false, 1>, grid, dim3(64), s, a);
 }
 
+template <int NRT, int TAIL, bool VERIFY, bool SINGLE = false>
+hipError_t launch_attn_kernel(const AttnArgs& a, dim3 grid, hipStream_t s) {
+  return a.group_table != nullptr ? launch(attn_kernel<NRT, TAIL, VERIFY, SINGLE, true>, grid, dim3(64), s, a)
+                                  : launch(attn_kernel<NRT, TAIL, VERIFY, SINGLE, false>, grid, dim3(64), s, a);
+}
+
+template <bool VERIFY, bool SINGLE>
+hipError_t launch_attn_cu(const AttnArgs& a, dim3 grid, hipStream_t s) {
+  return a.group_table != nullptr ? launch(attn_kernel_cu<VERIFY, SINGLE, true>, grid, dim3(64 * kCuWaves), s, a)
+                                  : launch(attn_kernel_cu<VERIFY, SINGLE, false>, grid, dim3(64 * kCuWaves), s, a);
+}
+
 template <int NRT, int TAIL>
 hipError_t launch_attn_tiles(const AttnArgs& a, int batch, bool verify, hipStream_t s) {
   constexpr int rows = 16 * (NRT - 1) + TAIL;
   dim3 grid(batch * a.n_kv_heads, a.n_split_q + a.n_split_b, (a.n_rows + rows - 1) / rows);
-  return verify ? launch(attn_kernel<NRT, TAIL, true>, grid, dim3(64), s, a)
-                : launch(attn_kernel<NRT, TAIL, false>, grid, dim3(64), s, a);
+  return verify ? launch_attn_kernel<NRT, TAIL, true>(a, grid, s) : launch_attn_kernel<NRT, TAIL, false>(a, grid, s);
 }
 
 }  // namespace
@@ -1593,14 +1619,14 @@ hipError_t launch_attn(const AttnArgs& a, int batch, bool verify, hipStream_t s)
     return hipErrorInvalidValue;
   }
   if (a.cu_wgs > 0) {   // at most 8 rows and enough groups: one workgroup per compute unit, groups drawn dynamically
-    dim3 grid(batch * a.n_kv_heads, a.cu_wgs, 1), block(64 * kCuWaves);
-    if (verify) return launch(attn_kernel_cu<true, false>, grid, block, s, a);
-    if (a.n_rows == 1) return launch(attn_kernel_cu<false, true>, grid, block, s, a);
-    return launch(attn_kernel_cu<false, false>, grid, block, s, a);
+    dim3 grid(batch * a.n_kv_heads, a.cu_wgs, 1);
+    if (verify) return launch_attn_cu<true, false>(a, grid, s);
+    if (a.n_rows == 1) return launch_attn_cu<false, true>(a, grid, s);
+    return launch_attn_cu<false, false>(a, grid, s);
   }
   if (a.n_rows == 1 && !verify) {   // one query row per kv-head: one token per lane in the softmax
     dim3 grid(batch * a.n_kv_heads, a.n_split_q + a.n_split_b, 1);
-    return launch(attn_kernel<1, 8, false, true>, grid, dim3(64), s, a);
+    return launch_attn_kernel<1, 8, false, true>(a, grid, s);
   }
   if (a.n_rows <= 8) return launch_attn_tiles<1, 8>(a, batch, verify, s);
   if (a.n_rows <= 16) return launch_attn_tiles<1, 16>(a, batch, verify, s);
