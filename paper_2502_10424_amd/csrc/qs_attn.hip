@@ -445,10 +445,13 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
     v = __builtin_amdgcn_readfirstlane(v);
     return v < g_count ? g_base + v : -1;
   };
+  // A wave holds the group it computes and the next one (blocks and key metadata are asked for one group
+  // ahead); with a group table also the one after, whose table entry must be on its way a group earlier.
+  constexpr bool kThreeHeld = PAGED;
   if constexpr (DYN) {
     gq[0] = first_claim < g_count ? g_base + first_claim : -1;
     gq[1] = gq[0] >= 0 ? draw() : -1;
-    gq[2] = gq[1] >= 0 ? draw() : -1;
+    if (kThreeHeld) gq[2] = gq[1] >= 0 ? draw() : -1;
     n_local = gq[0] >= 0 ? 1 : 0;
   } else {
     first = (int)((int64_t)split * n_groups / a.n_split_q);
@@ -486,9 +489,8 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
     return (int64_t)__builtin_amdgcn_readfirstlane(v);
   };
   auto block_index = [&](int j) -> int64_t {
-    if constexpr (DYN) {   // j: 0..3 the current group, 4..7 the next, 8..11 the one after; none left: the last real one
+    if constexpr (DYN) {   // j: 0..3 the current group, 4..7 the next; none left: the current one
       int sel = j >> 2;
-      if (sel == 2 && gq[2] < 0) sel = 1;
       if (gq[sel] < 0) sel = 0;
       return (paged ? held(sel) : (int64_t)unit * (a.q_cap / kG) + gq[sel]) * (kG / kBlkTok) + (j & 3);
     } else {
@@ -810,8 +812,12 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
     }
     if constexpr (DYN) {
       gq[0] = gq[1];
-      gq[1] = gq[2];
-      gq[2] = gq[1] >= 0 ? draw() : -1;
+      if (kThreeHeld) {
+        gq[1] = gq[2];
+        gq[2] = gq[1] >= 0 ? draw() : -1;
+      } else {
+        gq[1] = gq[0] >= 0 ? draw() : -1;
+      }
     }
     cur_lg = lg + 1;
     if (paged) {
