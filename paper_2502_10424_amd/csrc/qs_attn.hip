@@ -1220,7 +1220,7 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
     }
     eq[rt] = max(exponent_of(group_max(qmax)), -40);
   }
-  auto scaled_q = [&](const uint8_t* row, int key_group) {
+  auto scaled_q = [&](const uint8_t* row, int key_group) __attribute__((always_inline)) {
     const uint8_t* sp = row + lay.off_ks() + (key_group * D + 8 * g) * 2;
     const uint8_t* zp = row + lay.off_kz() + (key_group * D + 8 * g) * 2;
     half8 sh[KS];
@@ -1280,13 +1280,13 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
   };
   // Where the 128-token rows of the current block, the next and the one after lie (the same in every lane).
   // Paged caches: the table entry is asked for two blocks before the block's words are, and waited for there.
+  // (The loop exists twice, with and without a table: table entries carried from step to step would cost the
+  // cache without one a wait for every load in flight at the end of each step.)
   int place_cur = 0, place_nxt = 0, place_aft = 0;
-  auto look_up = [&](int blk) -> int {
-    const int logical = unit * (a.q_cap / kG) + (32 * min(blk, blk1 - 1)) / kSuper;
-    return a.group_table != nullptr ? a.group_table[logical] : logical;
-  };
-  auto load_raw = [&](int blk, Raw& r, int place) {
-    const int64_t pg = __builtin_amdgcn_readfirstlane(place);
+  auto logical_row = [&](int blk) -> int { return unit * (a.q_cap / kG) + (32 * min(blk, blk1 - 1)) / kSuper; };
+  auto look_up = [&](int blk) -> int { return a.group_table[logical_row(blk)]; };
+  auto load_raw = [&](int blk, Raw& r, int place) __attribute__((always_inline)) {
+    const int64_t pg = place;
     const int st0 = (32 * blk) % kSuper;
     const uint8_t* row = a.upper + pg * lay.upper_bytes();
 #pragma unroll
@@ -1336,12 +1336,16 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
 
   // one 32-token block; QUANT (a std::bool_constant): of the quantized region (its words in cur, those of the
   // next block requested into nxt), else of the buffer
-  auto block_step = [&](int blk, auto QUANT, Raw& cur, Raw& nxt) {
-    constexpr bool quantized = decltype(QUANT)::value;
+  auto block_step = [&](int blk, auto QUANT, auto PAGED, Raw& cur, Raw& nxt) __attribute__((always_inline)) {
+    constexpr bool quantized = decltype(QUANT)::value, paged = decltype(PAGED)::value;
     const int st0 = (32 * blk) % kSuper;   // first token of the block inside its 128-token row of the layout
     uint2 vs[2][VG], vz[2][VG];   // value scale / zero of this lane's tokens 16 t + 4 g .. + 3: four tokens x VG groups
     if constexpr (quantized) {
-      const uint8_t* row = a.upper + (int64_t)__builtin_amdgcn_readfirstlane(place_cur) * lay.upper_bytes();
+      const int64_t here = paged ? __builtin_amdgcn_readfirstlane(place_cur) : logical_row(blk);
+      const uint8_t* row = a.upper + here * lay.upper_bytes();
+      // The query operands of a new key group first: what they wait for (their own loads, and with them this
+      // block's words) is needed now anyway; after the request for the next block they would wait for that too.
+      if (blk == blk0 || st0 % G == 0) scaled_q(row, st0 / G);
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         const int tok = st0 + 16 * t + 4 * g;
@@ -1351,8 +1355,10 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
           vz[t][c] = *reinterpret_cast<const uint2*>(row + lay.off_vz() + (tok * VG + 4 * c) * 2);
         }
       }
-      if (blk + 1 < blk1) load_raw(blk + 1, nxt, place_nxt);
-      if (blk == blk0 || st0 % G == 0) scaled_q(row, st0 / G);
+      // head_dim 256, both planes: keep the small loads above ahead of the next block's 32 (measured: 193 vs 329 us
+      // at group 32, 115 vs 127 us at group 128; group 64 and the other shapes are 5 - 15 % faster with the order left to the compiler)
+      if constexpr (D == 256 && VERIFY && G != 64) __builtin_amdgcn_sched_barrier(0);
+      if (blk + 1 < blk1) load_raw(blk + 1, nxt, paged ? __builtin_amdgcn_readfirstlane(place_nxt) : logical_row(blk + 1));
     } else {
       wave_lds_sync();   // the previous block's LDS reads are done
       fill_values(blk);
@@ -1492,21 +1498,29 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
           o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vop, pb[rt], o[rt][n], 0, 0, 0);
       }
     }
-    if constexpr (quantized) place_cur = place_nxt, place_nxt = place_aft, place_aft = look_up(blk + 3);
+    if constexpr (quantized && paged) place_cur = place_nxt, place_nxt = place_aft, place_aft = look_up(blk + 3);
   };
   Raw ra, rb;
   if (quantized) {
-    if (blk0 < blk1) {
-      place_cur = look_up(blk0), place_nxt = look_up(blk0 + 1), place_aft = look_up(blk0 + 2);
-      load_raw(blk0, ra, place_cur);
-    }
-    for (int blk = blk0; blk < blk1; blk += 2) {   // the two sets of registers swap roles from block to block
-      block_step(blk, std::true_type{}, ra, rb);
-      if (blk + 1 < blk1) block_step(blk + 1, std::true_type{}, rb, ra);
+    if (a.group_table != nullptr) {
+      if (blk0 < blk1) {
+        place_cur = look_up(blk0), place_nxt = look_up(blk0 + 1), place_aft = look_up(blk0 + 2);
+        load_raw(blk0, ra, __builtin_amdgcn_readfirstlane(place_cur));
+      }
+      for (int blk = blk0; blk < blk1; blk += 2) {   // the two sets of registers swap roles from block to block
+        block_step(blk, std::true_type{}, std::true_type{}, ra, rb);
+        if (blk + 1 < blk1) block_step(blk + 1, std::true_type{}, std::true_type{}, rb, ra);
+      }
+    } else {
+      if (blk0 < blk1) load_raw(blk0, ra, logical_row(blk0));
+      for (int blk = blk0; blk < blk1; blk += 2) {
+        block_step(blk, std::true_type{}, std::false_type{}, ra, rb);
+        if (blk + 1 < blk1) block_step(blk + 1, std::true_type{}, std::false_type{}, rb, ra);
+      }
     }
   } else {
     plain_q();
-    for (int blk = blk0; blk < blk1; ++blk) block_step(blk, std::false_type{}, ra, rb);
+    for (int blk = blk0; blk < blk1; ++blk) block_step(blk, std::false_type{}, std::false_type{}, ra, rb);
   }
   // ---- partial: (m, l) and the unnormalised output row ----
   const int n_split = a.n_split_q + a.n_split_b;
