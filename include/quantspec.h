@@ -44,8 +44,9 @@
  *               [   0, 2048)  key codes C_L + 8 (0..15), same arrangement as in the upper array
  *               [2048, 4096)  value codes C_L + 8, likewise
  *   Other shapes (D, G) than (128, 128): both arrays are cut into rows of 128 tokens (four blocks of 32), VG = D/G
- *   value groups per token, 128/G key groups per row.  Codes are packed eight to a 32-bit word (nibble i in bits
- *   4i .. 4i+3), one word per lane of a 64-lane wave (lane = 16*g + r, g < 4, r < 16) and matrix-core step:
+ *   value groups per token, 128/G key groups per row.  Codes are packed eight to a 32-bit word, one word per lane
+ *   of a 64-lane wave (lane = 16*g + r, g < 4, r < 16) and matrix-core step; the word's code i (i < 8) sits in
+ *   nibble (i&1)*4 + (i>>1), i.e. bits 4*nibble .. 4*nibble+3, as in the value words above:
  *     upper : uint8 [B][Hkv][q_cap/128][128*D + 1024*VG]   per row
  *               block p (p < 4) at 32*D*p:
  *                 [0, 16*D)           key codes C_U: with KW = min(D/32, 4), word ((t*(D/32/KW) + s/KW)*64 + lane)*KW

@@ -110,7 +110,9 @@ Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf) {
   Plan p;
   if (!tuned_shape(c)) {   // one-wave workgroups over ranges of 32-token blocks, fixed ranges only
     const int blocks = max_quant / kBlkTok;
-    const int want_plain = std::max(1, cu_count(c) * (c->head_dim == 256 ? 4 : 8) / units);
+    // resident one-wave workgroups per compute unit: what the kernels' register budgets allow
+    const int per_cu = c->head_dim == 256 ? 4 : (c->head_dim == 64 && n_rows <= 16) ? 16 : 8;
+    const int want_plain = std::max(1, cu_count(c) * per_cu / units);
     p.n_split_q = std::max(1, std::min(want_plain, blocks));
     p.n_split_b = std::max(1, std::min((max_buf + kBufSplitTok - 1) / kBufSplitTok, std::max(want_plain, kMinBufSplits)));
     p.cu_wgs = 0;

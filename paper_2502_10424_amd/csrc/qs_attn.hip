@@ -73,6 +73,14 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t block_resource(const uint8_t* 
 __device__ __forceinline__ u32x4 ldb128_stream(__amdgpu_buffer_rsrc_t r, int off) {
   return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, kAuxStream);
 }
+__device__ __forceinline__ u32x4 ldb128(__amdgpu_buffer_rsrc_t r, int off) {
+  return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+}
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint2 ldb64(__amdgpu_buffer_rsrc_t r, int off) {
+  const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
+  return make_uint2(w[0], w[1]);
+}
 __device__ __forceinline__ uint32_t ldb16_stream(__amdgpu_buffer_rsrc_t r, int off) {
   return (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, off, 0, kAuxStream);
 }
@@ -1125,6 +1133,16 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
 // The next block's words are requested before the current block is worked on.
 // ------------------------------------------------------------------------------------------------
 using half4 = _Float16 __attribute__((ext_vector_type(4)));
+using ushort2v = unsigned short __attribute__((ext_vector_type(2)));
+
+// Largest of fp16 numbers that are not negative, two at a time: their bit patterns order like the numbers.
+__device__ __forceinline__ uint32_t max_bits(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2v, a), __builtin_bit_cast(ushort2v, b)));
+}
+__device__ __forceinline__ float larger_half(uint32_t a) {
+  const half2v h = as_half2(a);
+  return fmaxf((float)h[0], (float)h[1]);
+}
 
 // Row `row` (of the n_rows that share kv-head kvh of sequence b) in the [B][nq][Hq] order of q and out.
 __device__ __forceinline__ int64_t global_row(const AttnArgs& a, int b, int kvh, int row) {
@@ -1135,28 +1153,18 @@ __device__ __forceinline__ int64_t global_row(const AttnArgs& a, int b, int kvh,
 __device__ __forceinline__ float pow2(int e) { return __builtin_bit_cast(float, (uint32_t)(127 + e) << 23); }   // -126 <= e <= 127
 __device__ __forceinline__ int exponent_of(float x) { return (int)((__builtin_bit_cast(uint32_t, x) >> 23) & 255u) - 127; }
 
-// The eight codes of a word (C_U, or 16*C_U + C_L + 8 from the words of both planes) as 16-bit numbers in
-// nibble order: the matrix-core operand of the lane.
+// The eight codes of a word (C_U, or 16*C_U + C_L + 8 from the words of both planes) as 16-bit numbers: the
+// matrix-core operand of the lane, element i = code i of the word.  Of the upper plane alone, elements 2, 3, 6
+// and 7 come out 16 times too large (kLoneScale): the other operand makes up for it.
 template <bool VERIFY>
 __device__ __forceinline__ half8 code_operand(uint32_t u, uint32_t lw) {
-  uint32_t even, odd;   // byte k: the code in nibble 2k / 2k+1
-  if (VERIFY) {
-    even = ((u << 4) & 0xF0F0F0F0u) | (lw & 0x0F0F0F0Fu);
-    odd = (u & 0xF0F0F0F0u) | ((lw >> 4) & 0x0F0F0F0Fu);
-  } else {
-    even = u & 0x0F0F0F0Fu;
-    odd = (u >> 4) & 0x0F0F0F0Fu;
-  }
-  u32x4 w;   // bytes (even.k, 0, odd.k, 0)
-  w[0] = __builtin_amdgcn_perm(odd, even, 0x0c040c00u);
-  w[1] = __builtin_amdgcn_perm(odd, even, 0x0c050c01u);
-  w[2] = __builtin_amdgcn_perm(odd, even, 0x0c060c02u);
-  w[3] = __builtin_amdgcn_perm(odd, even, 0x0c070c03u);
-  return as_half8(w);
+  return VERIFY ? unpack8(u, lw) : unpack4(u);
 }
+constexpr float kLoneScale = 16.0f;
+__host__ __device__ constexpr bool scaled_element(int i) { return (i & 2) != 0; }
 
 template <int D, int G, bool VERIFY, int NRT>
-__global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnArgs a) {
+__global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) void attn_plain_kernel(AttnArgs a) {
   constexpr int KS = D / 32, NT = D / 16, VG = D / G;
   constexpr int KW = KS < 4 ? KS : 4, KQ = KS / KW;   // key words a lane holds side by side, and how many such runs
   constexpr int PL = VERIFY ? 2 : 1;                  // planes read
@@ -1164,12 +1172,19 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
   constexpr int kEvFloor = -40;                       // below every value scale that is not zero (2^-24 / 16)
   // LDS of the one wave: the two operands hi, lo of every (row tile, key step) for the quantized region, one
   // 16-byte slot per lane (a lane reads back what it wrote itself); or the values of a buffer block, [channel][token]
-  constexpr int kQBytes = 2 * NRT * KS * 64 * 16, kVtBytes = D * VSTRIDE * 2;
+  // then (one tile of rows only: two would not leave room for eight waves per compute unit at head_dim 128) the
+  // scaled queries in the same arrangement, and 4 D bytes through which a group's key scales and zeros pass
+  // from the lanes that loaded them to the lanes that use them
+  constexpr bool kQInLds = NRT == 1;
+  constexpr int kOpBytes = 2 * NRT * KS * 64 * 16, kQnBytes = kQInLds ? NRT * KS * 64 * 16 : 0;
+  constexpr int kQBytes = kOpBytes + kQnBytes + 4 * D, kVtBytes = D * VSTRIDE * 2;
   __shared__ __attribute__((aligned(16))) uint8_t lds[kQBytes > kVtBytes ? kQBytes : kVtBytes];
+  uint8_t* const km_lds = lds + kOpBytes + kQnBytes;
   uint16_t (*vt)[VSTRIDE] = reinterpret_cast<uint16_t (*)[VSTRIDE]>(lds);
   const ShapeLayout lay{D, G};
   const int lane = threadIdx.x & 63, rho = lane & 15, g = lane >> 4;
   half8* q_lds = reinterpret_cast<half8*>(lds) + lane;   // operand (part, rt, s) at [((part * NRT + rt) * KS + s) * 64]
+  half8* qn_lds = reinterpret_cast<half8*>(lds + kOpBytes) + lane;   // scaled queries (rt, s) at [(rt * KS + s) * 64]
   const int unit = blockIdx.x, split = blockIdx.y, row0 = blockIdx.z * 16 * NRT;
   const int b = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   const int nb = a.len.n_buf[b];
@@ -1207,57 +1222,92 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
       sc[rt] = a.c0, bias[rt] = 0.f;
     }
   };
-  // |q| of a row never exceeds 2^(eq + 1)
-  int eq[NRT];
+  // A row's queries are brought to |q| < 2^7 by a power of two, 2^fq (exact in fp16; at most 2^15, which only
+  // leaves a row of tiny queries with less headroom than it could have)
+  int fq[NRT];
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
-    float qmax = 0.f;
+    uint32_t qm = 0u;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-      const half8 qv = load_q(rt, s);
+      const u32x4 w = as_u32x4(load_q(rt, s));
 #pragma unroll
-      for (int i = 0; i < 8; ++i) qmax = fmaxf(qmax, __builtin_fabsf((float)qv[i]));
+      for (int r = 0; r < 4; ++r) qm = max_bits(qm, w[r] & 0x7FFF7FFFu);
     }
-    eq[rt] = max(exponent_of(group_max(qmax)), -40);
+    const float qmax = group_max(larger_half(qm));
+    fq[rt] = min(6 - max(exponent_of(qmax), -24), 15);
+    if constexpr (kQInLds) {
+      if (quantized) {
+        const _Float16 up_q = (_Float16)pow2(fq[rt]);
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qn_lds[(rt * KS + s) * 64] = load_q(rt, s) * up_q;
+      }
+    }
   }
-  auto scaled_q = [&](const uint8_t* row, int key_group) __attribute__((always_inline)) {
-    const uint8_t* sp = row + lay.off_ks() + (key_group * D + 8 * g) * 2;
-    const uint8_t* zp = row + lay.off_kz() + (key_group * D + 8 * g) * 2;
-    half8 sh[KS];
-    float smax = 0.f;
+  // The operands of one group of keys.  The key scales are brought below 2^7 the same way (2^fs, from the
+  // largest scale of the group over all channels), so a product q*S of the scaled numbers is below 2^14 and
+  // splits into hi = fp16(q*S) and lo = q*S - hi without loss down to 2^-24: both are packed fp16 operations
+  // (the remainder of an fp16 product is an fp16 number unless it underflows).
+  // km: this lane's 16 bytes of the group's scales (lanes below D/8) and zeros (the D/8 lanes after them), as
+  // they came with the block's words.  They go through LDS to the lanes that need them.
+  auto scaled_q = [&](const u32x4& km) __attribute__((always_inline)) {
+    wave_lds_sync();   // whoever still reads the previous group's numbers is done
+    if (D == 256 || lane < D / 4) *reinterpret_cast<u32x4*>(km_lds + 16 * lane) = km;
+    wave_lds_sync();
+    u32x4 sw[KS], zw[KS];
+    uint32_t sm = 0u;
+    u32x4 qw[NRT][KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-      sh[s] = as_half8(ldg128(sp + 64 * s));
-#pragma unroll
-      for (int i = 0; i < 8; ++i) smax = fmaxf(smax, (float)sh[s][i]);
+      sw[s] = *reinterpret_cast<const u32x4*>(km_lds + (32 * s + 8 * g) * 2);
+      zw[s] = *reinterpret_cast<const u32x4*>(km_lds + 2 * D + (32 * s + 8 * g) * 2);
     }
-    // the largest key scale of the group, over all channels: the lanes of a row of 16 hold the same channels
-    const int es = max(exponent_of(group_max(smax)), -40) - (VERIFY ? 4 : 0);
 #pragma unroll
-    for (int rt = 0; rt < NRT; ++rt) {
-      // every product q * mul is below 2^(eq + es + 2): 2^up brings that bound to 2^14
-      const int e = eq[rt] + es;
-      const float up = pow2(12 - e) * (VERIFY ? 0.0625f : 1.0f);
-      float bsum = 0.f;
+    for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
-        const half8 zh = as_half8(ldg128(zp + 64 * s)), qv = load_q(rt, s);
-        half8 h8, l8;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const float sf = (float)sh[s][i], qf = (float)qv[i];
-          const float add = VERIFY ? __builtin_fmaf(-0.5f, sf, (float)zh[i]) : (float)zh[i];
-          bsum = __builtin_fmaf(qf, add, bsum);
-          const float th = qf * (sf * up);          // both products exact: 11 x 11 bits and a power of two
-          const _Float16 hi = (_Float16)th;
-          h8[i] = hi;
-          l8[i] = (_Float16)(th - (float)hi);
-        }
-        q_lds[((0 * NRT + rt) * KS + s) * 64] = h8;
-        q_lds[((1 * NRT + rt) * KS + s) * 64] = l8;
+        if constexpr (kQInLds)
+          qw[rt][s] = as_u32x4(qn_lds[(rt * KS + s) * 64]);
+        else
+          qw[rt][s] = as_u32x4(load_q(rt, s));   // everything is requested before anything is waited for
       }
-      sc[rt] = a.c0 * pow2(e - 12 + 24);   // undoes 2^up and the 2^-24 of a code read as a subnormal
-      bias[rt] = a.c0 * group_sum(bsum);
+    if constexpr (!kQInLds) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) sm = max_bits(sm, sw[s][r]);
+    // the lanes of a row of 16 hold the same channels: the maximum over the four rows covers the group
+    const float smax = group_max(larger_half(sm));
+    const int fs = min(6 - max(exponent_of(smax), -24), 15);
+    // the upper plane alone: the scale of an element whose code comes out 16 times too large is a sixteenth
+    const _Float16 up_s = (_Float16)pow2(fs), up_s16 = (_Float16)pow2(fs - (VERIFY ? 0 : 4));
+#pragma unroll
+    for (int rt = 0; rt < NRT; ++rt) {
+      const _Float16 up_q = (_Float16)(kQInLds ? 1.0f : pow2(fq[rt]));
+      float bz = 0.f, bs = 0.f;   // sum of q Z and of q S over this lane's channels, q scaled
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        u32x4 h4, l4;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const half2v qn = as_half2(qw[rt][s][r]) * up_q, sh = as_half2(sw[s][r]), zh = as_half2(zw[s][r]);
+          const half2v sn = sh * (scaled_element(2 * r) ? up_s16 : up_s);
+          const half2v hi = qn * sn;
+          const half2v lo = __builtin_elementwise_fma(qn, sn, -hi);
+          h4[r] = as_u32(hi), l4[r] = as_u32(lo);
+          bz = __builtin_fmaf((float)qn[0], (float)zh[0], bz);
+          bz = __builtin_fmaf((float)qn[1], (float)zh[1], bz);
+          if (VERIFY) {
+            bs = __builtin_fmaf((float)qn[0], (float)sh[0], bs);
+            bs = __builtin_fmaf((float)qn[1], (float)sh[1], bs);
+          }
+        }
+        q_lds[((0 * NRT + rt) * KS + s) * 64] = as_half8(h4);
+        q_lds[((1 * NRT + rt) * KS + s) * 64] = as_half8(l4);
+      }
+      // (mul, add) = (S, Z), or (S/16, Z - S/2) for both planes; 2^24 for a code read as a subnormal
+      sc[rt] = a.c0 * pow2(24 - fq[rt] - fs - (VERIFY ? 4 : 0));
+      bias[rt] = a.c0 * pow2(-fq[rt]) * group_sum(VERIFY ? __builtin_fmaf(-0.5f, bs, bz) : bz);
     }
   };
 
@@ -1277,6 +1327,8 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
   struct Raw {
     uint32_t k[PL][2][KS];      // key words of the two 16-token tiles
     uint32_t v[PL][NT];         // value words
+    uint2 vs[2][VG], vz[2][VG]; // value scale / zero of this lane's tokens 16 t + 4 g .. + 3: four tokens x VG groups
+    u32x4 km;                   // 16 bytes of the key scales and zeros of the block's group, if the block starts one for the wave
   };
   // Where the 128-token rows of the current block, the next and the one after lie (the same in every lane).
   // Paged caches: the table entry is asked for two blocks before the block's words are, and waited for there.
@@ -1285,34 +1337,55 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
   int place_cur = 0, place_nxt = 0, place_aft = 0;
   auto logical_row = [&](int blk) -> int { return unit * (a.q_cap / kG) + (32 * min(blk, blk1 - 1)) / kSuper; };
   auto look_up = [&](int blk) -> int { return a.group_table[logical_row(blk)]; };
-  auto load_raw = [&](int blk, Raw& r, int place) __attribute__((always_inline)) {
+  // The words of block blk, requested through buffer resources that span the block's 128-token row: a block
+  // that does not exist (exists == false: the one after the range's last) gets resources of no bytes, whose loads
+  // return zero without touching memory - so every step of the loop issues the same loads and the waits
+  // for a block's words can be counted, not drained.
+  auto load_raw = [&](int blk, Raw& r, int place, bool exists) __attribute__((always_inline)) {
     const int64_t pg = place;
     const int st0 = (32 * blk) % kSuper;
-    const uint8_t* row = a.upper + pg * lay.upper_bytes();
+    const __amdgpu_buffer_rsrc_t ru = block_resource(a.upper + pg * lay.upper_bytes(), exists ? lay.upper_bytes() : 0);
+    {   // first, so that it is there first: lane l takes bytes [16 l, 16 l + 16) of the group's scales, then of its zeros
+      const bool starts = exists && (blk == blk0 || st0 % G == 0);
+      const __amdgpu_buffer_rsrc_t rm = block_resource(a.upper + pg * lay.upper_bytes(), starts ? lay.upper_bytes() : 0);
+      const int half_lanes = D / 8, which = lane / half_lanes, piece16 = lane % half_lanes;
+      const int off = (which == 0 ? lay.off_ks() : lay.off_kz()) + (st0 / G) * D * 2 + 16 * piece16;
+      r.km = ldb128(rm, which < 2 ? off : lay.upper_bytes());
+    }
+    __amdgpu_buffer_rsrc_t rl = ru;
+    if constexpr (PL == 2) rl = block_resource(a.lower + pg * lay.lower_bytes(), exists ? lay.lower_bytes() : 0);
 #pragma unroll
     for (int pl = 0; pl < PL; ++pl) {
-      const uint8_t* base = pl == 0 ? row : a.lower + pg * lay.lower_bytes();
-      const uint8_t* kp = base + lay.off_k(st0 / 32);
-      const uint8_t* vp = base + lay.off_v(st0 / 32);
+      const __amdgpu_buffer_rsrc_t rs = pl == 0 ? ru : rl;
+      const int kp = lay.off_k(st0 / 32), vp = lay.off_v(st0 / 32);
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int sq = 0; sq < KQ; ++sq) {
-          const uint8_t* src = kp + (((t * KQ + sq) * 64 + lane) * KW) * 4;
+          const int off = kp + (((t * KQ + sq) * 64 + lane) * KW) * 4;
           if constexpr (KW == 4) {
-            const u32x4 w = ldg128_stream(src);
+            const u32x4 w = ldb128_stream(rs, off);
 #pragma unroll
             for (int i = 0; i < 4; ++i) r.k[pl][t][4 * sq + i] = w[i];
           } else {
-            const uint2 w = *reinterpret_cast<const uint2*>(src);
+            const uint2 w = ldb64(rs, off);
             r.k[pl][t][0] = w.x, r.k[pl][t][1] = w.y;
           }
         }
 #pragma unroll
       for (int nq = 0; nq < NT / 4; ++nq) {
-        const u32x4 w = ldg128_stream(vp + (nq * 64 + lane) * 16);
+        const u32x4 w = ldb128_stream(rs, vp + (nq * 64 + lane) * 16);
 #pragma unroll
         for (int i = 0; i < 4; ++i) r.v[pl][4 * nq + i] = w[i];
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int tok = st0 + 16 * t + 4 * g;
+#pragma unroll
+      for (int c = 0; c < VG; ++c) {
+        r.vs[t][c] = ldb64(ru, lay.off_vs() + (tok * VG + 4 * c) * 2);
+        r.vz[t][c] = ldb64(ru, lay.off_vz() + (tok * VG + 4 * c) * 2);
       }
     }
   };
@@ -1339,26 +1412,13 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
   auto block_step = [&](int blk, auto QUANT, auto PAGED, Raw& cur, Raw& nxt) __attribute__((always_inline)) {
     constexpr bool quantized = decltype(QUANT)::value, paged = decltype(PAGED)::value;
     const int st0 = (32 * blk) % kSuper;   // first token of the block inside its 128-token row of the layout
-    uint2 vs[2][VG], vz[2][VG];   // value scale / zero of this lane's tokens 16 t + 4 g .. + 3: four tokens x VG groups
     if constexpr (quantized) {
       const int64_t here = paged ? __builtin_amdgcn_readfirstlane(place_cur) : logical_row(blk);
       const uint8_t* row = a.upper + here * lay.upper_bytes();
       // The query operands of a new key group first: what they wait for (their own loads, and with them this
       // block's words) is needed now anyway; after the request for the next block they would wait for that too.
-      if (blk == blk0 || st0 % G == 0) scaled_q(row, st0 / G);
-#pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        const int tok = st0 + 16 * t + 4 * g;
-#pragma unroll
-        for (int c = 0; c < VG; ++c) {
-          vs[t][c] = *reinterpret_cast<const uint2*>(row + lay.off_vs() + (tok * VG + 4 * c) * 2);
-          vz[t][c] = *reinterpret_cast<const uint2*>(row + lay.off_vz() + (tok * VG + 4 * c) * 2);
-        }
-      }
-      // head_dim 256, both planes: keep the small loads above ahead of the next block's 32 (measured: 193 vs 329 us
-      // at group 32, 115 vs 127 us at group 128; group 64 and the other shapes are 5 - 15 % faster with the order left to the compiler)
-      if constexpr (D == 256 && VERIFY && G != 64) __builtin_amdgcn_sched_barrier(0);
-      if (blk + 1 < blk1) load_raw(blk + 1, nxt, paged ? __builtin_amdgcn_readfirstlane(place_nxt) : logical_row(blk + 1));
+      if (blk == blk0 || st0 % G == 0) scaled_q(cur.km);
+      load_raw(blk + 1, nxt, paged ? __builtin_amdgcn_readfirstlane(place_nxt) : logical_row(blk + 1), blk + 1 < blk1);
     } else {
       wave_lds_sync();   // the previous block's LDS reads are done
       fill_values(blk);
@@ -1412,17 +1472,13 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
     // ---- largest value scale of the block ----
     int eb = ev;
     if constexpr (quantized) {
-      float smax = 0.f;
+      uint32_t sm = 0u;
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int c = 0; c < VG; ++c) {
-          const half4 s4 = __builtin_bit_cast(half4, vs[t][c]);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) smax = fmaxf(smax, (float)s4[e]);
-        }
-      if (VERIFY) smax *= 0.0625f;
-      eb = max(exponent_of(group_max(smax)), ev);   // the same in every lane: all lanes of a group of 16 share their tokens
+        for (int c = 0; c < VG; ++c) sm = max_bits(sm, max_bits(cur.vs[t][c].x, cur.vs[t][c].y));
+      // the same in every lane: all lanes of a group of 16 share their tokens
+      eb = max(exponent_of(group_max(larger_half(sm))) - (VERIFY ? 4 : 0), ev);
     }
     if (__any(grow) || eb > ev) {   // a running maximum or the scale exponent moves: rescale what is accumulated
       const float alpha_e = pow2(max(ev - eb, -120));
@@ -1440,7 +1496,8 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
         for (int n = 0; n < NT; ++n) o[rt][n] *= both;
       }
     }
-    const float pscale = pow2(14 - ev);
+    const float pscale = pow2(14 - ev) * (quantized && VERIFY ? 0.0625f : 1.0f);
+    float xs[NRT][8];   // the probabilities with the power of two of the P operand
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt) {
       float sum = 0.f;
@@ -1448,6 +1505,7 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
       for (int j = 0; j < 8; ++j) {
         x[rt][j] = __builtin_amdgcn_exp2f(x[rt][j] - m[rt]);
         sum += x[rt][j];
+        xs[rt][j] = x[rt][j] * (quantized && !VERIFY && scaled_element(j) ? pscale * (1.0f / kLoneScale) : pscale);
       }
       l[rt] += sum;
     }
@@ -1456,29 +1514,31 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
     for (int k = 0; k < (quantized ? VG : 1); ++k) {
       half8 pb[NRT];
       if constexpr (quantized) {
-        float vmul[8], vadd[8];   // of token j = 4 t + jj of this lane: element (jj * VG + k) of the four-token run
+        // (mul, add) of token j = 4 t + jj of this lane: element (jj * VG + k) of the four-token run; they enter as
+        // fp16 numbers (mixed-precision multiply-adds), the products are formed in binary32
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
           for (int jj = 0; jj < 4; ++jj) {
-            const int idx = jj * VG + k;
-            const half4 s4 = __builtin_bit_cast(half4, vs[t][idx / 4]), z4 = __builtin_bit_cast(half4, vz[t][idx / 4]);
-            const float sf = (float)s4[idx % 4], zf = (float)z4[idx % 4];
-            vmul[4 * t + jj] = (VERIFY ? sf * 0.0625f : sf) * pscale;
-            vadd[4 * t + jj] = VERIFY ? __builtin_fmaf(-0.5f, sf, zf) : zf;
-          }
+            const int idx = jj * VG + k, j = 4 * t + jj;
+            const half4 s4 = __builtin_bit_cast(half4, cur.vs[t][idx / 4]), z4 = __builtin_bit_cast(half4, cur.vz[t][idx / 4]);
+            const _Float16 sh = s4[idx % 4], zh = z4[idx % 4];
+            if (VERIFY) {
+              const float vadd = __builtin_fmaf(-0.5f, (float)sh, (float)zh);
 #pragma unroll
-        for (int rt = 0; rt < NRT; ++rt)
+              for (int rt = 0; rt < NRT; ++rt) zs[rt][k] = __builtin_fmaf(x[rt][j], vadd, zs[rt][k]);
+            } else {
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            zs[rt][k] = __builtin_fmaf(x[rt][j], vadd[j], zs[rt][k]);
-            pb[rt][j] = (_Float16)(x[rt][j] * vmul[j]);
+              for (int rt = 0; rt < NRT; ++rt) zs[rt][k] = __builtin_fmaf(x[rt][j], (float)zh, zs[rt][k]);
+            }
+#pragma unroll
+            for (int rt = 0; rt < NRT; ++rt) pb[rt][j] = (_Float16)__builtin_fmaf(xs[rt][j], (float)sh, 0.f);
           }
       } else {
 #pragma unroll
         for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
-          for (int j = 0; j < 8; ++j) pb[rt][j] = (_Float16)(x[rt][j] * pscale);
+          for (int j = 0; j < 8; ++j) pb[rt][j] = (_Float16)xs[rt][j];
       }
       constexpr int TILES = NT / VG;   // value tiles per value group (all of them for the buffer)
 #pragma unroll
@@ -1505,14 +1565,14 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : 2) void attn_plain_kernel(AttnAr
     if (a.group_table != nullptr) {
       if (blk0 < blk1) {
         place_cur = look_up(blk0), place_nxt = look_up(blk0 + 1), place_aft = look_up(blk0 + 2);
-        load_raw(blk0, ra, __builtin_amdgcn_readfirstlane(place_cur));
+        load_raw(blk0, ra, __builtin_amdgcn_readfirstlane(place_cur), true);
       }
       for (int blk = blk0; blk < blk1; blk += 2) {   // the two sets of registers swap roles from block to block
         block_step(blk, std::true_type{}, std::true_type{}, ra, rb);
         if (blk + 1 < blk1) block_step(blk + 1, std::true_type{}, std::true_type{}, rb, ra);
       }
     } else {
-      if (blk0 < blk1) load_raw(blk0, ra, logical_row(blk0));
+      if (blk0 < blk1) load_raw(blk0, ra, logical_row(blk0), true);
       for (int blk = blk0; blk < blk1; blk += 2) {
         block_step(blk, std::true_type{}, std::false_type{}, ra, rb);
         if (blk + 1 < blk1) block_step(blk + 1, std::true_type{}, std::false_type{}, rb, ra);

@@ -574,14 +574,14 @@ __global__ __launch_bounds__(256) void quantize_plain_kernel(FlushArgs a) {
         const int s = (tsq % KQ) * KW + r % KW, t = tsq / KQ;
         const int tok = 32 * bl + 16 * t + (lane & 15), c0 = 32 * s + 8 * (lane >> 4);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) wu |= (uint32_t)(cb[tok][c0 + i] & 15) << (4 * i), wl |= (uint32_t)(cb[tok][c0 + i] >> 4) << (4 * i);
+        for (int i = 0; i < 8; ++i) wu |= (uint32_t)(cb[tok][c0 + i] & 15) << (4 * tile_nibble(i)), wl |= (uint32_t)(cb[tok][c0 + i] >> 4) << (4 * tile_nibble(i));
       } else {
         const int lane = (r / 4) % 64, n = 4 * (r / 256) + r % 4;
         const int c = 16 * n + (lane & 15), tok0 = 32 * bl + 4 * (lane >> 4);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const uint32_t code = cb[tok0 + 16 * (j >> 2) + (j & 3)][c];
-          wu |= (code & 15u) << (4 * j), wl |= (code >> 4) << (4 * j);
+          wu |= (code & 15u) << (4 * tile_nibble(j)), wl |= (code >> 4) << (4 * tile_nibble(j));
         }
       }
       const int off = (values ? lay.off_v(sb_tok / 32 + bl) : lay.off_k(sb_tok / 32 + bl)) + 4 * r;
@@ -685,19 +685,19 @@ __global__ __launch_bounds__(256) void export_plain_kernel(ExportArgs a) {
   const uint8_t* ub = a.upper + physical_group(a, a.unit, tok / kSuper) * lay.upper_bytes();
   const uint8_t* lb = a.lower + physical_group(a, a.unit, tok / kSuper) * lay.lower_bytes();
   const int p = (tok % kSuper) / 32, tl = tok % 32, t = tl / 16;
-  {   // keys: the eight channels are the eight nibbles of one word
+  {   // keys: the eight channels are the eight nibbles of one word, channel i in nibble tile_nibble(i)
     const int off = lay.off_k(p) + 4 * lay.k_word(t, 16 * ((c0 / 8) % 4) + tl % 16, c0 / 32);
     const uint32_t wu = *reinterpret_cast<const uint32_t*>(ub + off);
     const uint32_t wl = *reinterpret_cast<const uint32_t*>(lb + off);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      if (a.k_u) a.k_u[(int64_t)tok * D + c0 + i] = (uint8_t)((wu >> (4 * i)) & 15u);
-      if (a.k_l) a.k_l[(int64_t)tok * D + c0 + i] = (int8_t)((int)((wl >> (4 * i)) & 15u) - 8);
+      if (a.k_u) a.k_u[(int64_t)tok * D + c0 + i] = (uint8_t)((wu >> (4 * tile_nibble(i))) & 15u);
+      if (a.k_l) a.k_l[(int64_t)tok * D + c0 + i] = (int8_t)((int)((wl >> (4 * tile_nibble(i))) & 15u) - 8);
     }
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) {   // values: one word per channel, the token picks the nibble
-    const int c = c0 + i, j = 4 * t + tl % 4;
+    const int c = c0 + i, j = tile_nibble(4 * t + tl % 4);
     const int off = lay.off_v(p) + 4 * lay.v_word(c / 16, 16 * ((tl % 16) / 4) + c % 16);
     const uint32_t wu = *reinterpret_cast<const uint32_t*>(ub + off);
     const uint32_t wl = *reinterpret_cast<const uint32_t*>(lb + off);

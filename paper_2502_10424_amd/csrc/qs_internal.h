@@ -40,11 +40,11 @@ struct ShapeLayout {
   // codes: four 32-token blocks per row, each 16 d bytes of key codes, then 16 d bytes of value codes
   __host__ __device__ int off_k(int p) const { return p * 32 * d; }
   __host__ __device__ int off_v(int p) const { return p * 32 * d + 16 * d; }
-  // 32-bit word of a key block with channels 32 s + 8 g + i (nibble i) of token 16 t + rho, lane = 16 g + rho
+  // 32-bit word of a key block with channels 32 s + 8 g + i (nibble (i&1)*4 + (i>>1)) of token 16 t + rho, lane = 16 g + rho
   __host__ __device__ int k_word(int t, int lane, int s) const {
     return ((t * (ks() / kw()) + s / kw()) * 64 + lane) * kw() + s % kw();
   }
-  // 32-bit word of a value block with channel 16 n + rho of tokens 16 (j >> 2) + 4 g + (j & 3) (nibble j)
+  // 32-bit word of a value block with channel 16 n + rho of tokens 16 (j >> 2) + 4 g + (j & 3) (nibble (j&1)*4 + (j>>1))
   __host__ __device__ int v_word(int n, int lane) const { return ((n >> 2) * 64 + lane) * 4 + (n & 3); }
   __host__ __device__ int off_vs() const { return 128 * d; }                 // value scale, fp16 [128][vg]
   __host__ __device__ int off_vz() const { return 128 * d + 256 * vg(); }    // value zero
