@@ -104,6 +104,32 @@ def test_attention_parity(env, d, g, hq, hkv, nq):
     _attn(env, cache, oc, q, sm, True, f"({d},{g}) verify Hq={hq} Hkv={hkv} nq={nq}")
 
 
+@pytest.mark.parametrize("d,g", [(64, 32), (128, 64), (256, 128)])
+@pytest.mark.parametrize("kmag,vmag,qmag", [(1e-3, 1.0, 1.0), (3000.0, 1.0, 1.0), (1.0, 1e-3, 1.0), (1.0, 3000.0, 1.0),
+                                            (1.0, 1.0, 1e-3), (1.0, 1.0, 200.0), (1e-2, 1e-2, 30.0)])
+def test_attention_magnitudes(env, d, g, kmag, vmag, qmag):
+    """Keys, values and queries many orders of magnitude away from 1, with a softmax scale that keeps the
+    scores at O(1): the kernel brings a row's queries and a group's key scales into a fixed range by powers of
+    two, and the value scales follow a running power of two, so none of this may cost accuracy."""
+    O, U = env["O"], env["U"]
+    rng = np.random.default_rng(int(d + g + 10 * np.log10(kmag) + 100 * np.log10(vmag) + 7 * np.log10(qmag)) + 500)
+    hq, hkv, nq = 4, 2, 3
+    nb = g + 9
+    t = 3 * 128 + 2 * g + nb
+    nb += (t - nb) % g
+    k = (rng.standard_normal((1, hkv, t, d)) * kmag).astype(np.float16)
+    v = (rng.standard_normal((1, hkv, t, d)) * vmag).astype(np.float16)
+    # a few tokens with much larger values: the value scale jumps inside a chunk
+    v[:, :, 200:203] = np.clip(v[:, :, 200:203].astype(np.float32) * 20.0, -6e4, 6e4).astype(np.float16)
+    q = (rng.standard_normal((1, nq, hq, d)) * qmag).astype(np.float16)
+    cache = U.make_device_cache(k, v, hq, nb, buf_cap=nb + 8, group=g)
+    oc = O.build_cache(k, v, hq, g, nb)
+    for peak in (0.5, 3.0):
+        sm = peak / (kmag * qmag * np.sqrt(d))
+        _attn(env, cache, oc, q[:, :1].copy(), sm, False, f"({d},{g}) draft |k|~{kmag:g} |v|~{vmag:g} |q|~{qmag:g} peak {peak}")
+        _attn(env, cache, oc, q, sm, True, f"({d},{g}) verify |k|~{kmag:g} |v|~{vmag:g} |q|~{qmag:g} peak {peak}")
+
+
 @pytest.mark.parametrize("d,g", [(64, 32), (256, 64)])
 def test_buffer_only_and_paged(env, d, g):
     """Nothing quantized yet (all tokens in the full-precision buffer), and a paged cache whose 128-token
