@@ -1177,9 +1177,11 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
   // from the lanes that loaded them to the lanes that use them
   constexpr bool kQInLds = NRT == 1;
   constexpr int kOpBytes = 2 * NRT * KS * 64 * 16, kQnBytes = kQInLds ? NRT * KS * 64 * 16 : 0;
-  constexpr int kQBytes = kOpBytes + kQnBytes + 4 * D, kVtBytes = D * VSTRIDE * 2;
+  constexpr int kVmBytes = 128 * VG;   // a block's value scales and zeros, likewise
+  constexpr int kQBytes = kOpBytes + kQnBytes + 4 * D + kVmBytes, kVtBytes = D * VSTRIDE * 2;
   __shared__ __attribute__((aligned(16))) uint8_t lds[kQBytes > kVtBytes ? kQBytes : kVtBytes];
   uint8_t* const km_lds = lds + kOpBytes + kQnBytes;
+  uint8_t* const vm_lds = km_lds + 4 * D;
   uint16_t (*vt)[VSTRIDE] = reinterpret_cast<uint16_t (*)[VSTRIDE]>(lds);
   const ShapeLayout lay{D, G};
   const int lane = threadIdx.x & 63, rho = lane & 15, g = lane >> 4;
@@ -1327,14 +1329,16 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
   struct Raw {
     uint32_t k[PL][2][KS];      // key words of the two 16-token tiles
     uint32_t v[PL][NT];         // value words
-    uint2 vs[2][VG], vz[2][VG]; // value scale / zero of this lane's tokens 16 t + 4 g .. + 3: four tokens x VG groups
+    u32x4 vm;                   // 16 bytes of the block's value scales (lanes below 4 VG) and zeros (the 4 VG lanes after them)
     u32x4 km;                   // 16 bytes of the key scales and zeros of the block's group, if the block starts one for the wave
   };
-  // Where the 128-token rows of the current block, the next and the one after lie (the same in every lane).
-  // Paged caches: the table entry is asked for two blocks before the block's words are, and waited for there.
-  // (The loop exists twice, with and without a table: table entries carried from step to step would cost the
-  // cache without one a wait for every load in flight at the end of each step.)
-  int place_cur = 0, place_nxt = 0, place_aft = 0;
+  // A block's words are requested one step before the block is worked on.  (Two steps, with a third set of
+  // registers, changed no shape's time by more than 2 %: a wave's step is as long as its own instructions.)
+  // Paged caches: where the 128-token row of the block to request in this step lies, and that of the step after
+  // (the same in every lane): a table entry is asked for two steps before the block's words are, and waited for
+  // there.  (The loop exists twice, with and without a table: table entries carried from step to step would
+  // cost the cache without one a wait for every load in flight at the end of each step.)
+  int place_load = 0, place_then = 0;
   auto logical_row = [&](int blk) -> int { return unit * (a.q_cap / kG) + (32 * min(blk, blk1 - 1)) / kSuper; };
   auto look_up = [&](int blk) -> int { return a.group_table[logical_row(blk)]; };
   // The words of block blk, requested through buffer resources that span the block's 128-token row: a block
@@ -1351,6 +1355,9 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
       const int half_lanes = D / 8, which = lane / half_lanes, piece16 = lane % half_lanes;
       const int off = (which == 0 ? lay.off_ks() : lay.off_kz()) + (st0 / G) * D * 2 + 16 * piece16;
       r.km = ldb128(rm, which < 2 ? off : lay.upper_bytes());
+      const int whichv = lane / (4 * VG), piecev = lane % (4 * VG);
+      const int offv = (whichv == 0 ? lay.off_vs() : lay.off_vz()) + st0 * VG * 2 + 16 * piecev;
+      r.vm = ldb128(ru, whichv < 2 ? offv : lay.upper_bytes());
     }
     __amdgpu_buffer_rsrc_t rl = ru;
     if constexpr (PL == 2) rl = block_resource(a.lower + pg * lay.lower_bytes(), exists ? lay.lower_bytes() : 0);
@@ -1379,15 +1386,6 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
         for (int i = 0; i < 4; ++i) r.v[pl][4 * nq + i] = w[i];
       }
     }
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int tok = st0 + 16 * t + 4 * g;
-#pragma unroll
-      for (int c = 0; c < VG; ++c) {
-        r.vs[t][c] = ldb64(ru, lay.off_vs() + (tok * VG + 4 * c) * 2);
-        r.vz[t][c] = ldb64(ru, lay.off_vz() + (tok * VG + 4 * c) * 2);
-      }
-    }
   };
 
   const uint16_t* kb = reinterpret_cast<const uint16_t*>(a.k_buf) + (int64_t)unit * a.buf_cap * D;
@@ -1413,12 +1411,10 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
     constexpr bool quantized = decltype(QUANT)::value, paged = decltype(PAGED)::value;
     const int st0 = (32 * blk) % kSuper;   // first token of the block inside its 128-token row of the layout
     if constexpr (quantized) {
-      const int64_t here = paged ? __builtin_amdgcn_readfirstlane(place_cur) : logical_row(blk);
-      const uint8_t* row = a.upper + here * lay.upper_bytes();
-      // The query operands of a new key group first: what they wait for (their own loads, and with them this
-      // block's words) is needed now anyway; after the request for the next block they would wait for that too.
-      if (blk == blk0 || st0 % G == 0) scaled_q(cur.km);
-      load_raw(blk + 1, nxt, paged ? __builtin_amdgcn_readfirstlane(place_nxt) : logical_row(blk + 1), blk + 1 < blk1);
+      if (blk == blk0 || st0 % G == 0) scaled_q(cur.km);   // the query operands of a new key group
+      wave_lds_sync();   // the previous block's reads of these numbers are done
+      if (VG == 8 || lane < 8 * VG) *reinterpret_cast<u32x4*>(vm_lds + 16 * lane) = cur.vm;
+      load_raw(blk + 1, nxt, paged ? __builtin_amdgcn_readfirstlane(place_load) : logical_row(blk + 1), blk + 1 < blk1);
     } else {
       wave_lds_sync();   // the previous block's LDS reads are done
       fill_values(blk);
@@ -1471,12 +1467,21 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
     }
     // ---- largest value scale of the block ----
     int eb = ev;
+    uint2 vs[2][VG], vz[2][VG];   // value scale / zero of this lane's tokens 16 t + 4 g .. + 3: four tokens x VG groups
     if constexpr (quantized) {
+      wave_lds_sync();
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int c = 0; c < VG; ++c) {
+          vs[t][c] = *reinterpret_cast<const uint2*>(vm_lds + ((16 * t + 4 * g) * VG + 4 * c) * 2);
+          vz[t][c] = *reinterpret_cast<const uint2*>(vm_lds + 64 * VG + ((16 * t + 4 * g) * VG + 4 * c) * 2);
+        }
       uint32_t sm = 0u;
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int c = 0; c < VG; ++c) sm = max_bits(sm, max_bits(cur.vs[t][c].x, cur.vs[t][c].y));
+        for (int c = 0; c < VG; ++c) sm = max_bits(sm, max_bits(vs[t][c].x, vs[t][c].y));
       // the same in every lane: all lanes of a group of 16 share their tokens
       eb = max(exponent_of(group_max(larger_half(sm))) - (VERIFY ? 4 : 0), ev);
     }
@@ -1521,7 +1526,7 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
 #pragma unroll
           for (int jj = 0; jj < 4; ++jj) {
             const int idx = jj * VG + k, j = 4 * t + jj;
-            const half4 s4 = __builtin_bit_cast(half4, cur.vs[t][idx / 4]), z4 = __builtin_bit_cast(half4, cur.vz[t][idx / 4]);
+            const half4 s4 = __builtin_bit_cast(half4, vs[t][idx / 4]), z4 = __builtin_bit_cast(half4, vz[t][idx / 4]);
             const _Float16 sh = s4[idx % 4], zh = z4[idx % 4];
             if (VERIFY) {
               const float vadd = __builtin_fmaf(-0.5f, (float)sh, (float)zh);
@@ -1558,26 +1563,29 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
           o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vop, pb[rt], o[rt][n], 0, 0, 0);
       }
     }
-    if constexpr (quantized && paged) place_cur = place_nxt, place_nxt = place_aft, place_aft = look_up(blk + 3);
+    if constexpr (quantized && paged) place_load = place_then, place_then = look_up(blk + 3);
   };
   Raw ra, rb;
-  if (quantized) {
-    if (a.group_table != nullptr) {
-      if (blk0 < blk1) {
-        place_cur = look_up(blk0), place_nxt = look_up(blk0 + 1), place_aft = look_up(blk0 + 2);
-        load_raw(blk0, ra, __builtin_amdgcn_readfirstlane(place_cur), true);
-      }
-      for (int blk = blk0; blk < blk1; blk += 2) {   // the two sets of registers swap roles from block to block
-        block_step(blk, std::true_type{}, std::true_type{}, ra, rb);
-        if (blk + 1 < blk1) block_step(blk + 1, std::true_type{}, std::true_type{}, rb, ra);
-      }
-    } else {
-      if (blk0 < blk1) load_raw(blk0, ra, logical_row(blk0), true);
-      for (int blk = blk0; blk < blk1; blk += 2) {
-        block_step(blk, std::true_type{}, std::false_type{}, ra, rb);
-        if (blk + 1 < blk1) block_step(blk + 1, std::true_type{}, std::false_type{}, rb, ra);
-      }
+  // The two sets of registers swap roles from block to block, so the loop body is two steps; both always run (a
+  // block left over follows the loop), which keeps the number of loads in flight known at every wait.
+  auto quantized_range = [&](auto PAGED) __attribute__((always_inline)) {
+    constexpr bool paged = decltype(PAGED)::value;
+    const std::true_type Q{};
+    if (blk0 >= blk1) return;
+    load_raw(blk0, ra, paged ? look_up(blk0) : logical_row(blk0), true);
+    if constexpr (paged) place_load = look_up(blk0 + 1), place_then = look_up(blk0 + 2);
+    int blk = blk0;
+    for (; blk + 1 < blk1; blk += 2) {
+      block_step(blk, Q, PAGED, ra, rb);
+      block_step(blk + 1, Q, PAGED, rb, ra);
     }
+    if (blk < blk1) block_step(blk, Q, PAGED, ra, rb);
+  };
+  if (quantized) {
+    if (a.group_table != nullptr)
+      quantized_range(std::true_type{});
+    else
+      quantized_range(std::false_type{});
   } else {
     plain_q();
     for (int blk = blk0; blk < blk1; ++blk) block_step(blk, std::false_type{}, std::false_type{}, ra, rb);
