@@ -174,14 +174,9 @@ int qs_append(const qs_cache *c, const void *k_new, const void *v_new, int32_t n
  * The query of sequence b attends the decoded upper plane of tokens [0, n_quant[b]) and buffer
  * tokens [0, n_buf[b]) (its own K/V must already be the last buffer token; Appendix A).
  * out = softmax(sm_scale * q K^T) V, sm_scale > 0 and finite (QS_ERR_RANGE otherwise).
- * Numerical domain (both attention calls): any fp16 q and V; keys whose quantization groups are not
- * all tiny - the 2e-3 accuracy of the outputs holds while the per-channel spread max - min of the keys
- * of a group reaches about 0.1 in at least the channels that carry the scores (keys of a
- * transformer are O(1); spreads up to the fp16 maximum are fine).  Uniformly smaller keys lose bits in
- * q * S, which enters the matrix cores as two fp16 numbers (spread 0.03: up to 3e-3; 0.003: 2.5e-2),
- * and the library cannot see that from its arguments.  A caller with such keys multiplies them by a
- * power of two before they enter the cache and divides sm_scale by it: the codes are the same, S and Z
- * scale exactly, and the result is that of the unscaled problem.
+ * Numerical domain (both attention calls): any finite fp16 q, K and V.  The 2e-3 accuracy of the outputs does
+ * not depend on their magnitudes: a row's queries, the key scales of a group and the value scales met so far are
+ * each brought into a fixed range by a power of two before they enter the matrix cores as fp16 numbers.
  * lse (device float [B][1][n_q_heads], natural log of the
  * softmax normaliser) is written if not NULL.
  */

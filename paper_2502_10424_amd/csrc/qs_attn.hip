@@ -130,6 +130,18 @@ __device__ __forceinline__ float group_sum(float x) {
   x += __shfl_xor(x, 16);
   return x + __shfl_xor(x, 32);
 }
+__device__ __forceinline__ float pow2(int e) { return __builtin_bit_cast(float, (uint32_t)(127 + e) << 23); }   // -126 <= e <= 127
+__device__ __forceinline__ int exponent_of(float x) { return (int)((__builtin_bit_cast(uint32_t, x) >> 23) & 255u) - 127; }
+using ushort2v = unsigned short __attribute__((ext_vector_type(2)));
+
+// Largest of fp16 numbers that are not negative, two at a time: their bit patterns order like the numbers.
+__device__ __forceinline__ uint32_t max_bits(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2v, a), __builtin_bit_cast(ushort2v, b)));
+}
+__device__ __forceinline__ float larger_half(uint32_t a) {
+  const half2v h = as_half2(a);
+  return fmaxf((float)h[0], (float)h[1]);
+}
 // Over the eight lanes (l & ~7) .. (l | 7): used by the single-row path, where the eight tokens a
 // lane group shares are spread over eight lanes.
 __device__ __forceinline__ float octet_max(float x) {
@@ -583,8 +595,8 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   }
 
   // Queries of this lane's column: channels 32*g + 8*s + operand order.  Each row is scaled by a power
-  // of two so that max|q| <= 1 (then |q*S| <= 8734 cannot overflow fp16 whatever the inputs are); the
-  // power goes into the row's score multiplier.  Elements 2,3,6,7 also take the code operand's 2^-4.
+  // of two so that max|q| <= 1 (the key scales are lifted below 2^15, see next_lift: q*S cannot overflow
+  // fp16 whatever the inputs are); the power goes into the row's score multiplier.  Elements 2,3,6,7 also take the code operand's 2^-4.
   half2v qv[NRT][16];
   float mul[NRT];
   static_for<NRT>([&](auto RT) {
@@ -622,14 +634,31 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
   // Query operand of the current group (qb, cin) and, built one k-step per block, of the next one.
   // q*S is split exactly into fp16(q*S) and the fp16 remainder q*S - fp16(q*S): two operands
   // accumulated into the same MFMA result for a tile of 16 rows, two columns of one operand otherwise.
+  // The scales of a group are first lifted by the power of two 2^fs that brings the largest of them, over all
+  // channels, into [2^14, 2^15): exact, and with |q| <= 1 the products stay inside fp16 while the remainder keeps
+  // its bits however small the keys' spread is.  gmul, the group's score multiplier, takes the lift back.
   half8 qb[NRT][2][4], qbn[NRT][2][4];
-  float cin[NRT], acc_a[NRT], acc_b[NRT], acc_sa[NRT], acc_sb[NRT];
+  float cin[NRT], gmul[NRT], acc_a[NRT], acc_b[NRT], acc_sa[NRT], acc_sb[NRT];
+  int fs_n = 0;
+  _Float16 up_n = (_Float16)1.0f;
+  auto next_lift = [&](const u32x4 (&S)[4]) {   // S: the key scales of this lane's 32 channels; the four lane groups cover all 128
+    uint32_t sm = 0u;
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) sm = max_bits(sm, S[s4][r]);
+    fs_n = min(14 - max(exponent_of(group_max(larger_half(sm))), -24), 15);
+    up_n = (_Float16)pow2(fs_n);
+  };
   auto prep_reset = [&]() {
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt) acc_a[rt] = acc_b[rt] = acc_sa[rt] = acc_sb[rt] = 0.f;
   };
   auto prep_kstep = [&](auto S, u32x4 sw, u32x4 zw) {   // sw, zw: key S / Z of channels 32g + 8s.., operand order
     constexpr int s = decltype(S)::value;
+    half2v lifted[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) lifted[r] = as_half2(sw[r]) * up_n;
     static_for<NRT>([&](auto RT) {
       constexpr int rt = decltype(RT)::value;
       constexpr int M = mode_of<NRT, TAIL>(rt);
@@ -637,8 +666,8 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const half2v qh = qv[rt][4 * s + r], sh = as_half2(sw[r]), zh = as_half2(zw[r]);
-        const half2v hi = qh * sh;
-        const half2v lo = __builtin_elementwise_fma(qh, sh, -hi);
+        const half2v hi = qh * lifted[r];
+        const half2v lo = __builtin_elementwise_fma(qh, lifted[r], -hi);
         if (M == 16) {
           out[r] = as_u32(hi);
           out_lo[r] = as_u32(lo);
@@ -664,7 +693,8 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
       float bias = __builtin_fmaf(acc_b[rt], 1.0f / kKeyPos, acc_a[rt]);
       if (VERIFY) bias -= 0.5f * __builtin_fmaf(acc_sb[rt], 1.0f / kKeyPos, acc_sa[rt]);
       bias = group_sum(bias);
-      cin[rt] = bias * (1.0f / kKeyRaw);   // added to the raw scores inside the softmax step
+      cin[rt] = bias * (1.0f / kKeyRaw) * pow2(fs_n);   // added to the raw scores inside the softmax step
+      gmul[rt] = mul[rt] * pow2(-fs_n);
       if (SINGLE) cin[rt] = __shfl(cin[rt], lane & 48);   // every lane works on the one row of column 0
 #pragma unroll
       for (int h = 0; h < (M == 16 ? 2 : 1); ++h)
@@ -702,7 +732,10 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
       });
     }
     // the next group's query operand, spread over the blocks that follow the arrival of its metadata
-    if constexpr (p == 1) prep_kstep(std::integral_constant<int, 0>{}, nkS[0], nkZ[0]);
+    if constexpr (p == 1) {
+      next_lift(nkS);
+      prep_kstep(std::integral_constant<int, 0>{}, nkS[0], nkZ[0]);
+    }
     if constexpr (p == 2) {
       prep_kstep(std::integral_constant<int, 1>{}, nkS[1], nkZ[1]);
       prep_kstep(std::integral_constant<int, 2>{}, nkS[2], nkZ[2]);
@@ -710,18 +743,18 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
     if constexpr (p == 3) prep_kstep(std::integral_constant<int, 3>{}, nkS[3], nkZ[3]);
     half8 pb[NRT];
     if constexpr (SINGLE) {
-      pb[0] = single_row_block<VERIFY>(st, x[0], mul[0], cin[0], d.vS[0], d.vZ[0], rho, p == 0 && fresh);
+      pb[0] = single_row_block<VERIFY>(st, x[0], gmul[0], cin[0], d.vS[0], d.vZ[0], rho, p == 0 && fresh);
     } else {
       // ---- probabilities relative to the rows' references (see above) ----
       float base[NRT];
 #pragma unroll
-      for (int rt = 0; rt < NRT; ++rt) base[rt] = cin[rt] * mul[rt];
+      for (int rt = 0; rt < NRT; ++rt) base[rt] = cin[rt] * gmul[rt];
       if (p == 0 && fresh) {
 #pragma unroll
         for (int rt = 0; rt < NRT; ++rt) {
           float s[8];
 #pragma unroll
-          for (int j = 0; j < 8; ++j) s[j] = __builtin_fmaf(x[rt][j], mul[rt], base[rt]);
+          for (int j = 0; j < 8; ++j) s[j] = __builtin_fmaf(x[rt][j], gmul[rt], base[rt]);
           first_reference(st, rt, s);
         }
       }
@@ -731,7 +764,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
       for (int rt = 0; rt < NRT; ++rt) {
         const float shift = base[rt] - st.m[rt];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) x[rt][j] = __builtin_fmaf(x[rt][j], mul[rt], shift);   // the exponent score - m
+        for (int j = 0; j < 8; ++j) x[rt][j] = __builtin_fmaf(x[rt][j], gmul[rt], shift);   // the exponent score - m
         high |= max_of(x[rt]) > limit;
       }
       if (__any(high)) {
@@ -790,6 +823,7 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
 
   // the first group's query operand from the metadata requested at the start
   prep_reset();
+  next_lift(ks0);
   prep_kstep(std::integral_constant<int, 0>{}, ks0[0], kz0[0]);
   prep_kstep(std::integral_constant<int, 1>{}, ks0[1], kz0[1]);
   prep_kstep(std::integral_constant<int, 2>{}, ks0[2], kz0[2]);
@@ -1133,16 +1167,6 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
 // The next block's words are requested before the current block is worked on.
 // ------------------------------------------------------------------------------------------------
 using half4 = _Float16 __attribute__((ext_vector_type(4)));
-using ushort2v = unsigned short __attribute__((ext_vector_type(2)));
-
-// Largest of fp16 numbers that are not negative, two at a time: their bit patterns order like the numbers.
-__device__ __forceinline__ uint32_t max_bits(uint32_t a, uint32_t b) {
-  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2v, a), __builtin_bit_cast(ushort2v, b)));
-}
-__device__ __forceinline__ float larger_half(uint32_t a) {
-  const half2v h = as_half2(a);
-  return fmaxf((float)h[0], (float)h[1]);
-}
 
 // Row `row` (of the n_rows that share kv-head kvh of sequence b) in the [B][nq][Hq] order of q and out.
 __device__ __forceinline__ int64_t global_row(const AttnArgs& a, int b, int kvh, int row) {
@@ -1150,8 +1174,6 @@ __device__ __forceinline__ int64_t global_row(const AttnArgs& a, int b, int kvh,
   return ((int64_t)b * a.nq + qi) * a.n_q_heads + head;
 }
 
-__device__ __forceinline__ float pow2(int e) { return __builtin_bit_cast(float, (uint32_t)(127 + e) << 23); }   // -126 <= e <= 127
-__device__ __forceinline__ int exponent_of(float x) { return (int)((__builtin_bit_cast(uint32_t, x) >> 23) & 255u) - 127; }
 
 // The eight codes of a word (C_U, or 16*C_U + C_L + 8 from the words of both planes) as 16-bit numbers: the
 // matrix-core operand of the lane, element i = code i of the word.  Of the upper plane alone, elements 2, 3, 6

@@ -438,12 +438,12 @@ def test_attention_value_magnitudes(env, vmag):
         _check_attn(env, cache, oc, q[:, :1].copy(), 0.088, False, tag=f"draft |v|~{vmag:g} |q|~{qmag:g}")
 
 
-@pytest.mark.parametrize("kmag", [0.1, 100.0, 3000.0])
+@pytest.mark.parametrize("kmag", [1e-4, 1e-3, 1e-2, 0.1, 100.0, 3000.0])
 def test_attention_key_magnitudes(env, kmag):
-    """Keys four orders of magnitude apart with a softmax scale that keeps the scores at O(1), flat and
-    peaked.  q * S_K travels as two fp16 numbers with q normalised to at most 1 per row, so key scales
-    down to about 1e-2 (key spread 0.1) are safe; much smaller ones push q * S_K into fp16 subnormals
-    and are outside the documented domain (see the next test for what a caller does then)."""
+    """Keys seven orders of magnitude apart with a softmax scale that keeps the scores at O(1), flat and
+    peaked.  q * S_K travels as two fp16 numbers, q normalised to at most 1 per row and the scales of a
+    group of keys lifted by a power of two taken from the largest of them, so neither large nor tiny
+    key spreads cost accuracy (1e-4: the scales themselves are fp16 subnormals)."""
     O, U = env["O"], env["U"]
     rng = np.random.default_rng(int(kmag * 10) + 11)
     t, nb = 1024, 19
@@ -460,11 +460,10 @@ def test_attention_key_magnitudes(env, kmag):
 
 @pytest.mark.parametrize("kmag", [1e-2, 1e-3])
 def test_attention_tiny_keys_through_the_documented_rescaling(env, kmag):
-    """Key spreads below the documented domain of the attention calls (every channel's max - min under
-    about 0.1) are handled by the caller as the header says: keys enter the cache multiplied by a power
-    of two and sm_scale is divided by it.  Scaling fp16 keys by a power of two scales S and Z by the same
-    and leaves the codes alone, so the result is that of the unscaled problem, which is what the oracle
-    computes here."""
+    """Scaling fp16 keys by a power of two scales S and Z by the same and leaves the codes alone, so a cache
+    that holds the lifted keys, called with sm_scale divided by the lift, answers the unscaled problem, which
+    is what the oracle computes here.  (What a caller with tiny keys had to do before the kernel lifted the
+    key scales itself; kept as a property of the quantizer and the attention calls.)"""
     O, U = env["O"], env["U"]
     rng = np.random.default_rng(int(1e4 * kmag) + 3)
     t, nb = 1024, 19
