@@ -1192,6 +1192,7 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
   constexpr int PL = VERIFY ? 2 : 1;                  // planes read
   constexpr int VSTRIDE = 40;                         // 16-bit elements per LDS row (keeps 8-byte reads aligned)
   constexpr int kEvFloor = -40;                       // below every value scale that is not zero (2^-24 / 16)
+  constexpr int kTauPlain = 6;                        // a score may exceed its row's reference by 2^6 before the reference is raised
   // LDS of the one wave: the two operands hi, lo of every (row tile, key step) for the quantized region, one
   // 16-byte slot per lane (a lane reads back what it wrote itself); or the values of a buffer block, [channel][token]
   // then (one tile of rows only: two would not leave room for eight waves per compute unit at head_dim 128) the
@@ -1337,7 +1338,7 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
 
   float m[NRT], l[NRT], zs[NRT][VG];
   float4v o[NRT][NT];   // O^T accumulators: tile n, element jj -> channel 16*n + 4*g + jj
-  int ev = quantized ? kEvFloor : 0;   // the P operand is p * mul * 2^(14 - ev)
+  int ev = quantized ? kEvFloor : 0;   // the P operand is p * mul * 2^(14 - kTauPlain - ev)
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
     m[rt] = kNegBig, l[rt] = 0.f;
@@ -1444,7 +1445,7 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
     }
     // ---- scores, in log2 units ----
     float x[NRT][8], mx[NRT];
-    bool grow = false;
+    bool high = false;
     float4v acc[NRT][2];
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt) acc[rt][0] = acc[rt][1] = (float4v){0.f, 0.f, 0.f, 0.f};
@@ -1483,12 +1484,12 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
           x[rt][4 * t + jj] = (quantized || tok < vis[rt]) ? __builtin_fmaf(acc[rt][t][jj], sc[rt], bias[rt]) : -__builtin_inff();
         }
 #pragma unroll
-    for (int rt = 0; rt < NRT; ++rt) {
-      mx[rt] = group_max(max_of(x[rt]));
-      grow |= mx[rt] > m[rt];
+    for (int rt = 0; rt < NRT; ++rt) {   // this lane's tokens only: the rows' references move rarely (see below)
+      mx[rt] = max_of(x[rt]);
+      high |= mx[rt] > m[rt] + kTauPlain;
     }
     // ---- largest value scale of the block ----
-    int eb = ev;
+    float smax = 0.f;
     uint2 vs[2][VG], vz[2][VG];   // value scale / zero of this lane's tokens 16 t + 4 g .. + 3: four tokens x VG groups
     if constexpr (quantized) {
       wave_lds_sync();
@@ -1504,15 +1505,20 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int c = 0; c < VG; ++c) sm = max_bits(sm, max_bits(vs[t][c].x, vs[t][c].y));
-      // the same in every lane: all lanes of a group of 16 share their tokens
-      eb = max(exponent_of(group_max(larger_half(sm))) - (VERIFY ? 4 : 0), ev);
+      smax = larger_half(sm);   // of this lane's tokens; all lanes of a group of 16 share their tokens
+      high |= exponent_of(smax) - (VERIFY ? 4 : 0) > ev;
     }
-    if (__any(grow) || eb > ev) {   // a running maximum or the scale exponent moves: rescale what is accumulated
+    // m is a reference, not the running maximum: it is raised, to the maximum so far, only when a score exceeds
+    // it by more than kTauPlain, so a probability is at most 2^kTauPlain and most blocks neither look across
+    // lanes nor touch what is accumulated; the same branch raises the scale exponent when a larger value scale
+    // appears.  A wave's first block always comes here (m starts at -infinity for all practical purposes).
+    if (__any(high)) {
+      const int eb = max(exponent_of(group_max(smax)) - (VERIFY ? 4 : 0), ev);
       const float alpha_e = pow2(max(ev - eb, -120));
       ev = eb;
 #pragma unroll
       for (int rt = 0; rt < NRT; ++rt) {
-        const float m_new = fmaxf(m[rt], mx[rt]);
+        const float m_new = fmaxf(m[rt], group_max(mx[rt]));
         const float alpha = __builtin_amdgcn_exp2f(m[rt] - m_new);
         m[rt] = m_new;
         l[rt] *= alpha;
@@ -1523,7 +1529,7 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
         for (int n = 0; n < NT; ++n) o[rt][n] *= both;
       }
     }
-    const float pscale = pow2(14 - ev) * (quantized && VERIFY ? 0.0625f : 1.0f);
+    const float pscale = pow2(14 - kTauPlain - ev) * (quantized && VERIFY ? 0.0625f : 1.0f);
     float xs[NRT][8];   // the probabilities with the power of two of the P operand
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt) {
@@ -1614,7 +1620,7 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
   }
   // ---- partial: (m, l) and the unnormalised output row ----
   const int n_split = a.n_split_q + a.n_split_b;
-  const float back = quantized ? pow2(ev + 10) : pow2(-14);   // 2^(ev - 14), and 2^24 for codes read as subnormals
+  const float back = quantized ? pow2(ev + 10 + kTauPlain) : pow2(kTauPlain - 14);   // 2^(ev + tau - 14), and 2^24 for codes read as subnormals
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
     const float lsum = group_sum(l[rt]);
