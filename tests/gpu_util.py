@@ -63,19 +63,21 @@ def export_unit(cache, b, h, n_tokens):
     return {k.replace("_", ""): v.cpu().numpy() for k, v in e.items()}
 
 
-def assert_unit_equals_oracle(cache, oc: O.CacheOracle, b, h):
-    """Bit-exact comparison of codes, scales and zeros of one unit, plus the buffer contents."""
+def assert_unit_equals_oracle(cache, oc: O.CacheOracle, b, h, oracle_head=None):
+    """Bit-exact comparison of codes, scales and zeros of one unit, plus the buffer contents.  oracle_head: the
+    unit's kv-head in the oracle's cache when that holds only some of the heads (default: h)."""
+    oh = h if oracle_head is None else oracle_head
     tq = oc.n_quant(b)
     assert cache.n_quant[b] == tq and cache.n_buf[b] == oc.n_buf(b)
     if tq:
         e = export_unit(cache, b, h, tq)
-        for name, ref in (("ku", oc.ku[b][h]), ("kl", oc.kl[b][h]), ("vu", oc.vu[b][h]), ("vl", oc.vl[b][h])):
+        for name, ref in (("ku", oc.ku[b][oh]), ("kl", oc.kl[b][oh]), ("vu", oc.vu[b][oh]), ("vl", oc.vl[b][oh])):
             assert np.array_equal(e[name], ref), f"{name} differs for unit ({b},{h})"
-        for name, ref in (("ks", oc.ks[b][h]), ("kz", oc.kz[b][h]), ("vs", oc.vs[b][h]), ("vz", oc.vz[b][h])):
+        for name, ref in (("ks", oc.ks[b][oh]), ("kz", oc.kz[b][oh]), ("vs", oc.vs[b][oh]), ("vz", oc.vz[b][oh])):
             assert np.array_equal(e[name].view(np.uint16).reshape(ref.shape), ref.view(np.uint16)), f"{name} differs for unit ({b},{h})"
     nb = oc.n_buf(b)
-    assert np.array_equal(cache.k_buf[b, h, :nb].cpu().numpy().view(np.uint16), oc.kbuf[b][h].view(np.uint16))
-    assert np.array_equal(cache.v_buf[b, h, :nb].cpu().numpy().view(np.uint16), oc.vbuf[b][h].view(np.uint16))
+    assert np.array_equal(cache.k_buf[b, h, :nb].cpu().numpy().view(np.uint16), oc.kbuf[b][oh].view(np.uint16))
+    assert np.array_equal(cache.v_buf[b, h, :nb].cpu().numpy().view(np.uint16), oc.vbuf[b][oh].view(np.uint16))
 
 
 def rel_err(out_gpu, out_ref):

@@ -130,6 +130,34 @@ def test_attention_magnitudes(env, d, g, kmag, vmag, qmag):
         _attn(env, cache, oc, q, sm, True, f"({d},{g}) verify |k|~{kmag:g} |v|~{vmag:g} |q|~{qmag:g} peak {peak}")
 
 
+@pytest.mark.parametrize("d,g", [(64, 64), (128, 32), (256, 128)])
+def test_attention_at_the_benchmarked_size(env, d, g):
+    """The configuration bench.py times for these shapes - one sequence, 32 kv-heads, no grouped queries, 32768 tokens
+    of which 256 are in the buffer, default planner - with three of the 32 units checked against the oracle:
+    all rows of draft and verify, codes and metadata of the unit's whole length bit for bit."""
+    O, U, B, torch = env["O"], env["U"], env["B"], env["torch"]
+    rng = np.random.default_rng(4000 + d + g)
+    heads, ctx, nb, nq = 32, 32768, 256, 5
+    k = rng.standard_normal((1, heads, ctx, d), dtype=np.float32).astype(np.float16)
+    v = rng.standard_normal((1, heads, ctx, d), dtype=np.float32).astype(np.float16)
+    q = rng.standard_normal((1, nq, heads, d), dtype=np.float32).astype(np.float16)
+    _say(f"({d},{g}) at 32 heads x {ctx} tokens: quantize")
+    cache = U.make_device_cache(k, v, heads, nb, buf_cap=nb + 8, group=g)
+    sm = 1.0 / np.sqrt(d)
+    qd = torch.from_numpy(q).cuda()
+    out_d = B.qs_attn_draft(cache, qd[:, :1].contiguous(), sm).cpu().numpy()
+    out_v = B.qs_attn_verify(cache, qd, sm).cpu().numpy()
+    torch.cuda.synchronize()
+    for h in (0, 13, 31):
+        oc = O.build_cache(k[:, h:h + 1], v[:, h:h + 1], 1, g, nb)
+        U.assert_unit_equals_oracle(cache, oc, 0, h, oracle_head=0)
+        ref_d, _ = oc.attn_draft(q[:, :1, h:h + 1], sm)
+        ref_v, _ = oc.attn_verify(q[:, :, h:h + 1], sm)
+        ed, ev = U.rel_err(out_d[:, :, h:h + 1], ref_d), U.rel_err(out_v[:, :, h:h + 1], ref_v)
+        _say(f"({d},{g}) unit {h}: draft max rel err {ed:.2e}, verify {ev:.2e}")
+        assert ed <= TOL and ev <= TOL
+
+
 @pytest.mark.parametrize("d,g", [(64, 32), (256, 64)])
 def test_buffer_only_and_paged(env, d, g):
     """Nothing quantized yet (all tokens in the full-precision buffer), and a paged cache whose 128-token
