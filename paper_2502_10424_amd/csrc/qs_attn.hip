@@ -204,31 +204,6 @@ __device__ __forceinline__ void tile_scores(const float4v& a0, const float4v& a1
   }
 }
 
-// Eight fp16 values (two per 32-bit word) as floats.
-__device__ __forceinline__ void meta_floats(const u32x4& d, float (&f)[8]) {
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const half2v h = as_half2(d[r]);
-    f[2 * r] = (float)h[0], f[2 * r + 1] = (float)h[1];
-  }
-}
-
-// p * S of this lane's tokens -> the lane's operand of the value contraction.  The draft pass scales
-// the words whose codes sit four bits higher in their half (odd words) by 2^-4; see the constants in
-// quant_chunk.
-template <bool VERIFY>
-__device__ __forceinline__ half8 p_operand(const float (&ps)[8]) {
-  u32x4 pw;
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    half2v h;
-    h[0] = (_Float16)ps[2 * r], h[1] = (_Float16)ps[2 * r + 1];
-    if (!VERIFY && (r & 1)) h = h * (_Float16)0.0625f;
-    pw[r] = as_u32(h);
-  }
-  return as_half8(pw);
-}
-
 // ------------------------------------------------------------------------------------------------
 // Online softmax with a reference that moves rarely.  A row keeps a reference exponent m (log2 units)
 // and everything it accumulates - sum l, zero-point term z, output o - is relative to it:
@@ -789,23 +764,31 @@ __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, 
 #pragma unroll
           for (int j = 0; j < 8; ++j) x[rt][j] *= alpha;
       });
-      float sv[8], zeff[8];
-      meta_floats(d.vS, sv);
-      meta_floats(d.vZ, zeff);
+      // The scales and zeros enter as the fp16 numbers they are (mixed-precision multiply-adds: no conversion
+      // of its own, and the product comes out as the fp16 half of the operand word), products in binary32.
+      const half8 sv = as_half8(d.vS), zv = as_half8(d.vZ);
+      float zeff[8];
       if (VERIFY) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) zeff[j] = __builtin_fmaf(-0.5f, sv[j], zeff[j]);
+        for (int j = 0; j < 8; ++j) zeff[j] = __builtin_fmaf(-0.5f, (float)sv[j], (float)zv[j]);
       }
 #pragma unroll
       for (int rt = 0; rt < NRT; ++rt) {
-        float zs = 0.f, ps[8];
+        float zs = 0.f;
+        half8 ph;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          zs = __builtin_fmaf(x[rt][j], zeff[j], zs);
-          ps[j] = x[rt][j] * sv[j];
+          zs = __builtin_fmaf(x[rt][j], VERIFY ? zeff[j] : (float)zv[j], zs);
+          ph[j] = (_Float16)__builtin_fmaf(x[rt][j], (float)sv[j], 0.f);
         }
         st.z[rt] += zs;
-        pb[rt] = p_operand<VERIFY>(ps);
+        if (!VERIFY) {   // the words whose codes sit four bits higher in their half (odd words) take 2^-4
+          u32x4 pw = as_u32x4(ph);
+          pw[1] = as_u32(as_half2(pw[1]) * (_Float16)0.0625f);
+          pw[3] = as_u32(as_half2(pw[3]) * (_Float16)0.0625f);
+          ph = as_half8(pw);
+        }
+        pb[rt] = ph;
       }
     }
 
