@@ -22,6 +22,9 @@ What it follows
   the concatenated cache (here: decoded quantized tokens, then buffer tokens).
 * Algorithm 1: the draft pass reads C_U and the buffer; the target pass reads
   C_U, C_L and the buffer, for gamma + 1 query tokens at once.
+* Abstract and Section 4 (first paragraph): the draft model's weights are INT4.  quantize_w /
+  linear_w4 at the end of this file: the same quantizer, one (S, Z) per output row and G input
+  channels, and the layer y = x W_hat^T in float64 (pins: tests/test_oracle_w4.py).
 
 Readings where the paper is silent (each is also listed in the design notes):
 * scale/zero: Z = min, S = (max - min) / 15, stored as fp16; S == 0 -> S := 1.
@@ -298,3 +301,29 @@ def build_cache(k: np.ndarray, v: np.ndarray, n_q_heads: int, group: int, n_buf)
                 c.kbuf[b][h] = c.kbuf[b][h][tq:].copy()
                 c.vbuf[b][h] = c.vbuf[b][h][tq:].copy()
     return c
+
+
+# --------------------------------------------------------------------------
+# The draft model's linear layers: 4-bit weights (abstract; Section 4, first paragraph; Section 5.3's ablation)
+# --------------------------------------------------------------------------
+# The paper quantizes the draft's weights into INT4 and names no quantizer for them (it cites weight-only
+# methods in its related work).  Reading: the quantizer of Section 4.2 itself, upper plane only - asymmetric
+# round-to-nearest, C in [0, 15], w_hat = C S + Z - with one (S, Z) per output row and per G consecutive
+# input channels (the group size of Section 5.1, 128), S and Z stored in fp16.  That is what quantize_v
+# computes for a [rows, channels] matrix, so the pinned functions above serve here unchanged.
+def quantize_w(w: np.ndarray, group: int):
+    """Weights [N, K] fp16 (y = x W^T) -> (C uint8 [N, K], S fp16 [N, K/G], Z fp16 [N, K/G])."""
+    c, _, s, z = quantize_v(w, group)
+    return c, s, z
+
+
+def decode_w(c: np.ndarray, s: np.ndarray, z: np.ndarray, group: int) -> np.ndarray:
+    """w_hat = C S + Z in float64, [N, K]."""
+    se = np.repeat(np.asarray(s, F16).astype(F64), group, axis=1)
+    ze = np.repeat(np.asarray(z, F16).astype(F64), group, axis=1)
+    return c.astype(F64) * se + ze
+
+
+def linear_w4(x: np.ndarray, c: np.ndarray, s: np.ndarray, z: np.ndarray, group: int) -> np.ndarray:
+    """y[m, n] = sum_k x[m, k] w_hat[n, k] in float64; x fp16 [M, K]."""
+    return np.asarray(x, F16).astype(F64) @ decode_w(c, s, z, group).T
