@@ -222,6 +222,50 @@ int qs_export_codes(const qs_cache *c, int32_t b, int32_t kv_head, int32_t n_tok
                     void *k_u, void *k_l, void *k_s, void *k_z,
                     void *v_u, void *v_l, void *v_s, void *v_z, void *stream);
 
+/*
+ * ---- The draft model's linear layers: 4-bit weights (abstract; Section 4, first paragraph) ----
+ * The draft model shares the target's architecture with its weights in INT4.  The paper names no quantizer for
+ * them; this library applies the one of Section 4.2 (upper plane only): asymmetric round-to-nearest codes
+ * C in [0, 15], w_hat = C S + Z, one fp16 pair (S, Z) per output row and QS_W4_GROUP consecutive input channels
+ * (the group size of Section 5.1), Z = min, S = (max - min) / 15, S = 1 where that is zero, code decisions
+ * in binary32 as for the cache.
+ *
+ * A layer y = x W^T with W [n_out][n_in]: n_out a multiple of 16, n_in a multiple of QS_W4_GROUP and at most 32768.
+ * packed (device, caller-owned, qs_w4_bytes() bytes, 16-byte aligned; qs_w4_quantize is its only writer) is cut
+ * into blocks of 16 output rows x 128 input channels, 1088 bytes each, block (T, g) at ((T*(n_in/128) + g)*1088):
+ *   [   0, 1024)  codes, one 32-bit word per lane of a 64-lane wave (lane = 16*a + r, a < 4, r < 16) and
+ *                 matrix-core step s < 4, at (lane*4 + s)*4: row 16*T + r, input channels
+ *                 128*g + 32*s + 8*a + i (i < 8), channel i in nibble (i&1)*4 + (i>>1)
+ *   [1024, 1056)  S of the 16 rows, fp16       [1056, 1088)  Z of the 16 rows, fp16
+ * Error behaviour as above: negative code, nothing enqueued.  QS_ERR_SHAPE for sizes that are not multiples
+ * as stated or m outside 1..QS_W4_MAX_ROWS, QS_ERR_NULL / QS_ERR_ALIGN for pointers.
+ */
+#define QS_W4_GROUP 128
+#define QS_W4_MAX_ROWS 16
+typedef struct {
+  int32_t n_out, n_in;
+  void *packed;
+} qs_w4;
+
+/* Bytes of `packed` for a layer of this size; 0 if the size is not supported. */
+size_t qs_w4_bytes(int32_t n_out, int32_t n_in);
+
+/* Quantizes w (device fp16 [n_out][n_in], row-major) into l->packed. */
+int qs_w4_quantize(const qs_w4 *l, const void *w, void *stream);
+
+/*
+ * y[i][n] = sum_k x[i][k] w_hat[n][k] for i < m:  x device fp16 [m][n_in], y device fp16 [m][n_out],
+ * 1 <= m <= QS_W4_MAX_ROWS (the draft's decode step is m = 1 per sequence).  Products of codes and inputs
+ * are exact, sums are binary32, y is rounded to fp16 once.  Deterministic: a row's sum is formed in a fixed order.
+ */
+int qs_w4_linear(const qs_w4 *l, const void *x, int32_t m, void *y, void *stream);
+
+/*
+ * Inspection helper: codes uint8 [n_out][n_in], scale and zero fp16 [n_out][n_in/128] (device pointers, any
+ * may be NULL to skip).
+ */
+int qs_w4_export(const qs_w4 *l, void *codes, void *scale, void *zero, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,7 +28,8 @@ QS_ERR_NULL, QS_ERR_SHAPE, QS_ERR_UNSUPPORTED, QS_ERR_ALIGN = -1, -2, -3, -4
 QS_ERR_RANGE, QS_ERR_WORKSPACE, QS_ERR_HIP = -5, -6, -7
 
 EXPORTS = ("qs_version", "qs_strerror", "qs_workspace_bytes", "qs_attn_static", "qs_quantize_flush", "qs_quantize_prefill",
-           "qs_append", "qs_attn_draft", "qs_attn_verify", "qs_export_codes")
+           "qs_append", "qs_attn_draft", "qs_attn_verify", "qs_export_codes",
+           "qs_w4_bytes", "qs_w4_quantize", "qs_w4_linear", "qs_w4_export")
 
 
 class qs_cache(ctypes.Structure):
@@ -42,6 +43,10 @@ class qs_cache(ctypes.Structure):
         ("group_table", ctypes.c_void_p), ("pool_groups", ctypes.c_int32),
         ("compute_units", ctypes.c_int32), ("flags", ctypes.c_uint32),
     ]
+
+
+class qs_w4(ctypes.Structure):
+    _fields_ = [("n_out", ctypes.c_int32), ("n_in", ctypes.c_int32), ("packed", ctypes.c_void_p)]
 
 
 class QsError(RuntimeError):
@@ -77,6 +82,11 @@ def lib() -> ctypes.CDLL:
         l.qs_attn_static.argtypes = [P, vp, i32, i32, vp, f32, vp, vp]
         l.qs_export_codes.restype = ctypes.c_int
         l.qs_export_codes.argtypes = [P, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        W = ctypes.POINTER(qs_w4)
+        l.qs_w4_bytes.restype, l.qs_w4_bytes.argtypes = sz, [i32, i32]
+        l.qs_w4_quantize.restype, l.qs_w4_quantize.argtypes = ctypes.c_int, [W, vp, vp]
+        l.qs_w4_linear.restype, l.qs_w4_linear.argtypes = ctypes.c_int, [W, vp, i32, vp, vp]
+        l.qs_w4_export.restype, l.qs_w4_export.argtypes = ctypes.c_int, [W, vp, vp, vp, vp]
         _lib = l
     return _lib
 
@@ -266,3 +276,55 @@ def qs_export_codes(cache: KVCache, b: int, kv_head: int, n_tokens: int, stream=
                                  v_s.data_ptr(), v_z.data_ptr(), _stream(stream)),
            "qs_export_codes")
     return dict(k_u=k_u, k_l=k_l, k_s=k_s, k_z=k_z, v_u=v_u, v_l=v_l, v_s=v_s, v_z=v_z)
+
+
+QS_W4_GROUP = 128
+QS_W4_MAX_ROWS = 16
+
+
+def qs_w4_bytes(n_out: int, n_in: int) -> int:
+    return int(lib().qs_w4_bytes(n_out, n_in))
+
+
+class W4Linear:
+    """Device storage of one 4-bit weight matrix W [n_out, n_in] (y = x W^T); memory only, the library fills it."""
+
+    def __init__(self, n_out: int, n_in: int, device="cuda"):
+        nbytes = qs_w4_bytes(n_out, n_in)
+        if nbytes == 0:
+            raise QsError(QS_ERR_SHAPE, "qs_w4_bytes")
+        self.n_out, self.n_in = n_out, n_in
+        self.packed = torch.zeros(nbytes, dtype=torch.uint8, device=device)
+
+    def struct(self) -> qs_w4:
+        return qs_w4(self.n_out, self.n_in, self.packed.data_ptr())
+
+
+def qs_w4_quantize(layer: W4Linear, w, stream=None) -> None:
+    """w: device fp16 [n_out, n_in], contiguous."""
+    assert w.dtype == torch.float16 and w.is_contiguous() and tuple(w.shape) == (layer.n_out, layer.n_in)
+    c = layer.struct()
+    _check(lib().qs_w4_quantize(ctypes.byref(c), w.data_ptr(), _stream(stream)), "qs_w4_quantize")
+
+
+def qs_w4_linear(layer: W4Linear, x, out=None, stream=None):
+    """x: device fp16 [m, n_in], contiguous, m <= QS_W4_MAX_ROWS; returns fp16 [m, n_out]."""
+    assert x.dtype == torch.float16 and x.is_contiguous() and x.dim() == 2 and x.shape[1] == layer.n_in
+    m = x.shape[0]
+    if out is None:
+        out = torch.empty((m, layer.n_out), dtype=torch.float16, device=x.device)
+    c = layer.struct()
+    _check(lib().qs_w4_linear(ctypes.byref(c), x.data_ptr(), m, out.data_ptr(), _stream(stream)), "qs_w4_linear")
+    return out
+
+
+def qs_w4_export(layer: W4Linear, stream=None):
+    """Codes uint8 [n_out, n_in], scale and zero fp16 [n_out, n_in / 128] as device tensors."""
+    dev = layer.packed.device
+    codes = torch.empty((layer.n_out, layer.n_in), dtype=torch.uint8, device=dev)
+    scale = torch.empty((layer.n_out, layer.n_in // QS_W4_GROUP), dtype=torch.float16, device=dev)
+    zero = torch.empty_like(scale)
+    c = layer.struct()
+    _check(lib().qs_w4_export(ctypes.byref(c), codes.data_ptr(), scale.data_ptr(), zero.data_ptr(), _stream(stream)),
+           "qs_w4_export")
+    return codes, scale, zero

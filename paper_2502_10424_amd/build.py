@@ -17,6 +17,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE,
 SOURCES = [
     ("qs_flush.hip", ["-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt"]),
     ("qs_attn.hip", []),
+    ("qs_w4.hip", []),
     ("qs_api.hip", []),
 ]
 

@@ -222,6 +222,19 @@ int quantize_common(const qs_cache* c, const _Float16* k_src, const _Float16* v_
   return launch_flush(f, c->batch, s) == hipSuccess ? QS_OK : QS_ERR_HIP;
 }
 
+// 4-bit weight layers: the sizes the kernels are built for (the sums of x per group of one launch live in LDS)
+constexpr int kW4MaxIn = 32768;
+int w4_args(const qs_w4* l, W4Args& a) {
+  if (l == nullptr || l->packed == nullptr) return QS_ERR_NULL;
+  if (l->n_out <= 0 || l->n_in <= 0 || l->n_out % 16 != 0 || l->n_in % QS_W4_GROUP != 0 || l->n_in > kW4MaxIn)
+    return QS_ERR_SHAPE;
+  if (!aligned16(l->packed)) return QS_ERR_ALIGN;
+  a.packed = static_cast<uint8_t*>(l->packed);
+  a.n_out = l->n_out;
+  a.n_in = l->n_in;
+  return QS_OK;
+}
+
 }  // namespace
 }  // namespace qs
 
@@ -367,6 +380,44 @@ int qs_export_codes(const qs_cache* c, int32_t b, int32_t kv_head, int32_t n_tok
   e.v_z = static_cast<_Float16*>(v_z);
   e.n_tokens = n_tokens;
   return launch_export(e, static_cast<hipStream_t>(stream)) == hipSuccess ? QS_OK : QS_ERR_HIP;
+}
+
+size_t qs_w4_bytes(int32_t n_out, int32_t n_in) {
+  if (n_out <= 0 || n_in <= 0 || n_out % 16 != 0 || n_in % QS_W4_GROUP != 0 || n_in > kW4MaxIn) return 0;
+  return (size_t)(n_out / 16) * (size_t)(n_in / QS_W4_GROUP) * kW4Block;
+}
+
+int qs_w4_quantize(const qs_w4* l, const void* w, void* stream) {
+  W4Args a{};
+  int rc = w4_args(l, a);
+  if (rc != QS_OK) return rc;
+  if (w == nullptr) return QS_ERR_NULL;
+  if (!aligned16(w)) return QS_ERR_ALIGN;
+  a.w = static_cast<const _Float16*>(w);
+  return launch_w4_quantize(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QS_OK : QS_ERR_HIP;
+}
+
+int qs_w4_linear(const qs_w4* l, const void* x, int32_t m, void* y, void* stream) {
+  W4Args a{};
+  int rc = w4_args(l, a);
+  if (rc != QS_OK) return rc;
+  if (x == nullptr || y == nullptr) return QS_ERR_NULL;
+  if (!aligned16(x) || !aligned16(y)) return QS_ERR_ALIGN;
+  if (m < 1 || m > QS_W4_MAX_ROWS) return QS_ERR_SHAPE;
+  a.x = static_cast<const _Float16*>(x);
+  a.y = static_cast<_Float16*>(y);
+  a.m = m;
+  return launch_w4_linear(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QS_OK : QS_ERR_HIP;
+}
+
+int qs_w4_export(const qs_w4* l, void* codes, void* scale, void* zero, void* stream) {
+  W4Args a{};
+  int rc = w4_args(l, a);
+  if (rc != QS_OK) return rc;
+  a.codes = static_cast<uint8_t*>(codes);
+  a.scale = static_cast<_Float16*>(scale);
+  a.zero = static_cast<_Float16*>(zero);
+  return launch_w4_export(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QS_OK : QS_ERR_HIP;
 }
 
 }  // extern "C"

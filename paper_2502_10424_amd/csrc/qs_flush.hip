@@ -720,6 +720,54 @@ __global__ __launch_bounds__(256) void export_plain_kernel(ExportArgs a) {
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// 4-bit weights of the draft model's linear layers (see quantspec.h): the quantizer above, one group per
+// output row and 128 input channels.  One workgroup per block of 16 rows x 128 channels; thread (r, c)
+// takes channels 8c .. 8c+7 of row r, which are exactly the eight codes of one word of the layout.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void w4_quantize_kernel(W4Args a) {
+  const int groups = a.n_in / 128;
+  const int T = blockIdx.x / groups, g = blockIdx.x % groups;
+  const int r = threadIdx.x >> 4, c = threadIdx.x & 15;
+  const half8 x = ld_half8(a.w + (int64_t)(16 * T + r) * a.n_in + 128 * g + 8 * c);
+  float lo = (float)x[0], hi = lo;
+#pragma unroll
+  for (int i = 1; i < 8; ++i) lo = fminf(lo, (float)x[i]), hi = fmaxf(hi, (float)x[i]);
+#pragma unroll
+  for (int m = 1; m < 16; m <<= 1) lo = fminf(lo, __shfl_xor(lo, m)), hi = fmaxf(hi, __shfl_xor(hi, m));
+  const _Float16 sh = make_scale(lo, hi);
+  const GroupScale gs = group_scale((float)sh, lo);
+  uint32_t word = 0u;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) word |= (uint32_t)encode_fast((float)x[i], gs).u << (4 * tile_nibble(i));
+  uint8_t* blk = a.packed + (int64_t)blockIdx.x * kW4Block;
+  const int lane = 16 * (c & 3) + r, s = c >> 2;
+  reinterpret_cast<uint32_t*>(blk)[lane * 4 + s] = word;
+  if (c == 0) {
+    reinterpret_cast<_Float16*>(blk + kW4OffS)[r] = sh;
+    reinterpret_cast<_Float16*>(blk + kW4OffZ)[r] = (_Float16)lo;
+  }
+}
+
+// Packed weights -> one code per byte [n_out][n_in], scales and zeros [n_out][n_in / 128].
+__global__ __launch_bounds__(256) void w4_export_kernel(W4Args a) {
+  const int groups = a.n_in / 128;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;      // eight channels of one row
+  if (idx >= (int64_t)a.n_out * (a.n_in / 8)) return;
+  const int n = (int)(idx / (a.n_in / 8)), c8 = (int)(idx % (a.n_in / 8));
+  const int g = c8 / 16, c = c8 % 16, r = n % 16;
+  const uint8_t* blk = a.packed + ((int64_t)(n / 16) * groups + g) * kW4Block;
+  const uint32_t word = reinterpret_cast<const uint32_t*>(blk)[(16 * (c & 3) + r) * 4 + (c >> 2)];
+  if (a.codes != nullptr) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a.codes[(int64_t)n * a.n_in + 8 * c8 + i] = (uint8_t)((word >> (4 * tile_nibble(i))) & 15u);
+  }
+  if (c == 0) {
+    if (a.scale != nullptr) a.scale[(int64_t)n * groups + g] = reinterpret_cast<const _Float16*>(blk + kW4OffS)[r];
+    if (a.zero != nullptr) a.zero[(int64_t)n * groups + g] = reinterpret_cast<const _Float16*>(blk + kW4OffZ)[r];
+  }
+}
+
 // Calls f with the compile-time shape that matches (d, g); false if the shape is not built.
 template <typename F>
 bool with_shape(int d, int g, F&& f) {
@@ -779,6 +827,15 @@ hipError_t launch_export(const ExportArgs& a, hipStream_t s) {
   }
   const int words = a.n_tokens * kRowDw;
   return launch(export_kernel, dim3((words + 255) / 256), dim3(256), s, a);
+}
+
+hipError_t launch_w4_quantize(const W4Args& a, hipStream_t s) {
+  return launch(w4_quantize_kernel, dim3((a.n_out / 16) * (a.n_in / 128)), dim3(256), s, a);
+}
+
+hipError_t launch_w4_export(const W4Args& a, hipStream_t s) {
+  const int64_t items = (int64_t)a.n_out * (a.n_in / 8);
+  return launch(w4_export_kernel, dim3((unsigned)((items + 255) / 256)), dim3(256), s, a);
 }
 
 }  // namespace qs

@@ -149,4 +149,21 @@ hipError_t launch_append(const AppendArgs& a, int batch, hipStream_t s);
 hipError_t launch_attn(const AttnArgs& a, int batch, bool verify, hipStream_t s);
 hipError_t launch_merge(const MergeArgs& a, int rows_total, hipStream_t s);
 
+// ---- 4-bit weights: blocks of 16 output rows x 128 input channels (see quantspec.h) ----
+constexpr int kW4Block = 1088, kW4OffS = 1024, kW4OffZ = 1056;
+struct W4Args {
+  uint8_t* packed;
+  int n_out, n_in;
+  const _Float16* w;        // quantize: [n_out][n_in]
+  const _Float16* x;        // linear: [m][n_in]
+  _Float16* y;              // linear: [m][n_out]
+  int m;
+  uint8_t* codes;           // export
+  _Float16* scale;
+  _Float16* zero;
+};
+hipError_t launch_w4_quantize(const W4Args& a, hipStream_t s);
+hipError_t launch_w4_export(const W4Args& a, hipStream_t s);
+hipError_t launch_w4_linear(const W4Args& a, hipStream_t s);
+
 }  // namespace qs

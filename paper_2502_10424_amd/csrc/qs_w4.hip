@@ -1,0 +1,152 @@
+// The draft model's linear layers with 4-bit weights (abstract; Section 4): y = x W_hat^T for a few rows
+// of x (the decode step of the draft model: one row per sequence).  Bound by the HBM stream of the codes.
+//
+// The weights lie in blocks of 16 output rows x 128 input channels (quantspec.h): 1 KB of codes in the
+// order the lanes of a wave take them as matrix-core operands, then the 16 rows' scales and zeros.  A code
+// c, zero-extended to 16 bits, is the fp16 subnormal c * 2^-24 and goes to the matrix cores as it is, x as
+// it is: products exact, sums in binary32.  For one block
+//     sum_k x_k (c_k S + Z) = S * (sum_k c_k x_k) + Z * (sum_k x_k):
+// the first sum is four MFMA steps, the second depends on x alone and is formed once per launch.
+//
+// One workgroup of eight waves per tile of 16 output rows; wave w takes the blocks g = w, w + 8, ... of the
+// tile's row of blocks (which is contiguous in memory, so the workgroup streams one run), with the words,
+// scales, zeros and inputs of the next kAhead of its blocks requested ahead; the eight partial sums meet in
+// LDS in a fixed order (deterministic).  Every step issues the same loads - a block past the end is asked
+// for through buffer resources of no bytes, which return zero without touching memory - so the wait for a
+// block's words is a count, not a drain.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "qs_internal.h"
+
+namespace qs {
+namespace {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kWaves = 8, kAhead = 4;
+constexpr int kBufferWord3 = 0x00020000;   // raw 32-bit elements (gfx9 family)
+constexpr int kAuxStream = 2;              // non-temporal: the weights are read once per launch
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t resource(const void* base, uint32_t bytes) {
+  // the address is the same in every lane; saying so keeps the descriptor in scalar registers
+  const uint64_t p = reinterpret_cast<uint64_t>(base);
+  const uint64_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)p);
+  const uint64_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(p >> 32));
+  return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<uint8_t*>((hi << 32) | lo), 0, (int)bytes, kBufferWord3);
+}
+
+// Eight 4-bit codes of a word -> eight fp16 subnormals c * 2^-24; element i comes from nibble (i&1)*4 + (i>>1).
+__device__ __forceinline__ half8 code_operand(uint32_t w) {
+  u32x4 r;
+  r[0] = w & 0x000F000Fu;
+  r[1] = (w >> 4) & 0x000F000Fu;
+  r[2] = (w >> 8) & 0x000F000Fu;
+  r[3] = (w >> 12) & 0x000F000Fu;
+  return __builtin_bit_cast(half8, r);
+}
+
+__global__ __launch_bounds__(64 * kWaves) void w4_linear_kernel(W4Args a) {
+  // sum of x over each group of 128 inputs, [group][row of x]; then the waves' partial results
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  const int groups = a.n_in / 128;
+  float* xsum = reinterpret_cast<float*>(lds);
+  float4v* red = reinterpret_cast<float4v*>(lds + (size_t)groups * 16 * sizeof(float));
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int rho = lane & 15, q4 = lane >> 4;   // lane = 16 * q4 + rho: output rows 4 q4 .. 4 q4 + 3, row rho of x
+  const int T = blockIdx.x;
+
+  struct Slot {
+    u32x4 w;        // code words of the four matrix-core steps
+    u32x2 s, z;     // S, Z of output rows 4 q4 .. 4 q4 + 3
+    u32x4 x[4];     // x[rho][128 g + 32 s + 8 q4 ..], s < 4
+  };
+  const uint8_t* row_of_blocks = a.packed + (int64_t)T * groups * kW4Block;
+  const uint32_t x_bytes = (uint32_t)a.m * (uint32_t)a.n_in * 2u;
+  auto request = [&](Slot& sl, int g) __attribute__((always_inline)) {
+    const bool exists = g < groups;
+    const __amdgpu_buffer_rsrc_t rw = resource(row_of_blocks + (int64_t)min(g, groups - 1) * kW4Block, exists ? kW4Block : 0);
+    const __amdgpu_buffer_rsrc_t rx = resource(a.x, exists ? x_bytes : 0);   // rows of x past m read as zero
+    sl.w = __builtin_amdgcn_raw_buffer_load_b128(rw, lane * 16, 0, kAuxStream);
+    sl.s = __builtin_amdgcn_raw_buffer_load_b64(rw, kW4OffS + 8 * q4, 0, 0);
+    sl.z = __builtin_amdgcn_raw_buffer_load_b64(rw, kW4OffZ + 8 * q4, 0, 0);
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      sl.x[s] = __builtin_amdgcn_raw_buffer_load_b128(rx, (rho * a.n_in + 128 * min(g, groups - 1) + 32 * s + 8 * q4) * 2, 0, 0);
+  };
+  Slot slot[kAhead];
+#pragma unroll
+  for (int k = 0; k < kAhead; ++k) request(slot[k], wave + kWaves * k);
+
+  // ---- sums of x per group: 16 lanes to a (group, row) pair, eight inputs each ----
+  {
+    const int sub = tid & 15;
+    for (int item = tid >> 4; item < groups * a.m; item += (64 * kWaves) >> 4) {
+      const int g = item / a.m, row = item % a.m;
+      const half8 v = *reinterpret_cast<const half8*>(a.x + (int64_t)row * a.n_in + 128 * g + 8 * sub);
+      float sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) sum += (float)v[i];
+#pragma unroll
+      for (int m = 1; m < 16; m <<= 1) sum += __shfl_xor(sum, m);
+      if (sub == 0) xsum[g * 16 + row] = sum;
+    }
+    // rows past m: never read with a weight other than zero... but they are read: keep them finite
+    for (int i = tid; i < groups * 16; i += 64 * kWaves)
+      if ((i & 15) >= a.m) xsum[i] = 0.f;
+  }
+  __syncthreads();
+
+  float4v out_s = {0.f, 0.f, 0.f, 0.f}, out_z = {0.f, 0.f, 0.f, 0.f};   // sum of S * (codes . x) * 2^-24, and of Z * sum x
+  auto consume = [&](const Slot& sl, int g) __attribute__((always_inline)) {
+    float4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_operand(sl.w[s]), __builtin_bit_cast(half8, sl.x[s]), acc, 0, 0, 0);
+    const float xs = xsum[min(g, groups - 1) * 16 + rho];
+    const half4 sh = __builtin_bit_cast(half4, sl.s), zh = __builtin_bit_cast(half4, sl.z);
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+      out_s[jj] = __builtin_fmaf(acc[jj], (float)sh[jj], out_s[jj]);
+      out_z[jj] = __builtin_fmaf(xs, (float)zh[jj], out_z[jj]);
+    }
+  };
+  for (int g0 = wave; g0 < groups; g0 += kWaves * kAhead) {
+#pragma unroll
+    for (int k = 0; k < kAhead; ++k) {
+      consume(slot[k], g0 + kWaves * k);   // a block past the end holds zeros
+      request(slot[k], g0 + kWaves * (k + kAhead));
+    }
+  }
+
+  // ---- the eight partial results, added in the order of the waves ----
+  float4v part;
+#pragma unroll
+  for (int jj = 0; jj < 4; ++jj) part[jj] = __builtin_fmaf(out_s[jj], 16777216.0f, out_z[jj]);
+  red[wave * 64 + lane] = part;
+  __syncthreads();
+  if (wave == 0 && rho < a.m) {
+    float4v y = red[lane];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) y += red[w * 64 + lane];
+    half4 h;
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) h[jj] = (_Float16)y[jj];
+    *reinterpret_cast<half4*>(a.y + (int64_t)rho * a.n_out + 16 * T + 4 * q4) = h;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_w4_linear(const W4Args& a, hipStream_t s) {
+  const size_t lds = (size_t)(a.n_in / 128) * 16 * sizeof(float) + (size_t)kWaves * 64 * sizeof(float4v);
+  void* kargs[] = {const_cast<W4Args*>(&a)};
+  return hipLaunchKernel(reinterpret_cast<const void*>(w4_linear_kernel), dim3(a.n_out / 16), dim3(64 * kWaves), kargs, lds, s);
+}
+
+}  // namespace qs

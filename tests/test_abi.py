@@ -21,7 +21,7 @@ def B():
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "quantspec.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(qs_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(qs_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_symbols_are_exported(B):
@@ -188,7 +188,7 @@ def test_validation_paths_under_sanitizers(B, tmp_path):
         clang = shutil.which("amdclang") or shutil.which("clang")
     if clang is None:
         pytest.skip("no clang for the sanitizer runtime")
-    objs = [os.path.join(build.CSRC, n) for n in ("qs_attn.o", "qs_flush.o")]
+    objs = [os.path.join(build.CSRC, n) for n in ("qs_attn.o", "qs_flush.o", "qs_w4.o")]
     if not all(os.path.exists(o) for o in objs):
         build.build()
     san = ["-fsanitize=address", "-fsanitize=undefined", "-fno-sanitize-recover=undefined"]
