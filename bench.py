@@ -323,8 +323,9 @@ def main():
     ap.add_argument("--steps", type=int, default=1000, help="timed cycles of the headline workload")
     ap.add_argument("--warmup", type=int, default=200, help="untimed cycles of the headline workload before them")
     ap.add_argument("--workload", default="all",
-                    help="'all' (headline mha128k, then the other baseline workloads), one workload's name, or 'other_shapes' "
-                         "(only the call times of the other (head_dim, group) shapes, for kernel traces)")
+                    help="'all' (headline mha128k, then the other baseline workloads), one workload's name, 'other_shapes' "
+                         "(only the call times of the other (head_dim, group) shapes, for kernel traces) or 'w4_linear' (only the "
+                         "draft model's 4-bit-weight linear layers)")
     ap.add_argument("--copies", type=int, default=4, help="independent cache copies a single-layer workload rotates over")
     ap.add_argument("--precondition", type=float, default=PRECONDITION_S,
                     help="seconds of the cycle run untimed before the warm-up steps (0 for counter collection runs)")
@@ -352,6 +353,9 @@ def main():
     if args.workload == "other_shapes":
         # --steps below 100: a few launches per kernel only (counter collection)
         print(json.dumps({"other_shapes": other_shapes(torch, B, seconds=0.25 if args.steps >= 100 else 0.002)}), flush=True)
+        return
+    if args.workload == "w4_linear":
+        print(json.dumps({"w4_linear": w4_linear(torch, B, seconds=0.25 if args.steps >= 100 else 0.002)}), flush=True)
         return
     names = ALL_WORKLOADS if args.workload == "all" else (args.workload,)
     if args.trace_transient:
@@ -420,6 +424,7 @@ def main():
     result["workloads"] = workloads
     if extras and args.workload == "all":
         result["other_shapes"] = other_shapes(torch, B)
+        result["w4_linear"] = w4_linear(torch, B)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, k_host, v_host, sm_scale)
     result["wall_s"] = round(time.time() - t_all, 1)
@@ -642,6 +647,65 @@ def other_shapes(torch, B, ctx=32768, n_buf=256, heads=32, nq_verify=5, seconds=
         out[f"d{d}_g{g}"] = entry
         del cache, ws
         torch.cuda.empty_cache()
+    return out
+
+
+# The linear layers of one decoder layer of a 7B model (hidden 4096, MLP 11008, 32 layers) and its output
+# layer, as the draft model's decode step sees them: 4-bit weights, one row of x.
+W4_LAYERS = (("qkv_proj", 12288, 4096), ("o_proj", 4096, 4096), ("gate_up_proj", 22016, 4096), ("down_proj", 4096, 11008),
+             ("lm_head", 32000, 4096))
+# the same projections of a 70B model (hidden 8192, MLP 28672, 8 kv-heads): where a launch's fixed cost no longer dominates
+W4_LAYERS_LARGE = (("qkv_proj_70b", 10240, 8192), ("o_proj_70b", 8192, 8192), ("gate_up_proj_70b", 57344, 8192),
+                   ("down_proj_70b", 8192, 28672))
+
+
+def w4_linear(torch, B, copies_bytes=1 << 30, seconds=0.25):
+    """Call times of qs_w4_linear (one row of x) per layer shape, each timed back to back over enough
+    independent copies of the weights (1 GiB of them) that the 256 MB last-level cache cannot serve them, as in a
+    decode step that walks through the model once per token.  Bytes: the packed weights, x and y."""
+    out = {}
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    for name, n_out, n_in in W4_LAYERS + W4_LAYERS_LARGE:
+        nbytes_w = B.qs_w4_bytes(n_out, n_in)
+        copies = max(4, -(-copies_bytes // nbytes_w))
+        layers = []
+        w = torch.randn((n_out, n_in), generator=gen, device="cuda", dtype=torch.float16) * 0.02
+        for _ in range(copies):
+            layer = B.W4Linear(n_out, n_in)
+            B.qs_w4_quantize(layer, w)
+            layers.append(layer.struct())
+            layers[-1]._keep = layer
+        del w
+        x = torch.randn((1, n_in), generator=gen, device="cuda", dtype=torch.float16)
+        y = torch.empty((1, n_out), device="cuda", dtype=torch.float16)
+        lib, stream = B.lib(), torch.cuda.current_stream().cuda_stream or None
+        import ctypes
+
+        def run(reps):
+            for i in range(reps):
+                rc = lib.qs_w4_linear(ctypes.byref(layers[i % copies]), x.data_ptr(), 1, y.data_ptr(), stream)
+                if rc != 0:
+                    raise B.QsError(rc, "qs_w4_linear")
+        run(copies)
+        torch.cuda.synchronize()
+        t0 = time.time()
+        run(copies)
+        torch.cuda.synchronize()
+        reps = int(min(4000, max(2 * copies, seconds / max((time.time() - t0) / copies, 1e-6))))
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        run(reps)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1000.0 / reps
+        nbytes = nbytes_w + 2 * n_in + 2 * n_out
+        out[name] = {"n_out": n_out, "n_in": n_in, "copies": copies, "us": round(us, 2), "bytes": nbytes,
+                     "GBps": round(nbytes / us / 1e3, 1), "frac": round(nbytes / us / 1e3 / HBM_PEAK_GBPS, 3)}
+        del layers, x, y
+        torch.cuda.empty_cache()
+    per_layer = sum(out[n]["us"] for n, _, _ in W4_LAYERS[:4])
+    out["decoder_layer_us"] = round(per_layer, 2)
+    out["model_32_layers_us"] = round(32 * per_layer + out["lm_head"]["us"], 1)
     return out
 
 

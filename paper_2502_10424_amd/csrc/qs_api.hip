@@ -19,9 +19,8 @@ constexpr int kMinBufSplits = 8;   // a decode-time buffer (2G + gamma + 1 token
 constexpr int kMaxDevices = 64;
 std::atomic<int> g_cu_count[kMaxDevices];   // compute units of each device, read once (0: not read yet)
 
-// Compute units to plan for: the caller's figure, else those of the current device.
-int cu_count(const qs_cache* c) {
-  if (c->compute_units > 0) return c->compute_units;
+// Compute units of the current device.
+int device_cu_count() {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return kDefaultCUs;
   int n = g_cu_count[dev].load(std::memory_order_relaxed);
@@ -32,6 +31,9 @@ int cu_count(const qs_cache* c) {
   g_cu_count[dev].store(n, std::memory_order_relaxed);
   return n;
 }
+
+// Compute units to plan for: the caller's figure, else those of the current device.
+int cu_count(const qs_cache* c) { return c->compute_units > 0 ? c->compute_units : device_cu_count(); }
 
 // Split-K partials of qs_attn_static: one array per device, part of the library's code object, so a
 // caller that must not allocate needs no workspace of its own.  In host code the array's name only
@@ -407,7 +409,7 @@ int qs_w4_linear(const qs_w4* l, const void* x, int32_t m, void* y, void* stream
   a.x = static_cast<const _Float16*>(x);
   a.y = static_cast<_Float16*>(y);
   a.m = m;
-  return launch_w4_linear(a, static_cast<hipStream_t>(stream)) == hipSuccess ? QS_OK : QS_ERR_HIP;
+  return launch_w4_linear(a, device_cu_count(), static_cast<hipStream_t>(stream)) == hipSuccess ? QS_OK : QS_ERR_HIP;
 }
 
 int qs_w4_export(const qs_w4* l, void* codes, void* scale, void* zero, void* stream) {

@@ -158,12 +158,13 @@ struct W4Args {
   const _Float16* x;        // linear: [m][n_in]
   _Float16* y;              // linear: [m][n_out]
   int m;
+  int waves_per_tile;       // linear: set by the launcher
   uint8_t* codes;           // export
   _Float16* scale;
   _Float16* zero;
 };
 hipError_t launch_w4_quantize(const W4Args& a, hipStream_t s);
 hipError_t launch_w4_export(const W4Args& a, hipStream_t s);
-hipError_t launch_w4_linear(const W4Args& a, hipStream_t s);
+hipError_t launch_w4_linear(const W4Args& a, int compute_units, hipStream_t s);
 
 }  // namespace qs

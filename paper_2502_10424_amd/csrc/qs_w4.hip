@@ -8,14 +8,19 @@
 //     sum_k x_k (c_k S + Z) = S * (sum_k c_k x_k) + Z * (sum_k x_k):
 // the first sum is four MFMA steps, the second depends on x alone and is formed once per launch.
 //
-// One workgroup of eight waves per tile of 16 output rows; wave w takes the blocks g = w, w + 8, ... of the
-// tile's row of blocks (which is contiguous in memory, so the workgroup streams one run), with the words,
-// scales, zeros and inputs of the next kAhead of its blocks requested ahead; the eight partial sums meet in
-// LDS in a fixed order (deterministic).  Every step issues the same loads - a block past the end is asked
-// for through buffer resources of no bytes, which return zero without touching memory - so the wait for a
-// block's words is a count, not a drain.
+// A tile of 16 output rows gets as many waves (W = 1 .. 16) as let all tiles be resident at once: a layer of a
+// few tens of MB is over in microseconds, and a second round of workgroups would pay the whole chain of
+// latencies again.  Wave w of the W takes the blocks g = w, w + W, ... of the tile's row of blocks (contiguous
+// in memory, so the waves of a tile stream one run), with the words, scales and zeros of the next kAhead of its
+// blocks requested ahead; the W partial sums meet in LDS in a fixed order (deterministic).  Tiles with few waves
+// each share a workgroup of up to eight waves, so that one copy of x in LDS serves several of them.
+// Every step issues the same loads - a block past the end is asked for through buffer resources of no bytes,
+// which return zero without touching memory - so the wait for a block's words is a count, not a drain.
+// x is staged in LDS once per workgroup when it fits (XLDS: the decode step's one or few rows); otherwise a
+// lane's pieces of x travel with the block's words.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdint>
 
 #include "qs_internal.h"
@@ -29,9 +34,11 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kWaves = 8, kAhead = 4;
+constexpr int kMaxWaves = 16, kAhead = 4;
+constexpr int kGroupedWaves = 8;           // tiles with fewer waves each share a workgroup of up to this many
 constexpr int kBufferWord3 = 0x00020000;   // raw 32-bit elements (gfx9 family)
 constexpr int kAuxStream = 2;              // non-temporal: the weights are read once per launch
+constexpr size_t kW4XLdsBytes = 65536;     // x is staged in LDS up to this size (one row of the longest x the library takes)
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t resource(const void* base, uint32_t bytes) {
   // the address is the same in every lane; saying so keeps the descriptor in scalar registers
@@ -51,44 +58,67 @@ __device__ __forceinline__ half8 code_operand(uint32_t w) {
   return __builtin_bit_cast(half8, r);
 }
 
-__global__ __launch_bounds__(64 * kWaves) void w4_linear_kernel(W4Args a) {
-  // sum of x over each group of 128 inputs, [group][row of x]; then the waves' partial results
+template <bool XLDS>
+__global__ __launch_bounds__(64 * kMaxWaves) void w4_linear_kernel(W4Args a) {
+  // sum of x over each group of 128 inputs, [group][row of x]; the waves' partial results; x itself (XLDS)
   extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
   const int groups = a.n_in / 128;
   float* xsum = reinterpret_cast<float*>(lds);
   float4v* red = reinterpret_cast<float4v*>(lds + (size_t)groups * 16 * sizeof(float));
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, n_waves = blockDim.x >> 6, n_threads = blockDim.x;
+  // the same in every lane of a wave; saying so keeps block numbers and resource descriptors in scalar registers
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wpt = a.waves_per_tile, tile_local = wave / wpt, w = wave % wpt, tiles = a.n_out / 16;
+  uint8_t* x_lds = reinterpret_cast<uint8_t*>(red + n_waves * 64);
   const int rho = lane & 15, q4 = lane >> 4;   // lane = 16 * q4 + rho: output rows 4 q4 .. 4 q4 + 3, row rho of x
-  const int T = blockIdx.x;
+  const int T = blockIdx.x * (n_waves / wpt) + tile_local;
+  const bool active = T < tiles;   // the last workgroup may have waves without a tile: they only help with x
 
   struct Slot {
-    u32x4 w;        // code words of the four matrix-core steps
-    u32x2 s, z;     // S, Z of output rows 4 q4 .. 4 q4 + 3
-    u32x4 x[4];     // x[rho][128 g + 32 s + 8 q4 ..], s < 4
+    u32x4 w;                  // code words of the four matrix-core steps
+    u32x2 s, z;               // S, Z of output rows 4 q4 .. 4 q4 + 3
+    u32x4 x[XLDS ? 1 : 4];    // x[rho][128 g + 32 s + 8 q4 ..], s < 4 (unless x is in LDS)
   };
-  const uint8_t* row_of_blocks = a.packed + (int64_t)T * groups * kW4Block;
+  const uint8_t* row_of_blocks = a.packed + (int64_t)min(T, tiles - 1) * groups * kW4Block;
   const uint32_t x_bytes = (uint32_t)a.m * (uint32_t)a.n_in * 2u;
   auto request = [&](Slot& sl, int g) __attribute__((always_inline)) {
-    const bool exists = g < groups;
+    const bool exists = active && g < groups;
     const __amdgpu_buffer_rsrc_t rw = resource(row_of_blocks + (int64_t)min(g, groups - 1) * kW4Block, exists ? kW4Block : 0);
     const __amdgpu_buffer_rsrc_t rx = resource(a.x, exists ? x_bytes : 0);   // rows of x past m read as zero
     sl.w = __builtin_amdgcn_raw_buffer_load_b128(rw, lane * 16, 0, kAuxStream);
     sl.s = __builtin_amdgcn_raw_buffer_load_b64(rw, kW4OffS + 8 * q4, 0, 0);
     sl.z = __builtin_amdgcn_raw_buffer_load_b64(rw, kW4OffZ + 8 * q4, 0, 0);
+    if constexpr (!XLDS) {
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
-      sl.x[s] = __builtin_amdgcn_raw_buffer_load_b128(rx, (rho * a.n_in + 128 * min(g, groups - 1) + 32 * s + 8 * q4) * 2, 0, 0);
+      for (int s = 0; s < 4; ++s)
+        sl.x[s] = __builtin_amdgcn_raw_buffer_load_b128(rx, (rho * a.n_in + 128 * min(g, groups - 1) + 32 * s + 8 * q4) * 2, 0, 0);
+    }
   };
   Slot slot[kAhead];
 #pragma unroll
-  for (int k = 0; k < kAhead; ++k) request(slot[k], wave + kWaves * k);
+  for (int k = 0; k < kAhead; ++k) request(slot[k], w + wpt * k);
+
+  if constexpr (XLDS) {   // x -> LDS, 16 bytes per thread and piece, eight pieces requested before the first is stored
+    const int pieces = a.m * a.n_in / 8;
+    const __amdgpu_buffer_rsrc_t rx = resource(a.x, x_bytes);
+    for (int base = tid; base < pieces; base += 8 * n_threads) {
+      u32x4 v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, (base + j * n_threads) * 16, 0, 0);   // past the end: zero
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (base + j * n_threads < pieces) reinterpret_cast<u32x4*>(x_lds)[base + j * n_threads] = v[j];
+    }
+    __syncthreads();
+  }
 
   // ---- sums of x per group: 16 lanes to a (group, row) pair, eight inputs each ----
   {
     const int sub = tid & 15;
-    for (int item = tid >> 4; item < groups * a.m; item += (64 * kWaves) >> 4) {
+    for (int item = tid >> 4; item < groups * a.m; item += n_threads >> 4) {
       const int g = item / a.m, row = item % a.m;
-      const half8 v = *reinterpret_cast<const half8*>(a.x + (int64_t)row * a.n_in + 128 * g + 8 * sub);
+      const int at = row * a.n_in + 128 * g + 8 * sub;
+      const half8 v = XLDS ? *reinterpret_cast<const half8*>(x_lds + 2 * at) : *reinterpret_cast<const half8*>(a.x + at);
       float sum = 0.f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) sum += (float)v[i];
@@ -96,19 +126,24 @@ __global__ __launch_bounds__(64 * kWaves) void w4_linear_kernel(W4Args a) {
       for (int m = 1; m < 16; m <<= 1) sum += __shfl_xor(sum, m);
       if (sub == 0) xsum[g * 16 + row] = sum;
     }
-    // rows past m: never read with a weight other than zero... but they are read: keep them finite
-    for (int i = tid; i < groups * 16; i += 64 * kWaves)
-      if ((i & 15) >= a.m) xsum[i] = 0.f;
   }
   __syncthreads();
 
   float4v out_s = {0.f, 0.f, 0.f, 0.f}, out_z = {0.f, 0.f, 0.f, 0.f};   // sum of S * (codes . x) * 2^-24, and of Z * sum x
   auto consume = [&](const Slot& sl, int g) __attribute__((always_inline)) {
     float4v acc = {0.f, 0.f, 0.f, 0.f};
+    const int gc = min(g, groups - 1);
 #pragma unroll
-    for (int s = 0; s < 4; ++s)
-      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_operand(sl.w[s]), __builtin_bit_cast(half8, sl.x[s]), acc, 0, 0, 0);
-    const float xs = xsum[min(g, groups - 1) * 16 + rho];
+    for (int s = 0; s < 4; ++s) {
+      u32x4 xw;
+      if constexpr (XLDS) {   // columns past m take the last row's numbers: their results are never stored
+        xw = *reinterpret_cast<const u32x4*>(x_lds + (min(rho, a.m - 1) * a.n_in + 128 * gc + 32 * s + 8 * q4) * 2);
+      } else {
+        xw = sl.x[s];
+      }
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_operand(sl.w[s]), __builtin_bit_cast(half8, xw), acc, 0, 0, 0);
+    }
+    const float xs = xsum[gc * 16 + min(rho, a.m - 1)];
     const half4 sh = __builtin_bit_cast(half4, sl.s), zh = __builtin_bit_cast(half4, sl.z);
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) {
@@ -116,24 +151,23 @@ __global__ __launch_bounds__(64 * kWaves) void w4_linear_kernel(W4Args a) {
       out_z[jj] = __builtin_fmaf(xs, (float)zh[jj], out_z[jj]);
     }
   };
-  for (int g0 = wave; g0 < groups; g0 += kWaves * kAhead) {
+  for (int g0 = active ? w : groups; g0 < groups; g0 += wpt * kAhead) {
 #pragma unroll
     for (int k = 0; k < kAhead; ++k) {
-      consume(slot[k], g0 + kWaves * k);   // a block past the end holds zeros
-      request(slot[k], g0 + kWaves * (k + kAhead));
+      if (g0 + wpt * k < groups) consume(slot[k], g0 + wpt * k);   // the requests stay unconditional
+      request(slot[k], g0 + wpt * (k + kAhead));
     }
   }
 
-  // ---- the eight partial results, added in the order of the waves ----
+  // ---- the waves' partial results, added in the order of the waves ----
   float4v part;
 #pragma unroll
   for (int jj = 0; jj < 4; ++jj) part[jj] = __builtin_fmaf(out_s[jj], 16777216.0f, out_z[jj]);
   red[wave * 64 + lane] = part;
   __syncthreads();
-  if (wave == 0 && rho < a.m) {
-    float4v y = red[lane];
-#pragma unroll
-    for (int w = 1; w < kWaves; ++w) y += red[w * 64 + lane];
+  if (w == 0 && active && rho < a.m) {
+    float4v y = red[wave * 64 + lane];
+    for (int j = 1; j < wpt; ++j) y += red[(wave + j) * 64 + lane];
     half4 h;
 #pragma unroll
     for (int jj = 0; jj < 4; ++jj) h[jj] = (_Float16)y[jj];
@@ -143,10 +177,19 @@ __global__ __launch_bounds__(64 * kWaves) void w4_linear_kernel(W4Args a) {
 
 }  // namespace
 
-hipError_t launch_w4_linear(const W4Args& a, hipStream_t s) {
-  const size_t lds = (size_t)(a.n_in / 128) * 16 * sizeof(float) + (size_t)kWaves * 64 * sizeof(float4v);
-  void* kargs[] = {const_cast<W4Args*>(&a)};
-  return hipLaunchKernel(reinterpret_cast<const void*>(w4_linear_kernel), dim3(a.n_out / 16), dim3(64 * kWaves), kargs, lds, s);
+hipError_t launch_w4_linear(const W4Args& a, int compute_units, hipStream_t s) {
+  const int tiles = a.n_out / 16, groups = a.n_in / 128;
+  // as many waves per tile as keep every tile resident at once (16 waves per compute unit), at most one per block
+  W4Args b = a;
+  b.waves_per_tile = std::max(1, std::min({kMaxWaves, groups, compute_units * 16 / tiles}));
+  const int tiles_per_wg = std::max(1, std::min(kGroupedWaves / b.waves_per_tile, tiles));
+  const int waves = b.waves_per_tile * tiles_per_wg;
+  const size_t x_bytes = (size_t)a.m * a.n_in * 2;
+  const bool xlds = x_bytes <= kW4XLdsBytes;
+  const size_t lds = (size_t)groups * 16 * sizeof(float) + (size_t)waves * 64 * sizeof(float4v) + (xlds ? x_bytes : 0);
+  void* kargs[] = {&b};
+  const void* kernel = xlds ? reinterpret_cast<const void*>(w4_linear_kernel<true>) : reinterpret_cast<const void*>(w4_linear_kernel<false>);
+  return hipLaunchKernel(kernel, dim3((tiles + tiles_per_wg - 1) / tiles_per_wg), dim3(64 * waves), kargs, lds, s);
 }
 
 }  // namespace qs
