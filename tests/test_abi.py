@@ -68,6 +68,29 @@ def test_static_scratch_entry_validates_before_touching_the_gpu(B):
     assert lib.qs_attn_static(ctypes.byref(big), q, 16, 1, out, 0.1, None, None) == B.QS_ERR_WORKSPACE
 
 
+def test_w4_validation_without_gpu(B):
+    """The 4-bit weight layer's calls check sizes, pointers and alignment before anything is enqueued."""
+    lib = B.lib()
+    assert B.qs_w4_bytes(4096, 4096) == 256 * 32 * 1088
+    for n_out, n_in in ((0, 128), (16, 0), (24, 128), (16, 64), (16, 32768 + 128), (-16, 128)):
+        assert B.qs_w4_bytes(n_out, n_in) == 0
+    good = B.qs_w4(32, 256, 0x10000)
+    x, y = 0x20000, 0x30000
+    assert lib.qs_w4_linear(ctypes.byref(good), x, 0, y, None) == B.QS_ERR_SHAPE
+    assert lib.qs_w4_linear(ctypes.byref(good), x, 17, y, None) == B.QS_ERR_SHAPE
+    assert lib.qs_w4_linear(ctypes.byref(good), None, 1, y, None) == B.QS_ERR_NULL
+    assert lib.qs_w4_linear(ctypes.byref(good), x, 1, None, None) == B.QS_ERR_NULL
+    assert lib.qs_w4_linear(ctypes.byref(good), x + 2, 1, y, None) == B.QS_ERR_ALIGN
+    assert lib.qs_w4_quantize(ctypes.byref(good), None, None) == B.QS_ERR_NULL
+    assert lib.qs_w4_quantize(ctypes.byref(good), x + 8, None) == B.QS_ERR_ALIGN
+    assert lib.qs_w4_linear(None, x, 1, y, None) == B.QS_ERR_NULL
+    for bad in (B.qs_w4(24, 256, 0x10000), B.qs_w4(32, 192, 0x10000), B.qs_w4(32, 65536, 0x10000)):
+        assert lib.qs_w4_linear(ctypes.byref(bad), x, 1, y, None) == B.QS_ERR_SHAPE
+        assert lib.qs_w4_export(ctypes.byref(bad), None, None, None, None) == B.QS_ERR_SHAPE
+    assert lib.qs_w4_quantize(ctypes.byref(B.qs_w4(32, 256, None)), x, None) == B.QS_ERR_NULL
+    assert lib.qs_w4_quantize(ctypes.byref(B.qs_w4(32, 256, 0x10004)), x, None) == B.QS_ERR_ALIGN
+
+
 def _fake_cache(B, **over):
     """A descriptor with plausible, never-dereferenced device addresses (validation only)."""
     c = B.qs_cache()
