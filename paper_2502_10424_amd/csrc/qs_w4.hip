@@ -34,7 +34,7 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kMaxWaves = 16, kAhead = 4;
+constexpr int kMaxWaves = 16, kAhead = 2;
 constexpr int kGroupedWaves = 8;           // tiles with fewer waves each share a workgroup of up to this many
 constexpr int kBufferWord3 = 0x00020000;   // raw 32-bit elements (gfx9 family)
 constexpr int kAuxStream = 2;              // non-temporal: the weights are read once per launch
