@@ -81,14 +81,17 @@ __global__ __launch_bounds__(64 * kMaxWaves) void w4_linear_kernel(W4Args a) {
   };
   const uint8_t* row_of_blocks = a.packed + (int64_t)min(T, tiles - 1) * groups * kW4Block;
   const uint32_t x_bytes = (uint32_t)a.m * (uint32_t)a.n_in * 2u;
+  // One resource for the tile's row of blocks (none of its bytes for a wave without a tile): a block is an offset
+  // into it (in the lanes' offsets, which the range check covers), and a block past the end of the row lies past
+  // the end of the resource.
+  const __amdgpu_buffer_rsrc_t rw = resource(row_of_blocks, active ? (uint32_t)groups * kW4Block : 0u);
+  const __amdgpu_buffer_rsrc_t rx = resource(a.x, active ? x_bytes : 0u);   // rows of x past m read as zero
   auto request = [&](Slot& sl, int g) __attribute__((always_inline)) {
-    const bool exists = active && g < groups;
-    const __amdgpu_buffer_rsrc_t rw = resource(row_of_blocks + (int64_t)min(g, groups - 1) * kW4Block, exists ? kW4Block : 0);
-    const __amdgpu_buffer_rsrc_t rx = resource(a.x, exists ? x_bytes : 0);   // rows of x past m read as zero
-    sl.w = __builtin_amdgcn_raw_buffer_load_b128(rw, lane * 16, 0, kAuxStream);
-    sl.s = __builtin_amdgcn_raw_buffer_load_b64(rw, kW4OffS + 8 * q4, 0, 0);
-    sl.z = __builtin_amdgcn_raw_buffer_load_b64(rw, kW4OffZ + 8 * q4, 0, 0);
-    if constexpr (!XLDS) {
+    const int at = g * kW4Block;
+    sl.w = __builtin_amdgcn_raw_buffer_load_b128(rw, at + lane * 16, 0, kAuxStream);
+    sl.s = __builtin_amdgcn_raw_buffer_load_b64(rw, at + kW4OffS + 8 * q4, 0, 0);
+    sl.z = __builtin_amdgcn_raw_buffer_load_b64(rw, at + kW4OffZ + 8 * q4, 0, 0);
+    if constexpr (!XLDS) {   // a block past the end: any block's inputs, against codes, scales and zeros that read as zero
 #pragma unroll
       for (int s = 0; s < 4; ++s)
         sl.x[s] = __builtin_amdgcn_raw_buffer_load_b128(rx, (rho * a.n_in + 128 * min(g, groups - 1) + 32 * s + 8 * q4) * 2, 0, 0);
@@ -100,11 +103,11 @@ __global__ __launch_bounds__(64 * kMaxWaves) void w4_linear_kernel(W4Args a) {
 
   if constexpr (XLDS) {   // x -> LDS, 16 bytes per thread and piece, eight pieces requested before the first is stored
     const int pieces = a.m * a.n_in / 8;
-    const __amdgpu_buffer_rsrc_t rx = resource(a.x, x_bytes);
+    const __amdgpu_buffer_rsrc_t rs = resource(a.x, x_bytes);   // every wave stages, also one without a tile
     for (int base = tid; base < pieces; base += 8 * n_threads) {
       u32x4 v[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) v[j] = __builtin_amdgcn_raw_buffer_load_b128(rx, (base + j * n_threads) * 16, 0, 0);   // past the end: zero
+      for (int j = 0; j < 8; ++j) v[j] = __builtin_amdgcn_raw_buffer_load_b128(rs, (base + j * n_threads) * 16, 0, 0);   // past the end: zero
 #pragma unroll
       for (int j = 0; j < 8; ++j)
         if (base + j * n_threads < pieces) reinterpret_cast<u32x4*>(x_lds)[base + j * n_threads] = v[j];
