@@ -1132,22 +1132,27 @@ __global__ __launch_bounds__(256) void merge_kernel(MergeArgs a) {
 
 // ------------------------------------------------------------------------------------------------
 // Other shapes than head_dim = group = 128 (plain layout, see quantspec.h).  One wave per workgroup, NRT
-// tiles of 16 query rows, chunks are ranges of 32-token blocks.  The arithmetic is that of the kernels
-// above without their tuning:
+// tiles of 16 query rows, chunks are ranges of 32-token blocks.  The arithmetic is that of the kernels above:
 //  * the codes lie in memory in the order the lanes of a wave take them as matrix-core operands: a
 //    32-bit word holds the eight codes of one lane for one key step (eight channels of a token) or
 //    one value tile (eight tokens of a channel).  A code c (4 or 8 bits), zero-extended to 16 bits,
 //    is the fp16 subnormal c * 2^-24 and serves as the A operand of both contractions, exactly;
 //  * keys: score = sum_c q_c (mul_c code_c + add_c) with (mul, add) = (S, Z) for the upper plane alone and
-//    (S/16, Z - S/2) for the 8-bit code 16 C_U + C_L + 8.  Once per group of G tokens the products
-//    q_c mul_c (exact in binary32: 11 x 11 bits) are scaled by a power of two per query row and split
-//    into two fp16 operands hi + lo, again exactly, and sum_c q_c add_c becomes a per-row bias;
+//    (S/16, Z - S/2) for the 8-bit code 16 C_U + C_L + 8.  Once per group of G tokens the row's queries and
+//    the group's scales, each brought into a fixed range by a power of two, are multiplied in packed fp16
+//    arithmetic: the rounded product and its exact remainder are the two operands hi + lo, and
+//    sum_c q_c add_c becomes a per-row bias;
 //  * values: out_c = sum_t (p_t mul_t) code_tc + sum_t p_t add_t per value group of the channel: the P operand
 //    carries the value scale (and a power of two that follows the largest scale seen, so that it stays
 //    inside fp16), the second sum is kept in binary32 beside the accumulators;
+//  * the softmax reference of a row moves rarely (see the kernels above): a block's main path has no
+//    cross-lane step;
 //  * the full-precision buffer is the same block step with the fp16 rows as "codes" (keys straight from
 //    memory, values transposed through LDS), q itself as the operand and no scales.
-// The next block's words are requested before the current block is worked on.
+// Everything a block needs - its words, its value scales and zeros, the key scales and zeros of a group it
+// starts - is requested one step before the block is worked on, through buffer resources, so that every
+// step issues the same loads; the metadata passes through LDS from the lanes that loaded it to the lanes
+// that use it.
 // ------------------------------------------------------------------------------------------------
 using half4 = _Float16 __attribute__((ext_vector_type(4)));
 
