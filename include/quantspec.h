@@ -231,12 +231,14 @@ int qs_export_codes(const qs_cache *c, int32_t b, int32_t kv_head, int32_t n_tok
  * in binary32 as for the cache.
  *
  * A layer y = x W^T with W [n_out][n_in]: n_out a multiple of 16, n_in a multiple of QS_W4_GROUP and at most 32768.
- * packed (device, caller-owned, qs_w4_bytes() bytes, 16-byte aligned; qs_w4_quantize is its only writer) is cut
- * into blocks of 16 output rows x 128 input channels, 1088 bytes each, block (T, g) at ((T*(n_in/128) + g)*1088):
- *   [   0, 1024)  codes, one 32-bit word per lane of a 64-lane wave (lane = 16*a + r, a < 4, r < 16) and
- *                 matrix-core step s < 4, at (lane*4 + s)*4: row 16*T + r, input channels
- *                 128*g + 32*s + 8*a + i (i < 8), channel i in nibble (i&1)*4 + (i>>1)
- *   [1024, 1056)  S of the 16 rows, fp16       [1056, 1088)  Z of the 16 rows, fp16
+ * packed (device, caller-owned, qs_w4_bytes() bytes, 16-byte aligned; qs_w4_quantize is its only writer) holds the
+ * weights in blocks of 16 output rows x 128 input channels, block (T, g) = tile T of rows, group g of channels,
+ * numbered b = T*(n_in/128) + g, in two regions:
+ *   codes, from byte 0, 1024 bytes per block at 1024*b: one 32-bit word per lane of a 64-lane wave
+ *                 (lane = 16*a + r, a < 4, r < 16) and matrix-core step s < 4, at (lane*4 + s)*4: row 16*T + r,
+ *                 input channels 128*g + 32*s + 8*a + i (i < 8), channel i in nibble (i&1)*4 + (i>>1)
+ *   scales and zeros, from byte 1024*(n_out/16)*(n_in/128), 64 bytes per block at 64*b: for a < 4, at 16*a,
+ *                 S of rows 16*T + 4*a .. + 3 (four fp16), then their Z (four fp16)
  * Error behaviour as above: negative code, nothing enqueued.  QS_ERR_SHAPE for sizes that are not multiples
  * as stated or m outside 1..QS_W4_MAX_ROWS, QS_ERR_NULL / QS_ERR_ALIGN for pointers.
  */

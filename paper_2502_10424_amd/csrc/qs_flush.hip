@@ -740,12 +740,13 @@ __global__ __launch_bounds__(256) void w4_quantize_kernel(W4Args a) {
   uint32_t word = 0u;
 #pragma unroll
   for (int i = 0; i < 8; ++i) word |= (uint32_t)encode_fast((float)x[i], gs).u << (4 * tile_nibble(i));
-  uint8_t* blk = a.packed + (int64_t)blockIdx.x * kW4Block;
+  uint8_t* blk = a.packed + (int64_t)blockIdx.x * kW4Codes;
   const int lane = 16 * (c & 3) + r, s = c >> 2;
   reinterpret_cast<uint32_t*>(blk)[lane * 4 + s] = word;
-  if (c == 0) {
-    reinterpret_cast<_Float16*>(blk + kW4OffS)[r] = sh;
-    reinterpret_cast<_Float16*>(blk + kW4OffZ)[r] = (_Float16)lo;
+  if (c == 0) {   // rows 4a .. 4a+3 keep S (8 bytes) and Z (8 bytes) side by side
+    _Float16* meta = reinterpret_cast<_Float16*>(a.packed + w4_meta_base(a.n_out, a.n_in) + (int64_t)blockIdx.x * kW4Meta);
+    meta[8 * (r >> 2) + (r & 3)] = sh;
+    meta[8 * (r >> 2) + 4 + (r & 3)] = (_Float16)lo;
   }
 }
 
@@ -756,15 +757,17 @@ __global__ __launch_bounds__(256) void w4_export_kernel(W4Args a) {
   if (idx >= (int64_t)a.n_out * (a.n_in / 8)) return;
   const int n = (int)(idx / (a.n_in / 8)), c8 = (int)(idx % (a.n_in / 8));
   const int g = c8 / 16, c = c8 % 16, r = n % 16;
-  const uint8_t* blk = a.packed + ((int64_t)(n / 16) * groups + g) * kW4Block;
+  const int64_t block = (int64_t)(n / 16) * groups + g;
+  const uint8_t* blk = a.packed + block * kW4Codes;
+  const _Float16* meta = reinterpret_cast<const _Float16*>(a.packed + w4_meta_base(a.n_out, a.n_in) + block * kW4Meta);
   const uint32_t word = reinterpret_cast<const uint32_t*>(blk)[(16 * (c & 3) + r) * 4 + (c >> 2)];
   if (a.codes != nullptr) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) a.codes[(int64_t)n * a.n_in + 8 * c8 + i] = (uint8_t)((word >> (4 * tile_nibble(i))) & 15u);
   }
   if (c == 0) {
-    if (a.scale != nullptr) a.scale[(int64_t)n * groups + g] = reinterpret_cast<const _Float16*>(blk + kW4OffS)[r];
-    if (a.zero != nullptr) a.zero[(int64_t)n * groups + g] = reinterpret_cast<const _Float16*>(blk + kW4OffZ)[r];
+    if (a.scale != nullptr) a.scale[(int64_t)n * groups + g] = meta[8 * (r >> 2) + (r & 3)];
+    if (a.zero != nullptr) a.zero[(int64_t)n * groups + g] = meta[8 * (r >> 2) + 4 + (r & 3)];
   }
 }
 

@@ -150,7 +150,10 @@ hipError_t launch_attn(const AttnArgs& a, int batch, bool verify, hipStream_t s)
 hipError_t launch_merge(const MergeArgs& a, int rows_total, hipStream_t s);
 
 // ---- 4-bit weights: blocks of 16 output rows x 128 input channels (see quantspec.h) ----
-constexpr int kW4Block = 1088, kW4OffS = 1024, kW4OffZ = 1056;
+constexpr int kW4Block = 1088;                   // bytes per block in all
+constexpr int kW4Codes = 1024, kW4Meta = 64;     // of which codes (first region of `packed`) and scales / zeros (second region)
+// Region of the scales and zeros, and where rows 4a .. 4a+3 of block (T, g) keep theirs in it: S (8 bytes), then Z
+__host__ __device__ inline int64_t w4_meta_base(int n_out, int n_in) { return (int64_t)(n_out / 16) * (n_in / 128) * kW4Codes; }
 struct W4Args {
   uint8_t* packed;
   int n_out, n_in;
