@@ -158,6 +158,50 @@ def test_attention_at_the_benchmarked_size(env, d, g):
         assert ed <= TOL and ev <= TOL
 
 
+@pytest.mark.parametrize("seed", [1, 2])
+def test_random_configurations(env, seed):
+    """Seeded random draws over the shapes: batch, kv-heads, grouped-query ratio, number of queries, ragged quantized
+    lengths (also none) and buffer lengths, contiguous or paged, planner told 1 / 7 / 64 / all compute units, inputs of
+    mixed magnitudes; draft and verify of each against the oracle."""
+    O, U, B, torch = env["O"], env["U"], env["B"], env["torch"]
+    rng = np.random.default_rng(seed)
+    worst = 0.0
+    for it in range(14):
+        d, g = SHAPES[rng.integers(len(SHAPES))]
+        bsz, hkv, rep = int(rng.integers(1, 4)), int(rng.integers(1, 4)), int(rng.choice([1, 2, 4, 8]))
+        nq = int(rng.integers(1, 6))
+        if rep * nq > 36:
+            nq = max(1, 36 // rep)
+        hq = hkv * rep
+        nb = [int(rng.integers(nq, 2 * g + 9)) for _ in range(bsz)]
+        t = max(int(rng.integers(0, 40)) * g + n for n in nb)
+        nb = [n + (t - n) % g for n in nb]            # every sequence quantizes whole groups of the common length
+        k = (rng.standard_normal((bsz, hkv, t, d)) * rng.choice([0.05, 1.0, 8.0])).astype(np.float16)
+        v = (rng.standard_normal((bsz, hkv, t, d)) * rng.choice([0.05, 1.0, 8.0])).astype(np.float16)
+        longest = max(t - n for n in nb)
+        paged = bool(rng.integers(2)) and longest > 0
+        q_cap = -(-longest // 128) * 128
+        kw = dict(q_cap=max(q_cap, 128), pool_groups=bsz * hkv * max(q_cap // 128, 1) + 5) if paged else {}
+        cache = U.make_device_cache(k, v, hq, nb, buf_cap=max(nb) + 4, group=g, **kw)
+        cache.compute_units = int(rng.choice([0, 1, 7, 64]))
+        oc = O.build_cache(k, v, hq, g, nb)
+        q = (rng.standard_normal((bsz, nq, hq, d)) * rng.choice([0.3, 1.0, 4.0])).astype(np.float16)
+        sm = float(rng.choice([0.3, 1.0, 2.0])) / np.sqrt(d) / (float(np.abs(k).max()) / 4 + 1e-3) * 4
+        tag = f"draw {it}: ({d},{g}) B={bsz} Hkv={hkv} x{rep} nq={nq} quantized {[t - n for n in nb]} buffer {nb} paged={paged} cu={cache.compute_units}"
+        _attn_no_lse(env, cache, oc, q[:, :1].copy(), sm, False, tag + " draft")
+        _attn_no_lse(env, cache, oc, q, sm, True, tag + " verify")
+
+
+def _attn_no_lse(env, cache, oc, q, sm_scale, verify, tag):
+    torch, B, U = env["torch"], env["B"], env["U"]
+    out = (B.qs_attn_verify if verify else B.qs_attn_draft)(cache, torch.from_numpy(q).cuda(), sm_scale).cpu().numpy()
+    ref, _ = (oc.attn_verify if verify else oc.attn_draft)(q, sm_scale)
+    assert np.isfinite(out).all(), tag
+    err = U.rel_err(out, ref)
+    _say(f"{tag}: max rel err {err:.2e}")
+    assert err <= TOL, tag
+
+
 @pytest.mark.parametrize("d,g", [(64, 32), (256, 64)])
 def test_buffer_only_and_paged(env, d, g):
     """Nothing quantized yet (all tokens in the full-precision buffer), and a paged cache whose 128-token
