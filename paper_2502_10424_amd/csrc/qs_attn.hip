@@ -1173,12 +1173,15 @@ __device__ __forceinline__ half8 code_operand(uint32_t u, uint32_t lw) {
 constexpr float kLoneScale = 16.0f;
 __host__ __device__ constexpr bool scaled_element(int i) { return (i & 2) != 0; }
 
-template <int D, int G, bool VERIFY, int NRT>
-__global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) void attn_plain_kernel(AttnArgs a) {
+// ONE: a single query row per kv-head (multi-head attention, one decode query): the quantized region takes the
+// one-token-per-lane softmax of the kernels above.
+template <int D, int G, bool VERIFY, int NRT, bool ONE = false>
+__global__ __launch_bounds__(64, D == 256 ? (ONE ? 2 : 1) : (D == 64 && NRT == 1) ? 4 : 2) void attn_plain_kernel(AttnArgs a) {
+  static_assert(!ONE || (NRT == 1 && !VERIFY), "the single-row path serves the draft call's one row");
   constexpr int KS = D / 32, NT = D / 16, VG = D / G;
   constexpr int KW = KS < 4 ? KS : 4, KQ = KS / KW;   // key words a lane holds side by side, and how many such runs
   constexpr int PL = VERIFY ? 2 : 1;                  // planes read
-  constexpr int VSTRIDE = 40;                         // 16-bit elements per LDS row (keeps 8-byte reads aligned)
+  constexpr int VSTRIDE = 36;                         // 16-bit elements per LDS row (keeps 8-byte reads aligned)
   constexpr int kEvFloor = -40;                       // below every value scale that is not zero (2^-24 / 16)
   constexpr int kTauPlain = 6;                        // a score may exceed its row's reference by 2^6 before the reference is raised
   // LDS of the one wave: the two operands hi, lo of every (row tile, key step) for the quantized region, one
@@ -1186,8 +1189,11 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
   // then (one tile of rows only: two would not leave room for eight waves per compute unit at head_dim 128) the
   // scaled queries in the same arrangement, and 4 D bytes through which a group's key scales and zeros pass
   // from the lanes that loaded them to the lanes that use them
+  // (ONE: all 16 columns of the tile carry the one row, so the four lanes of a column share a slot with the
+  // same lanes of every other column - a sixteenth of the room, which is what lets head_dim 256 run two waves per SIMD)
   constexpr bool kQInLds = NRT == 1;
-  constexpr int kOpBytes = 2 * NRT * KS * 64 * 16, kQnBytes = kQInLds ? NRT * KS * 64 * 16 : 0;
+  constexpr int QL = ONE ? 4 : 64;                    // operand slots per (part, tile, key step)
+  constexpr int kOpBytes = 2 * NRT * KS * QL * 16, kQnBytes = kQInLds ? NRT * KS * QL * 16 : 0;
   constexpr int kVmBytes = 128 * VG;   // a block's value scales and zeros, likewise
   constexpr int kQBytes = kOpBytes + kQnBytes + 4 * D + kVmBytes, kVtBytes = D * VSTRIDE * 2;
   __shared__ __attribute__((aligned(16))) uint8_t lds[kQBytes > kVtBytes ? kQBytes : kVtBytes];
@@ -1196,8 +1202,8 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
   uint16_t (*vt)[VSTRIDE] = reinterpret_cast<uint16_t (*)[VSTRIDE]>(lds);
   const ShapeLayout lay{D, G};
   const int lane = threadIdx.x & 63, rho = lane & 15, g = lane >> 4;
-  half8* q_lds = reinterpret_cast<half8*>(lds) + lane;   // operand (part, rt, s) at [((part * NRT + rt) * KS + s) * 64]
-  half8* qn_lds = reinterpret_cast<half8*>(lds + kOpBytes) + lane;   // scaled queries (rt, s) at [(rt * KS + s) * 64]
+  half8* q_lds = reinterpret_cast<half8*>(lds) + (ONE ? g : lane);   // operand (part, rt, s) at [((part * NRT + rt) * KS + s) * QL]
+  half8* qn_lds = reinterpret_cast<half8*>(lds + kOpBytes) + (ONE ? g : lane);   // scaled queries (rt, s) at [(rt * KS + s) * QL]
   const int unit = blockIdx.x, split = blockIdx.y, row0 = blockIdx.z * 16 * NRT;
   const int b = unit / a.n_kv_heads, kvh = unit % a.n_kv_heads;
   const int nb = a.len.n_buf[b];
@@ -1212,7 +1218,7 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
   int vis[NRT];   // buffer tokens [0, vis) are visible to this lane's query (causal among the nq queries)
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
-    const int row = row0 + 16 * rt + rho;
+    const int row = ONE ? 0 : row0 + 16 * rt + rho;
     valid[rt] = row < a.n_rows;
     const int rowc = valid[rt] ? row : 0;
     const int qi = rowc / a.rep, head = kvh * a.rep + rowc % a.rep;
@@ -1253,7 +1259,10 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
       if (quantized) {
         const _Float16 up_q = (_Float16)pow2(fq[rt]);
 #pragma unroll
-        for (int s = 0; s < KS; ++s) qn_lds[(rt * KS + s) * 64] = load_q(rt, s) * up_q;
+        for (int s = 0; s < KS; ++s) {
+          const half8 qn = load_q(rt, s) * up_q;
+          if (!ONE || rho == 0) qn_lds[(rt * KS + s) * QL] = qn;   // ONE: the columns hold the same; one of them writes
+        }
       }
     }
   }
@@ -1280,7 +1289,7 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
 #pragma unroll
       for (int s = 0; s < KS; ++s) {
         if constexpr (kQInLds)
-          qw[rt][s] = as_u32x4(qn_lds[(rt * KS + s) * 64]);
+          qw[rt][s] = as_u32x4(qn_lds[(rt * KS + s) * QL]);
         else
           qw[rt][s] = as_u32x4(load_q(rt, s));   // everything is requested before anything is waited for
       }
@@ -1315,8 +1324,10 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
             bs = __builtin_fmaf((float)qn[1], (float)sh[1], bs);
           }
         }
-        q_lds[((0 * NRT + rt) * KS + s) * 64] = as_half8(h4);
-        q_lds[((1 * NRT + rt) * KS + s) * 64] = as_half8(l4);
+        if (!ONE || rho == 0) {
+          q_lds[((0 * NRT + rt) * KS + s) * QL] = as_half8(h4);
+          q_lds[((1 * NRT + rt) * KS + s) * QL] = as_half8(l4);
+        }
       }
       // (mul, add) = (S, Z), or (S/16, Z - S/2) for both planes; 2^24 for a code read as a subnormal
       sc[rt] = a.c0 * pow2(24 - fq[rt] - fs - (VERIFY ? 4 : 0));
@@ -1450,7 +1461,7 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
 #pragma unroll
       for (int rt = 0; rt < NRT; ++rt) {
         if constexpr (quantized) {
-          const half8 bh = q_lds[((0 * NRT + rt) * KS + s) * 64], bl = q_lds[((1 * NRT + rt) * KS + s) * 64];
+          const half8 bh = q_lds[((0 * NRT + rt) * KS + s) * QL], bl = q_lds[((1 * NRT + rt) * KS + s) * QL];
 #pragma unroll
           for (int t = 0; t < 2; ++t) {
             acc[rt][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka[t], bh, acc[rt][t], 0, 0, 0);
@@ -1462,6 +1473,67 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
         }
       }
     }
+    if constexpr (ONE && quantized) {
+      // ---- one query row (carried by every column of the tile): its 32 scores sit eight per lane in the four lanes
+      // of a column.  Those of column 0 are dealt out to lanes (k, g), k = 0..7 (lanes 8..15 mirror them): lane (k, g)
+      // takes token 16 (k >> 2) + 4 g + (k & 3), so a
+      // lane does one exponential and one multiply per value group; the fp16 products go back in pairs, which
+      // completes the P operand in lane (0, g), the only column whose result is kept.  l and the zero-point sums
+      // stay per lane and are folded over the eight lanes when the partial is written. ----
+      auto bits = [](float f) { return __builtin_bit_cast(uint32_t, f); };
+      uint32_t w = bits(acc[0][0][0]);
+      w = row_shr_keep<1>(w, bits(acc[0][0][1]));
+      w = row_shr_keep<2>(w, bits(acc[0][0][2]));
+      w = row_shr_keep<3>(w, bits(acc[0][0][3]));
+      w = row_shr_keep<4>(w, bits(acc[0][1][0]));
+      w = row_shr_keep<5>(w, bits(acc[0][1][1]));
+      w = row_shr_keep<6>(w, bits(acc[0][1][2]));
+      w = row_shr_keep<7>(w, bits(acc[0][1][3]));
+      w = (uint32_t)__builtin_amdgcn_update_dpp((int)w, (int)w, 0x118, 0xF, 0xC, false);   // lanes 8..15 <- lanes 0..7
+      const float xv = __builtin_fmaf(__builtin_bit_cast(float, w), sc[0], bias[0]);
+      const int kk = rho & 7, tok = 16 * (kk >> 2) + 4 * g + (kk & 3);
+      using HV = _Float16 __attribute__((ext_vector_type(VG)));
+      wave_lds_sync();
+      const HV sv = *reinterpret_cast<const HV*>(vm_lds + tok * VG * 2);
+      const HV zv = *reinterpret_cast<const HV*>(vm_lds + 64 * VG + tok * VG * 2);
+      _Float16 sh_max = sv[0];
+#pragma unroll
+      for (int k = 1; k < VG; ++k) sh_max = __builtin_elementwise_max(sh_max, sv[k]);
+      const float smax = (float)sh_max;
+      const bool high = xv > m[0] + kTauPlain || exponent_of(smax) > ev;
+      if (__any(high)) {   // as in the general path below; m, ev are the same in every lane
+        const int eb = max(exponent_of(group_max(octet_max(smax))), ev);
+        const float alpha_e = pow2(max(ev - eb, -120));
+        ev = eb;
+        const float m_new = fmaxf(m[0], group_max(octet_max(xv)));
+        const float alpha = __builtin_amdgcn_exp2f(m[0] - m_new);
+        m[0] = m_new;
+        l[0] *= alpha;
+#pragma unroll
+        for (int k = 0; k < VG; ++k) zs[0][k] *= alpha;
+        const float both = alpha * alpha_e;
+#pragma unroll
+        for (int n = 0; n < NT; ++n) o[0][n] *= both;
+      }
+      const float p = __builtin_amdgcn_exp2f(xv - m[0]);
+      l[0] += p;
+      // elements 2, 3, 6, 7 of the operand meet codes that come out 16 times too large
+      const float ps = p * (pow2(14 - kTauPlain - ev) * ((rho & 2) ? 1.0f / kLoneScale : 1.0f));
+      constexpr int TILES = NT / VG;
+#pragma unroll
+      for (int k = 0; k < VG; ++k) {
+        zs[0][k] = __builtin_fmaf(p, (float)zv[k], zs[0][k]);
+        const _Float16 h = (_Float16)__builtin_fmaf(ps, (float)sv[k], 0.f);
+        const uint32_t hb = __builtin_bit_cast(uint16_t, h);
+        const uint32_t pair = hb | (row_shl_zero<1>(hb) << 16);
+        const half8 pb = as_half8((u32x4){pair, row_shl_zero<2>(pair), row_shl_zero<4>(pair), row_shl_zero<6>(pair)});
+#pragma unroll
+        for (int i = 0; i < TILES; ++i) {
+          const int n = k * TILES + i;
+          o[0][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(code_operand<false>(cur.v[0][n], 0u), pb, o[0][n], 0, 0, 0);
+        }
+      }
+    } else {
 #pragma unroll
     for (int rt = 0; rt < NRT; ++rt)
 #pragma unroll
@@ -1579,6 +1651,7 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
           o[rt][n] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vop, pb[rt], o[rt][n], 0, 0, 0);
       }
     }
+    }
     if constexpr (quantized && paged) place_load = place_then, place_then = look_up(blk + 3);
   };
   Raw ra, rb;
@@ -1611,10 +1684,11 @@ __global__ __launch_bounds__(64, D == 256 ? 1 : (D == 64 && NRT == 1) ? 4 : 2) v
   const float back = quantized ? pow2(ev + 10 + kTauPlain) : pow2(kTauPlain - 14);   // 2^(ev + tau - 14), and 2^24 for codes read as subnormals
 #pragma unroll
   for (int rt = 0; rt < NRT; ++rt) {
-    const float lsum = group_sum(l[rt]);
+    const bool spread = ONE && quantized;   // the sums lie one token per lane: over the eight lanes first
+    const float lsum = group_sum(spread ? octet_sum(l[rt]) : l[rt]);
     float zsum[VG];
 #pragma unroll
-    for (int k = 0; k < VG; ++k) zsum[k] = group_sum(zs[rt][k]);
+    for (int k = 0; k < VG; ++k) zsum[k] = group_sum(spread ? octet_sum(zs[rt][k]) : zs[rt][k]);
     const int row = row0 + 16 * rt + rho;
     if (row < a.n_rows) {
       const int64_t r = global_row(a, b, kvh, row) * n_split + split;
@@ -1686,6 +1760,7 @@ hipError_t launch_attn_plain(const AttnArgs& a, int batch, bool verify, hipStrea
       return verify ? launch(attn_plain_kernel<D, G, true, 2>, grid, dim3(64), s, a)
                     : launch(attn_plain_kernel<D, G, false, 2>, grid, dim3(64), s, a);
   }
+  if (!verify && a.n_rows == 1) return launch(attn_plain_kernel<D, G, false, 1, true>, grid, dim3(64), s, a);
   return verify ? launch(attn_plain_kernel<D, G, true, 1>, grid, dim3(64), s, a)
                 : launch(attn_plain_kernel<D, G, false, 1>, grid, dim3(64), s, a);
 }
