@@ -49,8 +49,9 @@
  *   nibble (i&1)*4 + (i>>1), i.e. bits 4*nibble .. 4*nibble+3, as in the value words above:
  *     upper : uint8 [B][Hkv][q_cap/128][128*D + 1024*VG]   per row
  *               block p (p < 4) at 32*D*p:
- *                 [0, 16*D)           key codes C_U: with KW = min(D/32, 4), word ((t*(D/32/KW) + s/KW)*64 + lane)*KW
- *                                     + s%KW (t < 2, s < D/32) holds channels 32*s + 8*g + i of token 32*p + 16*t + r
+ *                 [0, 16*D)           key codes C_U: word ((t*(D/128) + s/4)*64 + lane)*4 + s%4 (D = 64: word
+ *                                     4*lane + 2*t + s) holds channels 32*s + 8*g + i of token 32*p + 16*t + r
+ *                                     (t < 2, s < D/32)
  *                 [16*D, 32*D)        value codes C_U: word ((n/4)*64 + lane)*4 + n%4 (n < D/16) holds channel
  *                                     16*n + r of tokens 32*p + 16*(i/4) + 4*g + i%4
  *               [128*D, ...)          fp16, plain order: value scale S [128][VG], value zero Z [128][VG],

@@ -102,7 +102,7 @@ struct Plan {
   int ws_splits;   // partial slots per query row to size the workspace for: covers either way of dealing out
 };
 
-Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf) {
+Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf, bool verify) {
   const int units = c->batch * c->n_kv_heads;
   const int groups = max_quant / kG;
   const int n_rows = nq * (c->n_q_heads / c->n_kv_heads);
@@ -112,13 +112,19 @@ Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf) {
   Plan p;
   if (!tuned_shape(c)) {   // one-wave workgroups over ranges of 32-token blocks, fixed ranges only
     const int blocks = max_quant / kBlkTok;
-    // resident one-wave workgroups per compute unit: what the kernels' register budgets allow
-    // (head_dim 256: one wave per SIMD; the single-row kernel of the draft call has room for two, which pays
-    // with groups of 32, where a wave's step is long: 64 vs 73 us for 32 heads x 32k tokens; 61 vs 58 us with
-    // groups of 64, 57 vs 52 us with 128)
-    const int per_cu = c->head_dim == 256 ? (n_rows == 1 && c->group == 32 ? 8 : 4)
-                                          : (c->head_dim == 64 && n_rows <= 16) ? 16 : 8;
-    const int want_plain = std::max(1, cu_count(c) * per_cu / units);
+    // One-wave workgroups per compute unit, all row batches (grid.z) of a range counted.  Measured on 32 kv-heads x
+    // 32k tokens, 1 / 4 / 5 / 20 rows per kv-head, in workgroups per compute unit: fewer, longer ranges often beat
+    // filling every slot the registers allow (the waves of a SIMD do not advance at the same pace).
+    //   head_dim 64:  12 is within 2 % of the best everywhere (8 - 16 resident);
+    //   head_dim 128: 8 (two per SIMD); the verify call of up to 16 rows 4 (49 vs 53 us at groups of 64);
+    //   head_dim 256: 4 (one per SIMD); the single-row kernel of the draft call has room for two, which pays
+    //                 with groups of 32, where a wave's step is long (64 vs 73 us; 61 vs 58 us with groups of 64,
+    //                 57 vs 52 us with 128).
+    const int row_batches = c->head_dim == 256 ? (n_rows + 15) / 16 : (n_rows + 31) / 32;
+    const int per_cu = c->head_dim == 64    ? 12
+                       : c->head_dim == 128 ? (verify && n_rows <= 16 ? 4 : 8)
+                                            : (!verify && n_rows == 1 && c->group == 32 ? 8 : 4);
+    const int want_plain = std::max(1, cu_count(c) * per_cu / (units * row_batches));
     p.n_split_q = std::max(1, std::min(want_plain, blocks));
     p.n_split_b = std::max(1, std::min((max_buf + kBufSplitTok - 1) / kBufSplitTok, std::max(want_plain, kMinBufSplits)));
     p.cu_wgs = 0;
@@ -161,7 +167,7 @@ int attn_common(const qs_cache* c, const void* q, int32_t nq, void* out, float s
   if (dry_run) return QS_OK;
   if (workspace == nullptr || workspace_bytes < qs_workspace_bytes(c, nq)) return QS_ERR_WORKSPACE;
 
-  const Plan p = make_plan(c, nq, max_quant, max_buf);
+  const Plan p = make_plan(c, nq, max_quant, max_buf, verify);
   const int n_split = p.n_split_q + p.n_split_b;
   const int64_t rows_total = (int64_t)c->batch * nq * c->n_q_heads;
 
@@ -266,9 +272,11 @@ const char* qs_strerror(int code) {
 
 size_t qs_workspace_bytes(const qs_cache* c, int32_t nq) {
   if (validate_shape(c) != QS_OK || nq < 1 || nq > QS_MAX_NQ) return 0;
-  const Plan p = make_plan(c, nq, c->q_cap, c->buf_cap);
+  // the larger of the two calls' plans at full capacity
+  const int splits = std::max(make_plan(c, nq, c->q_cap, c->buf_cap, false).ws_splits,
+                              make_plan(c, nq, c->q_cap, c->buf_cap, true).ws_splits);
   const size_t rows_total = (size_t)c->batch * nq * c->n_q_heads;
-  return rows_total * (size_t)p.ws_splits * (c->head_dim + 2) * sizeof(float);
+  return rows_total * (size_t)splits * (c->head_dim + 2) * sizeof(float);
 }
 
 int qs_quantize_flush(const qs_cache* c, int32_t n_tokens, void* stream) {

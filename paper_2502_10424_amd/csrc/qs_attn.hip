@@ -76,11 +76,6 @@ __device__ __forceinline__ u32x4 ldb128_stream(__amdgpu_buffer_rsrc_t r, int off
 __device__ __forceinline__ u32x4 ldb128(__amdgpu_buffer_rsrc_t r, int off) {
   return __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
 }
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint2 ldb64(__amdgpu_buffer_rsrc_t r, int off) {
-  const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
-  return make_uint2(w[0], w[1]);
-}
 __device__ __forceinline__ uint32_t ldb16_stream(__amdgpu_buffer_rsrc_t r, int off) {
   return (uint16_t)__builtin_amdgcn_raw_buffer_load_b16(r, off, 0, kAuxStream);
 }
@@ -1179,7 +1174,6 @@ template <int D, int G, bool VERIFY, int NRT, bool ONE = false>
 __global__ __launch_bounds__(64, D == 256 ? (ONE ? 2 : 1) : (D == 64 && NRT == 1) ? 4 : 2) void attn_plain_kernel(AttnArgs a) {
   static_assert(!ONE || (NRT == 1 && !VERIFY), "the single-row path serves the draft call's one row");
   constexpr int KS = D / 32, NT = D / 16, VG = D / G;
-  constexpr int KW = KS < 4 ? KS : 4, KQ = KS / KW;   // key words a lane holds side by side, and how many such runs
   constexpr int PL = VERIFY ? 2 : 1;                  // planes read
   constexpr int VSTRIDE = 36;                         // 16-bit elements per LDS row (keeps 8-byte reads aligned)
   constexpr int kEvFloor = -40;                       // below every value scale that is not zero (2^-24 / 16)
@@ -1387,20 +1381,20 @@ __global__ __launch_bounds__(64, D == 256 ? (ONE ? 2 : 1) : (D == 64 && NRT == 1
     for (int pl = 0; pl < PL; ++pl) {
       const __amdgpu_buffer_rsrc_t rs = pl == 0 ? ru : rl;
       const int kp = lay.off_k(st0 / 32), vp = lay.off_v(st0 / 32);
+      if constexpr (KS == 2) {   // head_dim 64: a lane's four words are the two key steps of both token tiles
+        const u32x4 w = ldb128_stream(rs, kp + lane * 16);
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+        for (int i = 0; i < 4; ++i) r.k[pl][i >> 1][i & 1] = w[i];
+      } else {
 #pragma unroll
-        for (int sq = 0; sq < KQ; ++sq) {
-          const int off = kp + (((t * KQ + sq) * 64 + lane) * KW) * 4;
-          if constexpr (KW == 4) {
-            const u32x4 w = ldb128_stream(rs, off);
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int sq = 0; sq < KS / 4; ++sq) {
+            const u32x4 w = ldb128_stream(rs, kp + ((t * (KS / 4) + sq) * 64 + lane) * 16);
 #pragma unroll
             for (int i = 0; i < 4; ++i) r.k[pl][t][4 * sq + i] = w[i];
-          } else {
-            const uint2 w = ldb64(rs, off);
-            r.k[pl][t][0] = w.x, r.k[pl][t][1] = w.y;
           }
-        }
+      }
 #pragma unroll
       for (int nq = 0; nq < NT / 4; ++nq) {
         const u32x4 w = ldb128_stream(rs, vp + (nq * 64 + lane) * 16);

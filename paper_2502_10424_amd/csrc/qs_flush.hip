@@ -569,9 +569,9 @@ __global__ __launch_bounds__(256) void quantize_plain_kernel(FlushArgs a) {
       const int bl = w / WPB, r = w % WPB;
       uint32_t wu = 0, wl = 0;
       if (!values) {
-        constexpr int KS = D / 32, KW = KS < 4 ? KS : 4, KQ = KS / KW;
-        const int lane = (r / KW) % 64, tsq = r / (KW * 64);
-        const int s = (tsq % KQ) * KW + r % KW, t = tsq / KQ;
+        constexpr int KS = D / 32;   // word r -> (t, lane, s): the inverse of ShapeLayout::k_word
+        const int lane = (r / 4) % 64;
+        const int s = KS == 2 ? r % 2 : 4 * ((r / 256) % (KS / 4)) + r % 4, t = KS == 2 ? (r / 2) % 2 : r / (64 * KS);
         const int tok = 32 * bl + 16 * t + (lane & 15), c0 = 32 * s + 8 * (lane >> 4);
 #pragma unroll
         for (int i = 0; i < 8; ++i) wu |= (uint32_t)(cb[tok][c0 + i] & 15) << (4 * tile_nibble(i)), wl |= (uint32_t)(cb[tok][c0 + i] >> 4) << (4 * tile_nibble(i));

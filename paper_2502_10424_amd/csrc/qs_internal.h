@@ -36,13 +36,14 @@ struct ShapeLayout {
   int32_t d, g;
   __host__ __device__ int vg() const { return d / g; }                       // value groups per token
   __host__ __device__ int ks() const { return d / 32; }                      // 32-channel steps of a key row
-  __host__ __device__ int kw() const { return ks() < 4 ? ks() : 4; }         // key words a lane holds side by side
   // codes: four 32-token blocks per row, each 16 d bytes of key codes, then 16 d bytes of value codes
   __host__ __device__ int off_k(int p) const { return p * 32 * d; }
   __host__ __device__ int off_v(int p) const { return p * 32 * d + 16 * d; }
-  // 32-bit word of a key block with channels 32 s + 8 g + i (nibble (i&1)*4 + (i>>1)) of token 16 t + rho, lane = 16 g + rho
+  // 32-bit word of a key block with channels 32 s + 8 g + i (nibble (i&1)*4 + (i>>1)) of token 16 t + rho, lane = 16 g + rho:
+  // a lane's words lie four in a row (one 16-byte load): four key steps of one token tile, or, at head_dim 64, the
+  // two steps of both tiles
   __host__ __device__ int k_word(int t, int lane, int s) const {
-    return ((t * (ks() / kw()) + s / kw()) * 64 + lane) * kw() + s % kw();
+    return ks() == 2 ? lane * 4 + 2 * t + s : ((t * (ks() / 4) + s / 4) * 64 + lane) * 4 + s % 4;
   }
   // 32-bit word of a value block with channel 16 n + rho of tokens 16 (j >> 2) + 4 g + (j & 3) (nibble (j&1)*4 + (j>>1))
   __host__ __device__ int v_word(int n, int lane) const { return ((n >> 2) * 64 + lane) * 4 + (n & 3); }
