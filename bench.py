@@ -368,8 +368,8 @@ def main():
     w = synth.WORKLOADS[names[0]]
     bench = Bench(torch, B, synth, w, args.copies, keep_fp16=extras and w.n_layers == 1)
     head, avg = measure(bench, args.steps, args.warmup, graph=extras, fixed=extras, precondition_s=args.precondition)
-    kern = {"draft": "attn_kernel_cu<false,true>" if w.n_q_heads == w.n_kv_heads else "attn_kernel_cu<false,false>",
-            "verify": "attn_kernel_cu<true,false>" if w.nq_verify * w.n_q_heads // w.n_kv_heads <= 8 else "attn_kernel<2,8,true>"}
+    kern = {"draft": "attn_kernel<1,8,false,true>" if w.n_q_heads == w.n_kv_heads else "attn_kernel_cu",
+            "verify": "attn_kernel<1,8,true>" if w.nq_verify * w.n_q_heads // w.n_kv_heads <= 8 else "attn_kernel<2,8,true>"}
     roof = lambda what, plane: {
         "bound": "hbm", "kernel": f"{what} call: {kern[what]} + merge_kernel ({plane})",
         "achieved": head[f"{what}_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": head[f"{what}_frac"],

@@ -10,10 +10,10 @@ namespace {
 
 constexpr int kVersion = 210;   // 0.2.1
 constexpr int kDefaultCUs = 256;
-// resident chunk waves per compute unit the split planner aims for: the single-row-tile kernels run two
-// waves per SIMD, the multi-row-tile kernels (more than 8 query rows per kv-head) one
-constexpr int kWavesPerCU = kCuWaves;
-constexpr int kWavesPerCUMultiTile = 4;
+// resident chunk waves per compute unit the split planner aims for: one wave per SIMD, two for the draft call
+// of 2 - 8 query rows per kv-head (see make_plan)
+constexpr int kWavesPerCUSingle = 4;
+constexpr int kWavesPerCUPaired = kCuWaves;
 constexpr int kMinBufSplits = 8;   // a decode-time buffer (2G + gamma + 1 tokens) always gets its 64-token chunks
 
 constexpr int kMaxDevices = 64;
@@ -92,7 +92,7 @@ int validate_cache(const qs_cache* c) {
   return QS_OK;
 }
 
-// Number of chunks per unit.  The quantized region is cut so that about kWavesPerCU waves per
+// Number of chunks per unit.  The quantized region is cut so that about kWavesPerCUSingle (or Paired) waves per
 // compute unit are resident; the buffer is cut into 64-token chunks, or, when it is so long that
 // these would exceed that budget too, into as many equal chunks as the budget allows.  Depends on
 // the descriptor (shapes, compute units, flags) and on the given maximum lengths only.
@@ -106,7 +106,13 @@ Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf, bool verif
   const int units = c->batch * c->n_kv_heads;
   const int groups = max_quant / kG;
   const int n_rows = nq * (c->n_q_heads / c->n_kv_heads);
-  const int wpc = n_rows <= 8 ? kWavesPerCU : kWavesPerCUMultiTile;
+  // One wave per SIMD, each on a fixed range, is what the one-tile kernels run best as - measured in the steady
+  // state of a decode cycle at the power limit: one query row per kv-head at 128k context 89.8 us against 91.0 us
+  // of two waves per SIMD dealt through a queue, the 5-row verify call 169.4 against 173.5 us, at 32k 28.7 / 53.3
+  // against 31.2 / 54.5 us - with one exception, the draft call of 2 - 8 rows (grouped queries), which keeps
+  // two waves per SIMD and the queue (92.9 against 101.5 us at 128k, 4 rows).
+  const bool paired = !verify && n_rows >= 2 && n_rows <= 8;
+  const int wpc = paired ? kWavesPerCUPaired : kWavesPerCUSingle;
   // never more long chunks than resident slots: a chunk that starts late doubles the launch time
   const int want = std::max(1, cu_count(c) * wpc / units);
   Plan p;
@@ -135,13 +141,13 @@ Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf, bool verif
   // the buffer: 64-token chunks while they fit the same budget of resident waves, longer ones beyond
   p.n_split_b = std::max(1, std::min((max_buf + kBufSplitTok - 1) / kBufSplitTok, std::max(want, kMinBufSplits)));
   // Two waves per SIMD do not advance at the same pace (the older one wins the issue conflicts), so
-  // the one-tile kernels run as one eight-wave workgroup per compute unit whose waves share their
+  // where two are wanted they run as one eight-wave workgroup per compute unit whose waves share their
   // groups through a queue - when every wave still gets a group and the workgroup's share of the
   // buffer chunks fits its transpose tiles.
   p.cu_wgs = 0;
   p.ws_splits = p.n_split_q + p.n_split_b;
-  const int wgs = want / kWavesPerCU;
-  if ((c->flags & QS_FLAG_FIXED_RANGES) == 0 && n_rows <= 8 && wgs >= 1 &&
+  const int wgs = want / kCuWaves;
+  if (paired && (c->flags & QS_FLAG_FIXED_RANGES) == 0 && wgs >= 1 &&
       groups >= kCuWaves * wgs && p.n_split_b <= kCuBufItems * wgs) {
     p.cu_wgs = wgs;
     p.n_split_q = kCuWaves * wgs;
