@@ -90,11 +90,11 @@ extern "C" {
  * Appendix E's chunked decode out to the chip.
  *   QS_FLAG_FIXED_RANGES  every wave of the attention kernels gets a fixed range of 128-token groups, so
  *                         results are bit-reproducible from call to call.  That is how most calls run
- *                         anyway; without the flag (default) one kind of call - qs_attn_draft with 2 to 8
- *                         query heads per kv-head at head_dim = group = 128 - lets the waves of a compute
- *                         unit draw their groups from a shared queue at run time: about 3 % faster at
- *                         128k context, but which partial sum a group lands in - and with it the last bit
- *                         of an fp16 output - can differ between calls.                                 */
+ *                         anyway; without the flag (default) qs_attn_draft at head_dim = group = 128 with
+ *                         2 to 8 query heads per kv-head, or with one over a paged cache, lets the waves
+ *                         of a compute unit draw their groups from a shared queue at run time: 3 - 9 %
+ *                         faster at 128k context, but which partial sum a group lands in - and with it
+ *                         the last bit of an fp16 output - can differ between calls.                    */
 #define QS_FLAG_FIXED_RANGES 1u
 
 typedef enum qs_status {

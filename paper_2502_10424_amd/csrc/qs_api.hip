@@ -109,9 +109,10 @@ Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf, bool verif
   // One wave per SIMD, each on a fixed range, is what the one-tile kernels run best as - measured in the steady
   // state of a decode cycle at the power limit: one query row per kv-head at 128k context 89.8 us against 91.0 us
   // of two waves per SIMD dealt through a queue, the 5-row verify call 169.4 against 173.5 us, at 32k 28.7 / 53.3
-  // against 31.2 / 54.5 us - with one exception, the draft call of 2 - 8 rows (grouped queries), which keeps
-  // two waves per SIMD and the queue (92.9 against 101.5 us at 128k, 4 rows).
-  const bool paired = !verify && n_rows >= 2 && n_rows <= 8;
+  // against 31.2 / 54.5 us - with two exceptions that keep two waves per SIMD and the queue: the draft call
+  // of 2 - 8 rows (grouped queries: 92.9 against 101.5 us at 128k, 4 rows) and the draft call of one row over a
+  // paged cache (92.7 against 96.2 us; its verify call: 169.6 us with one wave per SIMD, 173.8 with two).
+  const bool paired = !verify && n_rows <= 8 && (n_rows >= 2 || c->group_table != nullptr);
   const int wpc = paired ? kWavesPerCUPaired : kWavesPerCUSingle;
   // never more long chunks than resident slots: a chunk that starts late doubles the launch time
   const int want = std::max(1, cu_count(c) * wpc / units);

@@ -1032,11 +1032,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NRT == 1 && 
 // serves faster - the older of the two waves of a SIMD wins every issue conflict, and finishes a
 // fixed share tens of microseconds before the younger one - simply takes more groups, and the eight
 // finish together.  Buffer chunks w, w + W, ... of the unit are the first items of the same queue.
-// Each wave still writes one partial for its quantized groups (slot 8*w + wave).  For the draft call
-// of 2 - 8 query rows per kv-head, the one case that runs faster with two waves per SIMD than with one
-// (see the planner); the planner guarantees at most four buffer items per workgroup (one transpose
-// tile each).
-template <bool PAGED>
+// Each wave still writes one partial for its quantized groups (slot 8*w + wave).  For the draft calls
+// that run faster with two waves per SIMD than with one: 2 - 8 query rows per kv-head, and one row
+// (SINGLE) over a paged cache (see the planner); the planner guarantees at most four buffer items per
+// workgroup (one transpose tile each).
+template <bool SINGLE, bool PAGED>
 __global__ __launch_bounds__(64 * kCuWaves) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_kernel_cu(AttnArgs a) {
   __shared__ _Float16 vt[kCuBufItems][kD][kVtStride];
   __shared__ int queue;
@@ -1059,7 +1059,7 @@ __global__ __launch_bounds__(64 * kCuWaves) __attribute__((amdgpu_waves_per_eu(2
     buffer_chunk<1>(a, unit, b, kvh, 0, a.n_split_q + w + n_wg * item, vt[item]);
     c = draw();
   }
-  quant_chunk<1, 8, false, false, PAGED, true>(a, unit, b, kvh, 0, kCuWaves * w + wave, &queue, g0, g1 - g0, c);
+  quant_chunk<1, 8, false, SINGLE, PAGED, true>(a, unit, b, kvh, 0, kCuWaves * w + wave, &queue, g0, g1 - g0, c);
 }
 
 // Merge of the per-chunk partials (Appendix E): M = max m_i, L = sum l_i 2^(m_i - M),
@@ -1767,8 +1767,9 @@ hipError_t launch_attn_kernel(const AttnArgs& a, dim3 grid, hipStream_t s) {
 }
 
 hipError_t launch_attn_cu(const AttnArgs& a, dim3 grid, hipStream_t s) {
-  return a.group_table != nullptr ? launch(attn_kernel_cu<true>, grid, dim3(64 * kCuWaves), s, a)
-                                  : launch(attn_kernel_cu<false>, grid, dim3(64 * kCuWaves), s, a);
+  if (a.n_rows == 1) return launch(attn_kernel_cu<true, true>, grid, dim3(64 * kCuWaves), s, a);
+  return a.group_table != nullptr ? launch(attn_kernel_cu<false, true>, grid, dim3(64 * kCuWaves), s, a)
+                                  : launch(attn_kernel_cu<false, false>, grid, dim3(64 * kCuWaves), s, a);
 }
 
 template <int NRT, int TAIL>
@@ -1791,8 +1792,8 @@ hipError_t launch_attn(const AttnArgs& a, int batch, bool verify, hipStream_t s)
 #undef QS_SHAPE
     return hipErrorInvalidValue;
   }
-  if (a.cu_wgs > 0) {   // the draft call of 2 - 8 rows with enough groups: one workgroup per compute unit, groups drawn dynamically
-    if (verify || a.n_rows < 2 || a.n_rows > 8) return hipErrorInvalidValue;
+  if (a.cu_wgs > 0) {   // a draft call the planner wants two waves per SIMD for: one workgroup per compute unit, groups drawn dynamically
+    if (verify || a.n_rows > 8 || (a.n_rows == 1 && a.group_table == nullptr)) return hipErrorInvalidValue;
     return launch_attn_cu(a, dim3(batch * a.n_kv_heads, a.cu_wgs, 1), s);
   }
   if (a.n_rows == 1 && !verify) {   // one query row per kv-head: one token per lane in the softmax
