@@ -44,10 +44,10 @@ PRECONDITION_S = 1.0            # untimed run of the cycle before the warm-up st
 # (calibrated against a plain copy kernel: FETCH_SIZE x 1.99991, WRITE_SIZE x 1.0, KiB per dispatch).
 # Filled from profiles/attn_hbm_traffic.md; a workload without an entry reports null.
 MEASURED_TRAFFIC_BYTES = {
-    ("mha128k", "draft"): int((288426.6 * 1.99991 + 1105.1) * 1024),
-    ("mha128k", "verify"): int((550508.8 * 1.99991 + 5527.3) * 1024),
-    ("gqa128k_b4", "draft"): int((288475.9 * 1.99991 + 4420.8) * 1024),
-    ("gqa128k_b4", "verify"): int((544804.3 * 1.99991 + 11701.1) * 1024),
+    ("mha128k", "draft"): int((281027.7 * 1.99991 + 585.0) * 1024),
+    ("mha128k", "verify"): int((543496.3 * 1.99991 + 2926.0) * 1024),
+    ("gqa128k_b4", "draft"): int((288478.6 * 1.99991 + 4420.7) * 1024),
+    ("gqa128k_b4", "verify"): int((544773.0 * 1.99991 + 11701.5) * 1024),
 }
 
 

@@ -8,9 +8,9 @@
 // Design
 //  * One wave walks 128-token groups of one (sequence, kv-head) unit for all query rows that share
 //    that kv-head (grouped-query heads x query tokens), so the planes are read once, and writes one
-//    partial.  Either every wave is a workgroup with a fixed contiguous range (attn_kernel), or the
-//    eight waves of a compute unit form one workgroup and draw their groups from a queue in LDS
-//    (attn_kernel_cu: the two waves of a SIMD do not advance at the same pace).
+//    partial.  Either every wave is a workgroup with a fixed contiguous range (attn_kernel; one wave per
+//    SIMD by default), or the eight waves of a compute unit form one workgroup and draw their groups from a
+//    queue in LDS (attn_kernel_cu: the two waves of a SIMD do not advance at the same pace).
 //    Every byte of the planes is loaded exactly once, by exactly one lane, with 128-bit loads that a
 //    wave issues as contiguous 1 KB requests, directly into the registers that feed the matrix cores;
 //    the cache is laid out in 32-token blocks so that these requests walk one array (draft) or two
@@ -422,7 +422,7 @@ template <int NRT, int TAIL, bool VERIFY, bool SINGLE, bool PAGED, bool DYN = fa
 __device__ __forceinline__ void quant_chunk(const AttnArgs& a, int unit, int b, int kvh, int row0, int split,
                                             int* queue = nullptr, int g_base = 0, int g_count = 0, int first_claim = 0) {
   static_assert(!SINGLE || (NRT == 1 && TAIL == 8), "the single-row path is a variant of the one-tile kernel");
-  constexpr bool kTwoWaves = NRT == 1 && TAIL != 16;   // two waves per SIMD: at most 256 registers, none of them accumulation registers
+  constexpr bool kTwoWaves = NRT == 1 && TAIL != 16;   // room for two waves per SIMD: at most 256 registers, none of them accumulation registers
   constexpr bool PIN = !kTwoWaves;
   const Lane L;
   const int lane = threadIdx.x & 63, rho = L.rho, g = L.g;
@@ -1010,7 +1010,8 @@ __device__ __forceinline__ void buffer_chunk(const AttnArgs& a, int unit, int b,
 }
 
 // A wave carries NRT tiles of query rows: 16 in each but the last, TAIL (16 or 8) in the last.
-// The kernels with one tile of at most 8 rows run two waves per SIMD, the others one.
+// The kernels with one tile of at most 8 rows keep within 256 registers, so that two of their waves fit a SIMD;
+// how many the planner asks for (one, mostly) is a measured choice, see make_plan.
 template <int NRT, int TAIL, bool VERIFY, bool SINGLE, bool PAGED>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(NRT == 1 && TAIL != 16 ? 2 : 1))) void attn_kernel(AttnArgs a) {
   __shared__ _Float16 vt[kD][kVtStride];   // value-tile transpose of the buffer chunk
