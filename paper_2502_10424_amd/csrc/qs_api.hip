@@ -139,8 +139,11 @@ Plan make_plan(const qs_cache* c, int nq, int max_quant, int max_buf, bool verif
     return p;
   }
   p.n_split_q = std::max(1, std::min(want, groups));
-  // the buffer: 64-token chunks while they fit the same budget of resident waves, longer ones beyond
-  p.n_split_b = std::max(1, std::min((max_buf + kBufSplitTok - 1) / kBufSplitTok, std::max(want, kMinBufSplits)));
+  // the buffer: 64-token chunks while they fit a budget of resident waves, longer ones beyond.  A long
+  // full-precision buffer (a cache without a quantized region) streams best with two waves per SIMD where
+  // the kernel's registers allow them: 128k tokens x 32 heads 370 us, 392 us with one.
+  const int want_buf = std::max(1, cu_count(c) * (n_rows <= 8 ? kWavesPerCUPaired : kWavesPerCUSingle) / units);
+  p.n_split_b = std::max(1, std::min((max_buf + kBufSplitTok - 1) / kBufSplitTok, std::max(want_buf, kMinBufSplits)));
   // Two waves per SIMD do not advance at the same pace (the older one wins the issue conflicts), so
   // where two are wanted they run as one eight-wave workgroup per compute unit whose waves share their
   // groups through a queue - when every wave still gets a group and the workgroup's share of the
