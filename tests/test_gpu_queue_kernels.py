@@ -1,9 +1,11 @@
-"""GPU parity of the attention kernels that deal 128-token groups out through a queue shared by the
-eight waves of a workgroup.  The planner takes them when a unit has at least eight groups per
-workgroup, i.e. at long contexts; here the caches tell the library to plan for a handful of compute units
-(qs_cache.compute_units), so that caches of a few thousand tokens run through exactly that code: with C compute
-units and U units the planner wants 8*C/U waves per unit, C/U workgroups of eight, and needs
-8*C/U groups or more and at most 4*C/U buffer chunks of 64 tokens."""
+"""GPU parity of the attention kernels under other planner settings, above all of the kernels that deal
+128-token groups out through a queue shared by the eight waves of a workgroup: the draft call of 2 - 8 query
+rows per kv-head, and that of one row over a paged cache.  The planner takes them when a unit has at least
+eight groups per workgroup, i.e. at long contexts; here the caches tell the library to plan for a handful of
+compute units (qs_cache.compute_units), so that caches of a few thousand tokens run through exactly that code:
+with C compute units and U units the planner wants 8*C/U waves per unit, C/U workgroups of eight, and needs
+8*C/U groups or more and at most 4*C/U buffer chunks of 64 tokens.  The other calls of the same cases (one
+row per kv-head, verify) run the fixed-range kernels with 4*C/U waves per unit."""
 import numpy as np
 import pytest
 
@@ -51,12 +53,13 @@ def test_queue_kernels_match_oracle(env, few_compute_units, bsz, hkv, rep, nq, c
     assert checked == 2
 
 
-def test_queue_kernels_paged_and_flush(env, few_compute_units):
+@pytest.mark.parametrize("hq", [4, 2])   # two rows per kv-head in the draft call, or one (queue-dealt only when paged)
+def test_queue_kernels_paged_and_flush(env, few_compute_units, hq):
     """Group-table mode under the queue kernels, before and after a flush."""
     torch, O, U, B = env["torch"], env["O"], env["U"], env["B"]
     rng = np.random.default_rng(77)
     few_compute_units(4)
-    bsz, hkv, hq, nq = 2, 2, 4, 5
+    bsz, hkv, nq = 2, 2, 5
     tq, nb, q_cap = 20 * 128, 128 + nq + 9, 24 * 128
     n_logical = bsz * hkv * (q_cap // 128)
     pool = n_logical + 5
@@ -80,6 +83,26 @@ def test_queue_kernels_paged_and_flush(env, few_compute_units):
     cache.n_buf -= 128
     oc.flush(128)
     _check_attn(env, cache, oc, q, 0.1, True, tag="queue paged verify after flush")
+    _check_attn(env, cache, oc, q[:, -1:], 0.1, False, tag="queue paged draft after flush")
+
+
+def test_calls_that_are_bit_reproducible_without_the_flag(env, few_compute_units):
+    """One query row per kv-head over a contiguous cache, and every verify call, run on fixed ranges whatever the
+    flag says: repeated calls give identical bits, and identical sequences of a batch identical rows."""
+    U = env["U"]
+    rng = np.random.default_rng(19)
+    few_compute_units(16)
+    reps = 3
+    for hq, hkv, nq, verify in ((2, 2, 1, False), (2, 2, 5, True), (8, 2, 2, True), (8, 2, 5, True)):
+        k1 = rng.standard_normal((1, hkv, 128 * 40 + 64, 128)).astype(np.float16)
+        v1 = rng.standard_normal(k1.shape).astype(np.float16)
+        q1 = rng.standard_normal((1, nq, hq, 128)).astype(np.float16)
+        cache = U.make_device_cache(np.repeat(k1, reps, 0), np.repeat(v1, reps, 0), hq, 64)
+        qn = np.repeat(q1, reps, 0)
+        first, _ = _run_attn(env, cache, qn, 0.09, verify)
+        again, _ = _run_attn(env, cache, qn, 0.09, verify)
+        assert np.array_equal(first.view(np.uint16), again.view(np.uint16)), (hq, hkv, nq, verify)
+        assert np.abs(first.astype(np.float32) - first[:1].astype(np.float32)).max() == 0.0, (hq, hkv, nq, verify)
 
 
 def test_deterministic_setting_is_bit_reproducible(env, few_compute_units):
